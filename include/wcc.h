@@ -1,0 +1,179 @@
+/*
+ * wcc.h -- C ABI of libwcc: the forward path of the Wavelet Compressed
+ * Convolution (WCC) layer,  WCC(K, x) = H^T T^T K_1x1 T H x  (Eq. WCC), on one
+ * AMD MI355X (gfx950).
+ *
+ * The five stage calls are the five panels of the workflow figure (A: Haar
+ * transform, B: joint shrinkage, C: 1x1 convolution on the compressed vectors,
+ * D: zero filling, E: inverse Haar transform) and the steps of the explicit
+ * algorithm in the appendix "Explicit WCC algorithm"; wcc_forward runs them all.
+ *
+ * Conventions common to every call
+ * --------------------------------
+ * Pointers.   Unless marked [host], every pointer is a DEVICE pointer owned by
+ *             the caller, 16-byte aligned, valid until the work enqueued by the
+ *             call has finished on `stream`.  The library never allocates or
+ *             frees tensors and keeps no pointer after the call's stream work.
+ * Workspace.  Scratch memory is one caller-owned device buffer attached with
+ *             wcc_set_workspace(); its size for a given layer comes from
+ *             wcc_workspace_bytes().  Calls on one context share it: two calls
+ *             that overlap in time on the same context race.
+ * Streams.    `stream` is a hipStream_t passed as void* (NULL = the null
+ *             stream).  Calls only enqueue work: no host synchronisation and no
+ *             device-to-host copy happens inside any call.
+ * Errors.     Arguments are checked before anything is enqueued; a failed check
+ *             returns a status and enqueues nothing.  No call aborts, throws or
+ *             prints.  A HIP launch failure returns WCC_ERR_HIP.
+ * Numbers.    Activations are fp32.  NaN/Inf inputs give unspecified results
+ *             (never undefined behaviour on the host).
+ *
+ * Layouts (all row-major, last index contiguous); N = H*W, n_l = (H>>l)*(W>>l)
+ * ---------------------------------------------------------------------------
+ *   x     [B, C_in,  H, W]  fp32   input feature map
+ *   y     [B, C_out, H, W]  fp32   output feature map
+ *   coef  [B, C,     N]     fp32   wavelet vector of every channel.  Position q
+ *                                  ("linear index") follows the concatenation of
+ *                                  Eq. (wavelet_transform) for d = levels:
+ *                                  [ y1^d | y2^d | y3^d | y4^d | y2^(d-1) | y3^(d-1)
+ *                                    | y4^(d-1) | ... | y2^1 | y3^1 | y4^1 ],
+ *                                  band j (1..3 -> y2..y4) of level l at offset
+ *                                  j*n_l, each band row-major (H>>l) x (W>>l).
+ *   norm  [B, N]            fp32   L1 norm over channels of coef at each position
+ *   idx   [B, k]            int32  kept positions of each sample, strictly ascending
+ *   xc    [B, C_in,  k]     fp32 (act_quant_bits = 0) or int8 codes (= 8)
+ *   yc    [B, C_out, k]     fp32
+ *   w     [C_out, C_in]     fp32 | bf16 | int8 codes (w_dtype)
+ *   w_scale [C_out]         fp32   per-output-channel scale of int8 weight codes
+ */
+#ifndef WCC_H
+#define WCC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct wcc_ctx wcc_ctx; /* opaque; holds the workspace pointer and device facts */
+
+typedef enum {
+  WCC_OK = 0,
+  WCC_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+  WCC_ERR_SHAPE = 2,       /* a dimension is < 1, too large, or H/W not divisible by 2^levels */
+  WCC_ERR_DTYPE = 3,       /* unknown w_dtype or act_quant_bits not in {0, 8}             */
+  WCC_ERR_KEEP = 4,        /* keep ratio does not give 1 <= k <= H*W                      */
+  WCC_ERR_WORKSPACE = 5,   /* no workspace attached, or it is too small / misaligned      */
+  WCC_ERR_UNSUPPORTED = 6, /* valid request this build has no kernel for                  */
+  WCC_ERR_HIP = 7,         /* the HIP runtime reported an error                           */
+  WCC_ERR_ALIGN = 8        /* a tensor pointer is not 16-byte aligned                     */
+} wcc_status;
+
+typedef enum { WCC_F32 = 0, WCC_BF16 = 1, WCC_I8 = 2 } wcc_dtype;
+
+/* One WCC layer: the inputs of the explicit algorithm (feature-map shape,
+ * kernel shape, wavelet level d, kept fraction gamma) plus storage types. */
+typedef struct {
+  int32_t B, C_in, C_out, H, W;
+  int32_t levels;             /* d >= 1; H and W must be divisible by 2^d (no padding)      */
+  int64_t keep_num, keep_den; /* gamma = keep_num/keep_den, the fraction KEPT;
+                                 k = ceil(keep_num*H*W/keep_den) in integer arithmetic      */
+  int32_t w_dtype;            /* wcc_dtype of w                                             */
+  int32_t act_quant_bits;     /* 0: kept coefficients stay fp32; 8: signed 8-bit codes      */
+} wcc_desc;
+
+/* Stages whose device time wcc_forward can record (wcc_set_profiling). */
+enum {
+  WCC_T_HAAR_FWD = 0,  /* the forward Haar kernel alone                   */
+  WCC_T_NORM_SELECT,   /* norm reduction + radix select + index emission  */
+  WCC_T_GATHER,        /* gather + max|c|                                 */
+  WCC_T_POINTWISE,     /* quantise + contraction + dequantise             */
+  WCC_T_SCATTER_IHAAR, /* position map + scatter + inverse Haar           */
+  WCC_T_COUNT
+};
+
+/* ---- context --------------------------------------------------------------------------- */
+
+/* Creates a context for HIP device `device` (makes no device allocation).  */
+wcc_status wcc_create(wcc_ctx **out /*[host]*/, int device);
+wcc_status wcc_destroy(wcc_ctx *ctx);
+
+/* Bytes of workspace that any call below needs for this layer (a multiple of 256). */
+wcc_status wcc_workspace_bytes(const wcc_desc *desc /*[host]*/, size_t *bytes /*[host]*/);
+
+/* Attaches a caller-owned device buffer (256-byte aligned) as the workspace.  The
+ * context only remembers the pointer; the caller frees it after the last call. */
+wcc_status wcc_set_workspace(wcc_ctx *ctx, void *dev_ptr, size_t bytes);
+
+/* k = ceil(gamma*H*W) of Alg. 1, or -1 if the descriptor is invalid.  Pure host function. */
+int64_t wcc_k(const wcc_desc *desc /*[host]*/);
+
+const char *wcc_status_string(wcc_status s);
+
+/* When enabled, wcc_forward brackets each stage with HIP events on `stream`.
+ * wcc_stage_times() waits for the last profiled wcc_forward and writes the
+ * WCC_T_COUNT stage durations in milliseconds to ms [host]. */
+wcc_status wcc_set_profiling(wcc_ctx *ctx, int enabled);
+wcc_status wcc_stage_times(wcc_ctx *ctx, float *ms /*[host], WCC_T_COUNT floats*/);
+
+/* ---- A: multi-level Haar transform (Eq. HaarKernel, Eq. wavelet_transform) -------------
+ * coef[b,c,:] = HWT_d(x[b,c,:,:]) for the C_in channels of desc; one level maps each 2x2
+ * block [[a,b],[c,d]] to y1=(a+b+c+d)/2, y2=(a-b+c-d)/2, y3=(a+b-c-d)/2, y4=(a-b-c+d)/2 and
+ * recurses on y1.  If norm != NULL it also receives norm[b,q] = sum_c |coef[b,c,q]| (the
+ * "vector norm along the channel dimension" of Alg. 1, read as L1; channel partial sums are
+ * combined in a fixed order, so the result does not vary from run to run).
+ * x is not modified.  Needs the workspace when norm != NULL. */
+wcc_status wcc_haar_fwd(wcc_ctx *ctx, const wcc_desc *desc, const float *x, float *coef,
+                        float *norm /*nullable*/, void *stream);
+
+/* ---- B: joint shrinkage, index set I (Alg. 1; Eq. T applied jointly to all channels) ----
+ * Per sample b: the k positions with the largest norm, ties broken toward the lower
+ * position q; idx[b,:] ascending.  Exactly one of coef / norm may be NULL: with norm given
+ * it is used as is; otherwise it is computed from coef ([B,C_in,N]) into the workspace.
+ * Norms are compared as fp32 numbers (they are >= 0). */
+wcc_status wcc_joint_topk(wcc_ctx *ctx, const wcc_desc *desc, const float *coef /*nullable*/,
+                          const float *norm /*nullable*/, int32_t *idx, void *stream);
+
+/* ---- B': extract the kept entries of every channel, then quantise them -------------------
+ * xc[b,c,j] = coef[b,c,idx[b,j]].  With act_quant_bits = 8 the kept coefficients go through
+ * the signed scheme of Eq. (quantweights) with b = 8:  u = c/alpha, clip to [-1,1],
+ * code = round_half_even(127*u), all in fp32, stored as int8; the value stood for is
+ * alpha*code/127.  alpha = alpha_in if alpha_in > 0, else the largest |kept coefficient| of
+ * the whole call (alpha = 0 gives all-zero codes).  alpha_dev (1 float, device) receives
+ * alpha; it may be NULL only when act_quant_bits = 0.  idx is trusted to hold values in
+ * [0, N).  Needs the workspace when act_quant_bits = 8. */
+wcc_status wcc_gather_quant(wcc_ctx *ctx, const wcc_desc *desc, const float *coef,
+                            const int32_t *idx, float alpha_in, void *xc, float *alpha_dev,
+                            void *stream);
+
+/* ---- C: the 1x1 convolution on the compressed signal,  y_i = sum_j k_ij x_j --------------
+ * yc[b,o,j] = s_x * s_w[o] * sum_c w[o,c] * xc[b,c,j]  with s_x = alpha/127 for int8 codes
+ * (alpha read from alpha_dev on the device) and 1 for fp32 xc; s_w = w_scale for int8
+ * weights (required then), else 1.  Arithmetic: bf16 or int8 weights with int8 codes run on
+ * the matrix cores (bf16 x bf16 -> fp32, int8 x int8 -> int32); every other combination
+ * is computed with fp32 FMAs on the weights widened to fp32. */
+wcc_status wcc_pointwise(wcc_ctx *ctx, const wcc_desc *desc, const void *w,
+                         const float *w_scale /*nullable unless w_dtype = I8*/, const void *xc,
+                         const float *alpha_dev /*nullable unless act_quant_bits = 8*/,
+                         float *yc, void *stream);
+
+/* ---- D+E: zero filling and inverse transform (T^T, then iHWT with levels reversed) -------
+ * z = 0, z[b,o,idx[b,j]] = yc[b,o,j];  y[b,o,:,:] = iHWT_d(z[b,o,:]), one level mapping
+ * (y1,y2,y3,y4) back to a=(y1+y2+y3+y4)/2, b=(y1-y2+y3-y4)/2, c=(y1+y2-y3-y4)/2,
+ * d=(y1-y2-y3+y4)/2.  z is never materialised.  idx must be strictly ascending per sample
+ * with values in [0, N).  Needs the workspace. */
+wcc_status wcc_scatter_ihaar(wcc_ctx *ctx, const wcc_desc *desc, const float *yc,
+                             const int32_t *idx, float *y, void *stream);
+
+/* ---- the whole layer (Alg. 1 with the quantiser between shrinkage and convolution) ------
+ * y = H^T T^T K T H x.  Intermediates live in the workspace.  Results are those of the five
+ * calls above run in sequence.  idx_out ([B,k]) and alpha_out_dev (1 float) are optional. */
+wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const void *w,
+                       const float *w_scale /*nullable unless I8*/, float alpha_in, float *y,
+                       int32_t *idx_out /*nullable*/, float *alpha_out_dev /*nullable*/,
+                       void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WCC_H */

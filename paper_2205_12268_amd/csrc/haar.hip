@@ -1,0 +1,493 @@
+// Multi-level Haar analysis / synthesis for gfx950 (Eq. HaarKernel, Eq. wavelet_transform;
+// "transposed operations in the opposite order" for the inverse), with the channel L1 norm
+// of Alg. 1 fused into the analysis and the zero filling T^T fused into the synthesis.
+//
+// Design.  A d-level Haar transform is local to 2^d x 2^d pixel blocks, so the whole
+// transform of a strip of 2^d image rows can live in registers: all levels cost one HBM read
+// and one HBM write.  A lane owns V = 4 adjacent columns of the strip (one 16-byte load per
+// row); a wavefront therefore reads 1 KiB-contiguous row segments.  Levels 1 and 2 pair
+// columns inside the lane; from level 3 on the horizontal partner is the lane at distance
+// 1, 2, ... and is reached with a DPP quad permute -- no LDS is needed.  The values a wave
+// produces for one band row are contiguous in the wavelet vector, so every store is a
+// contiguous run as well (8 bytes per lane at level 1, 4 at level 2, ...).
+// Each wave walks a group of channels over the same strip, prefetching the next channel's
+// rows while it transforms the current one; per-position |coefficient| sums stay in
+// registers and are written once per channel group.
+#include <type_traits>
+
+#include "wcc_internal.h"
+
+namespace wcc {
+namespace {
+
+// ---- compile-time shape of the per-lane tile at every level --------------------------------
+// level 0 tile: (1<<D) rows x V columns.  Going to level l halves the rows; it halves the
+// columns while there are >= 2 in the lane, afterwards it doubles the "span" (number of
+// lanes that hold the same value).
+__host__ __device__ constexpr int cols_at(int V, int l) { return (V >> l) > 0 ? (V >> l) : 1; }
+__host__ __device__ constexpr int span_at(int V, int l) {
+  int s = 1, v = V;
+  for (int i = 0; i < l; ++i) {
+    if (v >= 2) v /= 2; else s *= 2;
+  }
+  return s;
+}
+__host__ __device__ constexpr int rows_at(int D, int l) { return 1 << (D - l); }
+// register slot of (level l, band j, row i, column e); band 0 exists only at level D
+__host__ __device__ constexpr int slot_base(int D, int V, int l, int j) {
+  int s = 0;
+  for (int m = 1; m < l; ++m) s += 3 * rows_at(D, m) * cols_at(V, m);
+  if (l == D) return s + j * rows_at(D, l) * cols_at(V, l);  // 4 bands at the last level
+  return s + (j - 1) * rows_at(D, l) * cols_at(V, l);
+}
+__host__ __device__ constexpr int slot_count(int D, int V) {
+  return slot_base(D, V, D, 3) + rows_at(D, D) * cols_at(V, D);
+}
+
+template <int S>
+__device__ __forceinline__ float lane_xor(float v) {
+  int x = __float_as_int(v);
+  if constexpr (S == 1) {
+    x = __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+  } else if constexpr (S == 2) {
+    x = __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
+  } else {
+    x = __shfl_xor(x, S, kWave);
+  }
+  return __int_as_float(x);
+}
+
+// Where a lane's values of every level land inside one plane's wavelet vector.
+template <int D>
+struct LanePos {
+  int off[D + 1];     // off[l]: (first row >> l) * (W >> l) + (first column >> l), l = 1..D
+  int rowlen[D + 1];  // W >> l
+  int nl[D + 1];      // band size n_l
+  int lc;             // lane's column index inside its row of lanes
+};
+
+// ---- analysis ---------------------------------------------------------------------------
+template <int D, int V>
+struct FwdSink {
+  float *plane;  // wavelet vector of the current (b, c)
+  float acc[slot_count(D, V)];
+  template <int L, int J>
+  __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
+                                          bool owner) {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) acc[base + i * CV + e] += fabsf(v[e]);
+    if (!owner) return;
+    float *dst = plane + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
+    if constexpr (CV == 2) {
+      *reinterpret_cast<float2 *>(dst) = make_float2(v[0], v[1]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < CV; ++e) dst[e] = v[e];
+    }
+  }
+};
+
+template <int D, int V, int L, class Sink>
+__device__ __forceinline__ void fwd_levels(const float (&in)[rows_at(D, L - 1)][cols_at(V, L - 1)],
+                                           const LanePos<D> &p, Sink &sink) {
+  constexpr int R2 = rows_at(D, L), VI = cols_at(V, L - 1), V2 = cols_at(V, L);
+  constexpr int SI = span_at(V, L - 1), S2 = span_at(V, L);
+  float ll[R2][V2];
+  const bool owner = (S2 == 1) || ((p.lc & (S2 - 1)) == 0);
+#pragma unroll
+  for (int i = 0; i < R2; ++i) {
+    float y2[V2], y3[V2], y4[V2];
+#pragma unroll
+    for (int e = 0; e < V2; ++e) {
+      float a, b, c, d;
+      if constexpr (VI >= 2) {
+        a = in[2 * i][2 * e]; b = in[2 * i][2 * e + 1];
+        c = in[2 * i + 1][2 * e]; d = in[2 * i + 1][2 * e + 1];
+      } else {
+        const float o0 = in[2 * i][0], o1 = in[2 * i + 1][0];
+        const float q0 = lane_xor<SI>(o0), q1 = lane_xor<SI>(o1);
+        const bool left = (p.lc & SI) == 0;
+        a = left ? o0 : q0; b = left ? q0 : o0;
+        c = left ? o1 : q1; d = left ? q1 : o1;
+      }
+      const float s1 = a + b, s2 = c + d, d1 = a - b, d2 = c - d;
+      ll[i][e] = 0.5f * (s1 + s2);
+      y2[e] = 0.5f * (d1 + d2);
+      y3[e] = 0.5f * (s1 - s2);
+      y4[e] = 0.5f * (d1 - d2);
+    }
+    sink.template put_row<L, 1>(p, i, y2, owner);
+    sink.template put_row<L, 2>(p, i, y3, owner);
+    sink.template put_row<L, 3>(p, i, y4, owner);
+    if constexpr (L == D) sink.template put_row<L, 0>(p, i, ll[i], owner);
+  }
+  if constexpr (L < D) fwd_levels<D, V, L + 1>(ll, p, sink);
+}
+
+template <int V> struct VecT;
+template <> struct VecT<4> { using type = float4; };
+template <> struct VecT<2> { using type = float2; };
+
+template <int V>
+__device__ __forceinline__ void load_row(const float *src, float (&dst)[V]) {
+  using T = typename VecT<V>::type;
+  const T t = *reinterpret_cast<const T *>(src);
+  dst[0] = t.x; dst[1] = t.y;
+  if constexpr (V == 4) { dst[2] = t.z; dst[3] = t.w; }
+}
+template <int V>
+__device__ __forceinline__ void store_row(float *dst, const float (&src)[V]) {
+  using T = typename VecT<V>::type;
+  T t;
+  t.x = src[0]; t.y = src[1];
+  if constexpr (V == 4) { t.z = src[2]; t.w = src[3]; }
+  *reinterpret_cast<T *>(dst) = t;
+}
+
+// How waves tile one plane.
+struct StripMap {
+  int lpr;        // lanes per strip row (power of two <= 64)
+  int log_lpr;
+  int col_segs;   // 64-lane column segments per row (1 unless lpr == 64)
+  int lanes_w;    // W / V lanes needed per row
+  int strips;     // H >> D
+  int units;      // wave work items per plane
+};
+
+template <int D, int V>
+__device__ __forceinline__ bool locate(const StripMap &m, const Geo &g, int unit, LanePos<D> &p,
+                                       int &row0, int &col0) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int sub = lane >> m.log_lpr;
+  p.lc = lane & (m.lpr - 1);
+  const int ru = unit / m.col_segs, cs = unit - ru * m.col_segs;
+  const int strip = ru * (kWave >> m.log_lpr) + sub;
+  const int col_lane = cs * m.lpr + p.lc;
+  row0 = strip << D;
+  col0 = col_lane * V;
+#pragma unroll
+  for (int l = 1; l <= D; ++l) {
+    p.rowlen[l] = g.W >> l;
+    p.nl[l] = (g.H >> l) * (g.W >> l);
+    p.off[l] = (row0 >> l) * p.rowlen[l] + (col0 >> l);
+  }
+  return unit < m.units && strip < m.strips && col_lane < m.lanes_w;
+}
+
+// x [B, C, H, W] -> coef [B, C, N]; partial norms over this block's channel group to
+// norm_part [G, B, N] (nullable).  grid = (ceil(units/4), G, B), block = 256.
+template <int D, int V>
+__global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__ x,
+                                                       float *__restrict__ coef,
+                                                       float *__restrict__ norm_part, Geo g,
+                                                       StripMap m, int C, int Cg, int B) {
+  constexpr int R = 1 << D;
+  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int grp = blockIdx.y, b = blockIdx.z;
+  LanePos<D> p;
+  int row0, col0;
+  if (!locate<D, V>(m, g, unit, p, row0, col0)) return;
+  const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
+  if (c0 >= c1) return;
+
+  FwdSink<D, V> sink;
+#pragma unroll
+  for (int s = 0; s < slot_count(D, V); ++s) sink.acc[s] = 0.f;
+
+  const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+  sink.plane = coef + ((size_t)b * C + c0) * g.N;
+  float cur[R][V], nxt[R][V];
+#pragma unroll
+  for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)r * g.W, nxt[r]);
+  for (int c = c0; c < c1; ++c) {
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int e = 0; e < V; ++e) cur[r][e] = nxt[r][e];
+    if (c + 1 < c1) {
+      src += g.N;
+#pragma unroll
+      for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)r * g.W, nxt[r]);
+    }
+    fwd_levels<D, V, 1>(cur, p, sink);
+    sink.plane += g.N;
+  }
+
+  if (norm_part == nullptr) return;
+  float *np = norm_part + ((size_t)grp * B + b) * g.N;
+  // write the accumulated |coefficient| sums with the same addressing as the coefficients
+  auto flush = [&](auto Lc, auto Jc) {
+    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+    constexpr int CV = cols_at(V, L), S2 = span_at(V, L);
+    const bool owner = (S2 == 1) || ((p.lc & (S2 - 1)) == 0);
+    if (!owner) return;
+#pragma unroll
+    for (int i = 0; i < rows_at(D, L); ++i) {
+      float *dst = np + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
+#pragma unroll
+      for (int e = 0; e < CV; ++e) dst[e] = sink.acc[slot_base(D, V, L, J) + i * CV + e];
+    }
+  };
+  auto each_level = [&](auto Lc) {
+    constexpr int L = decltype(Lc)::value;
+    flush(Lc, std::integral_constant<int, 1>{});
+    flush(Lc, std::integral_constant<int, 2>{});
+    flush(Lc, std::integral_constant<int, 3>{});
+    if constexpr (L == D) flush(Lc, std::integral_constant<int, 0>{});
+  };
+  each_level(std::integral_constant<int, 1>{});
+  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+  if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+}
+
+// ---- synthesis with zero filling ------------------------------------------------------------
+// jj[slot] = rank j of the position inside the kept list, or -1 (dropped -> coefficient 0).
+template <int D, int V>
+struct InvSource {
+  const float *plane;  // yc[b, o, :]
+  int jj[slot_count(D, V)];
+  uint64_t any[2];     // wave-uniform: bit s set if some lane keeps slot s
+  template <int L, int J>
+  __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) {
+      const int s = base + i * CV + e;
+      float t = 0.f;
+      if ((any[s >> 6] >> (s & 63)) & 1) {
+        const int j = jj[s];
+        if (j >= 0) t = plane[j];
+      }
+      v[e] = t;
+    }
+  }
+};
+
+template <int D, int V, int L, class Source>
+__device__ __forceinline__ void inv_levels(float (&out)[rows_at(D, L - 1)][cols_at(V, L - 1)],
+                                           const LanePos<D> &p, const Source &src) {
+  constexpr int R2 = rows_at(D, L), VI = cols_at(V, L - 1), V2 = cols_at(V, L);
+  constexpr int SI = span_at(V, L - 1);
+  float ll[R2][V2];
+  if constexpr (L < D) {
+    inv_levels<D, V, L + 1>(ll, p, src);
+  } else {
+#pragma unroll
+    for (int i = 0; i < R2; ++i) src.template get_row<L, 0>(i, ll[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < R2; ++i) {
+    float y2[V2], y3[V2], y4[V2];
+    src.template get_row<L, 1>(i, y2);
+    src.template get_row<L, 2>(i, y3);
+    src.template get_row<L, 3>(i, y4);
+#pragma unroll
+    for (int e = 0; e < V2; ++e) {
+      const float s1 = ll[i][e] + y3[e], s2 = ll[i][e] - y3[e];
+      const float d1 = y2[e] + y4[e], d2 = y2[e] - y4[e];
+      const float a = 0.5f * (s1 + d1), b = 0.5f * (s1 - d1);
+      const float c = 0.5f * (s2 + d2), d = 0.5f * (s2 - d2);
+      if constexpr (VI >= 2) {
+        out[2 * i][2 * e] = a; out[2 * i][2 * e + 1] = b;
+        out[2 * i + 1][2 * e] = c; out[2 * i + 1][2 * e + 1] = d;
+      } else {
+        // every lane of the group holds the same (y1..y4); the left half keeps the left pixel
+        const bool left = (p.lc & SI) == 0;
+        out[2 * i][0] = left ? a : b;
+        out[2 * i + 1][0] = left ? c : d;
+      }
+    }
+  }
+}
+
+// yc [B, C, k] + jmap [B, N] -> y [B, C, H, W].  grid = (ceil(units/4), G, B), block = 256.
+template <int D, int V>
+__global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restrict__ yc,
+                                                            const int32_t *__restrict__ jmap,
+                                                            float *__restrict__ y, Geo g,
+                                                            StripMap m, int C, int Cg, int64_t k) {
+  constexpr int R = 1 << D;
+  constexpr int NS = slot_count(D, V);
+  static_assert(NS <= 128, "slot mask is 128 bits wide");
+  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int grp = blockIdx.y, b = blockIdx.z;
+  LanePos<D> p;
+  int row0, col0;
+  const bool active = locate<D, V>(m, g, unit, p, row0, col0);
+  const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
+
+  InvSource<D, V> src;
+  src.any[0] = src.any[1] = 0;
+  const int32_t *jm = jmap + (size_t)b * g.N;
+  // ranks of this lane's positions (the same for every channel)
+  auto fetch = [&](auto Lc, auto Jc) {
+    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+    constexpr int CV = cols_at(V, L);
+#pragma unroll
+    for (int i = 0; i < rows_at(D, L); ++i)
+#pragma unroll
+      for (int e = 0; e < CV; ++e) {
+        constexpr int base = slot_base(D, V, L, J);
+        const int s = base + i * CV + e;
+        int j = -1;
+        if (active) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
+        src.jj[s] = j;
+        if (__ballot(j >= 0) != 0) src.any[s >> 6] |= (uint64_t)1 << (s & 63);
+      }
+  };
+  auto each_level = [&](auto Lc) {
+    constexpr int L = decltype(Lc)::value;
+    fetch(Lc, std::integral_constant<int, 1>{});
+    fetch(Lc, std::integral_constant<int, 2>{});
+    fetch(Lc, std::integral_constant<int, 3>{});
+    if constexpr (L == D) fetch(Lc, std::integral_constant<int, 0>{});
+  };
+  each_level(std::integral_constant<int, 1>{});
+  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+  if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+  if (!active || c0 >= c1) return;
+
+  src.plane = yc + ((size_t)b * C + c0) * k;
+  float *dst = y + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+  for (int c = c0; c < c1; ++c) {
+    float out[R][V];
+    inv_levels<D, V, 1>(out, p, src);
+#pragma unroll
+    for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * g.W, out[r]);
+    src.plane += k;
+    dst += g.N;
+  }
+}
+
+// ---- small helpers ----------------------------------------------------------------------------
+// norm[i] = sum_g part[g][i], groups added in increasing order (fixed order: reproducible).
+__global__ __launch_bounds__(256) void norm_reduce_kernel(const float *__restrict__ part, int G,
+                                                          int64_t BN4, float4 *__restrict__ norm) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= BN4) return;
+  const float4 *p = reinterpret_cast<const float4 *>(part);
+  float4 s = p[i];
+  for (int gi = 1; gi < G; ++gi) {
+    const float4 t = p[(int64_t)gi * BN4 + i];
+    s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+  }
+  norm[i] = s;
+}
+
+// norm[b, q] = sum_c |coef[b, c, q]|, channels in increasing order.  grid = (ceil(N/4/256), B)
+__global__ __launch_bounds__(256) void channel_norm_kernel(const float *__restrict__ coef, int C,
+                                                           int64_t N, float *__restrict__ norm) {
+  const int64_t i4 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int b = blockIdx.y;
+  if (i4 * 4 >= N) return;
+  const float4 *p = reinterpret_cast<const float4 *>(coef + (size_t)b * C * N) + i4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int c = 0; c < C; ++c) {
+    const float4 t = p[(size_t)c * (N / 4)];
+    s.x += fabsf(t.x); s.y += fabsf(t.y); s.z += fabsf(t.z); s.w += fabsf(t.w);
+  }
+  reinterpret_cast<float4 *>(norm + (size_t)b * N)[i4] = s;
+}
+
+StripMap make_map(const wcc_desc &d, int V) {
+  StripMap m;
+  m.lanes_w = d.W / V;
+  int lpr = 1, lg = 0;
+  while (lpr < m.lanes_w && lpr < kWave) { lpr *= 2; ++lg; }
+  m.lpr = lpr;
+  m.log_lpr = lg;
+  m.col_segs = (m.lanes_w + lpr - 1) / lpr;
+  m.strips = d.H >> d.levels;
+  const int spw = kWave / lpr;
+  m.units = ((m.strips + spw - 1) / spw) * m.col_segs;
+  return m;
+}
+
+template <int D, int V>
+hipError_t fwd_launch(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
+                      hipStream_t s) {
+  const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
+  const StripMap m = make_map(d, V);
+  const int Cg = (d.C_in + G - 1) / G;
+  dim3 grid((m.units + 3) / 4, G, d.B);
+  hipLaunchKernelGGL((haar_fwd_kernel<D, V>), grid, dim3(256), 0, s, x, coef, norm_part, g, m,
+                     d.C_in, Cg, d.B);
+  return hipGetLastError();
+}
+
+template <int D, int V>
+hipError_t inv_launch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, float *y,
+                      int G, hipStream_t s) {
+  const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
+  const StripMap m = make_map(d, V);
+  const int Cg = (d.C_out + G - 1) / G;
+  dim3 grid((m.units + 3) / 4, G, d.B);
+  hipLaunchKernelGGL((scatter_ihaar_kernel<D, V>), grid, dim3(256), 0, s, yc, jmap, y, g, m,
+                     d.C_out, Cg, k);
+  return hipGetLastError();
+}
+
+// Channel groups: split the channels until the launch has `want_waves` waves to cover the
+// memory latency of 256 CUs, but keep at least `min_ch` channels in a group.
+int groups_for(const wcc_desc &d, int C, int64_t want_waves, int min_ch) {
+  const int V = (d.W % 4 == 0) ? 4 : 2;
+  const StripMap m = make_map(d, V);
+  const int64_t waves = (int64_t)m.units * d.B;
+  int G = 1;
+  while (waves * G < want_waves && C / (G * 2) >= min_ch) G *= 2;
+  return G;
+}
+
+}  // namespace
+
+// Every forward group costs one partial-norm plane (written once, read once): with >= 16
+// channels a group that is at most 1/16 of the transform's own traffic.
+int forward_groups(const wcc_desc &d) { return groups_for(d, d.C_in, 4096, 16); }
+
+hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
+                           hipStream_t s) {
+  const bool v4 = d.W % 4 == 0;
+  switch (d.levels) {
+    case 1: return v4 ? fwd_launch<1, 4>(d, x, coef, norm_part, G, s)
+                      : fwd_launch<1, 2>(d, x, coef, norm_part, G, s);
+    case 2: return fwd_launch<2, 4>(d, x, coef, norm_part, G, s);
+    case 3: return fwd_launch<3, 4>(d, x, coef, norm_part, G, s);
+    case 4: return fwd_launch<4, 4>(d, x, coef, norm_part, G, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
+                                float *y, hipStream_t s) {
+  const bool v4 = d.W % 4 == 0;
+  const int G = groups_for(d, d.C_out, 8192, 4);
+  switch (d.levels) {
+    case 1: return v4 ? inv_launch<1, 4>(d, k, yc, jmap, y, G, s)
+                      : inv_launch<1, 2>(d, k, yc, jmap, y, G, s);
+    case 2: return inv_launch<2, 4>(d, k, yc, jmap, y, G, s);
+    case 3: return inv_launch<3, 4>(d, k, yc, jmap, y, G, s);
+    case 4: return inv_launch<4, 4>(d, k, yc, jmap, y, G, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s) {
+  const int64_t n4 = BN / 4;
+  hipLaunchKernelGGL(norm_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
+                     norm_part, G, n4, reinterpret_cast<float4 *>(norm));
+  return hipGetLastError();
+}
+
+hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, float *norm,
+                               hipStream_t s) {
+  dim3 grid((unsigned)((N / 4 + 255) / 256), B);
+  hipLaunchKernelGGL(channel_norm_kernel, grid, dim3(256), 0, s, coef, C, N, norm);
+  return hipGetLastError();
+}
+
+}  // namespace wcc
