@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Throughput of the WCC forward path on one MI355X.
+
+A step is one ``wcc_forward`` (Haar transform -> joint top-k -> gather/quantise -> 1x1
+contraction -> scatter + inverse Haar) over one batch of seeded synthetic feature maps that
+are already resident in HBM.  Prints ONE JSON line: whole-layer Gpixel*ch/s, the roofline
+fraction of the dominant kernel (measured with HIP events inside the library around that
+kernel), and the CPU oracle timed on this host as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def algorithmic_bytes(cfg) -> dict:
+    """Bytes each stage must move per call (fp32 activations), by stage."""
+    B, Ci, Co, N, k = cfg.B, cfg.C_in, cfg.C_out, cfg.N, cfg.k
+    bx = 1 if cfg.act_bits else 4
+    bw = {0: 4, 1: 2, 2: 1}[cfg.w_dtype]
+    return {
+        "haar_fwd": 4 * B * Ci * N + 4 * B * Ci * N + 4 * B * N,
+        "norm_select": 4 * B * N + 4 * B * k,
+        "gather": 4 * B * Ci * k + 4 * B * k + bx * B * Ci * k,
+        "pointwise": bx * B * Ci * k + bw * Ci * Co + 4 * B * Co * k,
+        "scatter_ihaar": 4 * B * Co * k + 4 * B * k + 4 * B * Co * N,
+    }
+
+
+def read_traffic(profile_dir: str, workload: str):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary."""
+    path = os.path.join(profile_dir, f"traffic_haar_fwd_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            return float(line.split()[1])
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="single-layer workload 1..4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (see DESIGN.md, "
+              "'More than one GPU')", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2205_12268_amd import synth, wcc
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    wcc.lib()  # fails loudly if the HIP library is missing
+
+    cfg = synth.config(args.config)
+    x, w = synth.make_inputs(cfg)
+    d = wcc.make_desc(cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
+                      cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+    ctx = wcc.Context(0)
+    ctx.ensure_workspace(d)
+    xd = torch.from_numpy(x).cuda()
+    stored = w.stored.view(np.int16) if w.stored.dtype == np.uint16 else w.stored
+    wd = torch.from_numpy(np.ascontiguousarray(stored)).cuda()
+    wsd = None if w.scale is None else torch.from_numpy(w.scale).cuda()
+    y = torch.empty((cfg.B, cfg.C_out, cfg.H, cfg.W), dtype=torch.float32, device="cuda")
+
+    def step():
+        ctx.wcc_forward(d, xd, wd, wsd, 0.0, y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+
+    # per-stage device time: the same K steps again with the library's HIP events switched
+    # on (they bracket each stage on the stream the kernels run on)
+    ctx.set_profiling(True)
+    acc = {}
+    for _ in range(args.steps):
+        step()
+        for name, ms in ctx.stage_times().items():
+            acc[name] = acc.get(name, 0.0) + ms
+    ctx.set_profiling(False)
+    stage_us = {n: 1e3 * v / args.steps for n, v in acc.items()}
+
+    pix_ch = cfg.B * cfg.H * cfg.W * cfg.C_in
+    value = pix_ch / dt / 1e9
+    alg = algorithmic_bytes(cfg)
+    dom = "haar_fwd"
+    achieved = alg[dom] / (stage_us[dom] * 1e-6) / 1e9
+    traffic = read_traffic(os.path.join(ROOT, "profiles"), cfg.name)
+    out = {
+        "metric": "WCC layer forward throughput",
+        "value": round(value, 3),
+        "unit": "Gpixel*ch/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(dt * 1e3, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": {0: "f32", 1: "bf16", 2: "int8"}[cfg.w_dtype],
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "C_in": cfg.C_in, "C_out": cfg.C_out,
+                   "H": cfg.H, "W": cfg.W, "levels": cfg.levels,
+                   "keep": f"{cfg.keep_num}/{cfg.keep_den}", "act_bits": cfg.act_bits},
+        "roofline": {"bound": "hbm", "kernel": "haar_fwd_kernel", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": traffic, "algorithmic_bytes": alg[dom],
+                     "kernel_us": round(stage_us[dom], 2)},
+        "stages_us": {n: round(v, 2) for n, v in stage_us.items()},
+        "stages_alg_GBs": {n: round(alg[n] / (stage_us[n] * 1e-6) / 1e9, 1) for n in stage_us},
+        "gemm_tflops": round(2.0 * cfg.B * cfg.C_in * cfg.C_out * cfg.k
+                             / (stage_us["pointwise"] * 1e-6) / 1e12, 2),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import wcc_ref
+        cores = min(len(os.sched_getaffinity(0)), 16)
+        wcc_ref.set_threads(cores)
+        reps, spent = 0, 0.0
+        while reps < 1 or (spent < 10.0 and reps < 50):  # about 10 s of CPU work
+            t1 = time.perf_counter()
+            wcc_ref.forward(x, w.values, None if w.scale is None else w.scale, cfg.levels,
+                            cfg.keep_num, cfg.keep_den, act_bits=cfg.act_bits)
+            spent += time.perf_counter() - t1
+            reps += 1
+        cpu_dt = spent / reps
+        out["cpu_baseline"] = {"value": round(pix_ch / cpu_dt / 1e9, 5), "unit": "Gpixel*ch/s",
+                               "cores": cores, "kind": "oracle",
+                               "sample": f"full {cfg.name} forward, {reps} repetitions, "
+                                         f"{cpu_dt:.3f} s each"}
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
