@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="single-layer workload 1..4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="R",
+                    help="also run R plain device-to-device copies of the input tensor (a copy "
+                         "kernel of known size, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (see DESIGN.md, "
@@ -84,6 +87,13 @@ def main() -> int:
 
     def step():
         ctx.wcc_forward(d, xd, wd, wsd, 0.0, y)
+
+    if args.copy_probe:
+        probe = torch.empty_like(xd)
+        for _ in range(args.copy_probe):
+            probe.copy_(xd)  # reads and writes xd.numel() * 4 bytes
+        torch.cuda.synchronize()
+        del probe
 
     for _ in range(args.warmup):
         step()

@@ -140,8 +140,9 @@ wcc_status wcc_joint_topk(wcc_ctx *ctx, const wcc_desc *desc, const float *coef 
  * code = round_half_even(127*u), all in fp32, stored as int8; the value stood for is
  * alpha*code/127.  alpha = alpha_in if alpha_in > 0, else the largest |kept coefficient| of
  * the whole call (alpha = 0 gives all-zero codes).  alpha_dev (1 float, device) receives
- * alpha; it may be NULL only when act_quant_bits = 0.  idx is trusted to hold values in
- * [0, N).  Needs the workspace when act_quant_bits = 8. */
+ * alpha when act_quant_bits = 8 (required then; ignored and may be NULL otherwise).  idx
+ * values outside [0, N) are clamped into the plane.  Needs the workspace when
+ * act_quant_bits = 8. */
 wcc_status wcc_gather_quant(wcc_ctx *ctx, const wcc_desc *desc, const float *coef,
                             const int32_t *idx, float alpha_in, void *xc, float *alpha_dev,
                             void *stream);

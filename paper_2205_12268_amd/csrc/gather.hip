@@ -12,68 +12,87 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// alpha[0] = alpha_in if positive, else 0 (then raised by the gather's max reduction)
-__global__ void alpha_init_kernel(float *alpha, float alpha_in) {
-  if (threadIdx.x == 0) alpha[0] = alpha_in > 0.f ? alpha_in : 0.f;
+// every slot = alpha_in if positive, else 0 (then raised by the gather's max reduction)
+__global__ void alpha_init_kernel(float *slots, float alpha_in) {
+  if (threadIdx.x < kAlphaSlots) slots[threadIdx.x] = alpha_in > 0.f ? alpha_in : 0.f;
 }
 
-// xc[b, c, j] = coef[b, c, idx[b, j]].  grid = (ceil(k / 1024), C, B), block = 256, four
-// consecutive j per thread.  VEC: k is a multiple of 4 (16-byte idx loads and xc stores).
+constexpr int kGatherIters = 4;  // a workgroup covers 4 x 1024 consecutive j
+
+// xc[b, c, j] = coef[b, c, idx[b, j]].  grid = (ceil(k / 4096), C, B), block = 256, four
+// consecutive j per thread and iteration.  VEC: k is a multiple of 4 (16-byte idx loads and
+// xc stores).
 template <bool VEC>
 __global__ __launch_bounds__(256) void gather_kernel(const float *__restrict__ coef,
                                                      const int32_t *__restrict__ idx, int C,
                                                      int64_t N, int64_t k, float *__restrict__ xc,
-                                                     float *alpha_max) {
+                                                     float *alpha_slots) {
   __shared__ float wmax[4];
   const int c = blockIdx.y, b = blockIdx.z;
-  const int64_t j0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   const float *plane = coef + ((size_t)b * C + c) * N;
   const int32_t *ix = idx + (size_t)b * k;
   float *out = xc + ((size_t)b * C + c) * k;
   float m = 0.f;
-  if (j0 < k) {
-    if constexpr (VEC) {
-      int4 q = *reinterpret_cast<const int4 *>(ix + j0);
-      const int hi = (int)N - 1;  // an out-of-range index never leaves the plane
-      q.x = min(max(q.x, 0), hi); q.y = min(max(q.y, 0), hi);
-      q.z = min(max(q.z, 0), hi); q.w = min(max(q.w, 0), hi);
-      float4 v;
-      v.x = plane[q.x]; v.y = plane[q.y]; v.z = plane[q.z]; v.w = plane[q.w];
-      *reinterpret_cast<float4 *>(out + j0) = v;
-      m = fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w)));
-    } else {
+  const int hi = (int)N - 1;  // an out-of-range index never leaves the plane
+  if constexpr (VEC) {
+    // all index loads first, then all gathers, then the stores: 16 independent loads in flight
+    int4 q[kGatherIters];
+    int64_t j0[kGatherIters];
+#pragma unroll
+    for (int it = 0; it < kGatherIters; ++it) {
+      j0[it] = (((int64_t)blockIdx.x * kGatherIters + it) * 256 + threadIdx.x) * 4;
+      q[it] = make_int4(0, 0, 0, 0);
+      if (j0[it] < k) q[it] = *reinterpret_cast<const int4 *>(ix + j0[it]);
+    }
+    float4 v[kGatherIters];
+#pragma unroll
+    for (int it = 0; it < kGatherIters; ++it) {
+      v[it].x = plane[min(max(q[it].x, 0), hi)];
+      v[it].y = plane[min(max(q[it].y, 0), hi)];
+      v[it].z = plane[min(max(q[it].z, 0), hi)];
+      v[it].w = plane[min(max(q[it].w, 0), hi)];
+    }
+#pragma unroll
+    for (int it = 0; it < kGatherIters; ++it) {
+      if (j0[it] < k) {
+        *reinterpret_cast<float4 *>(out + j0[it]) = v[it];
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(v[it].x), fabsf(v[it].y)), fmaxf(fabsf(v[it].z), fabsf(v[it].w))));
+      }
+    }
+  } else {
+    for (int it = 0; it < kGatherIters; ++it) {
+      const int64_t j0 = (((int64_t)blockIdx.x * kGatherIters + it) * 256 + threadIdx.x) * 4;
       for (int e = 0; e < 4 && j0 + e < k; ++e) {
-        const float v = plane[min(max(ix[j0 + e], 0), (int)N - 1)];
+        const float v = plane[min(max(ix[j0 + e], 0), hi)];
         out[j0 + e] = v;
         m = fmaxf(m, fabsf(v));
       }
     }
   }
-  if (alpha_max == nullptr) return;
+  if (alpha_slots == nullptr) return;
   m = wave_max(m);
   if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
   __syncthreads();
   if (threadIdx.x == 0) {
     m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
-    // non-negative floats order like their bit patterns: an integer max is exact and
-    // independent of arrival order
-    if (m > 0.f) atomicMax(reinterpret_cast<unsigned int *>(alpha_max), __float_as_uint(m));
+    // Non-negative floats order like their bit patterns: an integer max is exact and
+    // independent of arrival order.  Atomics on one address serialise at the memory side, so
+    // the workgroups spread over kAlphaSlots addresses; the consumer takes the max of the
+    // slots.  A slot only grows: a workgroup at or below the value it observes skips.
+    unsigned int *a = reinterpret_cast<unsigned int *>(alpha_slots) +
+                      ((blockIdx.x + 3u * blockIdx.y + 11u * blockIdx.z) & (kAlphaSlots - 1));
+    const unsigned int mine = __float_as_uint(m);
+    if (mine > __hip_atomic_load(a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(a, mine);
   }
-}
-
-// The scale-clip-round of Eq. (quantweights), signed, b = 8, operation by operation in fp32.
-__device__ __forceinline__ int quant_code(float v, float alpha) {
-  if (!(alpha > 0.f)) return 0;
-  float u = __fdiv_rn(v, alpha);          // scale
-  u = fminf(fmaxf(u, -1.f), 1.f);         // clip
-  return (int)rintf(__fmul_rn(127.f, u)); // round half to even
 }
 
 // codes[i] = q(xc32[i]); 16 values per thread when n is a multiple of 16
 __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__ xc32, int64_t n,
-                                                       const float *__restrict__ alpha,
+                                                       const float *__restrict__ alpha_slots,
+                                                       float *__restrict__ alpha_out,
                                                        int8_t *__restrict__ codes) {
-  const float a = alpha[0];
+  const float a = alpha_from_slots(alpha_slots);
+  if (blockIdx.x == 0 && threadIdx.x == 0) alpha_out[0] = a;
   const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 16;
   if (i0 >= n) return;
   if (i0 + 16 <= n && (n & 15) == 0) {
@@ -99,25 +118,25 @@ __global__ __launch_bounds__(256) void copy_f32_kernel(const float *__restrict__
 
 }  // namespace
 
-hipError_t launch_alpha_init(float *alpha, float alpha_in, hipStream_t s) {
-  hipLaunchKernelGGL(alpha_init_kernel, dim3(1), dim3(64), 0, s, alpha, alpha_in);
+hipError_t launch_alpha_init(float *alpha_slots, float alpha_in, hipStream_t s) {
+  hipLaunchKernelGGL(alpha_init_kernel, dim3(1), dim3(64), 0, s, alpha_slots, alpha_in);
   return hipGetLastError();
 }
 
 hipError_t launch_gather(const float *coef, const int32_t *idx, int B, int C, int64_t N, int64_t k,
-                         float *xc, float *alpha_max, hipStream_t s) {
-  dim3 grid((unsigned)((k + 1023) / 1024), C, B);
+                         float *xc, float *alpha_slots, hipStream_t s) {
+  dim3 grid((unsigned)((k + 1024 * kGatherIters - 1) / (1024 * kGatherIters)), C, B);
   if (k % 4 == 0)
-    hipLaunchKernelGGL(gather_kernel<true>, grid, dim3(256), 0, s, coef, idx, C, N, k, xc, alpha_max);
+    hipLaunchKernelGGL(gather_kernel<true>, grid, dim3(256), 0, s, coef, idx, C, N, k, xc, alpha_slots);
   else
-    hipLaunchKernelGGL(gather_kernel<false>, grid, dim3(256), 0, s, coef, idx, C, N, k, xc, alpha_max);
+    hipLaunchKernelGGL(gather_kernel<false>, grid, dim3(256), 0, s, coef, idx, C, N, k, xc, alpha_slots);
   return hipGetLastError();
 }
 
-hipError_t launch_quantize(const float *xc32, int64_t n, const float *alpha, int8_t *codes,
-                           hipStream_t s) {
+hipError_t launch_quantize(const float *xc32, int64_t n, const float *alpha_slots, float *alpha_out,
+                           int8_t *codes, hipStream_t s) {
   hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)((n + 4095) / 4096)), dim3(256), 0, s, xc32, n,
-                     alpha, codes);
+                     alpha_slots, alpha_out, codes);
   return hipGetLastError();
 }
 

@@ -64,6 +64,7 @@ struct LanePos {
   int rowlen[D + 1];  // W >> l
   int nl[D + 1];      // band size n_l
   int lc;             // lane's column index inside its row of lanes
+  bool active;        // lane maps to pixels of the plane
 };
 
 // ---- analysis ---------------------------------------------------------------------------
@@ -95,7 +96,7 @@ __device__ __forceinline__ void fwd_levels(const float (&in)[rows_at(D, L - 1)][
   constexpr int R2 = rows_at(D, L), VI = cols_at(V, L - 1), V2 = cols_at(V, L);
   constexpr int SI = span_at(V, L - 1), S2 = span_at(V, L);
   float ll[R2][V2];
-  const bool owner = (S2 == 1) || ((p.lc & (S2 - 1)) == 0);
+  const bool owner = p.active && ((S2 == 1) || ((p.lc & (S2 - 1)) == 0));
 #pragma unroll
   for (int i = 0; i < R2; ++i) {
     float y2[V2], y3[V2], y4[V2];
@@ -173,49 +174,80 @@ __device__ __forceinline__ bool locate(const StripMap &m, const Geo &g, int unit
     p.nl[l] = (g.H >> l) * (g.W >> l);
     p.off[l] = (row0 >> l) * p.rowlen[l] + (col0 >> l);
   }
-  return unit < m.units && strip < m.strips && col_lane < m.lanes_w;
+  p.active = unit < m.units && strip < m.strips && col_lane < m.lanes_w;
+  return p.active;
 }
 
 // x [B, C, H, W] -> coef [B, C, N]; partial norms over this block's channel group to
-// norm_part [G, B, N] (nullable).  grid = (ceil(units/4), G, B), block = 256.
-template <int D, int V>
+// norm_part [G, B, N] (nullable).  block = 256.
+// SPLIT = false: grid = (ceil(units/4), G, B); each wave of a workgroup takes its own strip unit
+//                and walks all channels of the group.
+// SPLIT = true:  grid = (units, G, B); the four waves share one strip unit and take a quarter
+//                of the group's channels each (four times the waves in flight for the same
+//                number of partial-norm planes); their |coefficient| sums meet in LDS and are
+//                added in wave order.
+template <int D, int V, bool SPLIT>
 __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__ x,
                                                        float *__restrict__ coef,
                                                        float *__restrict__ norm_part, Geo g,
-                                                       StripMap m, int C, int Cg, int B) {
+                                                       StripMap m, int C, int Cg, int B,
+                                                       SelectPrep prep) {
   constexpr int R = 1 << D;
-  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+  constexpr int NS = slot_count(D, V);
+  const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int unit = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * 4 + wv;
   const int grp = blockIdx.y, b = blockIdx.z;
+  // one workgroup per sample clears the state of the selection that follows this kernel
+  if (blockIdx.x == 0 && grp == 0) prep_sample(prep, b, threadIdx.x, 256);
   LanePos<D> p;
   int row0, col0;
-  if (!locate<D, V>(m, g, unit, p, row0, col0)) return;
-  const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
-  if (c0 >= c1) return;
+  locate<D, V>(m, g, unit, p, row0, col0);
+  int c0 = grp * Cg, c1 = min(C, c0 + Cg);
+  if constexpr (SPLIT) {
+    const int Cw = (c1 - c0 + 3) / 4;
+    c0 = c0 + wv * Cw;
+    c1 = min(c1, c0 + Cw);
+  }
 
   FwdSink<D, V> sink;
 #pragma unroll
-  for (int s = 0; s < slot_count(D, V); ++s) sink.acc[s] = 0.f;
+  for (int s = 0; s < NS; ++s) sink.acc[s] = 0.f;
 
-  const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
-  sink.plane = coef + ((size_t)b * C + c0) * g.N;
-  float cur[R][V], nxt[R][V];
+  if (p.active && c0 < c1) {
+    const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+    sink.plane = coef + ((size_t)b * C + c0) * g.N;
+    float cur[R][V], nxt[R][V];
 #pragma unroll
-  for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)r * g.W, nxt[r]);
-  for (int c = c0; c < c1; ++c) {
+    for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)r * g.W, nxt[r]);
+    for (int c = c0; c < c1; ++c) {
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+      for (int r = 0; r < R; ++r)
 #pragma unroll
-      for (int e = 0; e < V; ++e) cur[r][e] = nxt[r][e];
-    if (c + 1 < c1) {
-      src += g.N;
+        for (int e = 0; e < V; ++e) cur[r][e] = nxt[r][e];
+      if (c + 1 < c1) {
+        src += g.N;
 #pragma unroll
-      for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)r * g.W, nxt[r]);
+        for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)r * g.W, nxt[r]);
+      }
+      fwd_levels<D, V, 1>(cur, p, sink);
+      sink.plane += g.N;
     }
-    fwd_levels<D, V, 1>(cur, p, sink);
-    sink.plane += g.N;
   }
 
   if (norm_part == nullptr) return;
+  if constexpr (SPLIT) {
+    __shared__ float comb[3][NS][kWave];
+    if (wv > 0) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) comb[wv - 1][s][lane] = sink.acc[s];
+    }
+    __syncthreads();
+    if (wv > 0) return;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      sink.acc[s] = ((sink.acc[s] + comb[0][s][lane]) + comb[1][s][lane]) + comb[2][s][lane];
+  }
+  if (!p.active) return;
   float *np = norm_part + ((size_t)grp * B + b) * g.N;
   // write the accumulated |coefficient| sums with the same addressing as the coefficients
   auto flush = [&](auto Lc, auto Jc) {
@@ -226,8 +258,13 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__
 #pragma unroll
     for (int i = 0; i < rows_at(D, L); ++i) {
       float *dst = np + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
+      if constexpr (CV == 2) {
+        *reinterpret_cast<float2 *>(dst) = make_float2(sink.acc[slot_base(D, V, L, J) + i * CV],
+                                                       sink.acc[slot_base(D, V, L, J) + i * CV + 1]);
+      } else {
 #pragma unroll
-      for (int e = 0; e < CV; ++e) dst[e] = sink.acc[slot_base(D, V, L, J) + i * CV + e];
+        for (int e = 0; e < CV; ++e) dst[e] = sink.acc[slot_base(D, V, L, J) + i * CV + e];
+      }
     }
   };
   auto each_level = [&](auto Lc) {
@@ -408,15 +445,24 @@ StripMap make_map(const wcc_desc &d, int V) {
   return m;
 }
 
+// the four waves of a workgroup split a channel group when each still gets >= 2 channels
+bool split_waves(int Cg) { return Cg >= 8; }
+
 template <int D, int V>
 hipError_t fwd_launch(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
-                      hipStream_t s) {
+                      const SelectPrep &prep, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_in + G - 1) / G;
-  dim3 grid((m.units + 3) / 4, G, d.B);
-  hipLaunchKernelGGL((haar_fwd_kernel<D, V>), grid, dim3(256), 0, s, x, coef, norm_part, g, m,
-                     d.C_in, Cg, d.B);
+  if (split_waves(Cg)) {
+    dim3 grid(m.units, G, d.B);
+    hipLaunchKernelGGL((haar_fwd_kernel<D, V, true>), grid, dim3(256), 0, s, x, coef, norm_part, g,
+                       m, d.C_in, Cg, d.B, prep);
+  } else {
+    dim3 grid((m.units + 3) / 4, G, d.B);
+    hipLaunchKernelGGL((haar_fwd_kernel<D, V, false>), grid, dim3(256), 0, s, x, coef, norm_part, g,
+                       m, d.C_in, Cg, d.B, prep);
+  }
   return hipGetLastError();
 }
 
@@ -446,18 +492,19 @@ int groups_for(const wcc_desc &d, int C, int64_t want_waves, int min_ch) {
 }  // namespace
 
 // Every forward group costs one partial-norm plane (written once, read once): with >= 16
-// channels a group that is at most 1/16 of the transform's own traffic.
-int forward_groups(const wcc_desc &d) { return groups_for(d, d.C_in, 4096, 16); }
+// channels a group that is at most 1/16 of the transform's own traffic.  The waves of a
+// workgroup split a group four ways, so a quarter of the wave target is asked of the groups.
+int forward_groups(const wcc_desc &d) { return groups_for(d, d.C_in, 2048, 16); }
 
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
-                           hipStream_t s) {
+                           const SelectPrep &prep, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
-    case 1: return v4 ? fwd_launch<1, 4>(d, x, coef, norm_part, G, s)
-                      : fwd_launch<1, 2>(d, x, coef, norm_part, G, s);
-    case 2: return fwd_launch<2, 4>(d, x, coef, norm_part, G, s);
-    case 3: return fwd_launch<3, 4>(d, x, coef, norm_part, G, s);
-    case 4: return fwd_launch<4, 4>(d, x, coef, norm_part, G, s);
+    case 1: return v4 ? fwd_launch<1, 4>(d, x, coef, norm_part, G, prep, s)
+                      : fwd_launch<1, 2>(d, x, coef, norm_part, G, prep, s);
+    case 2: return fwd_launch<2, 4>(d, x, coef, norm_part, G, prep, s);
+    case 3: return fwd_launch<3, 4>(d, x, coef, norm_part, G, prep, s);
+    case 4: return fwd_launch<4, 4>(d, x, coef, norm_part, G, prep, s);
   }
   return hipErrorInvalidValue;
 }

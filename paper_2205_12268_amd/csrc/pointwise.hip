@@ -33,10 +33,53 @@ __device__ __forceinline__ uint32_t code_to_bf16(uint32_t dw, int byte) {
   return __float_as_uint((float)v) >> 16;           // |v| <= 128: exact in bf16
 }
 
+// The layer's alpha: one float, or the max of the gather's slots.  The first workgroup also
+// publishes it to alpha_out (nullable).  Called by every thread of the workgroup.
+__device__ __forceinline__ float load_alpha(const float *__restrict__ alpha, bool slots,
+                                            float *alpha_out) {
+  const float a = slots ? alpha_from_slots(alpha) : alpha[0];
+  if (alpha_out && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)
+    alpha_out[0] = a;
+  return a;
+}
+
+// A thread's 8 (channels) x 4 (positions) patch of the activation tile as packed int8 codes:
+// dw[r] holds positions n..n+3 of channel c0 + r.  F32: the source holds unquantised kept
+// coefficients, quantised here with the layer's alpha.
+template <bool F32>
+__device__ __forceinline__ void load_patch(const void *__restrict__ xb, int K, int64_t k, int c0,
+                                           int64_t n, float alpha, uint32_t (&dw)[8]) {
+  if constexpr (F32) {
+    const float *xf = static_cast<const float *>(xb);
+    float4 v[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (c0 + r < K && n < k) v[r] = *reinterpret_cast<const float4 *>(xf + (size_t)(c0 + r) * k + n);
+    }
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      dw[r] = ((uint32_t)quant_code(v[r].x, alpha) & 0xFFu) |
+              (((uint32_t)quant_code(v[r].y, alpha) & 0xFFu) << 8) |
+              (((uint32_t)quant_code(v[r].z, alpha) & 0xFFu) << 16) |
+              (((uint32_t)quant_code(v[r].w, alpha) & 0xFFu) << 24);
+    }
+  } else {
+    const int8_t *xq = static_cast<const int8_t *>(xb);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      dw[r] = 0;
+      if (c0 + r < K && n < k) dw[r] = *reinterpret_cast<const uint32_t *>(xq + (size_t)(c0 + r) * k + n);
+    }
+  }
+}
+
 // grid = (ceil(k/128), ceil(M/128), B); needs K % 8 == 0 and k % 4 == 0
+template <bool F32>
 __global__ __launch_bounds__(256) void pointwise_bf16_kernel(const uint16_t *__restrict__ w,
-                                                             const int8_t *__restrict__ xq,
+                                                             const void *__restrict__ xq,
                                                              const float *__restrict__ alpha,
+                                                             bool slots, float *alpha_out,
                                                              float *__restrict__ yc, int M, int K,
                                                              int64_t k) {
   __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDB];
@@ -44,7 +87,8 @@ __global__ __launch_bounds__(256) void pointwise_bf16_kernel(const uint16_t *__r
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const int b = blockIdx.z, m0 = blockIdx.y * BM;
   const int64_t n0 = (int64_t)blockIdx.x * BN;
-  const int8_t *xb = xq + (size_t)b * K * k;
+  const void *xb = static_cast<const char *>(xq) + (size_t)b * K * k * (F32 ? 4 : 1);
+  const float al = load_alpha(alpha, slots, alpha_out);
 
   floatx16 acc[4];
 #pragma unroll
@@ -69,13 +113,7 @@ __global__ __launch_bounds__(256) void pointwise_bf16_kernel(const uint16_t *__r
     // activation tile: 8 channels x 4 positions per thread, transposed into Bs
     {
       uint32_t dw[8];
-      const int64_t n = n0 + 4 * g;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const int c = k0 + kq * 8 + r;
-        dw[r] = 0;
-        if (c < K && n < k) dw[r] = *reinterpret_cast<const uint32_t *>(xb + (size_t)c * k + n);
-      }
+      load_patch<F32>(xb, K, k, k0 + kq * 8, n0 + 4 * g, al, dw);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         uint4 v;
@@ -102,7 +140,7 @@ __global__ __launch_bounds__(256) void pointwise_bf16_kernel(const uint16_t *__r
     __syncthreads();
   }
   // epilogue: acc[i][r] is row (r/4)*8 + (lane/32)*4 + r%4, column 4*(lane%32) + i
-  const float sx = alpha[0] / 127.f;
+  const float sx = al / 127.f;
   const int64_t n = n0 + 4 * (lane & 31);
   if (n >= k) return;
 #pragma unroll
@@ -127,10 +165,12 @@ __device__ __forceinline__ uint32_t gather_byte(uint32_t d0, uint32_t d1, uint32
 }
 
 // grid = (ceil(k/128), ceil(M/128), B); needs K % 16 == 0 and k % 4 == 0
+template <bool F32>
 __global__ __launch_bounds__(256) void pointwise_i8_kernel(const int8_t *__restrict__ w,
                                                            const float *__restrict__ w_scale,
-                                                           const int8_t *__restrict__ xq,
+                                                           const void *__restrict__ xq,
                                                            const float *__restrict__ alpha,
+                                                           bool slots, float *alpha_out,
                                                            float *__restrict__ yc, int M, int K,
                                                            int64_t k) {
   __shared__ __attribute__((aligned(16))) int8_t As[BM * LDI];
@@ -138,7 +178,8 @@ __global__ __launch_bounds__(256) void pointwise_i8_kernel(const int8_t *__restr
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const int b = blockIdx.z, m0 = blockIdx.y * BM;
   const int64_t n0 = (int64_t)blockIdx.x * BN;
-  const int8_t *xb = xq + (size_t)b * K * k;
+  const void *xb = static_cast<const char *>(xq) + (size_t)b * K * k * (F32 ? 4 : 1);
+  const float al = load_alpha(alpha, slots, alpha_out);
 
   intx16 acc[4];
 #pragma unroll
@@ -161,13 +202,7 @@ __global__ __launch_bounds__(256) void pointwise_i8_kernel(const int8_t *__restr
     }
     {
       uint32_t dw[8];
-      const int64_t n = n0 + 4 * g;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const int c = k0 + kq * 8 + r;
-        dw[r] = 0;
-        if (c < K && n < k) dw[r] = *reinterpret_cast<const uint32_t *>(xb + (size_t)c * k + n);
-      }
+      load_patch<F32>(xb, K, k, k0 + kq * 8, n0 + 4 * g, al, dw);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         uint2 v;
@@ -191,7 +226,7 @@ __global__ __launch_bounds__(256) void pointwise_i8_kernel(const int8_t *__restr
     }
     __syncthreads();
   }
-  const float sx = alpha[0] / 127.f;
+  const float sx = al / 127.f;
   const int64_t n = n0 + 4 * (lane & 31);
   if (n >= k) return;
 #pragma unroll
@@ -224,11 +259,13 @@ constexpr int FT = 64, FK = 16;
 
 // grid = (ceil(k/64), ceil(M/64), B), block = 256; thread (ty, tx) computes rows ty*4..+3 and
 // columns tx, tx+16, tx+32, tx+48 of the tile; channels are accumulated in increasing order.
-template <int WDT, bool XQ>
+// XM: 0 = fp32 activations as they are, 1 = int8 codes, 2 = fp32 activations quantised on load
+template <int WDT, int XM>
 __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restrict__ w,
                                                             const float *__restrict__ w_scale,
                                                             const void *__restrict__ xc,
                                                             const float *__restrict__ alpha,
+                                                            bool slots, float *alpha_out,
                                                             float *__restrict__ yc, int M, int K,
                                                             int64_t k) {
   __shared__ float Ws[FK][FT + 1];
@@ -237,6 +274,7 @@ __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restri
   const int b = blockIdx.z, m0 = blockIdx.y * FT;
   const int64_t n0 = (int64_t)blockIdx.x * FT;
   float acc[4][4] = {};
+  const float al = XM != 0 ? load_alpha(alpha, slots, alpha_out) : 0.f;
   for (int k0 = 0; k0 < K; k0 += FK) {
     // Ws[kk][mm] = w[m0 + mm][k0 + kk]
     for (int e = t; e < FT * FK; e += 256) {
@@ -250,7 +288,9 @@ __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restri
       float v = 0.f;
       if (k0 + kk < K && n0 + nn < k) {
         const size_t at = ((size_t)b * K + k0 + kk) * k + n0 + nn;
-        v = XQ ? (float)static_cast<const int8_t *>(xc)[at] : static_cast<const float *>(xc)[at];
+        if (XM == 1) v = (float)static_cast<const int8_t *>(xc)[at];
+        else if (XM == 2) v = (float)quant_code(static_cast<const float *>(xc)[at], al);
+        else v = static_cast<const float *>(xc)[at];
       }
       Xs[kk][nn] = v;
     }
@@ -269,7 +309,7 @@ __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restri
     }
     __syncthreads();
   }
-  const float sx = XQ ? alpha[0] / 127.f : 1.f;
+  const float sx = XM != 0 ? al / 127.f : 1.f;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int m = m0 + ty * 4 + i;
@@ -283,43 +323,56 @@ __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restri
   }
 }
 
-template <int WDT, bool XQ>
+template <int WDT, int XM>
 hipError_t fma_launch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
-                      const void *xc, const float *alpha, float *yc, hipStream_t s) {
+                      const void *xc, const float *alpha, bool slots, float *alpha_out, float *yc,
+                      hipStream_t s) {
   dim3 grid((unsigned)((k + FT - 1) / FT), (d.C_out + FT - 1) / FT, d.B);
-  hipLaunchKernelGGL((pointwise_fma_kernel<WDT, XQ>), grid, dim3(256), 0, s, w, w_scale, xc, alpha,
-                     yc, d.C_out, d.C_in, k);
+  hipLaunchKernelGGL((pointwise_fma_kernel<WDT, XM>), grid, dim3(256), 0, s, w, w_scale, xc, alpha,
+                     slots, alpha_out, yc, d.C_out, d.C_in, k);
   return hipGetLastError();
+}
+
+template <int WDT>
+hipError_t fma_dispatch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
+                        const void *xc, int xm, const float *alpha, bool slots, float *alpha_out,
+                        float *yc, hipStream_t s) {
+  switch (xm) {
+    case 0: return fma_launch<WDT, 0>(d, k, w, w_scale, xc, alpha, slots, alpha_out, yc, s);
+    case 1: return fma_launch<WDT, 1>(d, k, w, w_scale, xc, alpha, slots, alpha_out, yc, s);
+    default: return fma_launch<WDT, 2>(d, k, w, w_scale, xc, alpha, slots, alpha_out, yc, s);
+  }
 }
 
 }  // namespace
 
 hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
-                            const void *xc, const float *alpha, float *yc, hipStream_t s) {
-  const bool xq = d.act_quant_bits == 8;
+                            const void *xc, bool xc_is_f32, const float *alpha, bool slots,
+                            float *alpha_out, float *yc, hipStream_t s) {
+  const bool quant = d.act_quant_bits == 8;
   const int M = d.C_out, K = d.C_in;
   dim3 grid((unsigned)((k + BN - 1) / BN), (M + BM - 1) / BM, d.B);
-  if (xq && d.w_dtype == WCC_BF16 && K % 8 == 0 && k % 4 == 0) {
-    hipLaunchKernelGGL(pointwise_bf16_kernel, grid, dim3(256), 0, s,
-                       static_cast<const uint16_t *>(w), static_cast<const int8_t *>(xc), alpha, yc,
-                       M, K, k);
+  if (quant && d.w_dtype == WCC_BF16 && K % 8 == 0 && k % 4 == 0) {
+    const uint16_t *wb = static_cast<const uint16_t *>(w);
+    if (xc_is_f32)
+      hipLaunchKernelGGL(pointwise_bf16_kernel<true>, grid, dim3(256), 0, s, wb, xc, alpha, slots, alpha_out, yc, M, K, k);
+    else
+      hipLaunchKernelGGL(pointwise_bf16_kernel<false>, grid, dim3(256), 0, s, wb, xc, alpha, slots, alpha_out, yc, M, K, k);
     return hipGetLastError();
   }
-  if (xq && d.w_dtype == WCC_I8 && K % 16 == 0 && k % 4 == 0) {
-    hipLaunchKernelGGL(pointwise_i8_kernel, grid, dim3(256), 0, s, static_cast<const int8_t *>(w),
-                       w_scale, static_cast<const int8_t *>(xc), alpha, yc, M, K, k);
+  if (quant && d.w_dtype == WCC_I8 && K % 16 == 0 && k % 4 == 0) {
+    const int8_t *wi = static_cast<const int8_t *>(w);
+    if (xc_is_f32)
+      hipLaunchKernelGGL(pointwise_i8_kernel<true>, grid, dim3(256), 0, s, wi, w_scale, xc, alpha, slots, alpha_out, yc, M, K, k);
+    else
+      hipLaunchKernelGGL(pointwise_i8_kernel<false>, grid, dim3(256), 0, s, wi, w_scale, xc, alpha, slots, alpha_out, yc, M, K, k);
     return hipGetLastError();
   }
+  const int xm = !quant ? 0 : (xc_is_f32 ? 2 : 1);
   switch (d.w_dtype) {
-    case WCC_F32:
-      return xq ? fma_launch<WCC_F32, true>(d, k, w, w_scale, xc, alpha, yc, s)
-                : fma_launch<WCC_F32, false>(d, k, w, w_scale, xc, alpha, yc, s);
-    case WCC_BF16:
-      return xq ? fma_launch<WCC_BF16, true>(d, k, w, w_scale, xc, alpha, yc, s)
-                : fma_launch<WCC_BF16, false>(d, k, w, w_scale, xc, alpha, yc, s);
-    case WCC_I8:
-      return xq ? fma_launch<WCC_I8, true>(d, k, w, w_scale, xc, alpha, yc, s)
-                : fma_launch<WCC_I8, false>(d, k, w, w_scale, xc, alpha, yc, s);
+    case WCC_F32: return fma_dispatch<WCC_F32>(d, k, w, w_scale, xc, xm, alpha, slots, alpha_out, yc, s);
+    case WCC_BF16: return fma_dispatch<WCC_BF16>(d, k, w, w_scale, xc, xm, alpha, slots, alpha_out, yc, s);
+    case WCC_I8: return fma_dispatch<WCC_I8>(d, k, w, w_scale, xc, xm, alpha, slots, alpha_out, yc, s);
   }
   return hipErrorInvalidValue;
 }

@@ -5,118 +5,68 @@
 // Design.  Non-negative floats order like their bit patterns, so the k-th largest norm is
 // found exactly by a most-significant-digit radix select on uint32 keys: three histogram
 // passes (11 + 11 + 10 bits) spread over many workgroups per sample, integer atomics only.
-// The workgroup that finishes a pass last (counted with a device-scope atomic after a
-// fence) turns the histogram into the digit to descend into; nobody spins on anybody.
-// With the threshold key T and the number r of keys equal to T still to take, a counting
-// pass and an ordered compaction write idx: a position is kept if key > T, or key == T and
-// fewer than r equal keys precede it.  Ordering comes from prefix sums, never from the
-// arrival order of atomics, so the result is the same on every run.
+// Every workgroup of the NEXT kernel turns the finished histogram of the previous pass into
+// the digit to descend into by itself (an 8 KiB read and one block scan): no workgroup waits
+// for another and no device-wide fence is needed -- on this chip such a fence writes back a
+// whole L2, which costs more than the pass.  The third pass also leaves, per workgroup, the
+// suffix sums of its own low-digit histogram; once the threshold key T is known they give every workgroup's count of keys
+// above T and equal to T without another pass over the keys.  The last kernel is an ordered
+// compaction: a position is kept if key > T, or key == T and fewer than r equal keys precede
+// it (r = how many keys equal to T are still needed).  Ordering comes from prefix sums,
+// never from the arrival order of atomics, so the result is the same on every run.
+// The first pass can take the channel-group partial norms of the forward transform and
+// reduce them on the fly (fixed order), writing the final norms as a by-product.
 #include "wcc_internal.h"
 
 namespace wcc {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kPerThread = kSelectChunk / kThreads;  // 16 keys per thread
+constexpr int kThreads = 256;                  // 4 waves
+constexpr int kWaves = kThreads / 64;
+constexpr int kPer = kSelectChunk / kThreads;  // 4 keys per thread
+static_assert(kPer == 4, "one 16-byte load per thread");
 
 __device__ __forceinline__ uint32_t digit_of(uint32_t key, int pass) {
   return pass == 0 ? key >> 21 : pass == 1 ? (key >> 10) & 0x7FFu : key & 0x3FFu;
 }
-// keys whose bits above the current digit equal `prefix`
+// keys whose bits above the current digit equal those of `prefix`
 __device__ __forceinline__ bool matches(uint32_t key, uint32_t prefix, int pass) {
   return pass == 0 ? true : pass == 1 ? (key >> 21) == (prefix >> 21) : (key >> 10) == (prefix >> 10);
 }
 
-// zero histograms and per-sample state; state.remain = k
-__global__ __launch_bounds__(kThreads) void select_init_kernel(uint32_t *hist, SelectState *st,
-                                                               int B, uint32_t k) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < B * 3 * kRadixBins) hist[i] = 0;
-  if (i < B) {
-    SelectState s;
-    s.prefix = 0; s.remain = k;
-    s.done[0] = s.done[1] = s.done[2] = 0;
-    s.pad[0] = s.pad[1] = s.pad[2] = 0;
-    st[i] = s;
+// lh[digit] += 1 for every valid lane; lanes of a wave that share a digit are counted by one
+// LDS atomic (two leader rounds catch the big tie classes, the rest goes lane by lane)
+__device__ __forceinline__ void hist_add(uint32_t *lh, uint32_t digit, bool valid) {
+  const int lane = threadIdx.x & 63;
+  uint64_t todo = __ballot(valid);
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    if (todo == 0) break;
+    const int leader = __ffsll((unsigned long long)todo) - 1;
+    const uint32_t d0 = __shfl(digit, leader, 64);
+    const uint64_t same = __ballot(valid && digit == d0);
+    if (lane == leader) atomicAdd(&lh[d0], (uint32_t)__popcll(same));
+    if (digit == d0) valid = false;
+    todo &= ~same;
   }
+  if (valid) atomicAdd(&lh[digit], 1u);
 }
 
-// One histogram pass.  grid = (nblk, B).
-template <int PASS>
-__global__ __launch_bounds__(kThreads) void select_hist_kernel(const float *__restrict__ norm,
-                                                               int64_t N, uint32_t *hist,
-                                                               SelectState *st, int nblk) {
-  __shared__ uint32_t lh[kRadixBins];
-  __shared__ uint32_t scan[kThreads];
-  __shared__ int is_last;
-  const int b = blockIdx.y, t = threadIdx.x;
-  const uint32_t *keys = reinterpret_cast<const uint32_t *>(norm) + (size_t)b * N;
-  uint32_t *gh = hist + ((size_t)b * 3 + PASS) * kRadixBins;
-  SelectState *s = st + b;
-  constexpr int bins = PASS == 2 ? 1024 : kRadixBins;
-
-  for (int i = t; i < bins; i += kThreads) lh[i] = 0;
-  __syncthreads();
-  const uint32_t prefix = PASS == 0 ? 0u : s->prefix;
-  const int64_t base = (int64_t)blockIdx.x * kSelectChunk;
-#pragma unroll 4
-  for (int r = 0; r < kPerThread; ++r) {
-    const int64_t q = base + r * kThreads + t;
-    if (q < N) {
-      const uint32_t key = keys[q];
-      if (matches(key, prefix, PASS)) atomicAdd(&lh[digit_of(key, PASS)], 1u);
-    }
-  }
-  __syncthreads();
-  for (int i = t; i < bins; i += kThreads) {
-    const uint32_t v = lh[i];
-    if (v) atomicAdd(&gh[i], v);
-  }
-  // last workgroup of this sample to finish picks the digit
-  __threadfence();
-  __syncthreads();
-  if (t == 0) {
-    const uint32_t prev = atomicAdd(&s->done[PASS], 1u);
-    is_last = (prev == (uint32_t)nblk - 1);
-  }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-
-  // descending cumulative count: find digit D with count(> D) < remain <= count(>= D)
-  constexpr int per = bins / kThreads;  // 8 (or 4) consecutive digits per thread, from the top
-  const uint32_t remain = s->remain;
-  uint32_t cnt[per], sum = 0;
+// block-wide sum of v (all threads get it); `tmp` has kWaves entries
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *tmp) {
 #pragma unroll
-  for (int i = 0; i < per; ++i) {
-    cnt[i] = __hip_atomic_load(&gh[bins - 1 - (t * per + i)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    sum += cnt[i];
-  }
-  scan[t] = sum;
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  __syncthreads();  // tmp may still be read from a previous use
+  if ((threadIdx.x & 63) == 0) tmp[threadIdx.x >> 6] = v;
   __syncthreads();
-  // exclusive prefix over threads (threads ordered from the top digit down)
-  for (int off = 1; off < kThreads; off <<= 1) {
-    uint32_t v = (t >= off) ? scan[t - off] : 0;
-    __syncthreads();
-    scan[t] += v;
-    __syncthreads();
-  }
-  uint32_t above = scan[t] - sum;  // keys in digits above this thread's digits
+  uint32_t s = 0;
 #pragma unroll
-  for (int i = 0; i < per; ++i) {
-    if (above < remain && remain <= above + cnt[i]) {
-      const uint32_t digit = bins - 1 - (t * per + i);
-      const uint32_t shifted = PASS == 0 ? digit << 21 : PASS == 1 ? digit << 10 : digit;
-      s->prefix = prefix | shifted;
-      s->remain = remain - above;
-    }
-    above += cnt[i];
-  }
+  for (int i = 0; i < kWaves; ++i) s += tmp[i];
+  return s;
 }
 
-// block-wide exclusive scan of a packed pair (hi16: gt, lo16: eq); returns the block total too
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot,
-                                                         uint32_t &total) {
+// block-wide exclusive scan in thread order; `tmp` has kWaves entries
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *tmp) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   uint32_t inc = v;
 #pragma unroll
@@ -124,105 +74,207 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
     const uint32_t n = __shfl_up(inc, off, 64);
     if (lane >= off) inc += n;
   }
-  if (lane == 63) wave_tot[wv] = inc;
   __syncthreads();
-  uint32_t before = 0, tot = 0;
+  if (lane == 63) tmp[wv] = inc;
+  __syncthreads();
+  uint32_t before = 0;
 #pragma unroll
-  for (int i = 0; i < kThreads / 64; ++i) {
-    const uint32_t w = wave_tot[i];
-    if (i < wv) before += w;
-    tot += w;
-  }
-  total = tot;
+  for (int i = 0; i < kWaves; ++i)
+    if (i < wv) before += tmp[i];
   return before + inc - v;
 }
 
-// per-workgroup counts of keys above / equal to the threshold.  grid = (nblk, B)
-__global__ __launch_bounds__(kThreads) void select_count_kernel(const float *__restrict__ norm,
-                                                                int64_t N, const SelectState *st,
-                                                                uint2 *blockcnt, int nblk) {
-  __shared__ uint32_t wave_tot[kThreads / 64];
-  const int b = blockIdx.y, t = threadIdx.x;
-  const uint32_t *keys = reinterpret_cast<const uint32_t *>(norm) + (size_t)b * N;
-  const uint32_t T = st[b].prefix;
-  const int64_t base = (int64_t)blockIdx.x * kSelectChunk + (int64_t)t * kPerThread;
-  uint32_t packed = 0;
-  if (base < N) {
-#pragma unroll
-    for (int r = 0; r < kPerThread; r += 4) {
-      if (base + r < N) {  // N is a multiple of 4
-        const uint4 k4 = *reinterpret_cast<const uint4 *>(keys + base + r);
-        packed += ((k4.x > T) << 16) + (k4.x == T);
-        packed += ((k4.y > T) << 16) + (k4.y == T);
-        packed += ((k4.z > T) << 16) + (k4.z == T);
-        packed += ((k4.w > T) << 16) + (k4.w == T);
-      }
-    }
-  }
-  uint32_t total;
-  (void)block_exclusive_scan(packed, wave_tot, total);
-  if (t == 0) blockcnt[(size_t)b * nblk + blockIdx.x] = make_uint2(total >> 16, total & 0xFFFFu);
+__global__ __launch_bounds__(256) void select_init_kernel(SelectPrep p, int B) {
+  if ((int)blockIdx.x < B) prep_sample(p, blockIdx.x, threadIdx.x, blockDim.x);
 }
 
-// ordered compaction.  grid = (nblk, B).  jmap (nullable) gets the rank of every kept
-// position and -1 for every dropped one.
+// Four keys of this thread.  REDUCE: keys are sums of G partial-norm planes (added in
+// increasing group order), and the sums are written to norm.
+template <bool REDUCE>
+__device__ __forceinline__ uint4 load_keys(const float *__restrict__ src, float *__restrict__ norm,
+                                           int G, int64_t BN, int64_t at) {
+  float4 v = *reinterpret_cast<const float4 *>(src + at);
+  if constexpr (REDUCE) {
+    for (int g = 1; g < G; ++g) {
+      const float4 t = *reinterpret_cast<const float4 *>(src + (int64_t)g * BN + at);
+      v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+    }
+    *reinterpret_cast<float4 *>(norm + at) = v;
+  }
+  return make_uint4(__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z),
+                    __float_as_uint(v.w));
+}
+
+// Turns the finished histogram of pass P into the digit that holds the remaining rank:
+// the digit D with count(> D) < remain <= count(>= D), scanning from the top digit down.
+// Every thread returns the same (prefix, remain) for the next pass.
+template <int P>
+__device__ __forceinline__ void pick_digit(const uint32_t *gh, uint32_t &prefix,
+                                           uint32_t &remain, uint32_t *tmp, uint32_t *bcast) {
+  constexpr int bins = P == 2 ? 1024 : kRadixBins;
+  constexpr int per = bins / kThreads;  // consecutive digits per thread, from the top
+  const int t = threadIdx.x;
+  uint32_t cnt[per], sum = 0;
+#pragma unroll
+  for (int i = 0; i < per; ++i) {
+    cnt[i] = gh[bins - 1 - (t * per + i)];
+    sum += cnt[i];
+  }
+  uint32_t above = block_exclusive_scan(sum, tmp);
+#pragma unroll
+  for (int i = 0; i < per; ++i) {
+    if (above < remain && remain <= above + cnt[i]) {
+      const uint32_t digit = bins - 1 - (t * per + i);
+      bcast[0] = prefix | (P == 0 ? digit << 21 : P == 1 ? digit << 10 : digit);
+      bcast[1] = remain - above;
+    }
+    above += cnt[i];
+  }
+  __syncthreads();
+  prefix = bcast[0];
+  remain = bcast[1];
+  __syncthreads();
+}
+
+// (prefix, remain) after passes 0..UPTO-1: earlier picks come from the state (stored by a
+// previous kernel), the newest one is computed here from the histogram that kernel finished.
+template <int UPTO>
+__device__ __forceinline__ void current_state(const uint32_t *hist_b, SelectState *s,
+                                              uint32_t k, uint32_t &prefix, uint32_t &remain,
+                                              uint32_t *tmp, uint32_t *bcast, bool store) {
+  prefix = 0;
+  remain = k;
+  if constexpr (UPTO == 0) return;
+  if constexpr (UPTO >= 2) {
+    prefix = s->prefix[UPTO - 2];
+    remain = s->remain[UPTO - 2];
+  }
+  if (threadIdx.x == 0) { bcast[0] = prefix; bcast[1] = remain; }  // rank beyond the data: unchanged
+  __syncthreads();
+  pick_digit<UPTO - 1>(hist_b + (size_t)(UPTO - 1) * kRadixBins, prefix, remain, tmp, bcast);
+  if (store && threadIdx.x == 0) {
+    s->prefix[UPTO - 1] = prefix;
+    s->remain[UPTO - 1] = remain;
+  }
+}
+
+// One histogram pass.  grid = (nblk, B), block = 256.
+// PASS 0 with REDUCE reads partial norms `src` [G, B, N] and writes `norm`; otherwise src is
+// the norm array itself.  PASS 2 also writes this workgroup's suffix sums and its count of
+// keys above the 22-bit prefix.
+template <int PASS, bool REDUCE>
+__global__ __launch_bounds__(kThreads) void select_hist_kernel(const float *__restrict__ src,
+                                                               float *__restrict__ norm, int G,
+                                                               int64_t N, int B, uint32_t k,
+                                                               uint32_t *hist, SelectState *st,
+                                                               int nblk,
+                                                               uint16_t *__restrict__ block_sfx,
+                                                               uint32_t *__restrict__ block_gthi) {
+  constexpr int bins = PASS == 2 ? 1024 : kRadixBins;
+  __shared__ uint32_t lh[kRadixBins];
+  __shared__ uint32_t tmp[kWaves];
+  __shared__ uint32_t bcast[2];
+  const int b = blockIdx.y, t = threadIdx.x;
+  uint32_t *hist_b = hist + (size_t)b * 3 * kRadixBins;
+  uint32_t *gh = hist_b + (size_t)PASS * kRadixBins;
+
+  for (int i = t; i < bins; i += kThreads) lh[i] = 0;
+  uint32_t prefix, remain;
+  current_state<PASS>(hist_b, st + b, k, prefix, remain, tmp, bcast, blockIdx.x == 0);
+  __syncthreads();
+  const int64_t q0 = (int64_t)blockIdx.x * kSelectChunk + (int64_t)t * kPer;
+  const bool in = q0 < N;  // N is a multiple of 4: a thread's four keys are all in or all out
+  uint4 k4 = make_uint4(0, 0, 0, 0);
+  if (in) k4 = load_keys<REDUCE>(src, norm, G, (int64_t)B * N, (int64_t)b * N + q0);
+  const uint32_t key[4] = {k4.x, k4.y, k4.z, k4.w};
+  uint32_t above = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    hist_add(lh, digit_of(key[e], PASS), in && matches(key[e], prefix, PASS));
+    if (PASS == 2) above += (in && (key[e] >> 10) > (prefix >> 10)) ? 1u : 0u;
+  }
+  __syncthreads();
+  for (int i = t; i < bins; i += kThreads) {
+    const uint32_t v = lh[i];
+    if (v) atomicAdd(&gh[i], v);
+  }
+  if constexpr (PASS == 2) {
+    // sfx[d] = number of this workgroup's matching keys with low digit >= d
+    constexpr int per = bins / kThreads;  // 4 digits per thread, from the top
+    uint32_t c[per], sum = 0;
+#pragma unroll
+    for (int i = 0; i < per; ++i) {
+      c[i] = lh[bins - 1 - (t * per + i)];
+      sum += c[i];
+    }
+    uint32_t run = block_exclusive_scan(sum, tmp);
+    const size_t blk = (size_t)b * nblk + blockIdx.x;
+#pragma unroll
+    for (int i = 0; i < per; ++i) {
+      run += c[i];
+      block_sfx[blk * kSfxStride + (bins - 1 - (t * per + i))] = (uint16_t)run;
+    }
+    const uint32_t tot_above = block_sum(above, tmp);
+    if (t == 0) block_gthi[blk] = tot_above;
+  }
+}
+
+// Ordered compaction.  grid = (nblk, B), block = 256.  jmap (nullable) gets the rank of
+// every kept position and -1 for every dropped one.
 __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__restrict__ norm,
                                                                int64_t N, int64_t k,
-                                                               const SelectState *st,
-                                                               const uint2 *blockcnt, int nblk,
-                                                               int32_t *__restrict__ idx,
+                                                               const uint32_t *__restrict__ hist,
+                                                               SelectState *st,
+                                                               const uint16_t *__restrict__ block_sfx,
+                                                               const uint32_t *__restrict__ block_gthi,
+                                                               int nblk, int32_t *__restrict__ idx,
                                                                int32_t *__restrict__ jmap) {
-  __shared__ uint32_t wave_tot[kThreads / 64];
-  __shared__ uint32_t red[2][kThreads / 64];
+  __shared__ uint32_t tmp[kWaves];
+  __shared__ uint32_t bcast[2];
   const int b = blockIdx.y, t = threadIdx.x;
   const uint32_t *keys = reinterpret_cast<const uint32_t *>(norm) + (size_t)b * N;
-  const uint32_t T = st[b].prefix, r_take = st[b].remain;
+  uint32_t T, r_take;  // threshold key, and how many keys equal to it are still needed
+  current_state<3>(hist + (size_t)b * 3 * kRadixBins, st + b, (uint32_t)k, T, r_take, tmp, bcast,
+                   blockIdx.x == 0);
+  const uint32_t tlow = T & 0x3FFu;
 
   // keys above / equal to T in the workgroups before this one
   uint32_t gt0 = 0, eq0 = 0;
   for (int i = t; i < (int)blockIdx.x; i += kThreads) {
-    const uint2 c = blockcnt[(size_t)b * nblk + i];
-    gt0 += c.x; eq0 += c.y;
+    const size_t blk = (size_t)b * nblk + i;
+    const uint32_t ge = block_sfx[blk * kSfxStride + tlow];
+    const uint32_t gtl = tlow + 1 < 1024 ? block_sfx[blk * kSfxStride + tlow + 1] : 0u;
+    gt0 += block_gthi[blk] + gtl;
+    eq0 += ge - gtl;
   }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    gt0 += __shfl_down(gt0, off, 64);
-    eq0 += __shfl_down(eq0, off, 64);
-  }
-  if ((t & 63) == 0) { red[0][t >> 6] = gt0; red[1][t >> 6] = eq0; }
-  __syncthreads();
-  gt0 = red[0][0] + red[0][1] + red[0][2] + red[0][3];
-  eq0 = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+  gt0 = block_sum(gt0, tmp);
+  eq0 = block_sum(eq0, tmp);
 
-  const int64_t base = (int64_t)blockIdx.x * kSelectChunk + (int64_t)t * kPerThread;
-  uint32_t key[kPerThread];
-  uint32_t packed = 0;
+  const int64_t q0 = (int64_t)blockIdx.x * kSelectChunk + (int64_t)t * kPer;
+  const bool in = q0 < N;
+  uint4 k4 = make_uint4(0, 0, 0, 0);
+  if (in) k4 = *reinterpret_cast<const uint4 *>(keys + q0);
+  const uint32_t key[4] = {k4.x, k4.y, k4.z, k4.w};
+  uint32_t packed = 0;  // hi16: keys above T, lo16: keys equal to T (each <= 1024 a workgroup)
 #pragma unroll
-  for (int r = 0; r < kPerThread; r += 4) {
-    uint4 k4 = make_uint4(0, 0, 0, 0);
-    if (base + r < N) k4 = *reinterpret_cast<const uint4 *>(keys + base + r);
-    key[r] = k4.x; key[r + 1] = k4.y; key[r + 2] = k4.z; key[r + 3] = k4.w;
-  }
-#pragma unroll
-  for (int r = 0; r < kPerThread; ++r)
-    if (base + r < N) packed += ((key[r] > T) << 16) + (key[r] == T);
-  uint32_t total;
-  const uint32_t ex = block_exclusive_scan(packed, wave_tot, total);
+  for (int e = 0; e < 4; ++e)
+    if (in) packed += ((key[e] > T) << 16) + (key[e] == T);
+  const uint32_t ex = block_exclusive_scan(packed, tmp);
   uint32_t gt = gt0 + (ex >> 16), eq = eq0 + (ex & 0xFFFFu);
+  if (!in) return;
 
   int32_t *out = idx + (size_t)b * k;
-  int32_t *jm = jmap ? jmap + (size_t)b * N : nullptr;
+  int32_t jm[4];
 #pragma unroll
-  for (int r = 0; r < kPerThread; ++r) {
-    const int64_t q = base + r;
-    if (q >= N) break;
-    const bool is_gt = key[r] > T, is_eq = key[r] == T;
+  for (int e = 0; e < 4; ++e) {
+    const bool is_gt = key[e] > T, is_eq = key[e] == T;
     const bool keep = is_gt || (is_eq && eq < r_take);
     const uint32_t j = gt + min(eq, r_take);
-    if (keep) out[j] = (int32_t)q;
-    if (jm) jm[q] = keep ? (int32_t)j : -1;
+    if (keep) out[j] = (int32_t)(q0 + e);
+    jm[e] = keep ? (int32_t)j : -1;
     gt += is_gt; eq += is_eq;
   }
+  if (jmap) *reinterpret_cast<int4 *>(jmap + (size_t)b * N + q0) = make_int4(jm[0], jm[1], jm[2], jm[3]);
 }
 
 // jmap from an arbitrary ascending index list: fill with -1, then jmap[b][idx[b][j]] = j
@@ -242,24 +294,47 @@ __global__ __launch_bounds__(256) void jmap_scatter_kernel(const int32_t *__rest
 
 }  // namespace
 
-hipError_t launch_select(const wcc_desc &d, const float *norm, int64_t k, void *ws_base,
-                         const WsLayout &L, int32_t *idx, int32_t *jmap, hipStream_t s) {
+SelectPrep make_prep(void *ws_base, const WsLayout &L, float *alpha_slots, float alpha_in) {
+  char *ws = static_cast<char *>(ws_base);
+  SelectPrep p;
+  p.hist = reinterpret_cast<uint32_t *>(ws + L.hist);
+  p.alpha = alpha_slots;
+  p.alpha_in = alpha_in;
+  return p;
+}
+
+hipError_t launch_select_init(const SelectPrep &p, int B, hipStream_t s) {
+  hipLaunchKernelGGL(select_init_kernel, dim3(B), dim3(256), 0, s, p, B);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, float *norm_out,
+                         int64_t k, void *ws_base, const WsLayout &L, int32_t *idx, int32_t *jmap,
+                         hipStream_t s) {
   const int64_t N = (int64_t)d.H * d.W;
   char *ws = static_cast<char *>(ws_base);
   uint32_t *hist = reinterpret_cast<uint32_t *>(ws + L.hist);
   SelectState *st = reinterpret_cast<SelectState *>(ws + L.state);
-  uint2 *blockcnt = reinterpret_cast<uint2 *>(ws + L.blockcnt);
+  uint16_t *sfx = reinterpret_cast<uint16_t *>(ws + L.block_sfx);
+  uint32_t *gthi = reinterpret_cast<uint32_t *>(ws + L.block_gthi);
   const int nblk = L.nblk;
-  const int init_n = d.B * 3 * kRadixBins;
-  hipLaunchKernelGGL(select_init_kernel, dim3((init_n + kThreads - 1) / kThreads), dim3(kThreads),
-                     0, s, hist, st, d.B, (uint32_t)k);
-  dim3 grid(nblk, d.B);
-  hipLaunchKernelGGL(select_hist_kernel<0>, grid, dim3(kThreads), 0, s, norm, N, hist, st, nblk);
-  hipLaunchKernelGGL(select_hist_kernel<1>, grid, dim3(kThreads), 0, s, norm, N, hist, st, nblk);
-  hipLaunchKernelGGL(select_hist_kernel<2>, grid, dim3(kThreads), 0, s, norm, N, hist, st, nblk);
-  hipLaunchKernelGGL(select_count_kernel, grid, dim3(kThreads), 0, s, norm, N, st, blockcnt, nblk);
-  hipLaunchKernelGGL(select_emit_kernel, grid, dim3(kThreads), 0, s, norm, N, k, st, blockcnt, nblk,
-                     idx, jmap);
+  const uint32_t k32 = (uint32_t)k;
+  dim3 grid(nblk, d.B), block(kThreads);
+  const float *norm = norm_or_part;
+  if (G > 1) {
+    hipLaunchKernelGGL((select_hist_kernel<0, true>), grid, block, 0, s, norm_or_part, norm_out, G, N,
+                       d.B, k32, hist, st, nblk, sfx, gthi);
+    norm = norm_out;
+  } else {
+    hipLaunchKernelGGL((select_hist_kernel<0, false>), grid, block, 0, s, norm, nullptr, 1, N, d.B,
+                       k32, hist, st, nblk, sfx, gthi);
+  }
+  hipLaunchKernelGGL((select_hist_kernel<1, false>), grid, block, 0, s, norm, nullptr, 1, N, d.B, k32,
+                     hist, st, nblk, sfx, gthi);
+  hipLaunchKernelGGL((select_hist_kernel<2, false>), grid, block, 0, s, norm, nullptr, 1, N, d.B, k32,
+                     hist, st, nblk, sfx, gthi);
+  hipLaunchKernelGGL(select_emit_kernel, grid, block, 0, s, norm, N, k, hist, st, sfx, gthi, nblk, idx,
+                     jmap);
   return hipGetLastError();
 }
 

@@ -64,13 +64,13 @@ WsLayout ws_layout(const wcc_desc &d) {
   L.norm = take(B * N * 4);
   L.hist = take(B * 3 * kRadixBins * 4);
   L.state = take(B * sizeof(SelectState));
-  L.blockcnt = take(B * (size_t)L.nblk * 8);
+  L.block_sfx = take(B * (size_t)L.nblk * kSfxStride * 2);
+  L.block_gthi = take(B * (size_t)L.nblk * 4);
   L.jmap = take(B * N * 4);
   L.idx = take(B * k * 4);
   L.alpha = take(256);
   L.coef = take(B * (size_t)d.C_in * N * 4);
   L.xc32 = take(B * (size_t)d.C_in * k * 4);
-  L.xq = take(B * (size_t)d.C_in * k);
   L.yc = take(B * (size_t)d.C_out * k * 4);
   L.total = off;
   return L;
@@ -173,17 +173,18 @@ wcc_status wcc_haar_fwd(wcc_ctx *ctx, const wcc_desc *desc, const float *x, floa
   if (misaligned(x) || misaligned(coef) || misaligned(norm)) return WCC_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const WsLayout L = ws_layout(*desc);
+  const SelectPrep no_prep{nullptr, nullptr, 0.f};
   if (!norm) {
-    WCC_TRY(launch_haar_fwd(*desc, x, coef, nullptr, L.G, s));
+    WCC_TRY(launch_haar_fwd(*desc, x, coef, nullptr, L.G, no_prep, s));
     return WCC_OK;
   }
   if ((st = need_ws(ctx, L)) != WCC_OK) return st;
   const int64_t BN = (int64_t)desc->B * desc->H * desc->W;
   if (L.G == 1) {
-    WCC_TRY(launch_haar_fwd(*desc, x, coef, norm, 1, s));
+    WCC_TRY(launch_haar_fwd(*desc, x, coef, norm, 1, no_prep, s));
   } else {
     float *part = reinterpret_cast<float *>(static_cast<char *>(ctx->ws) + L.norm_part);
-    WCC_TRY(launch_haar_fwd(*desc, x, coef, part, L.G, s));
+    WCC_TRY(launch_haar_fwd(*desc, x, coef, part, L.G, no_prep, s));
     WCC_TRY(launch_norm_reduce(part, L.G, BN, norm, s));
   }
   return WCC_OK;
@@ -204,7 +205,9 @@ wcc_status wcc_joint_topk(wcc_ctx *ctx, const wcc_desc *desc, const float *coef,
     WCC_TRY(launch_channel_norm(coef, desc->B, desc->C_in, (int64_t)desc->H * desc->W, nw, s));
     norm = nw;
   }
-  WCC_TRY(launch_select(*desc, norm, k_of(*desc), ws, L, idx, nullptr, s));
+  const int64_t k = k_of(*desc);
+  WCC_TRY(launch_select_init(make_prep(ws, L, nullptr, 0.f), desc->B, s));
+  WCC_TRY(launch_select(*desc, norm, 1, nullptr, k, ws, L, idx, nullptr, s));
   return WCC_OK;
 }
 
@@ -220,18 +223,17 @@ wcc_status wcc_gather_quant(wcc_ctx *ctx, const wcc_desc *desc, const float *coe
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t N = (int64_t)desc->H * desc->W, k = k_of(*desc);
   if (!quant) {
-    if (alpha_dev) WCC_TRY(launch_alpha_init(alpha_dev, alpha_in, s));
-    WCC_TRY(launch_gather(coef, idx, desc->B, desc->C_in, N, k, static_cast<float *>(xc),
-                          (alpha_dev && !(alpha_in > 0.f)) ? alpha_dev : nullptr, s));
+    WCC_TRY(launch_gather(coef, idx, desc->B, desc->C_in, N, k, static_cast<float *>(xc), nullptr, s));
     return WCC_OK;
   }
   const WsLayout L = ws_layout(*desc);
   if ((st = need_ws(ctx, L)) != WCC_OK) return st;
-  float *xc32 = reinterpret_cast<float *>(static_cast<char *>(ctx->ws) + L.xc32);
-  WCC_TRY(launch_alpha_init(alpha_dev, alpha_in, s));
-  WCC_TRY(launch_gather(coef, idx, desc->B, desc->C_in, N, k, xc32,
-                        alpha_in > 0.f ? nullptr : alpha_dev, s));
-  WCC_TRY(launch_quantize(xc32, (int64_t)desc->B * desc->C_in * k, alpha_dev,
+  char *ws = static_cast<char *>(ctx->ws);
+  float *xc32 = reinterpret_cast<float *>(ws + L.xc32);
+  float *slots = reinterpret_cast<float *>(ws + L.alpha);
+  WCC_TRY(launch_alpha_init(slots, alpha_in, s));
+  WCC_TRY(launch_gather(coef, idx, desc->B, desc->C_in, N, k, xc32, alpha_in > 0.f ? nullptr : slots, s));
+  WCC_TRY(launch_quantize(xc32, (int64_t)desc->B * desc->C_in * k, slots, alpha_dev,
                           static_cast<int8_t *>(xc), s));
   return WCC_OK;
 }
@@ -244,8 +246,8 @@ wcc_status wcc_pointwise(wcc_ctx *ctx, const wcc_desc *desc, const void *w, cons
   if (desc->w_dtype == WCC_I8 && !w_scale) return WCC_ERR_NULL;
   if (desc->act_quant_bits == 8 && !alpha_dev) return WCC_ERR_NULL;
   if (misaligned(w) || misaligned(xc) || misaligned(yc)) return WCC_ERR_ALIGN;
-  WCC_TRY(launch_pointwise(*desc, k_of(*desc), w, w_scale, xc, alpha_dev, yc,
-                           static_cast<hipStream_t>(stream)));
+  WCC_TRY(launch_pointwise(*desc, k_of(*desc), w, w_scale, xc, desc->act_quant_bits == 0, alpha_dev,
+                           false, nullptr, yc, static_cast<hipStream_t>(stream)));
   return WCC_OK;
 }
 
@@ -278,17 +280,16 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   hipStream_t s = static_cast<hipStream_t>(stream);
   char *ws = static_cast<char *>(ctx->ws);
   const wcc_desc &d = *desc;
-  const int64_t N = (int64_t)d.H * d.W, k = k_of(d), BN = (int64_t)d.B * N;
+  const int64_t N = (int64_t)d.H * d.W, k = k_of(d);
   const bool quant = d.act_quant_bits == 8;
 
   float *part = reinterpret_cast<float *>(ws + L.norm_part);
   float *norm = reinterpret_cast<float *>(ws + L.norm);
   int32_t *jmap = reinterpret_cast<int32_t *>(ws + L.jmap);
   int32_t *idx = idx_out ? idx_out : reinterpret_cast<int32_t *>(ws + L.idx);
-  float *alpha = alpha_out_dev ? alpha_out_dev : reinterpret_cast<float *>(ws + L.alpha);
+  float *slots = reinterpret_cast<float *>(ws + L.alpha);
   float *coef = reinterpret_cast<float *>(ws + L.coef);
   float *xc32 = reinterpret_cast<float *>(ws + L.xc32);
-  int8_t *xq = reinterpret_cast<int8_t *>(ws + L.xq);
   float *yc = reinterpret_cast<float *>(ws + L.yc);
 
   const bool prof = ctx->profiling && ctx->ev_ok;
@@ -296,29 +297,24 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
     return prof ? hipEventRecord(ctx->ev[stage][which], s) : hipSuccess;
   };
 
-  // A: X_wt = HWT_d(X), partial channel norms
+  // A: X_wt = HWT_d(X) and partial channel norms; the same kernel clears the selection state
   WCC_TRY(mark(WCC_T_HAAR_FWD, 0));
-  WCC_TRY(launch_haar_fwd(d, x, coef, L.G == 1 ? norm : part, L.G, s));
+  WCC_TRY(launch_haar_fwd(d, x, coef, L.G == 1 ? norm : part, L.G,
+                          make_prep(ws, L, slots, quant ? alpha_in : 0.f), s));
   WCC_TRY(mark(WCC_T_HAAR_FWD, 1));
   // B: norms, index set I (ascending), rank map for the inverse
   WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
-  if (L.G > 1) WCC_TRY(launch_norm_reduce(part, L.G, BN, norm, s));
-  WCC_TRY(launch_select(d, norm, k, ws, L, idx, jmap, s));
+  WCC_TRY(launch_select(d, L.G == 1 ? norm : part, L.G, norm, k, ws, L, idx, jmap, s));
   WCC_TRY(mark(WCC_T_NORM_SELECT, 1));
   // B': X_wt[I], alpha
   WCC_TRY(mark(WCC_T_GATHER, 0));
-  WCC_TRY(launch_alpha_init(alpha, alpha_in, s));
   WCC_TRY(launch_gather(coef, idx, d.B, d.C_in, N, k, xc32,
-                        (quant && !(alpha_in > 0.f)) ? alpha : nullptr, s));
+                        (quant && !(alpha_in > 0.f)) ? slots : nullptr, s));
   WCC_TRY(mark(WCC_T_GATHER, 1));
-  // C: Y_wt = Conv(K_1x1, X_wt[I])
+  // C: Y_wt = Conv(K_1x1, X_wt[I]); the kept coefficients are quantised as they are loaded
   WCC_TRY(mark(WCC_T_POINTWISE, 0));
-  if (quant) {
-    WCC_TRY(launch_quantize(xc32, (int64_t)d.B * d.C_in * k, alpha, xq, s));
-    WCC_TRY(launch_pointwise(d, k, w, w_scale, xq, alpha, yc, s));
-  } else {
-    WCC_TRY(launch_pointwise(d, k, w, w_scale, xc32, alpha, yc, s));
-  }
+  WCC_TRY(launch_pointwise(d, k, w, w_scale, xc32, true, slots, true, quant ? alpha_out_dev : nullptr,
+                           yc, s));
   WCC_TRY(mark(WCC_T_POINTWISE, 1));
   // D + E: Y^0[I] = Y_wt, inverse levels
   WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 0));

@@ -11,7 +11,9 @@ namespace wcc {
 constexpr int kWave = 64;          // CDNA wavefront width
 constexpr int kMaxLevels = 4;      // register-resident strip transform up to 16 rows per lane
 constexpr int kRadixBins = 2048;   // 11 + 11 + 10 bit radix select
-constexpr int kSelectChunk = 4096; // keys per workgroup in the select kernels
+constexpr int kSelectChunk = 1024; // keys per workgroup in the select kernels
+constexpr int kSfxStride = 1024;   // per-workgroup suffix sums of the low-digit histogram
+constexpr int kAlphaSlots = 64;    // max|kept c| is reduced into this many slots, then combined
 
 // Geometry of the wavelet vector of one plane (Eq. wavelet_transform for d levels).
 struct Geo {
@@ -26,15 +28,15 @@ struct Geo {
 struct WsLayout {
   size_t norm_part;   // [G, B, N] fp32 partial channel norms
   size_t norm;        // [B, N] fp32
-  size_t hist;        // [B, 3, kRadixBins] u32 + per-sample select state
+  size_t hist;        // [B, 3, kRadixBins] u32
   size_t state;       // [B] SelectState
-  size_t blockcnt;    // [B, nblk] u32 x2 (gt, eq)
+  size_t block_sfx;   // [B, nblk, kSfxStride] u16
+  size_t block_gthi;  // [B, nblk] u32
   size_t jmap;        // [B, N] int32: rank of a kept position, -1 otherwise
   size_t idx;         // [B, k] int32
-  size_t alpha;       // 64 floats (alpha bits at [0])
+  size_t alpha;       // kAlphaSlots floats: partial maxima of |kept coefficient|
   size_t coef;        // [B, C_in, N] fp32   (wcc_forward only)
   size_t xc32;        // [B, C_in, k] fp32
-  size_t xq;          // [B, C_in, k] int8
   size_t yc;          // [B, C_out, k] fp32  (wcc_forward only)
   size_t total;
   int G;              // channel groups of the forward transform
@@ -42,32 +44,77 @@ struct WsLayout {
 };
 
 struct SelectState {
-  uint32_t prefix;   // key bits fixed so far (high bits)
-  uint32_t remain;   // how many more keys to take at or below this prefix
-  uint32_t done[3];  // workgroups finished per pass ("last one picks")
-  uint32_t pad[3];
+  uint32_t prefix[3];  // key bits fixed after pass 0, 1, 2 (prefix[2] is the threshold key)
+  uint32_t remain[3];  // rank still to be resolved inside that prefix
+  uint32_t pad[2];
 };
+
+// Per-call state that has to be cleared before the select passes run.  The forward
+// transform's kernel does it on the side (one workgroup per sample) so that the fused path
+// needs no separate clearing launch.
+struct SelectPrep {
+  uint32_t *hist;   // [B, 3, kRadixBins]; nullptr: nothing to prepare
+  float *alpha;     // kAlphaSlots floats or nullptr
+  float alpha_in;
+};
+
+__device__ inline void prep_sample(const SelectPrep &p, int b, int tid, int nthreads) {
+  if (p.hist == nullptr) return;
+  uint32_t *h = p.hist + (size_t)b * 3 * kRadixBins;
+  for (int i = tid; i < 3 * kRadixBins; i += nthreads) h[i] = 0;
+  if (b == 0 && p.alpha && tid < kAlphaSlots) p.alpha[tid] = p.alpha_in > 0.f ? p.alpha_in : 0.f;
+}
+
+// alpha = max over the slots the gather's workgroups raised (all slots hold alpha_in when the
+// caller supplied it).  Called by whole waves; every lane gets the result.
+__device__ __forceinline__ float alpha_from_slots(const float *__restrict__ slots) {
+  float v = slots[threadIdx.x & (kAlphaSlots - 1)];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+// The scale-clip-round of Eq. (quantweights), signed, b = 8, operation by operation in fp32:
+// u = v / alpha; clip to [-1, 1]; code = round_half_even(127 * u).  alpha <= 0 gives code 0.
+__device__ __forceinline__ int quant_code(float v, float alpha) {
+  if (!(alpha > 0.f)) return 0;
+  float u = __fdiv_rn(v, alpha);
+  u = fminf(fmaxf(u, -1.f), 1.f);
+  return (int)rintf(__fmul_rn(127.f, u));
+}
 
 WsLayout ws_layout(const wcc_desc &d);
 int forward_groups(const wcc_desc &d);
 
 // launchers (each returns hipGetLastError() after its launches)
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part,
-                           int G, hipStream_t s);
+                           int G, const SelectPrep &prep, hipStream_t s);
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s);
 hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, float *norm, hipStream_t s);
-hipError_t launch_select(const wcc_desc &d, const float *norm, int64_t k, void *ws_base,
-                         const WsLayout &L, int32_t *idx, int32_t *jmap /*nullable*/, hipStream_t s);
+SelectPrep make_prep(void *ws_base, const WsLayout &L, float *alpha_slots, float alpha_in);
+hipError_t launch_select_init(const SelectPrep &p, int B, hipStream_t s);
+// G > 1: norm_or_part is [G, B, N] partial norms, reduced into norm_out on the fly;
+// G == 1: norm_or_part is the norm array and norm_out is unused.  Needs prepared state.
+hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, float *norm_out,
+                         int64_t k, void *ws_base, const WsLayout &L, int32_t *idx,
+                         int32_t *jmap /*nullable*/, hipStream_t s);
 hipError_t launch_jmap_from_idx(const int32_t *idx, int B, int64_t N, int64_t k, int32_t *jmap,
                                 hipStream_t s);
-hipError_t launch_alpha_init(float *alpha, float alpha_in, hipStream_t s);
+hipError_t launch_alpha_init(float *alpha_slots, float alpha_in, hipStream_t s);
+// alpha_slots nullable: no maximum is taken
 hipError_t launch_gather(const float *coef, const int32_t *idx, int B, int C, int64_t N, int64_t k,
-                         float *xc, float *alpha_max /*nullable: no max*/, hipStream_t s);
-hipError_t launch_quantize(const float *xc32, int64_t n, const float *alpha, int8_t *codes,
-                           hipStream_t s);
+                         float *xc, float *alpha_slots, hipStream_t s);
+// codes = q(xc32) with alpha = max(slots); also writes alpha to alpha_out[0]
+hipError_t launch_quantize(const float *xc32, int64_t n, const float *alpha_slots, float *alpha_out,
+                           int8_t *codes, hipStream_t s);
 hipError_t launch_copy_f32(const float *src, float *dst, int64_t n, hipStream_t s);
+// xc_is_f32 with act_quant_bits = 8: xc holds the unquantised kept coefficients and the
+// kernel quantises them while loading (the fused path); otherwise xc is what the ABI says.
+// alpha_is_slots: alpha points at kAlphaSlots partial maxima (combined in the kernel, and
+// written to alpha_out[0] if that is not null) instead of at one float.
 hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
-                            const void *xc, const float *alpha, float *yc, hipStream_t s);
+                            const void *xc, bool xc_is_f32, const float *alpha, bool alpha_is_slots,
+                            float *alpha_out, float *yc, hipStream_t s);
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
                                 float *y, hipStream_t s);
 
