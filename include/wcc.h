@@ -84,11 +84,11 @@ typedef struct {
 
 /* Stages whose device time wcc_forward can record (wcc_set_profiling). */
 enum {
-  WCC_T_HAAR_FWD = 0,  /* the forward Haar kernel alone                   */
-  WCC_T_NORM_SELECT,   /* norm reduction + radix select + index emission  */
-  WCC_T_GATHER,        /* gather + max|c|                                 */
-  WCC_T_POINTWISE,     /* quantise + contraction + dequantise             */
-  WCC_T_SCATTER_IHAAR, /* position map + scatter + inverse Haar           */
+  WCC_T_HAAR_FWD = 0,  /* first transform pass (channel norms), one kernel            */
+  WCC_T_NORM_SELECT,   /* norm reduction + radix select + index emission               */
+  WCC_T_GATHER,        /* second transform pass: kept coefficients + max|c|, one kernel */
+  WCC_T_POINTWISE,     /* quantise + contraction + dequantise, one kernel              */
+  WCC_T_SCATTER_IHAAR, /* scatter + inverse Haar, one kernel                           */
   WCC_T_COUNT
 };
 

@@ -68,7 +68,8 @@ struct LanePos {
 };
 
 // ---- analysis ---------------------------------------------------------------------------
-template <int D, int V>
+// STORE = false: only the |coefficient| sums are kept (the norm-only pass of the fused layer).
+template <int D, int V, bool STORE>
 struct FwdSink {
   float *plane;  // wavelet vector of the current (b, c)
   float acc[slot_count(D, V)];
@@ -79,7 +80,7 @@ struct FwdSink {
     constexpr int base = slot_base(D, V, L, J);
 #pragma unroll
     for (int e = 0; e < CV; ++e) acc[base + i * CV + e] += fabsf(v[e]);
-    if (!owner) return;
+    if (!STORE || !owner) return;
     float *dst = plane + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
     if constexpr (CV == 2) {
       *reinterpret_cast<float2 *>(dst) = make_float2(v[0], v[1]);
@@ -178,6 +179,36 @@ __device__ __forceinline__ bool locate(const StripMap &m, const Geo &g, int unit
   return p.active;
 }
 
+// Walks n_ch channel planes (stride N floats) of one strip: loads run PF channels ahead of the
+// arithmetic, in a ring of PF + 1 register tiles.  after(sink) runs once per channel.
+template <int D, int V, int PF, class Sink, class After>
+__device__ __forceinline__ void channel_loop(const float *__restrict__ src, int64_t N, int W,
+                                             int n_ch, const LanePos<D> &p, Sink &sink,
+                                             After &&after) {
+  constexpr int R = 1 << D;
+  float buf[PF + 1][R][V];
+#pragma unroll
+  for (int u = 0; u < PF; ++u)
+    if (u < n_ch) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)u * N + (size_t)r * W, buf[u][r]);
+    }
+  for (int c = 0; c < n_ch; c += PF + 1) {
+#pragma unroll
+    for (int u = 0; u <= PF; ++u) {
+      if (c + u < n_ch) {
+        if (c + u + PF < n_ch) {
+          const float *nx = src + (size_t)(c + u + PF) * N;
+#pragma unroll
+          for (int r = 0; r < R; ++r) load_row<V>(nx + (size_t)r * W, buf[(u + PF) % (PF + 1)][r]);
+        }
+        fwd_levels<D, V, 1>(buf[u], p, sink);
+        after(sink);
+      }
+    }
+  }
+}
+
 // x [B, C, H, W] -> coef [B, C, N]; partial norms over this block's channel group to
 // norm_part [G, B, N] (nullable).  block = 256.
 // SPLIT = false: grid = (ceil(units/4), G, B); each wave of a workgroup takes its own strip unit
@@ -186,13 +217,12 @@ __device__ __forceinline__ bool locate(const StripMap &m, const Geo &g, int unit
 //                of the group's channels each (four times the waves in flight for the same
 //                number of partial-norm planes); their |coefficient| sums meet in LDS and are
 //                added in wave order.
-template <int D, int V, bool SPLIT>
+template <int D, int V, bool SPLIT, bool STORE, int PF>
 __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__ x,
                                                        float *__restrict__ coef,
                                                        float *__restrict__ norm_part, Geo g,
                                                        StripMap m, int C, int Cg, int B,
                                                        SelectPrep prep) {
-  constexpr int R = 1 << D;
   constexpr int NS = slot_count(D, V);
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int unit = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * 4 + wv;
@@ -202,6 +232,7 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__
   LanePos<D> p;
   int row0, col0;
   locate<D, V>(m, g, unit, p, row0, col0);
+  (void)coef;
   int c0 = grp * Cg, c1 = min(C, c0 + Cg);
   if constexpr (SPLIT) {
     const int Cw = (c1 - c0 + 3) / 4;
@@ -209,29 +240,17 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__
     c1 = min(c1, c0 + Cw);
   }
 
-  FwdSink<D, V> sink;
+  FwdSink<D, V, STORE> sink;
 #pragma unroll
   for (int s = 0; s < NS; ++s) sink.acc[s] = 0.f;
 
   if (p.active && c0 < c1) {
     const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
-    sink.plane = coef + ((size_t)b * C + c0) * g.N;
-    float cur[R][V], nxt[R][V];
-#pragma unroll
-    for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)r * g.W, nxt[r]);
-    for (int c = c0; c < c1; ++c) {
-#pragma unroll
-      for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int e = 0; e < V; ++e) cur[r][e] = nxt[r][e];
-      if (c + 1 < c1) {
-        src += g.N;
-#pragma unroll
-        for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)r * g.W, nxt[r]);
-      }
-      fwd_levels<D, V, 1>(cur, p, sink);
-      sink.plane += g.N;
-    }
+    sink.plane = STORE ? coef + ((size_t)b * C + c0) * g.N : nullptr;
+    const int64_t N = g.N;
+    channel_loop<D, V, PF>(src, N, g.W, c1 - c0, p, sink, [N](FwdSink<D, V, STORE> &sk) {
+      if (STORE) sk.plane += N;
+    });
   }
 
   if (norm_part == nullptr) return;
@@ -278,6 +297,103 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__
   if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
   if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
   if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+}
+
+// ---- second pass of the fused layer: transform again, keep only the selected positions ----
+// xc[b, c, jmap[b, q]] = HWT_d(x[b, c])[q] for the kept q; dropped coefficients never reach
+// memory.  Also raises the alpha slots to max |kept coefficient| (nullable).
+template <int D, int V>
+struct KeepSink {
+  float *plane;  // xc[b, c, :]
+  int jj[slot_count(D, V)];
+  uint64_t any[2];  // wave-uniform: bit s set if some lane keeps slot s
+  float vmax;
+  template <int L, int J>
+  __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
+                                          bool owner) {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+    (void)p;
+#pragma unroll
+    for (int e = 0; e < CV; ++e) {
+      const int s = base + i * CV + e;
+      if ((any[s >> 6] >> (s & 63)) & 1) {
+        const int j = jj[s];
+        if (owner && j >= 0) {
+          plane[j] = v[e];
+          vmax = fmaxf(vmax, fabsf(v[e]));
+        }
+      }
+    }
+  }
+};
+
+// grid = (ceil(units/4), G, B), block = 256
+template <int D, int V, int PF>
+__global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict__ x,
+                                                        const int32_t *__restrict__ jmap,
+                                                        float *__restrict__ xc, float *alpha_slots,
+                                                        Geo g, StripMap m, int C, int Cg, int64_t k) {
+  __shared__ float wmax[4];
+  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int grp = blockIdx.y, b = blockIdx.z;
+  LanePos<D> p;
+  int row0, col0;
+  const bool active = locate<D, V>(m, g, unit, p, row0, col0);
+  const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
+
+  KeepSink<D, V> sink;
+  sink.any[0] = sink.any[1] = 0;
+  sink.vmax = 0.f;
+  const int32_t *jm = jmap + (size_t)b * g.N;
+  auto fetch = [&](auto Lc, auto Jc) {
+    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+    constexpr int CV = cols_at(V, L), S2 = span_at(V, L);
+    const bool owner = (S2 == 1) || ((p.lc & (S2 - 1)) == 0);
+#pragma unroll
+    for (int i = 0; i < rows_at(D, L); ++i)
+#pragma unroll
+      for (int e = 0; e < CV; ++e) {
+        constexpr int base = slot_base(D, V, L, J);
+        const int s = base + i * CV + e;
+        int j = -1;
+        if (active && owner) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
+        sink.jj[s] = j;
+        if (__ballot(j >= 0) != 0) sink.any[s >> 6] |= (uint64_t)1 << (s & 63);
+      }
+  };
+  auto each_level = [&](auto Lc) {
+    constexpr int L = decltype(Lc)::value;
+    fetch(Lc, std::integral_constant<int, 1>{});
+    fetch(Lc, std::integral_constant<int, 2>{});
+    fetch(Lc, std::integral_constant<int, 3>{});
+    if constexpr (L == D) fetch(Lc, std::integral_constant<int, 0>{});
+  };
+  each_level(std::integral_constant<int, 1>{});
+  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+  if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+
+  if (active && c0 < c1) {
+    const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+    sink.plane = xc + ((size_t)b * C + c0) * k;
+    channel_loop<D, V, PF>(src, g.N, g.W, c1 - c0, p, sink, [k](KeepSink<D, V> &sk) { sk.plane += k; });
+  }
+  if (alpha_slots == nullptr) return;
+  float mx = sink.vmax;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    mx = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    // integer max on the bit pattern of a non-negative float: exact and order-independent;
+    // workgroups spread over the slots because atomics on one address serialise
+    unsigned int *a = reinterpret_cast<unsigned int *>(alpha_slots) +
+                      ((blockIdx.x + 3u * blockIdx.y + 11u * blockIdx.z) & (kAlphaSlots - 1));
+    const unsigned int mine = __float_as_uint(mx);
+    if (mine > __hip_atomic_load(a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(a, mine);
+  }
 }
 
 // ---- synthesis with zero filling ------------------------------------------------------------
@@ -445,24 +561,42 @@ StripMap make_map(const wcc_desc &d, int V) {
   return m;
 }
 
-// the four waves of a workgroup split a channel group when each still gets >= 2 channels
-bool split_waves(int Cg) { return Cg >= 8; }
+// How a pass over the channels is cut into waves.
+struct Plan {
+  int G;       // channel groups (grid.y)
+  bool split;  // forward/norm pass only: the 4 waves of a workgroup split a group's channels
+  int pf;      // prefetch depth in channels (1 or 2)
+};
 
-template <int D, int V>
-hipError_t fwd_launch(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
+template <int D, int V, bool STORE>
+hipError_t fwd_launch(const wcc_desc &d, const float *x, float *coef, float *norm_part, Plan pl,
                       const SelectPrep &prep, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
-  const int Cg = (d.C_in + G - 1) / G;
-  if (split_waves(Cg)) {
-    dim3 grid(m.units, G, d.B);
-    hipLaunchKernelGGL((haar_fwd_kernel<D, V, true>), grid, dim3(256), 0, s, x, coef, norm_part, g,
-                       m, d.C_in, Cg, d.B, prep);
-  } else {
-    dim3 grid((m.units + 3) / 4, G, d.B);
-    hipLaunchKernelGGL((haar_fwd_kernel<D, V, false>), grid, dim3(256), 0, s, x, coef, norm_part, g,
-                       m, d.C_in, Cg, d.B, prep);
-  }
+  const int Cg = (d.C_in + pl.G - 1) / pl.G;
+  const dim3 grid_split(m.units, pl.G, d.B), grid_flat((m.units + 3) / 4, pl.G, d.B), block(256);
+#define WCC_FWD(SPLIT, PF)                                                                        \
+  hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, STORE, PF>), SPLIT ? grid_split : grid_flat,   \
+                     block, 0, s, x, coef, norm_part, g, m, d.C_in, Cg, d.B, prep)
+  if (pl.split) { if (pl.pf == 2) WCC_FWD(true, 2); else WCC_FWD(true, 1); }
+  else          { if (pl.pf == 2) WCC_FWD(false, 2); else WCC_FWD(false, 1); }
+#undef WCC_FWD
+  return hipGetLastError();
+}
+
+template <int D, int V>
+hipError_t keep_launch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, float *xc,
+                       float *alpha_slots, Plan pl, hipStream_t s) {
+  const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
+  const StripMap m = make_map(d, V);
+  const int Cg = (d.C_in + pl.G - 1) / pl.G;
+  dim3 grid((m.units + 3) / 4, pl.G, d.B);
+  if (pl.pf == 2)
+    hipLaunchKernelGGL((haar_keep_kernel<D, V, 2>), grid, dim3(256), 0, s, x, jmap, xc, alpha_slots, g,
+                       m, d.C_in, Cg, k);
+  else
+    hipLaunchKernelGGL((haar_keep_kernel<D, V, 1>), grid, dim3(256), 0, s, x, jmap, xc, alpha_slots, g,
+                       m, d.C_in, Cg, k);
   return hipGetLastError();
 }
 
@@ -485,6 +619,7 @@ int groups_for(const wcc_desc &d, int C, int64_t want_waves, int min_ch) {
   const StripMap m = make_map(d, V);
   const int64_t waves = (int64_t)m.units * d.B;
   int G = 1;
+  if (waves >= want_waves / 2) return G;  // already enough strips: keep the channel walk whole
   while (waves * G < want_waves && C / (G * 2) >= min_ch) G *= 2;
   return G;
 }
@@ -492,27 +627,41 @@ int groups_for(const wcc_desc &d, int C, int64_t want_waves, int min_ch) {
 }  // namespace
 
 // Every forward group costs one partial-norm plane (written once, read once): with >= 16
-// channels a group that is at most 1/16 of the transform's own traffic.  The waves of a
-// workgroup split a group four ways, so a quarter of the wave target is asked of the groups.
-int forward_groups(const wcc_desc &d) { return groups_for(d, d.C_in, 2048, 16); }
+// channels a group that is at most 1/16 of the transform's own traffic.  Measured on gfx950:
+// about a thousand waves, each walking as many channels as possible, stream best; more
+// groups only pay when a layer has fewer strips than that.
+int forward_groups(const wcc_desc &d) { return groups_for(d, d.C_in, 1024, 16); }
 
-hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
-                           const SelectPrep &prep, hipStream_t s) {
+template <bool STORE>
+hipError_t fwd_dispatch(const wcc_desc &d, const float *x, float *coef, float *norm_part, Plan pl,
+                        const SelectPrep &prep, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
-    case 1: return v4 ? fwd_launch<1, 4>(d, x, coef, norm_part, G, prep, s)
-                      : fwd_launch<1, 2>(d, x, coef, norm_part, G, prep, s);
-    case 2: return fwd_launch<2, 4>(d, x, coef, norm_part, G, prep, s);
-    case 3: return fwd_launch<3, 4>(d, x, coef, norm_part, G, prep, s);
-    case 4: return fwd_launch<4, 4>(d, x, coef, norm_part, G, prep, s);
+    case 1: return v4 ? fwd_launch<1, 4, STORE>(d, x, coef, norm_part, pl, prep, s)
+                      : fwd_launch<1, 2, STORE>(d, x, coef, norm_part, pl, prep, s);
+    case 2: return fwd_launch<2, 4, STORE>(d, x, coef, norm_part, pl, prep, s);
+    case 3: return fwd_launch<3, 4, STORE>(d, x, coef, norm_part, pl, prep, s);
+    case 4: return fwd_launch<4, 4, STORE>(d, x, coef, norm_part, pl, prep, s);
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
-                                float *y, hipStream_t s) {
+hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, float *xc,
+                         float *alpha_slots, Plan pl, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
-  const int G = groups_for(d, d.C_out, 8192, 4);
+  switch (d.levels) {
+    case 1: return v4 ? keep_launch<1, 4>(d, k, x, jmap, xc, alpha_slots, pl, s)
+                      : keep_launch<1, 2>(d, k, x, jmap, xc, alpha_slots, pl, s);
+    case 2: return keep_launch<2, 4>(d, k, x, jmap, xc, alpha_slots, pl, s);
+    case 3: return keep_launch<3, 4>(d, k, x, jmap, xc, alpha_slots, pl, s);
+    case 4: return keep_launch<4, 4>(d, k, x, jmap, xc, alpha_slots, pl, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t inv_dispatch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, float *y,
+                        int G, hipStream_t s) {
+  const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
     case 1: return v4 ? inv_launch<1, 4>(d, k, yc, jmap, y, G, s)
                       : inv_launch<1, 2>(d, k, yc, jmap, y, G, s);
@@ -521,6 +670,37 @@ hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, c
     case 4: return inv_launch<4, 4>(d, k, yc, jmap, y, G, s);
   }
   return hipErrorInvalidValue;
+}
+
+// G is fixed by the workspace layout (one partial-norm plane per group).  On small layers,
+// where even the groups leave fewer than 1024 waves, the four waves of a workgroup split a
+// group's channels (if each still gets >= 2).
+Plan fwd_plan(const wcc_desc &d, int G) {
+  const int Cg = (d.C_in + G - 1) / G;
+  const StripMap m = make_map(d, (d.W % 4 == 0) ? 4 : 2);
+  const int64_t waves = (int64_t)m.units * d.B * G;
+  return Plan{G, waves < 1024 && Cg >= 8, 1};
+}
+
+hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
+                           const SelectPrep &prep, hipStream_t s) {
+  return fwd_dispatch<true>(d, x, coef, norm_part, fwd_plan(d, G), prep, s);
+}
+
+hipError_t launch_haar_norm(const wcc_desc &d, const float *x, float *norm_part, int G,
+                            const SelectPrep &prep, hipStream_t s) {
+  return fwd_dispatch<false>(d, x, nullptr, norm_part, fwd_plan(d, G), prep, s);
+}
+
+hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap,
+                            float *xc, float *alpha_slots, hipStream_t s) {
+  const Plan pl{groups_for(d, d.C_in, 1024, 8), false, 1};
+  return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, s);
+}
+
+hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
+                                float *y, hipStream_t s) {
+  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 2048, 8), s);
 }
 
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s) {

@@ -69,7 +69,6 @@ WsLayout ws_layout(const wcc_desc &d) {
   L.jmap = take(B * N * 4);
   L.idx = take(B * k * 4);
   L.alpha = take(256);
-  L.coef = take(B * (size_t)d.C_in * N * 4);
   L.xc32 = take(B * (size_t)d.C_in * k * 4);
   L.yc = take(B * (size_t)d.C_out * k * 4);
   L.total = off;
@@ -280,7 +279,7 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   hipStream_t s = static_cast<hipStream_t>(stream);
   char *ws = static_cast<char *>(ctx->ws);
   const wcc_desc &d = *desc;
-  const int64_t N = (int64_t)d.H * d.W, k = k_of(d);
+  const int64_t k = k_of(d);
   const bool quant = d.act_quant_bits == 8;
 
   float *part = reinterpret_cast<float *>(ws + L.norm_part);
@@ -288,7 +287,6 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   int32_t *jmap = reinterpret_cast<int32_t *>(ws + L.jmap);
   int32_t *idx = idx_out ? idx_out : reinterpret_cast<int32_t *>(ws + L.idx);
   float *slots = reinterpret_cast<float *>(ws + L.alpha);
-  float *coef = reinterpret_cast<float *>(ws + L.coef);
   float *xc32 = reinterpret_cast<float *>(ws + L.xc32);
   float *yc = reinterpret_cast<float *>(ws + L.yc);
 
@@ -297,19 +295,20 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
     return prof ? hipEventRecord(ctx->ev[stage][which], s) : hipSuccess;
   };
 
-  // A: X_wt = HWT_d(X) and partial channel norms; the same kernel clears the selection state
+  // A: the transform, first pass: only the channel norms of X_wt leave the chip (the same
+  // kernel clears the selection state)
   WCC_TRY(mark(WCC_T_HAAR_FWD, 0));
-  WCC_TRY(launch_haar_fwd(d, x, coef, L.G == 1 ? norm : part, L.G,
-                          make_prep(ws, L, slots, quant ? alpha_in : 0.f), s));
+  WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, L.G,
+                           make_prep(ws, L, slots, quant ? alpha_in : 0.f), s));
   WCC_TRY(mark(WCC_T_HAAR_FWD, 1));
   // B: norms, index set I (ascending), rank map for the inverse
   WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
   WCC_TRY(launch_select(d, L.G == 1 ? norm : part, L.G, norm, k, ws, L, idx, jmap, s));
   WCC_TRY(mark(WCC_T_NORM_SELECT, 1));
-  // B': X_wt[I], alpha
+  // A again + B': the transform, second pass: X_wt[I] is written straight into its compressed
+  // place (the dropped coefficients never reach memory); alpha = max |kept coefficient|
   WCC_TRY(mark(WCC_T_GATHER, 0));
-  WCC_TRY(launch_gather(coef, idx, d.B, d.C_in, N, k, xc32,
-                        (quant && !(alpha_in > 0.f)) ? slots : nullptr, s));
+  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !(alpha_in > 0.f)) ? slots : nullptr, s));
   WCC_TRY(mark(WCC_T_GATHER, 1));
   // C: Y_wt = Conv(K_1x1, X_wt[I]); the kept coefficients are quantised as they are loaded
   WCC_TRY(mark(WCC_T_POINTWISE, 0));

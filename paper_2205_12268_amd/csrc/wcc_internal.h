@@ -35,7 +35,6 @@ struct WsLayout {
   size_t jmap;        // [B, N] int32: rank of a kept position, -1 otherwise
   size_t idx;         // [B, k] int32
   size_t alpha;       // kAlphaSlots floats: partial maxima of |kept coefficient|
-  size_t coef;        // [B, C_in, N] fp32   (wcc_forward only)
   size_t xc32;        // [B, C_in, k] fp32
   size_t yc;          // [B, C_out, k] fp32  (wcc_forward only)
   size_t total;
@@ -89,6 +88,11 @@ int forward_groups(const wcc_desc &d);
 // launchers (each returns hipGetLastError() after its launches)
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part,
                            int G, const SelectPrep &prep, hipStream_t s);
+// norm-only pass (no coefficient is written) and keep-only pass of the fused layer
+hipError_t launch_haar_norm(const wcc_desc &d, const float *x, float *norm_part, int G,
+                            const SelectPrep &prep, hipStream_t s);
+hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap,
+                            float *xc, float *alpha_slots /*nullable*/, hipStream_t s);
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s);
 hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, float *norm, hipStream_t s);
 SelectPrep make_prep(void *ws_base, const WsLayout &L, float *alpha_slots, float alpha_in);

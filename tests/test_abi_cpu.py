@@ -41,7 +41,7 @@ def test_k_and_workspace_are_pure_host_functions():
         ws = wcc.workspace_bytes(d)
         assert ws % 256 == 0
         N = cfg.H * cfg.W
-        must_hold = 4 * cfg.B * (cfg.C_in * N + cfg.C_in * k + cfg.C_out * k + 2 * N)
+        must_hold = 4 * cfg.B * (cfg.C_in * k + cfg.C_out * k + 2 * N)
         assert ws >= must_hold
     d = wcc.make_desc(1, 4, 4, 8, 8, 1, 1, 3, wcc.F32, 0)
     assert wcc.k_of(d) == 22  # ceil(64/3)
