@@ -89,6 +89,7 @@ enum {
   WCC_T_GATHER,        /* second transform pass: kept coefficients + max|c|, one kernel */
   WCC_T_POINTWISE,     /* quantise + contraction + dequantise, one kernel              */
   WCC_T_SCATTER_IHAAR, /* scatter + inverse Haar, one kernel                           */
+  WCC_T_EVENT_PAIR,    /* an empty bracket: what two event records cost by themselves  */
   WCC_T_COUNT
 };
 

@@ -319,6 +319,8 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 0));
   WCC_TRY(launch_scatter_ihaar(d, k, yc, jmap, y, s));
   WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 1));
+  WCC_TRY(mark(WCC_T_EVENT_PAIR, 0));
+  WCC_TRY(mark(WCC_T_EVENT_PAIR, 1));
   if (prof) ctx->have_times = true;
   return WCC_OK;
 }

@@ -1,0 +1,63 @@
+"""Turns rocprofv3 CSV output into the short text summaries kept under profiles/.
+
+  python -m paper_2205_12268_amd.profsum stats   <dir>/<prefix>_kernel_stats.csv
+  python -m paper_2205_12268_amd.profsum traffic <fetch>/..._counter_collection.csv \\
+         <write>/..._counter_collection.csv <copy_bytes>
+
+`traffic` scales FETCH_SIZE and WRITE_SIZE (KiB per dispatch) by what the same counters read
+for the plain copy kernel of known size that `bench.py --copy-probe` runs in the same process.
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import re
+import sys
+
+
+def short(name: str) -> str:
+    m = re.search(r"(\w+_kernel)(<[^>]*>)?", name)
+    return (m.group(1) + (m.group(2) or "")) if m else name.split("(")[0][:48]
+
+
+def stats(path: str) -> str:
+    out = [f"{'kernel':58s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'pct':>6s}"]
+    for r in csv.DictReader(open(path)):
+        out.append(f"{short(r['Name']).replace(' ', ''):58s} {r['Calls']:>6s} "
+                   f"{float(r['AverageNs']) / 1e3:9.2f} {float(r['MinNs']) / 1e3:9.2f} "
+                   f"{float(r['MaxNs']) / 1e3:9.2f} {float(r['Percentage']):6.2f}")
+    return "\n".join(out)
+
+
+def _mean_counter(path: str, counter: str):
+    acc = collections.defaultdict(list)
+    for r in csv.DictReader(open(path)):
+        if r["Counter_Name"] == counter:
+            acc[short(r["Kernel_Name"]).replace(" ", "")].append(float(r["Counter_Value"]))
+    return {k: sum(v) / len(v) for k, v in acc.items()}
+
+
+def traffic(fetch_csv: str, write_csv: str, copy_bytes: float) -> str:
+    f = _mean_counter(fetch_csv, "FETCH_SIZE")
+    w = _mean_counter(write_csv, "WRITE_SIZE")
+    copy = next(k for k in f if "copyBuffer" in k or "copy" in k.lower())
+    fs = copy_bytes / (f[copy] * 1024.0)
+    ws = copy_bytes / (w[copy] * 1024.0)
+    out = [f"# copy kernel {copy}: {copy_bytes:.0f} bytes read and written per launch; "
+           f"FETCH_SIZE read {f[copy]:.1f} KiB -> scale {fs:.4f}; WRITE_SIZE read {w[copy]:.1f} KiB -> scale {ws:.4f}",
+           f"# {'kernel':56s} {'fetch_bytes':>14s} {'write_bytes':>14s} {'total_bytes':>14s}"]
+    for k in f:
+        if k == copy:
+            continue
+        fb, wb = f[k] * 1024 * fs, w.get(k, 0.0) * 1024 * ws
+        out.append(f"{k:58s} {fb:14.0f} {wb:14.0f} {fb + wb:14.0f}")
+    return "\n".join(out)
+
+
+if __name__ == "__main__":
+    if sys.argv[1] == "stats":
+        print(stats(sys.argv[2]))
+    elif sys.argv[1] == "traffic":
+        print(traffic(sys.argv[2], sys.argv[3], float(sys.argv[4])))
+    else:
+        sys.exit(__doc__)

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libwcc.so")
 
 F32, BF16, I8 = 0, 1, 2
-STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar")
+STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "event_pair")
 
 EXPORTS = ("wcc_create", "wcc_destroy", "wcc_workspace_bytes", "wcc_set_workspace", "wcc_k",
            "wcc_status_string", "wcc_set_profiling", "wcc_stage_times", "wcc_haar_fwd",
