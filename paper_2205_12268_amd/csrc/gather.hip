@@ -91,8 +91,9 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
                                                        const float *__restrict__ alpha_slots,
                                                        float *__restrict__ alpha_out,
                                                        int8_t *__restrict__ codes) {
-  const float a = alpha_from_slots(alpha_slots);
-  if (blockIdx.x == 0 && threadIdx.x == 0) alpha_out[0] = a;
+  const float alpha = alpha_from_slots(alpha_slots);
+  if (blockIdx.x == 0 && threadIdx.x == 0) alpha_out[0] = alpha;
+  const Quant a(alpha);
   const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 16;
   if (i0 >= n) return;
   if (i0 + 16 <= n && (n & 15) == 0) {
@@ -100,13 +101,13 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const float4 v = *reinterpret_cast<const float4 *>(xc32 + i0 + 4 * g);
-      const uint32_t c0 = (uint32_t)quant_code(v.x, a) & 0xFFu, c1 = (uint32_t)quant_code(v.y, a) & 0xFFu;
-      const uint32_t c2 = (uint32_t)quant_code(v.z, a) & 0xFFu, c3 = (uint32_t)quant_code(v.w, a) & 0xFFu;
+      const uint32_t c0 = (uint32_t)a.code(v.x) & 0xFFu, c1 = (uint32_t)a.code(v.y) & 0xFFu;
+      const uint32_t c2 = (uint32_t)a.code(v.z) & 0xFFu, c3 = (uint32_t)a.code(v.w) & 0xFFu;
       packed[g] = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
     }
     *reinterpret_cast<uint4 *>(codes + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
   } else {
-    for (int e = 0; e < 16 && i0 + e < n; ++e) codes[i0 + e] = (int8_t)quant_code(xc32[i0 + e], a);
+    for (int e = 0; e < 16 && i0 + e < n; ++e) codes[i0 + e] = (int8_t)a.code(xc32[i0 + e]);
   }
 }
 

@@ -2,13 +2,17 @@
 // "y_i = sum_j k_ij x_j" with x_j the length-k compressed channel vectors): per sample a
 // [C_out x C_in] . [C_in x k] contraction, k contiguous in memory on both sides.
 //
-// Matrix-core kernels (int8 activation codes):
-//   bf16 weights: v_mfma_f32_32x32x16_bf16.  The int8 codes (|n| <= 127) are exact in bf16
-//                 and every product is exact in fp32; only the fp32 accumulation rounds.
+// Matrix-core kernel (int8 activation codes):
+//   bf16 weights: v_mfma_f32_32x32x16_bf16.  The codes (|n| <= 127) are exact in bf16 and
+//                 every product is exact in fp32; only the fp32 accumulation rounds.
 //   int8 weights: v_mfma_i32_32x32x32_i8, exact int32 accumulation.
-// A workgroup (4 waves) computes a 128 x 128 tile; wave w owns rows 32w..32w+31 and all 128
-// columns.  The activation tile arrives k-contiguous-along-n from HBM; each thread takes a
-// 4(n) x 8(c) patch in registers, transposes it, and stores it to LDS with the n rows permuted
+// At the layer's shapes the contraction is bound by HBM (a few tens of flop per byte), so the
+// kernel is built around the activation stream: a workgroup owns BM = 128 or 256 output rows
+// (all of C_out when it fits, so every activation is read and quantised once) and 128
+// positions; each thread loads its share of up to 256 channels' worth of the [C_in x 128]
+// activation tile up front (one exposure to memory latency), quantises it in registers,
+// transposes 4(n) x CPT(c) patches into LDS, and the waves (wave w owns rows 32w..32w+31 and
+// all 128 columns) run the MFMAs 64 channels at a time.  The n rows are stored permuted
 // (row (n%4)*32 + n/4) so that MFMA column c of column block i is n = 4c + i: after the four
 // column blocks a lane holds four adjacent n of one output row and stores them as 16 bytes.
 // Everything else (fp32 weights, unquantised activations, odd shapes) takes a plain fp32 FMA
@@ -23,15 +27,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef __attribute__((__vector_size__(4 * sizeof(int)))) int intx4;
 typedef __attribute__((__vector_size__(16 * sizeof(int)))) int intx16;
 
-constexpr int BM = 128, BN = 128, BK = 64;
-
-// ---- bf16 x (int8 codes as bf16) -> fp32 ----------------------------------------------------
-constexpr int LDB = BK + 8;  // bf16 elements per LDS row (144 bytes: 16-byte aligned, 36 banks)
-
-__device__ __forceinline__ uint32_t code_to_bf16(uint32_t dw, int byte) {
-  const int v = (int)(dw << (24 - 8 * byte)) >> 24;  // sign-extended byte
-  return __float_as_uint((float)v) >> 16;           // |v| <= 128: exact in bf16
-}
+constexpr int BN = 128, BK = 64;
 
 // The layer's alpha: one float, or the max of the gather's slots.  The first workgroup also
 // publishes it to alpha_out (nullable).  Called by every thread of the workgroup.
@@ -43,101 +39,151 @@ __device__ __forceinline__ float load_alpha(const float *__restrict__ alpha, boo
   return a;
 }
 
-// A thread's 8 (channels) x 4 (positions) patch of the activation tile as packed int8 codes:
-// dw[r] holds positions n..n+3 of channel c0 + r.  F32: the source holds unquantised kept
-// coefficients, quantised here with the layer's alpha.
-template <bool F32>
-__device__ __forceinline__ void load_patch(const void *__restrict__ xb, int K, int64_t k, int c0,
-                                           int64_t n, float alpha, uint32_t (&dw)[8]) {
-  if constexpr (F32) {
-    const float *xf = static_cast<const float *>(xb);
-    float4 v[8];
+// A thread's raw CPT (channels) x 4 (positions) patch of one 64-channel chunk.
+// F32: unquantised kept coefficients (16 bytes a channel); else int8 codes (4 bytes a channel).
+template <bool F32, int CPT>
+struct Patch {
+  float4 f[F32 ? CPT : 1];
+  uint32_t c[F32 ? 1 : CPT];
+  __device__ __forceinline__ void load(const void *__restrict__ xb, int K, int64_t k, int c0,
+                                       int64_t n) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (c0 + r < K && n < k) v[r] = *reinterpret_cast<const float4 *>(xf + (size_t)(c0 + r) * k + n);
-    }
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      dw[r] = ((uint32_t)quant_code(v[r].x, alpha) & 0xFFu) |
-              (((uint32_t)quant_code(v[r].y, alpha) & 0xFFu) << 8) |
-              (((uint32_t)quant_code(v[r].z, alpha) & 0xFFu) << 16) |
-              (((uint32_t)quant_code(v[r].w, alpha) & 0xFFu) << 24);
-    }
-  } else {
-    const int8_t *xq = static_cast<const int8_t *>(xb);
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      dw[r] = 0;
-      if (c0 + r < K && n < k) dw[r] = *reinterpret_cast<const uint32_t *>(xq + (size_t)(c0 + r) * k + n);
+    for (int r = 0; r < CPT; ++r) {
+      const bool in = c0 + r < K && n < k;
+      if constexpr (F32) {
+        f[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (in) f[r] = *reinterpret_cast<const float4 *>(static_cast<const float *>(xb) + (size_t)(c0 + r) * k + n);
+      } else {
+        c[r] = 0;
+        if (in) c[r] = *reinterpret_cast<const uint32_t *>(static_cast<const int8_t *>(xb) + (size_t)(c0 + r) * k + n);
+      }
     }
   }
-}
+  // level of channel r, position i, as a float holding an integer in [-127, 127]
+  __device__ __forceinline__ float level(int r, int i, const Quant &q) const {
+    if constexpr (F32) {
+      const float v = i == 0 ? f[r].x : i == 1 ? f[r].y : i == 2 ? f[r].z : f[r].w;
+      return q.level(v);
+    } else {
+      return (float)((int)(c[r] << (24 - 8 * i)) >> 24);
+    }
+  }
+};
 
-// grid = (ceil(k/128), ceil(M/128), B); needs K % 8 == 0 and k % 4 == 0
-template <bool F32>
-__global__ __launch_bounds__(256) void pointwise_bf16_kernel(const uint16_t *__restrict__ w,
-                                                             const void *__restrict__ xq,
-                                                             const float *__restrict__ alpha,
-                                                             bool slots, float *alpha_out,
-                                                             float *__restrict__ yc, int M, int K,
-                                                             int64_t k) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDB];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDB];
+// grid = (ceil(k/128), ceil(M/BM), B), block = 2*BM threads.  Needs k % 4 == 0 and
+// K % 8 == 0 (bf16 weights) or K % 16 == 0 (int8 weights).
+template <int BM, bool F32, bool I8W>
+__global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
+    const void *__restrict__ w, const float *__restrict__ w_scale, const void *__restrict__ xq,
+    const float *__restrict__ alpha, bool slots, float *alpha_out, float *__restrict__ yc, int M,
+    int K, int64_t k) {
+  constexpr int T = 2 * BM;
+  constexpr int CPT = BK / (T / 32);         // channels of a chunk per thread: 8 or 4
+  constexpr int NPF = T == 512 ? 4 : 2;      // chunks loaded ahead (64 / 64 registers)
+  constexpr int ESZ = I8W ? 1 : 2;           // bytes of an LDS element
+  constexpr int LDR = I8W ? BK + 16 : (BK + 8) * 2;  // LDS row bytes: 80 / 144 (16-byte aligned,
+                                                      // fragment reads free of bank conflicts)
+  constexpr int APT = BK * ESZ / 2 / 16;     // 16-byte weight loads per thread and chunk: 2 / 4
+  __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDR];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * LDR];
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const int b = blockIdx.z, m0 = blockIdx.y * BM;
   const int64_t n0 = (int64_t)blockIdx.x * BN;
   const void *xb = static_cast<const char *>(xq) + (size_t)b * K * k * (F32 ? 4 : 1);
-  const float al = load_alpha(alpha, slots, alpha_out);
+  const unsigned char *wb = static_cast<const unsigned char *>(w);
+  const int a_row = t >> 1, a_half = t & 1;  // weight loader: row, which half of the chunk
+  const int g = t & 31, kq = t >> 5;         // activation loader: n group (4 n), channel group
+  const int nchunks = (K + BK - 1) / BK;
 
-  floatx16 acc[4];
+  floatx16 accf[4];
+  intx16 acci[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int r = 0; r < 16; ++r) { accf[i][r] = 0.f; acci[i][r] = 0; }
 
-  const int a_row = t >> 1, a_half = t & 1;       // A loader: row, which 32 of the 64 k
-  const int g = t & 31, kq = t >> 5;              // B loader: n group (4 n), k octet
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    // weights tile: As[row][kk] = w[m0 + row][k0 + kk], zero outside
-    {
-      const int m = m0 + a_row;
+  Patch<F32, CPT> raw[NPF];
+  float al = 0.f;
+  for (int kc0 = 0; kc0 < nchunks; kc0 += NPF) {
+    // every load of the next NPF chunks goes out before anything waits on one
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int kk = a_half * 32 + q * 8;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (m < M && k0 + kk < K) v = *reinterpret_cast<const uint4 *>(w + (size_t)m * K + k0 + kk);
-        *reinterpret_cast<uint4 *>(&As[a_row * LDB + kk]) = v;
+    for (int u = 0; u < NPF; ++u)
+      if (kc0 + u < nchunks) raw[u].load(xb, K, k, (kc0 + u) * BK + kq * CPT, n0 + 4 * g);
+    if (kc0 == 0) al = load_alpha(alpha, slots, alpha_out);
+    const Quant quant(al);
+#pragma unroll
+    for (int u = 0; u < NPF; ++u) {
+      if (kc0 + u >= nchunks) break;
+      const int k0 = (kc0 + u) * BK;
+      // weights of this chunk: As[row][kk] = w[m0 + row][k0 + kk], zero outside
+      uint4 wreg[APT];
+#pragma unroll
+      for (int q = 0; q < APT; ++q) {
+        const int kk = (a_half * (BK / 2)) + q * (16 / ESZ);  // element offset inside the chunk
+        wreg[q] = make_uint4(0, 0, 0, 0);
+        if (m0 + a_row < M && k0 + kk < K)
+          wreg[q] = *reinterpret_cast<const uint4 *>(wb + ((size_t)(m0 + a_row) * K + k0 + kk) * ESZ);
       }
-    }
-    // activation tile: 8 channels x 4 positions per thread, transposed into Bs
-    {
-      uint32_t dw[8];
-      load_patch<F32>(xb, K, k, k0 + kq * 8, n0 + 4 * g, al, dw);
+      // activations: quantise, transpose the CPT x 4 patch, store with the n rows permuted
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        uint4 v;
-        v.x = code_to_bf16(dw[0], i) | (code_to_bf16(dw[1], i) << 16);
-        v.y = code_to_bf16(dw[2], i) | (code_to_bf16(dw[3], i) << 16);
-        v.z = code_to_bf16(dw[4], i) | (code_to_bf16(dw[5], i) << 16);
-        v.w = code_to_bf16(dw[6], i) | (code_to_bf16(dw[7], i) << 16);
-        *reinterpret_cast<uint4 *>(&Bs[(i * 32 + g) * LDB + kq * 8]) = v;
-      }
-    }
-    __syncthreads();
-    const int fr = lane & 31, fk = (lane >> 5) * 8;
+        uint32_t pk[I8W ? (CPT / 4) : (CPT / 2)];
+        if constexpr (I8W) {
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const bf16x8 a = __builtin_bit_cast(
-          bf16x8, *reinterpret_cast<const uint4 *>(&As[(wv * 32 + fr) * LDB + ks * 16 + fk]));
+          for (int r = 0; r < CPT; r += 4) {
+            const uint32_t c0 = (uint32_t)(int)raw[u].level(r, i, quant) & 0xFFu;
+            const uint32_t c1 = (uint32_t)(int)raw[u].level(r + 1, i, quant) & 0xFFu;
+            const uint32_t c2 = (uint32_t)(int)raw[u].level(r + 2, i, quant) & 0xFFu;
+            const uint32_t c3 = (uint32_t)(int)raw[u].level(r + 3, i, quant) & 0xFFu;
+            pk[r / 4] = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+          }
+        } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bf16x8 bb = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const uint4 *>(&Bs[(i * 32 + fr) * LDB + ks * 16 + fk]));
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[i], 0, 0, 0);
+          for (int r = 0; r < CPT; r += 2) {
+            // an integer |v| <= 127 is exact in bf16: its bf16 pattern is the float's high half
+            const uint32_t lo = __float_as_uint(raw[u].level(r, i, quant));
+            const uint32_t hi = __float_as_uint(raw[u].level(r + 1, i, quant));
+            pk[r / 2] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+          }
+        }
+        unsigned char *dst = &Bs[(i * 32 + g) * LDR + kq * CPT * ESZ];
+        constexpr int words = I8W ? CPT / 4 : CPT / 2;
+        if constexpr (words == 4) *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        else if constexpr (words == 2) *reinterpret_cast<uint2 *>(dst) = make_uint2(pk[0], pk[1]);
+        else *reinterpret_cast<uint32_t *>(dst) = pk[0];
       }
+#pragma unroll
+      for (int q = 0; q < APT; ++q)
+        *reinterpret_cast<uint4 *>(&As[a_row * LDR + a_half * (BK / 2) * ESZ + q * 16]) = wreg[q];
+      __syncthreads();
+      const int fr = lane & 31, half = lane >> 5;
+      if constexpr (I8W) {
+#pragma unroll
+        for (int ks = 0; ks < BK / 32; ++ks) {
+          const intx4 a = __builtin_bit_cast(
+              intx4, *reinterpret_cast<const uint4 *>(&As[(wv * 32 + fr) * LDR + ks * 32 + half * 16]));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const intx4 bb = __builtin_bit_cast(
+                intx4, *reinterpret_cast<const uint4 *>(&Bs[(i * 32 + fr) * LDR + ks * 32 + half * 16]));
+            acci[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bb, acci[i], 0, 0, 0);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+          const bf16x8 a = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const uint4 *>(&As[(wv * 32 + fr) * LDR + (ks * 16 + half * 8) * 2]));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const bf16x8 bb = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const uint4 *>(&Bs[(i * 32 + fr) * LDR + (ks * 16 + half * 8) * 2]));
+            accf[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, accf[i], 0, 0, 0);
+          }
+        }
+      }
+      __syncthreads();
     }
-    __syncthreads();
   }
   // epilogue: acc[i][r] is row (r/4)*8 + (lane/32)*4 + r%4, column 4*(lane%32) + i
   const float sx = al / 127.f;
@@ -147,98 +193,31 @@ __global__ __launch_bounds__(256) void pointwise_bf16_kernel(const uint16_t *__r
   for (int r = 0; r < 16; ++r) {
     const int m = m0 + wv * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
     if (m < M) {
-      const float4 v = make_float4(acc[0][r] * sx, acc[1][r] * sx, acc[2][r] * sx, acc[3][r] * sx);
+      float4 v;
+      if constexpr (I8W) {
+        const float sc = sx * w_scale[m];
+        v = make_float4((float)acci[0][r] * sc, (float)acci[1][r] * sc, (float)acci[2][r] * sc,
+                        (float)acci[3][r] * sc);
+      } else {
+        v = make_float4(accf[0][r] * sx, accf[1][r] * sx, accf[2][r] * sx, accf[3][r] * sx);
+      }
       *reinterpret_cast<float4 *>(yc + ((size_t)b * M + m) * k + n) = v;
     }
   }
 }
 
-// ---- int8 x int8 -> int32 ------------------------------------------------------------------------
-constexpr int LDI = BK + 16;  // bytes per LDS row (80 bytes: 16-byte aligned, 20 banks)
-
-// byte `i` of four dwords -> one dword
-__device__ __forceinline__ uint32_t gather_byte(uint32_t d0, uint32_t d1, uint32_t d2, uint32_t d3, int i) {
-  const uint32_t sel = (uint32_t)i | ((uint32_t)(4 + i) << 8);
-  const uint32_t lo = __builtin_amdgcn_perm(d1, d0, sel);  // [d0.b_i, d1.b_i, -, -]
-  const uint32_t hi = __builtin_amdgcn_perm(d3, d2, sel);
-  return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-}
-
-// grid = (ceil(k/128), ceil(M/128), B); needs K % 16 == 0 and k % 4 == 0
-template <bool F32>
-__global__ __launch_bounds__(256) void pointwise_i8_kernel(const int8_t *__restrict__ w,
-                                                           const float *__restrict__ w_scale,
-                                                           const void *__restrict__ xq,
-                                                           const float *__restrict__ alpha,
-                                                           bool slots, float *alpha_out,
-                                                           float *__restrict__ yc, int M, int K,
-                                                           int64_t k) {
-  __shared__ __attribute__((aligned(16))) int8_t As[BM * LDI];
-  __shared__ __attribute__((aligned(16))) int8_t Bs[BN * LDI];
-  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
-  const int b = blockIdx.z, m0 = blockIdx.y * BM;
-  const int64_t n0 = (int64_t)blockIdx.x * BN;
-  const void *xb = static_cast<const char *>(xq) + (size_t)b * K * k * (F32 ? 4 : 1);
-  const float al = load_alpha(alpha, slots, alpha_out);
-
-  intx16 acc[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0;
-
-  const int a_row = t >> 1, a_half = t & 1;
-  const int g = t & 31, kq = t >> 5;
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    {
-      const int m = m0 + a_row;
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int kk = a_half * 32 + q * 16;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (m < M && k0 + kk < K) v = *reinterpret_cast<const uint4 *>(w + (size_t)m * K + k0 + kk);
-        *reinterpret_cast<uint4 *>(&As[a_row * LDI + kk]) = v;
-      }
-    }
-    {
-      uint32_t dw[8];
-      load_patch<F32>(xb, K, k, k0 + kq * 8, n0 + 4 * g, al, dw);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        uint2 v;
-        v.x = gather_byte(dw[0], dw[1], dw[2], dw[3], i);
-        v.y = gather_byte(dw[4], dw[5], dw[6], dw[7], i);
-        *reinterpret_cast<uint2 *>(&Bs[(i * 32 + g) * LDI + kq * 8]) = v;
-      }
-    }
-    __syncthreads();
-    const int fr = lane & 31, fk = (lane >> 5) * 16;
-#pragma unroll
-    for (int ks = 0; ks < BK / 32; ++ks) {
-      const intx4 a = __builtin_bit_cast(
-          intx4, *reinterpret_cast<const uint4 *>(&As[(wv * 32 + fr) * LDI + ks * 32 + fk]));
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const intx4 bb = __builtin_bit_cast(
-            intx4, *reinterpret_cast<const uint4 *>(&Bs[(i * 32 + fr) * LDI + ks * 32 + fk]));
-        acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bb, acc[i], 0, 0, 0);
-      }
-    }
-    __syncthreads();
-  }
-  const float sx = al / 127.f;
-  const int64_t n = n0 + 4 * (lane & 31);
-  if (n >= k) return;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int m = m0 + wv * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-    if (m < M) {
-      const float sc = sx * w_scale[m];
-      const float4 v = make_float4((float)acc[0][r] * sc, (float)acc[1][r] * sc,
-                                   (float)acc[2][r] * sc, (float)acc[3][r] * sc);
-      *reinterpret_cast<float4 *>(yc + ((size_t)b * M + m) * k + n) = v;
-    }
-  }
+template <int BM, bool I8W>
+hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
+                       const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
+                       float *yc, hipStream_t s) {
+  dim3 grid((unsigned)((k + BN - 1) / BN), (d.C_out + BM - 1) / BM, d.B), block(2 * BM);
+  if (f32)
+    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, true, I8W>), grid, block, 0, s, w, w_scale, xc, alpha,
+                       slots, alpha_out, yc, d.C_out, d.C_in, k);
+  else
+    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, false, I8W>), grid, block, 0, s, w, w_scale, xc,
+                       alpha, slots, alpha_out, yc, d.C_out, d.C_in, k);
+  return hipGetLastError();
 }
 
 // ---- plain fp32 FMA tile kernel (any storage types, any shape) ------------------------------------
@@ -275,6 +254,7 @@ __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restri
   const int64_t n0 = (int64_t)blockIdx.x * FT;
   float acc[4][4] = {};
   const float al = XM != 0 ? load_alpha(alpha, slots, alpha_out) : 0.f;
+  const Quant quant(al);
   for (int k0 = 0; k0 < K; k0 += FK) {
     // Ws[kk][mm] = w[m0 + mm][k0 + kk]
     for (int e = t; e < FT * FK; e += 256) {
@@ -289,7 +269,7 @@ __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restri
       if (k0 + kk < K && n0 + nn < k) {
         const size_t at = ((size_t)b * K + k0 + kk) * k + n0 + nn;
         if (XM == 1) v = (float)static_cast<const int8_t *>(xc)[at];
-        else if (XM == 2) v = (float)quant_code(static_cast<const float *>(xc)[at], al);
+        else if (XM == 2) v = quant.level(static_cast<const float *>(xc)[at]);
         else v = static_cast<const float *>(xc)[at];
       }
       Xs[kk][nn] = v;
@@ -350,24 +330,14 @@ hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const f
                             const void *xc, bool xc_is_f32, const float *alpha, bool slots,
                             float *alpha_out, float *yc, hipStream_t s) {
   const bool quant = d.act_quant_bits == 8;
-  const int M = d.C_out, K = d.C_in;
-  dim3 grid((unsigned)((k + BN - 1) / BN), (M + BM - 1) / BM, d.B);
-  if (quant && d.w_dtype == WCC_BF16 && K % 8 == 0 && k % 4 == 0) {
-    const uint16_t *wb = static_cast<const uint16_t *>(w);
-    if (xc_is_f32)
-      hipLaunchKernelGGL(pointwise_bf16_kernel<true>, grid, dim3(256), 0, s, wb, xc, alpha, slots, alpha_out, yc, M, K, k);
-    else
-      hipLaunchKernelGGL(pointwise_bf16_kernel<false>, grid, dim3(256), 0, s, wb, xc, alpha, slots, alpha_out, yc, M, K, k);
-    return hipGetLastError();
-  }
-  if (quant && d.w_dtype == WCC_I8 && K % 16 == 0 && k % 4 == 0) {
-    const int8_t *wi = static_cast<const int8_t *>(w);
-    if (xc_is_f32)
-      hipLaunchKernelGGL(pointwise_i8_kernel<true>, grid, dim3(256), 0, s, wi, w_scale, xc, alpha, slots, alpha_out, yc, M, K, k);
-    else
-      hipLaunchKernelGGL(pointwise_i8_kernel<false>, grid, dim3(256), 0, s, wi, w_scale, xc, alpha, slots, alpha_out, yc, M, K, k);
-    return hipGetLastError();
-  }
+  const int K = d.C_in;
+  const bool big = d.C_out > 128;  // all of C_out in one workgroup when it fits 256 rows
+  if (quant && d.w_dtype == WCC_BF16 && K % 8 == 0 && k % 4 == 0)
+    return big ? mfma_launch<256, false>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s)
+               : mfma_launch<128, false>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s);
+  if (quant && d.w_dtype == WCC_I8 && K % 16 == 0 && k % 4 == 0)
+    return big ? mfma_launch<256, true>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s)
+               : mfma_launch<128, true>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s);
   const int xm = !quant ? 0 : (xc_is_f32 ? 2 : 1);
   switch (d.w_dtype) {
     case WCC_F32: return fma_dispatch<WCC_F32>(d, k, w, w_scale, xc, xm, alpha, slots, alpha_out, yc, s);

@@ -74,13 +74,40 @@ __device__ __forceinline__ float alpha_from_slots(const float *__restrict__ slot
 }
 
 // The scale-clip-round of Eq. (quantweights), signed, b = 8, operation by operation in fp32:
-// u = v / alpha; clip to [-1, 1]; code = round_half_even(127 * u).  alpha <= 0 gives code 0.
-__device__ __forceinline__ int quant_code(float v, float alpha) {
-  if (!(alpha > 0.f)) return 0;
-  float u = __fdiv_rn(v, alpha);
-  u = fminf(fmaxf(u, -1.f), 1.f);
-  return (int)rintf(__fmul_rn(127.f, u));
-}
+// u = v / alpha (correctly rounded); clip to [-1, 1]; level = round_half_even(127 * u).
+// alpha <= 0 gives level 0.
+//
+// The division is the hot part (one per kept coefficient).  With y = RN(1/alpha) computed once,
+// q0 = v*y, r = fma(-q0, alpha, v), q = fma(r, y, q0) is the correctly rounded quotient
+// (Markstein's division theorem) unless alpha's significand is all ones; that case, and alpha
+// outside [2^-60, 2^60] (where r could underflow for a v that still matters), take the IEEE
+// divide.  Quotients too small to matter (|v| < alpha * 2^-9) round to level 0 either way.
+struct Quant {
+  float alpha, y;
+  bool on, fast;
+  __device__ __forceinline__ explicit Quant(float a) : alpha(a), y(0.f), on(a > 0.f), fast(false) {
+    if (on) {
+      y = __fdiv_rn(1.f, a);
+      const uint32_t bits = __float_as_uint(a);
+      fast = (bits & 0x7FFFFFu) != 0x7FFFFFu && a >= 0x1p-60f && a <= 0x1p60f;
+    }
+  }
+  // the code as a float holding an integer in [-127, 127]
+  __device__ __forceinline__ float level(float v) const {
+    if (!on) return 0.f;
+    float u;
+    if (fast) {
+      const float q0 = __fmul_rn(v, y);
+      const float r = __fmaf_rn(-q0, alpha, v);
+      u = __fmaf_rn(r, y, q0);
+    } else {
+      u = __fdiv_rn(v, alpha);
+    }
+    u = fminf(fmaxf(u, -1.f), 1.f);
+    return rintf(__fmul_rn(127.f, u));
+  }
+  __device__ __forceinline__ int code(float v) const { return (int)level(v); }
+};
 
 WsLayout ws_layout(const wcc_desc &d);
 int forward_groups(const wcc_desc &d);

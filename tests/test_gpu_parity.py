@@ -272,3 +272,29 @@ def test_error_paths_enqueue_nothing(ctx):
     torch.cuda.synchronize()
     assert torch.all(y == 3.0)
     fresh.close()
+
+
+@pytest.mark.parametrize("alpha_bits", [0x40490FDB, 0x3F7FFFFF, 0x41B4A3D7, 0x3A83126F, 0x7F000000, 0x00800000])
+def test_quantiser_codes_on_arbitrary_floats(ref, ctx, alpha_bits):
+    """Non-dyadic coefficients and clipping parameters (including a significand of all ones and
+    the ends of the exponent range): the codes must still be the oracle's, bit for bit."""
+    alpha = float(np.array([alpha_bits], dtype=np.uint32).view(np.float32)[0])
+    cfg = case("anyfloat", 1, 16, 16, 64, 64, 1, 1, 1, F32, 8)
+    d = desc_of(cfg)
+    ctx.ensure_workspace(d)
+    rng = np.random.default_rng(alpha_bits & 0xFFFF)
+    n = 16 * cfg.N
+    v = (rng.uniform(-1.2, 1.2, n) * alpha).astype(np.float32)
+    # values that sit next to code boundaries (j + 0.5) * alpha / 127
+    j = rng.integers(-127, 127, n // 4)
+    near = ((j + 0.5) * (np.float64(alpha) / 127.0)).astype(np.float32)
+    v[: n // 4] = np.nextafter(near, np.float32(np.inf) * rng.choice([-1, 1], n // 4).astype(np.float32))
+    v[n // 4: n // 2] = near
+    v = np.where(np.isfinite(v), v, np.float32(0)).astype(np.float32)
+    coef = v.reshape(1, 16, cfg.N)
+    idx = torch.arange(cfg.N, dtype=torch.int32, device="cuda")[None].contiguous()
+    xc = torch.zeros((1, 16, cfg.N), dtype=torch.int8, device="cuda")
+    a = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ctx.wcc_gather_quant(d, dev(coef), idx, alpha, xc, a)
+    assert float(a.item()) == alpha
+    np.testing.assert_array_equal(xc.cpu().numpy().astype(np.float64), ref.quant_codes(coef, alpha, 8))
