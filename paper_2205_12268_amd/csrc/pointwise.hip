@@ -72,14 +72,14 @@ struct Patch {
 
 // grid = (ceil(k/128), ceil(M/BM), B), block = 2*BM threads.  Needs k % 4 == 0 and
 // K % 8 == 0 (bf16 weights) or K % 16 == 0 (int8 weights).
-template <int BM, bool F32, bool I8W>
+// NPF: 64-channel chunks whose activation loads are issued together (1, 2 or 4).
+template <int BM, int NPF, bool F32, bool I8W>
 __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
     const void *__restrict__ w, const float *__restrict__ w_scale, const void *__restrict__ xq,
     const float *__restrict__ alpha, bool slots, float *alpha_out, float *__restrict__ yc, int M,
     int K, int64_t k) {
   constexpr int T = 2 * BM;
   constexpr int CPT = BK / (T / 32);         // channels of a chunk per thread: 8 or 4
-  constexpr int NPF = T == 512 ? 4 : 2;      // chunks loaded ahead (64 / 64 registers)
   constexpr int ESZ = I8W ? 1 : 2;           // bytes of an LDS element
   constexpr int LDR = I8W ? BK + 16 : (BK + 8) * 2;  // LDS row bytes: 80 / 144 (16-byte aligned,
                                                       // fragment reads free of bank conflicts)
@@ -206,18 +206,31 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   }
 }
 
-template <int BM, bool I8W>
+template <int BM, int NPF, bool I8W>
 hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
                        const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
                        float *yc, hipStream_t s) {
   dim3 grid((unsigned)((k + BN - 1) / BN), (d.C_out + BM - 1) / BM, d.B), block(2 * BM);
   if (f32)
-    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, true, I8W>), grid, block, 0, s, w, w_scale, xc, alpha,
-                       slots, alpha_out, yc, d.C_out, d.C_in, k);
+    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, NPF, true, I8W>), grid, block, 0, s, w, w_scale, xc,
+                       alpha, slots, alpha_out, yc, d.C_out, d.C_in, k);
   else
-    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, false, I8W>), grid, block, 0, s, w, w_scale, xc,
+    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, NPF, false, I8W>), grid, block, 0, s, w, w_scale, xc,
                        alpha, slots, alpha_out, yc, d.C_out, d.C_in, k);
   return hipGetLastError();
+}
+
+// BM = 256 when C_out needs it (every activation is then read once); the loads of up to four
+// chunks go out together when C_in is that deep and the registers allow it
+template <bool I8W>
+hipError_t mfma_dispatch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
+                         const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
+                         float *yc, hipStream_t s) {
+  const int nchunks = (d.C_in + BK - 1) / BK;
+  if (d.C_out <= 128) return mfma_launch<128, 1, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s);
+  if (nchunks >= 4) return mfma_launch<256, 4, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s);
+  if (nchunks >= 2) return mfma_launch<256, 2, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s);
+  return mfma_launch<256, 1, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s);
 }
 
 // ---- plain fp32 FMA tile kernel (any storage types, any shape) ------------------------------------
@@ -331,13 +344,10 @@ hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const f
                             float *alpha_out, float *yc, hipStream_t s) {
   const bool quant = d.act_quant_bits == 8;
   const int K = d.C_in;
-  const bool big = d.C_out > 128;  // all of C_out in one workgroup when it fits 256 rows
   if (quant && d.w_dtype == WCC_BF16 && K % 8 == 0 && k % 4 == 0)
-    return big ? mfma_launch<256, false>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s)
-               : mfma_launch<128, false>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s);
+    return mfma_dispatch<false>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s);
   if (quant && d.w_dtype == WCC_I8 && K % 16 == 0 && k % 4 == 0)
-    return big ? mfma_launch<256, true>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s)
-               : mfma_launch<128, true>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s);
+    return mfma_dispatch<true>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s);
   const int xm = !quant ? 0 : (xc_is_f32 ? 2 : 1);
   switch (d.w_dtype) {
     case WCC_F32: return fma_dispatch<WCC_F32>(d, k, w, w_scale, xc, xm, alpha, slots, alpha_out, yc, s);
