@@ -54,12 +54,51 @@ def read_traffic(profile_dir: str, workload: str, kernel: str):
     return None
 
 
+def bench_stack(args, synth, run_layer, ctx) -> int:
+    """The 16 point-wise layers of the backbone stack, one after the other (each on its own
+    synthetic input; the depthwise convolutions between them are not on the path)."""
+    num, den = (int(t) for t in args.keep.split("/"))
+    layers = synth.stack_layers(num, den, B=4)
+    per_layer, total_s, total_pix, total_alg = [], 0.0, 0, 0
+    worst = None
+    for cfg in layers:
+        dt, stage_us, _, _, _ = run_layer(cfg, ctx)
+        alg = algorithmic_bytes(cfg)
+        total_s += dt
+        total_pix += cfg.B * cfg.H * cfg.W * cfg.C_in
+        total_alg += sum(alg.values())
+        per_layer.append({"layer": cfg.name, "us": round(dt * 1e6, 2), "levels": cfg.levels,
+                          "stages_us": {n: round(v, 2) for n, v in stage_us.items()}})
+        dom = max(STAGE_KERNEL, key=lambda n: stage_us[n])
+        if worst is None or stage_us[dom] > worst[0]:
+            worst = (stage_us[dom], dom, alg[dom], cfg.name)
+    achieved = worst[2] / (worst[0] * 1e-6) / 1e9
+    out = {
+        "metric": "WCC layer forward throughput", "value": round(total_pix / total_s / 1e9, 3),
+        "unit": "Gpixel*ch/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(total_s * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"stack16_B4_keep{num}/{den}", "layers": len(layers), "act_bits": 8},
+        "roofline": {"bound": "hbm", "kernel": STAGE_KERNEL[worst[1]], "layer": worst[3],
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": worst[2], "kernel_us": round(worst[0], 2)},
+        "layer_alg_GBs": round(total_alg / total_s / 1e9, 1),
+        "per_layer": per_layer,
+    }
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="single-layer workload 1..4")
+    ap.add_argument("--config", type=int, default=2,
+                    help="single-layer workload 1..4, or 5 = the 16-layer backbone stack")
+    ap.add_argument("--keep", default="1/4", help="kept fraction for --config 5 (num/den)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="R",
                     help="also run R plain device-to-device copies of the input tensor (a copy "
@@ -80,49 +119,54 @@ def main() -> int:
         return 2
     wcc.lib()  # fails loudly if the HIP library is missing
 
-    cfg = synth.config(args.config)
-    x, w = synth.make_inputs(cfg)
-    d = wcc.make_desc(cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
-                      cfg.keep_den, cfg.w_dtype, cfg.act_bits)
-    ctx = wcc.Context(0)
-    ctx.ensure_workspace(d)
-    xd = torch.from_numpy(x).cuda()
-    stored = w.stored.view(np.int16) if w.stored.dtype == np.uint16 else w.stored
-    wd = torch.from_numpy(np.ascontiguousarray(stored)).cuda()
-    wsd = None if w.scale is None else torch.from_numpy(w.scale).cuda()
-    y = torch.empty((cfg.B, cfg.C_out, cfg.H, cfg.W), dtype=torch.float32, device="cuda")
+    def run_layer(cfg, ctx):
+        """Times args.steps forwards of one layer; returns (seconds per step, stage us, event pair us, x, w)."""
+        x, w = synth.make_inputs(cfg)
+        d = wcc.make_desc(cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
+                          cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+        ctx.ensure_workspace(d)
+        xd = torch.from_numpy(x).cuda()
+        stored = w.stored.view(np.int16) if w.stored.dtype == np.uint16 else w.stored
+        wd = torch.from_numpy(np.ascontiguousarray(stored)).cuda()
+        wsd = None if w.scale is None else torch.from_numpy(w.scale).cuda()
+        y = torch.empty((cfg.B, cfg.C_out, cfg.H, cfg.W), dtype=torch.float32, device="cuda")
 
-    def step():
-        ctx.wcc_forward(d, xd, wd, wsd, 0.0, y)
+        def step():
+            ctx.wcc_forward(d, xd, wd, wsd, 0.0, y)
 
-    if args.copy_probe:
-        probe = torch.empty_like(xd)
-        for _ in range(args.copy_probe):
-            probe.copy_(xd)  # reads and writes xd.numel() * 4 bytes
+        if args.copy_probe:
+            probe = torch.empty_like(xd)
+            for _ in range(args.copy_probe):
+                probe.copy_(xd)  # reads and writes xd.numel() * 4 bytes
+            torch.cuda.synchronize()
+            del probe
+        for _ in range(args.warmup):
+            step()
         torch.cuda.synchronize()
-        del probe
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        # per-stage device time: the same K steps again with the library's HIP events switched
+        # on (they bracket each stage on the stream the kernels run on)
+        ctx.set_profiling(True)
+        acc = {}
+        for _ in range(args.steps):
+            step()
+            for name, ms in ctx.stage_times().items():
+                acc[name] = acc.get(name, 0.0) + ms
+        ctx.set_profiling(False)
+        # an empty event bracket measures what the two records cost by themselves; take it off
+        pair_us = 1e3 * acc.pop("event_pair") / args.steps
+        stage_us = {n: max(1e3 * v / args.steps - pair_us, 0.0) for n, v in acc.items()}
+        return dt, stage_us, pair_us, x, w
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / args.steps
-
-    # per-stage device time: the same K steps again with the library's HIP events switched
-    # on (they bracket each stage on the stream the kernels run on)
-    ctx.set_profiling(True)
-    acc = {}
-    for _ in range(args.steps):
-        step()
-        for name, ms in ctx.stage_times().items():
-            acc[name] = acc.get(name, 0.0) + ms
-    ctx.set_profiling(False)
-    # an empty event bracket measures what the two records cost by themselves; take it off
-    pair_us = 1e3 * acc.pop("event_pair") / args.steps
-    stage_us = {n: max(1e3 * v / args.steps - pair_us, 0.0) for n, v in acc.items()}
+    ctx = wcc.Context(0)
+    if args.config == 5:
+        return bench_stack(args, synth, run_layer, ctx)
+    cfg = synth.config(args.config)
+    dt, stage_us, pair_us, x, w = run_layer(cfg, ctx)
 
     pix_ch = cfg.B * cfg.H * cfg.W * cfg.C_in
     value = pix_ch / dt / 1e9

@@ -111,12 +111,6 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
   }
 }
 
-__global__ __launch_bounds__(256) void copy_f32_kernel(const float *__restrict__ src,
-                                                       float *__restrict__ dst, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) dst[i] = src[i];
-}
-
 }  // namespace
 
 hipError_t launch_alpha_init(float *alpha_slots, float alpha_in, hipStream_t s) {
@@ -141,9 +135,5 @@ hipError_t launch_quantize(const float *xc32, int64_t n, const float *alpha_slot
   return hipGetLastError();
 }
 
-hipError_t launch_copy_f32(const float *src, float *dst, int64_t n, hipStream_t s) {
-  hipLaunchKernelGGL(copy_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, dst, n);
-  return hipGetLastError();
-}
 
 }  // namespace wcc

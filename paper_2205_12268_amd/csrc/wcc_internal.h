@@ -138,7 +138,6 @@ hipError_t launch_gather(const float *coef, const int32_t *idx, int B, int C, in
 // codes = q(xc32) with alpha = max(slots); also writes alpha to alpha_out[0]
 hipError_t launch_quantize(const float *xc32, int64_t n, const float *alpha_slots, float *alpha_out,
                            int8_t *codes, hipStream_t s);
-hipError_t launch_copy_f32(const float *src, float *dst, int64_t n, hipStream_t s);
 // xc_is_f32 with act_quant_bits = 8: xc holds the unquantised kept coefficients and the
 // kernel quantises them while loading (the fused path); otherwise xc is what the ABI says.
 // alpha_is_slots: alpha points at kAlphaSlots partial maxima (combined in the kernel, and
