@@ -102,8 +102,22 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) { accf[i][r] = 0.f; acci[i][r] = 0; }
 
+  // weights of chunk kc: wreg <- w[m0 + a_row][kc*64 + this thread's share], zero outside.
+  // They are fetched one chunk ahead (while the MFMAs of the previous chunk run).
+  uint4 wreg[APT];
+  auto load_w = [&](int kc) {
+#pragma unroll
+    for (int q = 0; q < APT; ++q) {
+      const int kk = kc * BK + (a_half * (BK / 2)) + q * (16 / ESZ);  // first element of the load
+      wreg[q] = make_uint4(0, 0, 0, 0);
+      if (m0 + a_row < M && kk < K)
+        wreg[q] = *reinterpret_cast<const uint4 *>(wb + ((size_t)(m0 + a_row) * K + kk) * ESZ);
+    }
+  };
+
   Patch<F32, CPT> raw[NPF];
   float al = 0.f;
+  load_w(0);
   for (int kc0 = 0; kc0 < nchunks; kc0 += NPF) {
     // every load of the next NPF chunks goes out before anything waits on one
 #pragma unroll
@@ -114,16 +128,6 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
 #pragma unroll
     for (int u = 0; u < NPF; ++u) {
       if (kc0 + u >= nchunks) break;
-      const int k0 = (kc0 + u) * BK;
-      // weights of this chunk: As[row][kk] = w[m0 + row][k0 + kk], zero outside
-      uint4 wreg[APT];
-#pragma unroll
-      for (int q = 0; q < APT; ++q) {
-        const int kk = (a_half * (BK / 2)) + q * (16 / ESZ);  // element offset inside the chunk
-        wreg[q] = make_uint4(0, 0, 0, 0);
-        if (m0 + a_row < M && k0 + kk < K)
-          wreg[q] = *reinterpret_cast<const uint4 *>(wb + ((size_t)(m0 + a_row) * K + k0 + kk) * ESZ);
-      }
       // activations: quantise, transpose the CPT x 4 patch, store with the n rows permuted
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -156,6 +160,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
       for (int q = 0; q < APT; ++q)
         *reinterpret_cast<uint4 *>(&As[a_row * LDR + a_half * (BK / 2) * ESZ + q * 16]) = wreg[q];
       __syncthreads();
+      if (kc0 + u + 1 < nchunks) load_w(kc0 + u + 1);
       const int fr = lane & 31, half = lane >> 5;
       if constexpr (I8W) {
 #pragma unroll
