@@ -52,7 +52,20 @@ __device__ __forceinline__ void hist_add(uint32_t *lh, uint32_t digit, bool vali
   if (valid) atomicAdd(&lh[digit], 1u);
 }
 
-// block-wide sum of v (all threads get it); `tmp` has kWaves entries
+// The same for a workgroup whose digits are spread out: one round, the class of the first
+// valid lane is counted by one atomic, every other lane adds for itself.
+__device__ __forceinline__ void hist_add_spread(uint32_t *lh, uint32_t digit, bool valid) {
+  if (valid) {
+    const uint32_t d0 = __builtin_amdgcn_readfirstlane(digit);
+    const uint64_t same = __ballot(digit == d0);
+    const int first = __ffsll((unsigned long long)same) - 1;
+    const uint32_t val = digit != d0 ? 1u : ((int)(threadIdx.x & 63) == first ? (uint32_t)__popcll(same) : 0u);
+    if (val) atomicAdd(&lh[digit], val);
+  }
+}
+
+// block-wide sum of v (all threads get it); `tmp` has NW (waves per workgroup) entries
+template <int NW = kWaves>
 __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *tmp) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -61,11 +74,12 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *tmp) {
   __syncthreads();
   uint32_t s = 0;
 #pragma unroll
-  for (int i = 0; i < kWaves; ++i) s += tmp[i];
+  for (int i = 0; i < NW; ++i) s += tmp[i];
   return s;
 }
 
-// block-wide exclusive scan in thread order; `tmp` has kWaves entries
+// block-wide exclusive scan in thread order; `tmp` has NW (waves per workgroup) entries
+template <int NW = kWaves>
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *tmp) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   uint32_t inc = v;
@@ -79,7 +93,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *t
   __syncthreads();
   uint32_t before = 0;
 #pragma unroll
-  for (int i = 0; i < kWaves; ++i)
+  for (int i = 0; i < NW; ++i)
     if (i < wv) before += tmp[i];
   return before + inc - v;
 }
@@ -95,7 +109,15 @@ __device__ __forceinline__ uint4 load_keys(const float *__restrict__ src, float 
                                            int G, int64_t BN, int64_t at) {
   float4 v = *reinterpret_cast<const float4 *>(src + at);
   if constexpr (REDUCE) {
-    for (int g = 1; g < G; ++g) {
+    int g = 1;
+    for (; g + 4 <= G; g += 4) {  // four loads in flight, added in increasing group order
+      float4 t[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) t[i] = *reinterpret_cast<const float4 *>(src + (int64_t)(g + i) * BN + at);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { v.x += t[i].x; v.y += t[i].y; v.z += t[i].z; v.w += t[i].w; }
+    }
+    for (; g < G; ++g) {
       const float4 t = *reinterpret_cast<const float4 *>(src + (int64_t)g * BN + at);
       v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
     }
@@ -108,11 +130,11 @@ __device__ __forceinline__ uint4 load_keys(const float *__restrict__ src, float 
 // Turns the finished histogram of pass P into the digit that holds the remaining rank:
 // the digit D with count(> D) < remain <= count(>= D), scanning from the top digit down.
 // Every thread returns the same (prefix, remain) for the next pass.
-template <int P>
+template <int P, int THREADS = kThreads>
 __device__ __forceinline__ void pick_digit(const uint32_t *gh, uint32_t &prefix,
                                            uint32_t &remain, uint32_t *tmp, uint32_t *bcast) {
   constexpr int bins = P == 2 ? 1024 : kRadixBins;
-  constexpr int per = bins / kThreads;  // consecutive digits per thread, from the top
+  constexpr int per = bins / THREADS;  // consecutive digits per thread, from the top
   const int t = threadIdx.x;
   uint32_t cnt[per], sum = 0;
 #pragma unroll
@@ -120,7 +142,7 @@ __device__ __forceinline__ void pick_digit(const uint32_t *gh, uint32_t &prefix,
     cnt[i] = gh[bins - 1 - (t * per + i)];
     sum += cnt[i];
   }
-  uint32_t above = block_exclusive_scan(sum, tmp);
+  uint32_t above = block_exclusive_scan<THREADS / 64>(sum, tmp);
 #pragma unroll
   for (int i = 0; i < per; ++i) {
     if (above < remain && remain <= above + cnt[i]) {
@@ -277,6 +299,181 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__re
   if (jmap) *reinterpret_cast<int4 *>(jmap + (size_t)b * N + q0) = make_int4(jm[0], jm[1], jm[2], jm[3]);
 }
 
+// ---- small planes: the whole select of one sample in ONE workgroup -------------------------
+// For N <= 16384 the four kernels above are launch gaps and little else.  Here one workgroup of
+// 1024 threads holds all keys of a sample in registers (slot s of thread t covers the four
+// positions from (s * 1024 + t) * 4 on: every load is one contiguous 16 KiB row), runs the
+// digit passes on an LDS histogram and emits idx and jmap in position order.  Same result,
+// bit for bit.
+//
+// With all keys in one place the digits need not be raw bit fields: the passes work on
+// rel = key - min(keys), whose significant bits (those of max - min) are cut into fields of at
+// most 11 bits from the top.  Norms of one plane share their upper exponent bits, so the raw
+// top field would put nearly all keys into a handful of bins and the LDS atomics of the 16
+// waves would serialise on them; the relative top field spreads them over the whole histogram.
+// Passes whose field is empty are skipped.
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallWaves = kSmallThreads / 64;
+constexpr int kSmallSlots = 4;  // 16-byte loads per thread at most (beyond that the one
+                                // workgroup is slower than the four spread-out kernels)
+constexpr int64_t kSmallMaxN = (int64_t)4 * kSmallSlots * kSmallThreads;
+
+// One pass over the field rel[hi-1 : lo] (hi - lo <= 11) of the keys that agree with `prefix`
+// above bit hi (FIRST: no bit is set above hi, all keys take part); then the digit that holds
+// the remaining rank is appended to prefix.
+template <bool FIRST>
+__device__ __forceinline__ void small_pass(const uint32_t (&rel)[4 * kSmallSlots], uint32_t vmask,
+                                           int slots, int hi, int lo, uint32_t &prefix,
+                                           uint32_t &remain, uint32_t *lh, uint32_t *tmp,
+                                           uint32_t *bcast) {
+  const int t = threadIdx.x;
+  const uint32_t fmask = (1u << (hi - lo)) - 1u;
+  for (int i = t; i < kRadixBins; i += kSmallThreads) lh[i] = 0;
+  if (t == 0) { bcast[0] = prefix; bcast[1] = remain; }  // rank beyond the data: unchanged
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < kSmallSlots; ++s) {
+    if (s < slots) {  // uniform over the workgroup
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t r = rel[4 * s + e];
+        bool agrees = true;
+        if constexpr (!FIRST) agrees = (r >> hi) == (prefix >> hi);
+        hist_add_spread(lh, (r >> lo) & fmask, ((vmask >> s) & 1u) && agrees);
+      }
+    }
+  }
+  __syncthreads();
+  // two consecutive digits per thread, from the top
+  uint32_t cnt[2], sum = 0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    cnt[i] = lh[kRadixBins - 1 - (t * 2 + i)];
+    sum += cnt[i];
+  }
+  uint32_t above = block_exclusive_scan<kSmallWaves>(sum, tmp);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    if (above < remain && remain <= above + cnt[i]) {
+      const uint32_t digit = kRadixBins - 1 - (t * 2 + i);
+      bcast[0] = prefix | (digit << lo);
+      bcast[1] = remain - above;
+    }
+    above += cnt[i];
+  }
+  __syncthreads();
+  prefix = bcast[0];
+  remain = bcast[1];
+  __syncthreads();
+}
+
+// grid = B, block = 1024.  REDUCE as in load_keys.
+template <bool REDUCE>
+__global__ __launch_bounds__(kSmallThreads) void select_small_kernel(
+    const float *__restrict__ src, float *__restrict__ norm, int G, int64_t N, int B, uint32_t k,
+    int slots, int32_t *__restrict__ idx, int32_t *__restrict__ jmap) {
+  __shared__ uint32_t lh[kRadixBins];
+  __shared__ uint32_t tmp[kSmallSlots * kSmallWaves];
+  __shared__ uint32_t bcast[2];
+  const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  uint32_t rel[4 * kSmallSlots];
+  uint32_t vmask = 0;  // bit s: slot s of this thread lies inside the plane (N is a multiple of 4)
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+#pragma unroll
+  for (int s = 0; s < kSmallSlots; ++s) {
+    const int64_t pos = ((int64_t)s * kSmallThreads + t) * 4;
+    uint4 k4 = make_uint4(0, 0, 0, 0);
+    if (s < slots && pos < N) {
+      k4 = load_keys<REDUCE>(src, norm, G, (int64_t)B * N, (int64_t)b * N + pos);
+      vmask |= 1u << s;
+      kmin = min(kmin, min(min(k4.x, k4.y), min(k4.z, k4.w)));
+      kmax = max(kmax, max(max(k4.x, k4.y), max(k4.z, k4.w)));
+    }
+    rel[4 * s] = k4.x; rel[4 * s + 1] = k4.y; rel[4 * s + 2] = k4.z; rel[4 * s + 3] = k4.w;
+  }
+  // smallest and largest key of the sample
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, 64));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, 64));
+  }
+  if (lane == 0) { tmp[wv] = kmin; tmp[kSmallWaves + wv] = kmax; }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kSmallWaves; ++i) {
+    kmin = min(kmin, tmp[i]);
+    kmax = max(kmax, tmp[kSmallWaves + i]);
+  }
+#pragma unroll
+  for (int i = 0; i < 4 * kSmallSlots; ++i) rel[i] -= kmin;  // slots outside the plane: unused
+  const int nbits = 32 - __clz((int)(kmax - kmin));  // 0 when all keys are equal (clz(0) = 32)
+
+  uint32_t T = 0, r_take = k;  // threshold (relative key) and how many keys equal to it to take
+  const int lo0 = max(nbits - 11, 0), lo1 = max(nbits - 22, 0);
+  small_pass<true>(rel, vmask, slots, nbits, lo0, T, r_take, lh, tmp, bcast);
+  if (lo0 > 0) small_pass<false>(rel, vmask, slots, lo0, lo1, T, r_take, lh, tmp, bcast);
+  if (lo1 > 0) small_pass<false>(rel, vmask, slots, lo1, 0, T, r_take, lh, tmp, bcast);
+
+  // Ordered compaction as in select_emit_kernel.  Position order is slot-major, then thread,
+  // then the four keys of a slot: a wave scan per slot, then a scan over the 64 (slot, wave)
+  // totals.  Counts (above T | equal to T) are packed 16 + 16 bits: N <= 16384.
+  uint32_t ex[kSmallSlots];
+#pragma unroll
+  for (int s = 0; s < kSmallSlots; ++s) {
+    uint32_t packed = 0;
+    if ((vmask >> s) & 1u) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) packed += ((rel[4 * s + e] > T) << 16) + (rel[4 * s + e] == T);
+    }
+    uint32_t inc = packed;
+    if (s < slots) {
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t n = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += n;
+      }
+    }
+    ex[s] = inc - packed;
+    if (lane == 63) tmp[s * kSmallWaves + wv] = inc;
+  }
+  __syncthreads();
+  static_assert(kSmallSlots * kSmallWaves == 64, "one wave scans the totals");
+  if (t < 64) {  // wave 0: exclusive scan of the 64 totals
+    const uint32_t v = tmp[t];
+    uint32_t inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t n = __shfl_up(inc, off, 64);
+      if (lane >= off) inc += n;
+    }
+    tmp[t] = inc - v;
+  }
+  __syncthreads();
+
+  int32_t *out = idx + (size_t)b * k;
+#pragma unroll
+  for (int s = 0; s < kSmallSlots; ++s) {
+    if ((vmask >> s) & 1u) {
+      const int e0 = s * kSmallWaves + wv;
+      const uint32_t before = tmp[e0] + ex[s];
+      uint32_t gt = before >> 16, eq = before & 0xFFFFu;
+      const int64_t pos = ((int64_t)s * kSmallThreads + t) * 4;
+      int32_t jm[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t ky = rel[4 * s + e];
+        const bool is_gt = ky > T, is_eq = ky == T;
+        const bool keep = is_gt || (is_eq && eq < r_take);
+        const uint32_t j = gt + min(eq, r_take);
+        if (keep) out[j] = (int32_t)(pos + e);
+        jm[e] = keep ? (int32_t)j : -1;
+        gt += is_gt; eq += is_eq;
+      }
+      if (jmap) *reinterpret_cast<int4 *>(jmap + (size_t)b * N + pos) = make_int4(jm[0], jm[1], jm[2], jm[3]);
+    }
+  }
+}
+
 // jmap from an arbitrary ascending index list: fill with -1, then jmap[b][idx[b][j]] = j
 __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t *p, int64_t n, int32_t v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -319,6 +516,16 @@ hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, fl
   uint32_t *gthi = reinterpret_cast<uint32_t *>(ws + L.block_gthi);
   const int nblk = L.nblk;
   const uint32_t k32 = (uint32_t)k;
+  if (N <= kSmallMaxN) {
+    const int slots = (int)((N + 4 * kSmallThreads - 1) / (4 * kSmallThreads));
+    if (G > 1)
+      hipLaunchKernelGGL((select_small_kernel<true>), dim3(d.B), dim3(kSmallThreads), 0, s,
+                         norm_or_part, norm_out, G, N, d.B, k32, slots, idx, jmap);
+    else
+      hipLaunchKernelGGL((select_small_kernel<false>), dim3(d.B), dim3(kSmallThreads), 0, s,
+                         norm_or_part, nullptr, 1, N, d.B, k32, slots, idx, jmap);
+    return hipGetLastError();
+  }
   dim3 grid(nblk, d.B), block(kThreads);
   const float *norm = norm_or_part;
   if (G > 1) {

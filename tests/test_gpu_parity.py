@@ -151,12 +151,14 @@ def test_perfect_reconstruction_with_identity_index_list(ref, ctx):
     assert torch.equal(y, xd)  # dyadic inputs: bit-exact
 
 
+# W = 200: a plane small enough for the one-workgroup select; W = 520: the multi-kernel one
+@pytest.mark.parametrize("W", [200, 520])
 @pytest.mark.parametrize("kind", ["constant", "zeros", "two_tie_classes"])
-def test_tie_heavy_selection(ref, ctx, kind):
-    B, N, k = 2, 3 * 4096 + 512, 5000
-    cfg = case("ties", B, 4, 4, 64, 200, 1, 1, 1, F32, 0)
-    assert cfg.N == 12800
-    d = wcc.make_desc(B, 4, 4, 64, 200, 1, k, cfg.N, wcc.F32, 0)
+def test_tie_heavy_selection(ref, ctx, kind, W):
+    B, k = 2, 5000
+    cfg = case("ties", B, 4, 4, 64, W, 1, 1, 1, F32, 0)
+    assert cfg.N == 64 * W
+    d = wcc.make_desc(B, 4, 4, 64, W, 1, k, cfg.N, wcc.F32, 0)
     assert wcc.k_of(d) == k
     ctx.ensure_workspace(d)
     rng = np.random.default_rng(77)
@@ -174,9 +176,10 @@ def test_tie_heavy_selection(ref, ctx, kind):
     np.testing.assert_array_equal(idx.cpu().numpy().astype(np.int64), ref.topk(norm, k))
 
 
-def test_random_norms_all_bit_patterns(ref, ctx):
+@pytest.mark.parametrize("W", [200, 520])
+def test_random_norms_all_bit_patterns(ref, ctx, W):
     """Keys that differ only in low mantissa bits, denormals and large values."""
-    B, H, W = 3, 64, 200
+    B, H = 3, 64
     N, k = H * W, 4321
     d = wcc.make_desc(B, 4, 4, H, W, 1, k, N, wcc.F32, 0)
     ctx.ensure_workspace(d)
