@@ -8,15 +8,20 @@
 //   int8 weights: v_mfma_i32_32x32x32_i8, exact int32 accumulation.
 // At the layer's shapes the contraction is bound by HBM (a few tens of flop per byte), so the
 // kernel is built around the activation stream: a workgroup owns BM = 128 or 256 output rows
-// (all of C_out when it fits, so every activation is read and quantised once) and 128
-// positions; each thread loads its share of up to 256 channels' worth of the [C_in x 128]
+// (all of C_out when it fits, so every activation is read and quantised once) and BN = 128
+// positions; each thread loads its share of up to 256 channels' worth of the [C_in x BN]
 // activation tile up front (one exposure to memory latency), quantises it in registers,
 // transposes 4(n) x CPT(c) patches into LDS, and the waves (wave w owns rows 32w..32w+31 and
-// all 128 columns) run the MFMAs 64 channels at a time.  The n rows are stored permuted
-// (row (n%4)*32 + n/4) so that MFMA column c of column block i is n = 4c + i: after the four
-// column blocks a lane holds four adjacent n of one output row and stores them as 16 bytes.
+// all BN columns) run the MFMAs 64 channels at a time.  The n rows are stored permuted
+// (row (n%NB)*32 + n/NB, NB = BN/32) so that MFMA column c of column block i is n = NB*c + i:
+// after the NB column blocks a lane holds NB adjacent n of one output row and stores them as
+// one 16- or 8-byte word.  Layers whose kept signal is short would leave most of the chip
+// idle with such tiles and turn the kernel into a chain of memory latencies; they take
+// smaller tiles (down to 64 x 64), re-reading the activations once per row tile from L2.
 // Everything else (fp32 weights, unquantised activations, odd shapes) takes a plain fp32 FMA
 // tile kernel on the weights widened to fp32.
+#include <type_traits>
+
 #include "wcc_internal.h"
 
 namespace wcc {
@@ -27,7 +32,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef __attribute__((__vector_size__(4 * sizeof(int)))) int intx4;
 typedef __attribute__((__vector_size__(16 * sizeof(int)))) int intx16;
 
-constexpr int BN = 128, BK = 64;
+constexpr int BK = 64;
 
 // The layer's alpha: one float, or the max of the gather's slots.  The first workgroup also
 // publishes it to alpha_out (nullable).  Called by every thread of the workgroup.
@@ -45,41 +50,45 @@ template <bool F32, int CPT>
 struct Patch {
   float4 f[F32 ? CPT : 1];
   uint32_t c[F32 ? 1 : CPT];
-  __device__ __forceinline__ void load(const void *__restrict__ xb, int K, int64_t k, int c0,
-                                       int64_t n) {
+  // xp: this thread's position in channel c0 (an element pointer); n_in: the position exists
+  __device__ __forceinline__ void load(const void *__restrict__ xp, int K, int64_t k, int c0,
+                                       bool n_in) {
 #pragma unroll
     for (int r = 0; r < CPT; ++r) {
-      const bool in = c0 + r < K && n < k;
+      const bool in = n_in && c0 + r < K;
       if constexpr (F32) {
         f[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (in) f[r] = *reinterpret_cast<const float4 *>(static_cast<const float *>(xb) + (size_t)(c0 + r) * k + n);
+        if (in) f[r] = *reinterpret_cast<const float4 *>(static_cast<const float *>(xp) + r * k);
       } else {
         c[r] = 0;
-        if (in) c[r] = *reinterpret_cast<const uint32_t *>(static_cast<const int8_t *>(xb) + (size_t)(c0 + r) * k + n);
+        if (in) c[r] = *reinterpret_cast<const uint32_t *>(static_cast<const int8_t *>(xp) + r * k);
       }
     }
   }
   // level of channel r, position i, as a float holding an integer in [-127, 127]
+  template <bool FAST>
   __device__ __forceinline__ float level(int r, int i, const Quant &q) const {
     if constexpr (F32) {
       const float v = i == 0 ? f[r].x : i == 1 ? f[r].y : i == 2 ? f[r].z : f[r].w;
-      return q.level(v);
+      return q.template level_as<FAST>(v);
     } else {
       return (float)((int)(c[r] << (24 - 8 * i)) >> 24);
     }
   }
 };
 
-// grid = (ceil(k/128), ceil(M/BM), B), block = 2*BM threads.  Needs k % 4 == 0 and
+// grid = (ceil(k/BN), ceil(M/BM), B), block = 2*BM threads.  Needs k % 4 == 0 and
 // K % 8 == 0 (bf16 weights) or K % 16 == 0 (int8 weights).
 // NPF: 64-channel chunks whose activation loads are issued together (1, 2 or 4).
-template <int BM, int NPF, bool F32, bool I8W>
+template <int BM, int BN, int NPF, bool F32, bool I8W>
 __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
     const void *__restrict__ w, const float *__restrict__ w_scale, const void *__restrict__ xq,
     const float *__restrict__ alpha, bool slots, float *alpha_out, float *__restrict__ yc, int M,
     int K, int64_t k) {
   constexpr int T = 2 * BM;
-  constexpr int CPT = BK / (T / 32);         // channels of a chunk per thread: 8 or 4
+  constexpr int NB = BN / 32;                // 32-column blocks of the tile: 4 or 2
+  constexpr int NG = BN / 4;                 // groups of four positions
+  constexpr int CPT = BK / (T / NG);         // channels of a chunk per thread: 4, 8 or 16
   constexpr int ESZ = I8W ? 1 : 2;           // bytes of an LDS element
   constexpr int LDR = I8W ? BK + 16 : (BK + 8) * 2;  // LDS row bytes: 80 / 144 (16-byte aligned,
                                                       // fragment reads free of bank conflicts)
@@ -92,13 +101,13 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   const void *xb = static_cast<const char *>(xq) + (size_t)b * K * k * (F32 ? 4 : 1);
   const unsigned char *wb = static_cast<const unsigned char *>(w);
   const int a_row = t >> 1, a_half = t & 1;  // weight loader: row, which half of the chunk
-  const int g = t & 31, kq = t >> 5;         // activation loader: n group (4 n), channel group
+  const int g = t % NG, kq = t / NG;         // activation loader: n group (4 n), channel group
   const int nchunks = (K + BK - 1) / BK;
 
-  floatx16 accf[4];
-  intx16 acci[4];
+  floatx16 accf[NB];
+  intx16 acci[NB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < NB; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { accf[i][r] = 0.f; acci[i][r] = 0; }
 
@@ -116,46 +125,60 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   };
 
   Patch<F32, CPT> raw[NPF];
+  // activations: quantise, transpose the CPT x 4 patch, store with the n rows permuted
+  auto stage_patch = [&](const Patch<F32, CPT> &pt, const Quant &quant, auto fast_c) {
+    constexpr bool FAST = decltype(fast_c)::value;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t pk[I8W ? (CPT / 4) : (CPT / 2)];
+      if constexpr (I8W) {
+#pragma unroll
+        for (int r = 0; r < CPT; r += 4) {
+          const uint32_t c0 = (uint32_t)(int)pt.template level<FAST>(r, i, quant) & 0xFFu;
+          const uint32_t c1 = (uint32_t)(int)pt.template level<FAST>(r + 1, i, quant) & 0xFFu;
+          const uint32_t c2 = (uint32_t)(int)pt.template level<FAST>(r + 2, i, quant) & 0xFFu;
+          const uint32_t c3 = (uint32_t)(int)pt.template level<FAST>(r + 3, i, quant) & 0xFFu;
+          pk[r / 4] = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < CPT; r += 2) {
+          // an integer |v| <= 127 is exact in bf16: its bf16 pattern is the float's high half
+          const uint32_t lo = __float_as_uint(pt.template level<FAST>(r, i, quant));
+          const uint32_t hi = __float_as_uint(pt.template level<FAST>(r + 1, i, quant));
+          pk[r / 2] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+        }
+      }
+      const int nl = 4 * g + i;  // position inside the tile
+      unsigned char *dst = &Bs[((nl % NB) * 32 + nl / NB) * LDR + kq * CPT * ESZ];
+      constexpr int words = I8W ? CPT / 4 : CPT / 2;
+      if constexpr (words == 8) {
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        *reinterpret_cast<uint4 *>(dst + 16) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+      } else if constexpr (words == 4) *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+      else if constexpr (words == 2) *reinterpret_cast<uint2 *>(dst) = make_uint2(pk[0], pk[1]);
+      else *reinterpret_cast<uint32_t *>(dst) = pk[0];
+    }
+  };
+
+  // this thread's four positions in channel kq * CPT of chunk 0
+  const bool n_in = n0 + 4 * g < k;
+  const char *xp = static_cast<const char *>(xb) + ((size_t)(kq * CPT) * k + n0 + 4 * g) * (F32 ? 4 : 1);
   float al = 0.f;
   load_w(0);
   for (int kc0 = 0; kc0 < nchunks; kc0 += NPF) {
     // every load of the next NPF chunks goes out before anything waits on one
 #pragma unroll
     for (int u = 0; u < NPF; ++u)
-      if (kc0 + u < nchunks) raw[u].load(xb, K, k, (kc0 + u) * BK + kq * CPT, n0 + 4 * g);
+      if (kc0 + u < nchunks)
+        raw[u].load(xp + (size_t)(kc0 + u) * BK * k * (F32 ? 4 : 1), K, k, (kc0 + u) * BK + kq * CPT, n_in);
     if (kc0 == 0) al = load_alpha(alpha, slots, alpha_out);
     const Quant quant(al);
 #pragma unroll
     for (int u = 0; u < NPF; ++u) {
       if (kc0 + u >= nchunks) break;
-      // activations: quantise, transpose the CPT x 4 patch, store with the n rows permuted
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        uint32_t pk[I8W ? (CPT / 4) : (CPT / 2)];
-        if constexpr (I8W) {
-#pragma unroll
-          for (int r = 0; r < CPT; r += 4) {
-            const uint32_t c0 = (uint32_t)(int)raw[u].level(r, i, quant) & 0xFFu;
-            const uint32_t c1 = (uint32_t)(int)raw[u].level(r + 1, i, quant) & 0xFFu;
-            const uint32_t c2 = (uint32_t)(int)raw[u].level(r + 2, i, quant) & 0xFFu;
-            const uint32_t c3 = (uint32_t)(int)raw[u].level(r + 3, i, quant) & 0xFFu;
-            pk[r / 4] = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
-          }
-        } else {
-#pragma unroll
-          for (int r = 0; r < CPT; r += 2) {
-            // an integer |v| <= 127 is exact in bf16: its bf16 pattern is the float's high half
-            const uint32_t lo = __float_as_uint(raw[u].level(r, i, quant));
-            const uint32_t hi = __float_as_uint(raw[u].level(r + 1, i, quant));
-            pk[r / 2] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
-          }
-        }
-        unsigned char *dst = &Bs[(i * 32 + g) * LDR + kq * CPT * ESZ];
-        constexpr int words = I8W ? CPT / 4 : CPT / 2;
-        if constexpr (words == 4) *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        else if constexpr (words == 2) *reinterpret_cast<uint2 *>(dst) = make_uint2(pk[0], pk[1]);
-        else *reinterpret_cast<uint32_t *>(dst) = pk[0];
-      }
+      if (quant.fast) stage_patch(raw[u], quant, std::true_type{});
+      else stage_patch(raw[u], quant, std::false_type{});
 #pragma unroll
       for (int q = 0; q < APT; ++q)
         *reinterpret_cast<uint4 *>(&As[a_row * LDR + a_half * (BK / 2) * ESZ + q * 16]) = wreg[q];
@@ -168,7 +191,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
           const intx4 a = __builtin_bit_cast(
               intx4, *reinterpret_cast<const uint4 *>(&As[(wv * 32 + fr) * LDR + ks * 32 + half * 16]));
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
+          for (int i = 0; i < NB; ++i) {
             const intx4 bb = __builtin_bit_cast(
                 intx4, *reinterpret_cast<const uint4 *>(&Bs[(i * 32 + fr) * LDR + ks * 32 + half * 16]));
             acci[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bb, acci[i], 0, 0, 0);
@@ -180,7 +203,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
           const bf16x8 a = __builtin_bit_cast(
               bf16x8, *reinterpret_cast<const uint4 *>(&As[(wv * 32 + fr) * LDR + (ks * 16 + half * 8) * 2]));
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
+          for (int i = 0; i < NB; ++i) {
             const bf16x8 bb = __builtin_bit_cast(
                 bf16x8, *reinterpret_cast<const uint4 *>(&Bs[(i * 32 + fr) * LDR + (ks * 16 + half * 8) * 2]));
             accf[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, accf[i], 0, 0, 0);
@@ -190,52 +213,67 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
       __syncthreads();
     }
   }
-  // epilogue: acc[i][r] is row (r/4)*8 + (lane/32)*4 + r%4, column 4*(lane%32) + i
+  // epilogue: acc[i][r] is row (r/4)*8 + (lane/32)*4 + r%4, column NB*(lane%32) + i
   const float sx = al / 127.f;
-  const int64_t n = n0 + 4 * (lane & 31);
-  if (n >= k) return;
+  const int64_t n = n0 + NB * (lane & 31);
+  if (n >= k) return;  // k % 4 == 0: a lane's NB positions are all inside or all outside
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int m = m0 + wv * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
     if (m < M) {
-      float4 v;
-      if constexpr (I8W) {
-        const float sc = sx * w_scale[m];
-        v = make_float4((float)acci[0][r] * sc, (float)acci[1][r] * sc, (float)acci[2][r] * sc,
-                        (float)acci[3][r] * sc);
-      } else {
-        v = make_float4(accf[0][r] * sx, accf[1][r] * sx, accf[2][r] * sx, accf[3][r] * sx);
-      }
-      *reinterpret_cast<float4 *>(yc + ((size_t)b * M + m) * k + n) = v;
+      float v[NB];
+      const float sc = I8W ? sx * w_scale[m] : sx;
+#pragma unroll
+      for (int i = 0; i < NB; ++i) v[i] = I8W ? (float)acci[i][r] * sc : accf[i][r] * sc;
+      float *dst = yc + ((size_t)b * M + m) * k + n;
+      if constexpr (NB == 4) *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+      else *reinterpret_cast<float2 *>(dst) = make_float2(v[0], v[1]);
     }
   }
 }
 
-template <int BM, int NPF, bool I8W>
+template <int BM, int BN, int NPF, bool I8W>
 hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
                        const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
                        float *yc, hipStream_t s) {
   dim3 grid((unsigned)((k + BN - 1) / BN), (d.C_out + BM - 1) / BM, d.B), block(2 * BM);
   if (f32)
-    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, NPF, true, I8W>), grid, block, 0, s, w, w_scale, xc,
-                       alpha, slots, alpha_out, yc, d.C_out, d.C_in, k);
+    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, NPF, true, I8W>), grid, block, 0, s, w, w_scale,
+                       xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k);
   else
-    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, NPF, false, I8W>), grid, block, 0, s, w, w_scale, xc,
-                       alpha, slots, alpha_out, yc, d.C_out, d.C_in, k);
+    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, NPF, false, I8W>), grid, block, 0, s, w, w_scale,
+                       xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k);
   return hipGetLastError();
 }
 
-// BM = 256 when C_out needs it (every activation is then read once); the loads of up to four
-// chunks go out together when C_in is that deep and the registers allow it
+// Tile choice.  Large tiles first (BM = 256 when C_out needs it: every activation is then read
+// once), as long as they give every compute unit a workgroup; otherwise smaller ones.  The
+// loads of up to four chunks go out together when C_in is that deep and the registers allow.
 template <bool I8W>
 hipError_t mfma_dispatch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
                          const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
                          float *yc, hipStream_t s) {
+#define WCC_MFMA(BM_, BN_, NPF_) \
+  return mfma_launch<BM_, BN_, NPF_, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s)
   const int nchunks = (d.C_in + BK - 1) / BK;
-  if (d.C_out <= 128) return mfma_launch<128, 1, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s);
-  if (nchunks >= 4) return mfma_launch<256, 4, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s);
-  if (nchunks >= 2) return mfma_launch<256, 2, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s);
-  return mfma_launch<256, 1, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s);
+  const int64_t want = 256;  // compute units
+  auto wgs = [&](int bm, int bn) {
+    return ((k + bn - 1) / bn) * ((d.C_out + bm - 1) / bm) * (int64_t)d.B;
+  };
+  if (d.C_out > 128 && wgs(256, 128) >= want) {
+    if (nchunks >= 4) WCC_MFMA(256, 128, 4);
+    if (nchunks >= 2) WCC_MFMA(256, 128, 2);
+    WCC_MFMA(256, 128, 1);
+  }
+  if (d.C_out <= 128 && wgs(128, 128) >= want) WCC_MFMA(128, 128, 1);
+  if (d.C_out > 64 && wgs(128, 64) >= want) {
+    if (nchunks >= 4) WCC_MFMA(128, 64, 4);
+    if (nchunks >= 2) WCC_MFMA(128, 64, 2);
+    WCC_MFMA(128, 64, 1);
+  }
+  if (nchunks >= 2) WCC_MFMA(64, 64, 2);
+  WCC_MFMA(64, 64, 1);
+#undef WCC_MFMA
 }
 
 // ---- plain fp32 FMA tile kernel (any storage types, any shape) ------------------------------------

@@ -85,26 +85,35 @@ __device__ __forceinline__ float alpha_from_slots(const float *__restrict__ slot
 struct Quant {
   float alpha, y;
   bool on, fast;
-  __device__ __forceinline__ explicit Quant(float a) : alpha(a), y(0.f), on(a > 0.f), fast(false) {
+  // alpha is the same in every lane; reading it into a scalar register lets the compiler see
+  // that (otherwise each level() becomes a divergent branch)
+  __device__ __forceinline__ explicit Quant(float a)
+      : alpha(__uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(a)))), y(0.f) {
+    on = alpha > 0.f;
+    fast = false;
     if (on) {
-      y = __fdiv_rn(1.f, a);
-      const uint32_t bits = __float_as_uint(a);
-      fast = (bits & 0x7FFFFFu) != 0x7FFFFFu && a >= 0x1p-60f && a <= 0x1p60f;
+      y = __fdiv_rn(1.f, alpha);
+      const uint32_t bits = __float_as_uint(alpha);
+      fast = (bits & 0x7FFFFFu) != 0x7FFFFFu && alpha >= 0x1p-60f && alpha <= 0x1p60f;
     }
   }
-  // the code as a float holding an integer in [-127, 127]
-  __device__ __forceinline__ float level(float v) const {
-    if (!on) return 0.f;
+  // the code as a float holding an integer in [-127, 127]; FAST: the caller has checked `fast`
+  template <bool FAST>
+  __device__ __forceinline__ float level_as(float v) const {
     float u;
-    if (fast) {
+    if constexpr (FAST) {
       const float q0 = __fmul_rn(v, y);
       const float r = __fmaf_rn(-q0, alpha, v);
       u = __fmaf_rn(r, y, q0);
     } else {
+      if (!on) return 0.f;
       u = __fdiv_rn(v, alpha);
     }
     u = fminf(fmaxf(u, -1.f), 1.f);
     return rintf(__fmul_rn(127.f, u));
+  }
+  __device__ __forceinline__ float level(float v) const {
+    return fast ? level_as<true>(v) : level_as<false>(v);
   }
   __device__ __forceinline__ int code(float v) const { return (int)level(v); }
 };
