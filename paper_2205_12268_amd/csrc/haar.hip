@@ -181,6 +181,11 @@ __device__ __forceinline__ bool locate(const StripMap &m, const Geo &g, int unit
 
 // Walks n_ch channel planes (stride N floats) of one strip: loads run PF channels ahead of the
 // arithmetic, in a ring of PF + 1 register tiles.  after(sink) runs once per channel.
+// Inside the main loop every step issues its prefetch and there is no branch: the number of
+// outstanding loads must be the same on every path, or the wait in front of the arithmetic
+// has to drain the prefetch as well (the counter is in order).  A prefetch past the last
+// channel reads the last channel again (a cache hit); the at most PF channels left after the
+// main loop are already in registers.
 template <int D, int V, int PF, class Sink, class After>
 __device__ __forceinline__ void channel_loop(const float *__restrict__ src, int64_t N, int W,
                                              int n_ch, const LanePos<D> &p, Sink &sink,
@@ -188,23 +193,28 @@ __device__ __forceinline__ void channel_loop(const float *__restrict__ src, int6
   constexpr int R = 1 << D;
   float buf[PF + 1][R][V];
 #pragma unroll
-  for (int u = 0; u < PF; ++u)
-    if (u < n_ch) {
+  for (int u = 0; u < PF; ++u) {
+    const float *nx = src + (size_t)min(u, n_ch - 1) * N;
 #pragma unroll
-      for (int r = 0; r < R; ++r) load_row<V>(src + (size_t)u * N + (size_t)r * W, buf[u][r]);
-    }
-  for (int c = 0; c < n_ch; c += PF + 1) {
+    for (int r = 0; r < R; ++r) load_row<V>(nx + (size_t)r * W, buf[u][r]);
+  }
+  int c = 0;
+  for (; c + PF < n_ch; c += PF + 1) {
 #pragma unroll
     for (int u = 0; u <= PF; ++u) {
-      if (c + u < n_ch) {
-        if (c + u + PF < n_ch) {
-          const float *nx = src + (size_t)(c + u + PF) * N;
+      const float *nx = src + (size_t)min(c + u + PF, n_ch - 1) * N;
 #pragma unroll
-          for (int r = 0; r < R; ++r) load_row<V>(nx + (size_t)r * W, buf[(u + PF) % (PF + 1)][r]);
-        }
-        fwd_levels<D, V, 1>(buf[u], p, sink);
-        after(sink);
-      }
+      for (int r = 0; r < R; ++r) load_row<V>(nx + (size_t)r * W, buf[(u + PF) % (PF + 1)][r]);
+      __builtin_amdgcn_sched_barrier(0);  // the loads go out before the arithmetic, not after
+      fwd_levels<D, V, 1>(buf[u], p, sink);
+      after(sink);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < PF; ++u) {
+    if (c + u < n_ch) {
+      fwd_levels<D, V, 1>(buf[u], p, sink);
+      after(sink);
     }
   }
 }
@@ -547,16 +557,27 @@ __global__ __launch_bounds__(256) void channel_norm_kernel(const float *__restri
   reinterpret_cast<float4 *>(norm + (size_t)b * N)[i4] = s;
 }
 
+// A wave covers (64 / lpr) strips x (lpr lanes of V columns).  lpr is the power of two that
+// leaves the fewest lanes idle (ties: the wider one, for longer contiguous row segments);
+// rows narrower than 16 lanes are not split further.
 StripMap make_map(const wcc_desc &d, int V) {
   StripMap m;
   m.lanes_w = d.W / V;
-  int lpr = 1, lg = 0;
-  while (lpr < m.lanes_w && lpr < kWave) { lpr *= 2; ++lg; }
-  m.lpr = lpr;
-  m.log_lpr = lg;
-  m.col_segs = (m.lanes_w + lpr - 1) / lpr;
   m.strips = d.H >> d.levels;
-  const int spw = kWave / lpr;
+  int top = 1, lg_top = 0;
+  while (top < m.lanes_w && top < kWave) { top *= 2; ++lg_top; }
+  int best = top, best_lg = lg_top;
+  int64_t best_units = 0;
+  for (int lpr = top, lg = lg_top; lpr >= 16 || lpr == top; lpr /= 2, --lg) {
+    const int spw = kWave / lpr;
+    const int64_t units = (int64_t)((m.strips + spw - 1) / spw) * ((m.lanes_w + lpr - 1) / lpr);
+    if (best_units == 0 || units < best_units) { best = lpr; best_lg = lg; best_units = units; }
+    if (lpr == 1) break;
+  }
+  m.lpr = best;
+  m.log_lpr = best_lg;
+  m.col_segs = (m.lanes_w + best - 1) / best;
+  const int spw = kWave / best;
   m.units = ((m.strips + spw - 1) / spw) * m.col_segs;
   return m;
 }
