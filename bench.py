@@ -77,7 +77,7 @@ def bench_stack(args, synth, run_layer, ctx) -> int:
         "metric": "WCC layer forward throughput", "value": round(total_pix / total_s / 1e9, 3),
         "unit": "Gpixel*ch/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(total_s * 1e3, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": args.launch,
         "config": {"workload": f"stack16_B4_keep{num}/{den}", "layers": len(layers), "act_bits": 8},
         "roofline": {"bound": "hbm", "kernel": STAGE_KERNEL[worst[1]], "layer": worst[3],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -100,6 +100,8 @@ def main() -> int:
                     help="single-layer workload 1..4, or 5 = the 16-layer backbone stack")
     ap.add_argument("--keep", default="1/4", help="kept fraction for --config 5 (num/den)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
+                    help="graph: the step is recorded once into a HIP graph and replayed")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="R",
                     help="also run R plain device-to-device copies of the input tensor (a copy "
                          "kernel of known size, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -143,9 +145,23 @@ def main() -> int:
         for _ in range(args.warmup):
             step()
         torch.cuda.synchronize()
+        timed = step
+        if args.launch == "graph":
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+            timed = graph.replay
+            for _ in range(args.warmup):
+                timed()
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            step()
+            timed()
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / args.steps
         # per-stage device time: the same K steps again with the library's HIP events switched
@@ -187,6 +203,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": {0: "f32", 1: "bf16", 2: "int8"}[cfg.w_dtype],
         "data": "synthetic",
+        "launch": args.launch,
         "config": {"workload": cfg.name, "B": cfg.B, "C_in": cfg.C_in, "C_out": cfg.C_out,
                    "H": cfg.H, "W": cfg.W, "levels": cfg.levels,
                    "keep": f"{cfg.keep_num}/{cfg.keep_den}", "act_bits": cfg.act_bits},
