@@ -369,7 +369,6 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict_
         int j = -1;
         if (active && owner) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
         sink.jj[s] = j;
-        if (__ballot(j >= 0) != 0) sink.any[s >> 6] |= (uint64_t)1 << (s & 63);
       }
   };
   auto each_level = [&](auto Lc) {
@@ -383,6 +382,10 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict_
   if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
   if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
   if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+  // (all map loads are in flight before the first vote waits for one)
+#pragma unroll
+  for (int s = 0; s < slot_count(D, V); ++s)
+    if (__ballot(sink.jj[s] >= 0) != 0) sink.any[s >> 6] |= (uint64_t)1 << (s & 63);
 
   if (active && c0 < c1) {
     const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
@@ -407,11 +410,52 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict_
 }
 
 // ---- synthesis with zero filling ------------------------------------------------------------
-// jj[slot] = rank j of the position inside the kept list, or -1 (dropped -> coefficient 0).
+// On this chip loads and stores retire through one in-order counter: a load issued after a
+// store cannot be waited for without waiting for the store.  A wave that alternates "fetch the
+// kept values of channel c, rebuild, store" therefore pays a full store round trip per channel.
+// The kernel below issues the fetches of channel c + 1 BEFORE the stores of channel c, with
+// the same number of memory instructions on every path (no branch around a load or a store),
+// so that waiting for them only needs the stores of channel c - 1 to have retired.
+//
+// To make that cheap the kept positions of a strip -- the same for every channel, and few --
+// are packed once per wave into a list (rank j, cell), slot by slot and lane by lane, held in
+// registers, 64 entries a row.  Per channel the wave fetches yc[.., j] for the whole list with
+// a few dense loads (neighbouring entries have mostly neighbouring j), drops the values into an
+// LDS tile laid out [slot][lane] whose other cells stay zero, and every lane reads its slots
+// back from there.  Lanes outside the plane take part in the list work and send their stores
+// to a scratch line.  Strips that keep more than kInvCap positions, layers with more than 2^20
+// kept positions, and d = 4 (whose tile would not fit) take the plain path: ranks re-read from
+// the map, one conditional load per slot.
+constexpr int kInvCap = 1024;          // packed entries per wave
+constexpr uint32_t kInvNone = ~0u;     // list padding
+constexpr int kInvRankBits = 20;       // entry = rank | cell << 20
+
+// Plain path: the rank of every position is read from the map again for every channel.
 template <int D, int V>
-struct InvSource {
-  const float *plane;  // yc[b, o, :]
-  int jj[slot_count(D, V)];
+struct InvReload {
+  const float *plane;   // yc[b, o, :]
+  const int32_t *jm;    // jmap[b, :]
+  const LanePos<D> *p;
+  bool active;
+  template <int L, int J>
+  __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
+    constexpr int CV = cols_at(V, L);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) {
+      float t = 0.f;
+      if (active) {
+        const int j = jm[J * p->nl[L] + p->off[L] + i * p->rowlen[L] + e];
+        if (j >= 0) t = plane[j];
+      }
+      v[e] = t;
+    }
+  }
+};
+
+// Staged: the lane's cell of the [slot][lane] LDS tile (zero unless the position is kept).
+template <int D, int V>
+struct InvStaged {
+  const float *cell;   // &tile[0][lane]
   uint64_t any[2];     // wave-uniform: bit s set if some lane keeps slot s
   template <int L, int J>
   __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
@@ -420,12 +464,7 @@ struct InvSource {
 #pragma unroll
     for (int e = 0; e < CV; ++e) {
       const int s = base + i * CV + e;
-      float t = 0.f;
-      if ((any[s >> 6] >> (s & 63)) & 1) {
-        const int j = jj[s];
-        if (j >= 0) t = plane[j];
-      }
-      v[e] = t;
+      v[e] = ((any[s >> 6] >> (s & 63)) & 1) ? cell[s * kWave] : 0.f;
     }
   }
 };
@@ -467,61 +506,174 @@ __device__ __forceinline__ void inv_levels(float (&out)[rows_at(D, L - 1)][cols_
   }
 }
 
+// LDS traffic of one wave with itself: the hardware runs a wave's LDS instructions in order;
+// this keeps the compiler from moving them across
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The channel walk of the staged path with NI dense fetches per channel.  mine[i]: the lane's
+// list entries (kInvNone: padding).  row_step: W for lanes inside the plane, 0 for the others
+// (whose dst is the scratch line).
+template <int D, int V, int NI>
+__device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane, int64_t k, int n_ch,
+                                                const uint32_t (&mine)[kInvCap / kWave],
+                                                uint32_t *tile, const InvStaged<D, V> &staged,
+                                                const LanePos<D> &p, float *dst, int row_step,
+                                                int64_t dst_step) {
+  constexpr int R = 1 << D;
+  constexpr uint32_t kRank = (1u << kInvRankBits) - 1u;
+  float vn[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) vn[i] = plane[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+  auto channel = [&](int c) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      if (mine[i] != kInvNone) tile[mine[i] >> kInvRankBits] = __float_as_uint(vn[i]);
+    // the next channel's values travel while this one is built (past the end: the last again)
+    const float *nx = plane + (size_t)min(c + 1, n_ch - 1) * k;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) vn[i] = nx[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+    __builtin_amdgcn_sched_barrier(0);
+    wave_lds_fence();
+    float out[R][V];
+    inv_levels<D, V, 1>(out, p, staged);
+    wave_lds_fence();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * row_step, out[r]);
+    dst += dst_step;
+  };
+  // The first channel stands outside the loop: at the loop head the outstanding memory
+  // operations are then "fetches, then R stores" on both incoming paths, and the wait for a
+  // fetch need not cover the stores.
+  channel(0);
+  for (int c = 1; c < n_ch; ++c) channel(c);
+}
+
 // yc [B, C, k] + jmap [B, N] -> y [B, C, H, W].  grid = (ceil(units/4), G, B), block = 256.
+// scratch: 1 KiB that lanes outside the plane may overwrite.
 template <int D, int V>
 __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restrict__ yc,
                                                             const int32_t *__restrict__ jmap,
                                                             float *__restrict__ y, Geo g,
-                                                            StripMap m, int C, int Cg, int64_t k) {
+                                                            StripMap m, int C, int Cg, int64_t k,
+                                                            float *scratch) {
   constexpr int R = 1 << D;
   constexpr int NS = slot_count(D, V);
+  constexpr bool kStaged = D <= 3;  // the [slot][lane] tiles of four waves fit in LDS
+  constexpr int CAP = NS * kWave < kInvCap ? NS * kWave : kInvCap;  // entries a wave can pack
   static_assert(NS <= 128, "slot mask is 128 bits wide");
-  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+  static_assert(!kStaged || NS * kWave <= (1 << (32 - kInvRankBits)), "cell index fits above the rank");
+  __shared__ uint32_t tiles[kStaged ? 4 : 1][kStaged ? NS * kWave : 1];
+  const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int unit = blockIdx.x * 4 + wv;
   const int grp = blockIdx.y, b = blockIdx.z;
   LanePos<D> p;
   int row0, col0;
   const bool active = locate<D, V>(m, g, unit, p, row0, col0);
   const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
+  if (__ballot(active) == 0 || c0 >= c1) return;  // whole waves leave
 
-  InvSource<D, V> src;
-  src.any[0] = src.any[1] = 0;
   const int32_t *jm = jmap + (size_t)b * g.N;
-  // ranks of this lane's positions (the same for every channel)
-  auto fetch = [&](auto Lc, auto Jc) {
-    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
-    constexpr int CV = cols_at(V, L);
-#pragma unroll
-    for (int i = 0; i < rows_at(D, L); ++i)
-#pragma unroll
-      for (int e = 0; e < CV; ++e) {
-        constexpr int base = slot_base(D, V, L, J);
-        const int s = base + i * CV + e;
-        int j = -1;
-        if (active) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
-        src.jj[s] = j;
-        if (__ballot(j >= 0) != 0) src.any[s >> 6] |= (uint64_t)1 << (s & 63);
-      }
-  };
-  auto each_level = [&](auto Lc) {
-    constexpr int L = decltype(Lc)::value;
-    fetch(Lc, std::integral_constant<int, 1>{});
-    fetch(Lc, std::integral_constant<int, 2>{});
-    fetch(Lc, std::integral_constant<int, 3>{});
-    if constexpr (L == D) fetch(Lc, std::integral_constant<int, 0>{});
-  };
-  each_level(std::integral_constant<int, 1>{});
-  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
-  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
-  if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
-  if (!active || c0 >= c1) return;
-
-  src.plane = yc + ((size_t)b * C + c0) * k;
+  const float *plane = yc + ((size_t)b * C + c0) * k;
   float *dst = y + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+
+  bool fast = false;
+  if constexpr (kStaged) {
+    // ranks of this lane's positions (the same for every channel), slot by slot
+    int jj[NS];
+    uint64_t any[2] = {0, 0};
+    int count = 0;  // kept positions of this wave's strip (wave-uniform)
+    auto fetch = [&](auto Lc, auto Jc) {
+      constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+      constexpr int CV = cols_at(V, L);
+#pragma unroll
+      for (int i = 0; i < rows_at(D, L); ++i)
+#pragma unroll
+        for (int e = 0; e < CV; ++e) {
+          constexpr int base = slot_base(D, V, L, J);
+          const int s = base + i * CV + e;
+          int j = -1;
+          if (active) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
+          jj[s] = j;
+        }
+    };
+    auto each_level = [&](auto Lc) {
+      constexpr int L = decltype(Lc)::value;
+      fetch(Lc, std::integral_constant<int, 1>{});
+      fetch(Lc, std::integral_constant<int, 2>{});
+      fetch(Lc, std::integral_constant<int, 3>{});
+      if constexpr (L == D) fetch(Lc, std::integral_constant<int, 0>{});
+    };
+    each_level(std::integral_constant<int, 1>{});
+    if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+    if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+    // (all map loads are in flight before the first vote waits for one)
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const uint64_t kept = __ballot(jj[s] >= 0);
+      if (kept != 0) any[s >> 6] |= (uint64_t)1 << (s & 63);
+      count += __popcll(kept);
+    }
+
+    fast = count <= CAP && k <= ((int64_t)1 << kInvRankBits);
+    if (fast) {
+      // pack (rank, cell): slot-major, then lane (a band row's kept positions have consecutive
+      // j).  The tile serves as scratch for the list before it becomes the staging area.
+      uint32_t *tile = tiles[wv];
+      int running = 0;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        if ((any[s >> 6] >> (s & 63)) & 1) {
+          const int j = jj[s];
+          const uint64_t kept = __ballot(j >= 0);
+          const int at = running + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32),
+                                       __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
+          if (j >= 0) tile[at] = (uint32_t)j | ((uint32_t)(s * kWave + lane) << kInvRankBits);
+          running += __popcll(kept);
+        }
+      }
+      wave_lds_fence();
+      uint32_t mine[kInvCap / kWave];  // this lane's share of the list: entries lane + 64 i
+#pragma unroll
+      for (int i = 0; i < kInvCap / kWave; ++i) {
+        const int e = lane + 64 * i;
+        mine[i] = (i < CAP / kWave && e < count) ? tile[e] : kInvNone;
+      }
+      wave_lds_fence();
+#pragma unroll
+      for (int s = 0; s < NS; ++s) tile[s * kWave + lane] = 0u;
+
+      InvStaged<D, V> staged;
+      staged.cell = reinterpret_cast<const float *>(tile) + lane;
+      staged.any[0] = any[0];
+      staged.any[1] = any[1];
+      float *to = active ? dst : scratch + lane * V;
+      const int row_step = active ? g.W : 0;
+      const int64_t dst_step = active ? g.N : 0;
+      const int ni = (count + 63) >> 6;
+      if (ni <= 4)
+        inv_staged_walk<D, V, 4>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step);
+      else if (ni <= 8)
+        inv_staged_walk<D, V, 8>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step);
+      else
+        inv_staged_walk<D, V, 16>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step);
+      return;
+    }
+  }
+
+  // plain path
+  InvReload<D, V> src{plane, jm, &p, active};
   for (int c = c0; c < c1; ++c) {
     float out[R][V];
     inv_levels<D, V, 1>(out, p, src);
+    if (active) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * g.W, out[r]);
+      for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * g.W, out[r]);
+    }
     src.plane += k;
     dst += g.N;
   }
@@ -623,13 +775,13 @@ hipError_t keep_launch(const wcc_desc &d, int64_t k, const float *x, const int32
 
 template <int D, int V>
 hipError_t inv_launch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, float *y,
-                      int G, hipStream_t s) {
+                      int G, float *scratch, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_out + G - 1) / G;
   dim3 grid((m.units + 3) / 4, G, d.B);
   hipLaunchKernelGGL((scatter_ihaar_kernel<D, V>), grid, dim3(256), 0, s, yc, jmap, y, g, m,
-                     d.C_out, Cg, k);
+                     d.C_out, Cg, k, scratch);
   return hipGetLastError();
 }
 
@@ -681,14 +833,14 @@ hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const float *x, const int
 }
 
 hipError_t inv_dispatch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, float *y,
-                        int G, hipStream_t s) {
+                        int G, float *scratch, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
-    case 1: return v4 ? inv_launch<1, 4>(d, k, yc, jmap, y, G, s)
-                      : inv_launch<1, 2>(d, k, yc, jmap, y, G, s);
-    case 2: return inv_launch<2, 4>(d, k, yc, jmap, y, G, s);
-    case 3: return inv_launch<3, 4>(d, k, yc, jmap, y, G, s);
-    case 4: return inv_launch<4, 4>(d, k, yc, jmap, y, G, s);
+    case 1: return v4 ? inv_launch<1, 4>(d, k, yc, jmap, y, G, scratch, s)
+                      : inv_launch<1, 2>(d, k, yc, jmap, y, G, scratch, s);
+    case 2: return inv_launch<2, 4>(d, k, yc, jmap, y, G, scratch, s);
+    case 3: return inv_launch<3, 4>(d, k, yc, jmap, y, G, scratch, s);
+    case 4: return inv_launch<4, 4>(d, k, yc, jmap, y, G, scratch, s);
   }
   return hipErrorInvalidValue;
 }
@@ -720,8 +872,8 @@ hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const 
 }
 
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
-                                float *y, hipStream_t s) {
-  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 2048, 8), s);
+                                float *y, float *scratch, hipStream_t s) {
+  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 2048, 8), scratch, s);
 }
 
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s) {

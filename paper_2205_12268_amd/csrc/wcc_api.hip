@@ -69,6 +69,7 @@ WsLayout ws_layout(const wcc_desc &d) {
   L.jmap = take(B * N * 4);
   L.idx = take(B * k * 4);
   L.alpha = take(256);
+  L.scratch = take(kInvScratchBytes);
   L.xc32 = take(B * (size_t)d.C_in * k * 4);
   L.yc = take(B * (size_t)d.C_out * k * 4);
   L.total = off;
@@ -262,7 +263,8 @@ wcc_status wcc_scatter_ihaar(wcc_ctx *ctx, const wcc_desc *desc, const float *yc
   const int64_t N = (int64_t)desc->H * desc->W, k = k_of(*desc);
   int32_t *jmap = reinterpret_cast<int32_t *>(static_cast<char *>(ctx->ws) + L.jmap);
   WCC_TRY(launch_jmap_from_idx(idx, desc->B, N, k, jmap, s));
-  WCC_TRY(launch_scatter_ihaar(*desc, k, yc, jmap, y, s));
+  WCC_TRY(launch_scatter_ihaar(*desc, k, yc, jmap, y,
+                               reinterpret_cast<float *>(static_cast<char *>(ctx->ws) + L.scratch), s));
   return WCC_OK;
 }
 
@@ -317,7 +319,7 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   WCC_TRY(mark(WCC_T_POINTWISE, 1));
   // D + E: Y^0[I] = Y_wt, inverse levels
   WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 0));
-  WCC_TRY(launch_scatter_ihaar(d, k, yc, jmap, y, s));
+  WCC_TRY(launch_scatter_ihaar(d, k, yc, jmap, y, reinterpret_cast<float *>(ws + L.scratch), s));
   WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 1));
   WCC_TRY(mark(WCC_T_EVENT_PAIR, 0));
   WCC_TRY(mark(WCC_T_EVENT_PAIR, 1));

@@ -13,7 +13,8 @@ constexpr int kMaxLevels = 4;      // register-resident strip transform up to 16
 constexpr int kRadixBins = 2048;   // 11 + 11 + 10 bit radix select
 constexpr int kSelectChunk = 1024; // keys per workgroup in the select kernels
 constexpr int kSfxStride = 1024;   // per-workgroup suffix sums of the low-digit histogram
-constexpr int kAlphaSlots = 64;    // max|kept c| is reduced into this many slots, then combined
+constexpr int kAlphaSlots = 64;
+constexpr int kInvScratchBytes = 1024;  // one 16-byte line per lane for stores that must go nowhere    // max|kept c| is reduced into this many slots, then combined
 
 // Geometry of the wavelet vector of one plane (Eq. wavelet_transform for d levels).
 struct Geo {
@@ -35,6 +36,7 @@ struct WsLayout {
   size_t jmap;        // [B, N] int32: rank of a kept position, -1 otherwise
   size_t idx;         // [B, k] int32
   size_t alpha;       // kAlphaSlots floats: partial maxima of |kept coefficient|
+  size_t scratch;     // kInvScratchBytes: sink for the stores of lanes outside the plane
   size_t xc32;        // [B, C_in, k] fp32
   size_t yc;          // [B, C_out, k] fp32  (wcc_forward only)
   size_t total;
@@ -154,7 +156,8 @@ hipError_t launch_quantize(const float *xc32, int64_t n, const float *alpha_slot
 hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
                             const void *xc, bool xc_is_f32, const float *alpha, bool alpha_is_slots,
                             float *alpha_out, float *yc, hipStream_t s);
+// scratch: kInvScratchBytes of device memory that the kernel may overwrite with anything
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
-                                float *y, hipStream_t s);
+                                float *y, float *scratch, hipStream_t s);
 
 }  // namespace wcc
