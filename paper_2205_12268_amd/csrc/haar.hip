@@ -424,27 +424,29 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict_
 // LDS tile laid out [slot][lane] whose other cells stay zero, and every lane reads its slots
 // back from there.  Lanes outside the plane take part in the list work and send their stores
 // to a scratch line.  Strips that keep more than kInvCap positions, layers with more than 2^20
-// kept positions, and d = 4 (whose tile would not fit) take the plain path: ranks re-read from
-// the map, one conditional load per slot.
+// kept positions, and d = 4 (whose tile would not fit) take the plain path: ranks in registers,
+// one conditional load per slot.
 constexpr int kInvCap = 1024;          // packed entries per wave
 constexpr uint32_t kInvNone = ~0u;     // list padding
 constexpr int kInvRankBits = 20;       // entry = rank | cell << 20
 
-// Plain path: the rank of every position is read from the map again for every channel.
+// Plain path: jj[slot] = rank j of the position inside the kept list, or -1 (dropped -> 0);
+// one conditional load per slot that some lane keeps.
 template <int D, int V>
-struct InvReload {
-  const float *plane;   // yc[b, o, :]
-  const int32_t *jm;    // jmap[b, :]
-  const LanePos<D> *p;
-  bool active;
+struct InvDirect {
+  const float *plane;  // yc[b, o, :]
+  int jj[slot_count(D, V)];
+  uint64_t any[2];     // wave-uniform: bit s set if some lane keeps slot s
   template <int L, int J>
   __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
     constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
 #pragma unroll
     for (int e = 0; e < CV; ++e) {
+      const int s = base + i * CV + e;
       float t = 0.f;
-      if (active) {
-        const int j = jm[J * p->nl[L] + p->off[L] + i * p->rowlen[L] + e];
+      if ((any[s >> 6] >> (s & 63)) & 1) {
+        const int j = jj[s];
         if (j >= 0) t = plane[j];
       }
       v[e] = t;
@@ -581,54 +583,52 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
   const float *plane = yc + ((size_t)b * C + c0) * k;
   float *dst = y + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
 
-  bool fast = false;
-  if constexpr (kStaged) {
-    // ranks of this lane's positions (the same for every channel), slot by slot
-    int jj[NS];
-    uint64_t any[2] = {0, 0};
-    int count = 0;  // kept positions of this wave's strip (wave-uniform)
-    auto fetch = [&](auto Lc, auto Jc) {
-      constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
-      constexpr int CV = cols_at(V, L);
+  // ranks of this lane's positions (the same for every channel), slot by slot
+  InvDirect<D, V> src;
+  src.any[0] = src.any[1] = 0;
+  int count = 0;  // kept positions of this wave's strip (wave-uniform)
+  auto fetch = [&](auto Lc, auto Jc) {
+    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+    constexpr int CV = cols_at(V, L);
 #pragma unroll
-      for (int i = 0; i < rows_at(D, L); ++i)
+    for (int i = 0; i < rows_at(D, L); ++i)
 #pragma unroll
-        for (int e = 0; e < CV; ++e) {
-          constexpr int base = slot_base(D, V, L, J);
-          const int s = base + i * CV + e;
-          int j = -1;
-          if (active) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
-          jj[s] = j;
-        }
-    };
-    auto each_level = [&](auto Lc) {
-      constexpr int L = decltype(Lc)::value;
-      fetch(Lc, std::integral_constant<int, 1>{});
-      fetch(Lc, std::integral_constant<int, 2>{});
-      fetch(Lc, std::integral_constant<int, 3>{});
-      if constexpr (L == D) fetch(Lc, std::integral_constant<int, 0>{});
-    };
-    each_level(std::integral_constant<int, 1>{});
-    if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
-    if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
-    // (all map loads are in flight before the first vote waits for one)
+      for (int e = 0; e < CV; ++e) {
+        constexpr int base = slot_base(D, V, L, J);
+        int j = -1;
+        if (active) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
+        src.jj[base + i * CV + e] = j;
+      }
+  };
+  auto each_level = [&](auto Lc) {
+    constexpr int L = decltype(Lc)::value;
+    fetch(Lc, std::integral_constant<int, 1>{});
+    fetch(Lc, std::integral_constant<int, 2>{});
+    fetch(Lc, std::integral_constant<int, 3>{});
+    if constexpr (L == D) fetch(Lc, std::integral_constant<int, 0>{});
+  };
+  each_level(std::integral_constant<int, 1>{});
+  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+  if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+  // (all map loads are in flight before the first vote waits for one)
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const uint64_t kept = __ballot(jj[s] >= 0);
-      if (kept != 0) any[s >> 6] |= (uint64_t)1 << (s & 63);
-      count += __popcll(kept);
-    }
+  for (int s = 0; s < NS; ++s) {
+    const uint64_t kept = __ballot(src.jj[s] >= 0);
+    if (kept != 0) src.any[s >> 6] |= (uint64_t)1 << (s & 63);
+    count += __popcll(kept);
+  }
 
-    fast = count <= CAP && k <= ((int64_t)1 << kInvRankBits);
-    if (fast) {
+  if constexpr (kStaged) {
+    if (count <= CAP && k <= ((int64_t)1 << kInvRankBits)) {
       // pack (rank, cell): slot-major, then lane (a band row's kept positions have consecutive
       // j).  The tile serves as scratch for the list before it becomes the staging area.
       uint32_t *tile = tiles[wv];
       int running = 0;
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        if ((any[s >> 6] >> (s & 63)) & 1) {
-          const int j = jj[s];
+        if ((src.any[s >> 6] >> (s & 63)) & 1) {
+          const int j = src.jj[s];
           const uint64_t kept = __ballot(j >= 0);
           const int at = running + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32),
                                        __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
@@ -649,8 +649,8 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
 
       InvStaged<D, V> staged;
       staged.cell = reinterpret_cast<const float *>(tile) + lane;
-      staged.any[0] = any[0];
-      staged.any[1] = any[1];
+      staged.any[0] = src.any[0];
+      staged.any[1] = src.any[1];
       float *to = active ? dst : scratch + lane * V;
       const int row_step = active ? g.W : 0;
       const int64_t dst_step = active ? g.N : 0;
@@ -666,14 +666,13 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
   }
 
   // plain path
-  InvReload<D, V> src{plane, jm, &p, active};
+  if (!active) return;
+  src.plane = plane;
   for (int c = c0; c < c1; ++c) {
     float out[R][V];
     inv_levels<D, V, 1>(out, p, src);
-    if (active) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * g.W, out[r]);
-    }
+    for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * g.W, out[r]);
     src.plane += k;
     dst += g.N;
   }
