@@ -14,9 +14,17 @@ from tests.util import desc_of, dev, oracle_scale, rel_l2, tol_for, upload_weigh
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("n", [2, 3, 4])
+def _huge_plane():
+    """More than 2**20 kept positions per sample: the packed (rank | cell) lists of the strip
+    kernels do not apply, 4096 select workgroups per sample, a one-chunk contraction."""
+    return synth.small(synth.config(2), name="huge_plane", B=1, C_in=8, C_out=16, H=2048, W=2048,
+                       levels=2, keep_num=1, keep_den=2, seed=synth.SEED_BASE + 0x800)
+
+
+@pytest.mark.parametrize("n", [2, 3, 4, "huge_plane"])
 def test_full_size_forward(ref, n):
-    cfg = synth.config(n)
+    cfg = _huge_plane() if n == "huge_plane" else synth.config(n)
+    n = 9 if n == "huge_plane" else n
     print(f"workload {cfg.name}: generating inputs", flush=True)
     x, w = synth.make_inputs(cfg)
     d = desc_of(cfg)
