@@ -29,7 +29,8 @@
  * Eq. (HaarKernel), keep-ratio-1 == direct 1x1 convolution, the commutation
  * identity of the section "Equivalence of the convolutions", brute-force top-k,
  * quantiser closed-form properties, the BOPs example of the appendix on bit
- * operations.  Numeric WCC outputs on the paper's datasets: parity unpinned
+ * operations; the depthwise 3x3 convolution against a library correlation and shifted
+ * impulses, the block of Eq. (inverted) at keep ratio 1 against its dense definition.  Numeric WCC outputs on the paper's datasets: parity unpinned
  * (the paper prints none).
  *
  * Loops marked with an OpenMP pragma run over independent outputs; the
@@ -344,6 +345,33 @@ int wcc_ref_forward(const double *x, const double *w, const double *w_scale, int
 done:
   free(coef); free(norm); free(idx); free(xc); free(yc); free(z); free(scale);
   return rc;
+}
+
+/* ---- depthwise 3x3 convolution: the K_dw of the inverted residual block (appendix
+ * "Inference times", Eq. (inverted)) ----
+ * y[p][r][c] = sum_{i,j = 0..2} w[p % C][i][j] * x[p][r + i - 1][c + j - 1], terms outside the
+ * plane are zero.  Readings (the paper only names the operator): cross-correlation as in the
+ * Haar kernels, stride 1, zero padding 1 -- the residual of Eq. (inverted) needs equal sizes --
+ * no bias.  x, y [planes, H, W]; w [C, 3, 3]; plane p uses channel p % C.  Returns 0 or -1. */
+int wcc_ref_depthwise3x3(const double *x, const double *w, int64_t planes, int64_t C, int64_t H,
+                         int64_t W, double *y) {
+  if (planes < 0 || C < 1 || H < 1 || W < 1) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t p = 0; p < planes; ++p) {
+    const double *xp = x + p * H * W, *wp = w + (p % C) * 9;
+    double *yp = y + p * H * W;
+    for (int64_t r = 0; r < H; ++r)
+      for (int64_t c = 0; c < W; ++c) {
+        double acc = 0.0;
+        for (int i = 0; i < 3; ++i)
+          for (int j = 0; j < 3; ++j) {
+            const int64_t rr = r + i - 1, cc = c + j - 1;
+            if (rr >= 0 && rr < H && cc >= 0 && cc < W) acc += wp[i * 3 + j] * xp[rr * W + cc];
+          }
+        yp[r * W + c] = acc;
+      }
+  }
+  return 0;
 }
 
 /* ---- cost model (appendix on bit operations) ---- */

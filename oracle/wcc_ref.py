@@ -49,6 +49,8 @@ def lib():
         L.wcc_ref_forward.argtypes = [_pd, _pd, _pd, _i64, _i64, _i64, _i64, _i64, C.c_int,
                                       _i64, _i64, C.c_int, C.c_double, _pd, _pi, _pd]
         L.wcc_ref_conv_mac.restype = _i64
+        L.wcc_ref_depthwise3x3.argtypes = [_pd, _pd, _i64, _i64, _i64, _i64, _pd]
+        L.wcc_ref_depthwise3x3.restype = C.c_int
         L.wcc_ref_conv_mac.argtypes = [_i64] * 8
         L.wcc_ref_conv_bops.restype = _i64
         L.wcc_ref_conv_bops.argtypes = [_i64] * 3
@@ -186,6 +188,31 @@ def forward(x, w, w_scale, levels: int, keep_num: int, keep_den: int, act_bits: 
     if rc:
         raise ValueError("wcc_ref_forward: bad arguments or out of memory")
     return y, idx, float(alpha.value)
+
+
+def depthwise3x3(x, w):
+    """K_dw of Eq. (inverted): x [B, C, H, W], w [C, 3, 3] -> [B, C, H, W] (zero padding 1)."""
+    x = _d(x)
+    w = _d(w)
+    B, Cc, H, W = x.shape
+    assert w.shape == (Cc, 3, 3)
+    y = np.empty_like(x)
+    if lib().wcc_ref_depthwise3x3(_p(x), _p(w), B * Cc, Cc, H, W, _p(y)):
+        raise ValueError("wcc_ref_depthwise3x3: bad arguments")
+    return y
+
+
+def block_forward(x, w1, w1_scale, w_dw, w3, w3_scale, levels: int, keep_num: int, keep_den: int,
+                  act_bits: int = 0):
+    """The inverted residual block of Eq. (inverted) with both 1x1 convolutions as WCC layers
+    (activations left out, as in the paper's timings):
+    x + WCC(K3, K_dw(WCC(K1, x))).  Returns (y, t1, t2, idx1, idx3, alpha1, alpha3) where
+    t1 = WCC(K1, x) and t2 = K_dw t1."""
+    x = _d(x)
+    t1, idx1, a1 = forward(x, w1, w1_scale, levels, keep_num, keep_den, act_bits)
+    t2 = depthwise3x3(t1, w_dw)
+    t3, idx3, a3 = forward(t2, w3, w3_scale, levels, keep_num, keep_den, act_bits)
+    return x + t3, t1, t2, idx1, idx3, a1, a3
 
 
 def conv_mac(C_in, C_out, N_W, N_H, K_W=1, K_H=1, S_W=1, S_H=1) -> int:

@@ -448,3 +448,91 @@ def test_mac_table_rows(ref):
         ci, co, K, groups, S, H, W, mac = map(int, t[1:])
         assert groups == 1
         assert ref.conv_mac(ci, co, W, H, K, K, S, S) == mac, t[0]
+
+
+# ---- the depthwise 3x3 convolution and the inverted residual block (Eq. (inverted)) ----------
+def test_depthwise_matches_library_correlation(ref):
+    from scipy import ndimage
+    rng = np.random.default_rng(21)
+    x = rng.standard_normal((2, 3, 7, 10))
+    w = rng.standard_normal((3, 3, 3))
+    y = ref.depthwise3x3(x, w)
+    for b in range(2):
+        for c in range(3):
+            want = ndimage.correlate(x[b, c], w[c], mode="constant", cval=0.0)
+            np.testing.assert_allclose(y[b, c], want, rtol=0, atol=1e-13)
+    # and against the framework's grouped convolution (cross-correlation, padding 1)
+    t = torch.nn.functional.conv2d(torch.from_numpy(x), torch.from_numpy(w)[:, None], padding=1, groups=3)
+    np.testing.assert_allclose(y, t.numpy(), rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("i,j", list(itertools.product(range(3), range(3))))
+def test_depthwise_shifted_impulse_kernels(ref, i, j):
+    """A kernel that is 1 at tap (i, j) shifts the plane by (i-1, j-1) with zero fill: pins the
+    orientation of the taps (no flip, rows before columns) and the border handling."""
+    rng = np.random.default_rng(22)
+    x = rng.standard_normal((1, 2, 5, 6))
+    w = np.zeros((2, 3, 3))
+    w[:, i, j] = 1.0
+    y = ref.depthwise3x3(x, w)
+    want = np.zeros_like(x)
+    H, W = 5, 6
+    for r in range(H):
+        for c in range(W):
+            rr, cc = r + i - 1, c + j - 1
+            if 0 <= rr < H and 0 <= cc < W:
+                want[:, :, r, c] = x[:, :, rr, cc]
+    np.testing.assert_array_equal(y, want)
+
+
+def test_depthwise_uses_its_own_channel_kernel(ref):
+    x = np.ones((2, 3, 4, 4))
+    w = np.zeros((3, 3, 3))
+    w[0, 1, 1], w[1, 1, 1], w[2, 1, 1] = 2.0, 3.0, 5.0
+    y = ref.depthwise3x3(x, w)
+    for c, f in enumerate((2.0, 3.0, 5.0)):
+        np.testing.assert_array_equal(y[:, c], f * np.ones((2, 4, 4)))
+    # constant plane, all-ones kernel: 9 inside, 6 on edges, 4 in corners
+    y = ref.depthwise3x3(np.ones((1, 1, 4, 5)), np.ones((1, 3, 3)))
+    assert y[0, 0, 1, 1] == 9 and y[0, 0, 0, 2] == 6 and y[0, 0, 2, 0] == 6 and y[0, 0, 0, 0] == 4
+    assert y[0, 0, 3, 4] == 4
+
+
+def block_problem(seed, B=2, Cc=4, t=3, H=8, W=16):
+    rng = np.random.default_rng(seed)
+    x = np.rint(np.maximum(rng.standard_normal((B, Cc, H, W)), 0) * 64) / 64
+    w1 = np.rint(rng.standard_normal((t * Cc, Cc)) * 1024) / 1024
+    wd = np.rint(rng.standard_normal((t * Cc, 3, 3)) * 256) / 256
+    w3 = np.rint(rng.standard_normal((Cc, t * Cc)) * 1024) / 1024
+    return x, w1, wd, w3
+
+
+@pytest.mark.parametrize("d", [1, 2])
+def test_block_at_keep_all_equals_its_dense_definition(ref, d):
+    """Eq. (inverted) with T = I in both WCC layers: x + K3 (K_dw (K1 x))."""
+    x, w1, wd, w3 = block_problem(31)
+    y, t1, t2, idx1, idx3, _, _ = ref.block_forward(x, w1, None, wd, w3, None, d, 1, 1)
+    tx = torch.from_numpy(x)
+    a = torch.nn.functional.conv2d(tx, torch.from_numpy(w1)[:, :, None, None])
+    b = torch.nn.functional.conv2d(a, torch.from_numpy(wd)[:, None], padding=1, groups=w1.shape[0])
+    c = torch.nn.functional.conv2d(b, torch.from_numpy(w3)[:, :, None, None])
+    np.testing.assert_allclose(t1, a.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(t2, b.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(y, (tx + c).numpy(), rtol=0, atol=1e-11)
+
+
+def test_block_structure(ref):
+    """The residual is the input itself, the two layers pick their own index sets, and the
+    block is the composition of the stages it returns."""
+    x, w1, wd, w3 = block_problem(32)
+    y0 = ref.block_forward(x, w1, None, wd, np.zeros_like(w3), None, 2, 1, 4, 8)[0]
+    np.testing.assert_array_equal(y0, x)  # K3 = 0: only the skip connection is left
+    y, t1, t2, idx1, idx3, a1, a3 = ref.block_forward(x, w1, None, wd, w3, None, 2, 1, 4, 8)
+    want_t1, want_idx1, want_a1 = ref.forward(x, w1, None, 2, 1, 4, 8)
+    np.testing.assert_array_equal(t1, want_t1)
+    np.testing.assert_array_equal(idx1, want_idx1)
+    t3, want_idx3, want_a3 = ref.forward(ref.depthwise3x3(t1, wd), w3, None, 2, 1, 4, 8)
+    np.testing.assert_array_equal(idx3, want_idx3)
+    np.testing.assert_array_equal(y, x + t3)
+    assert a1 == want_a1 and a3 == want_a3 and a1 > 0 and a3 > 0
+    assert idx1.shape == idx3.shape == (2, 32)
