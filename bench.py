@@ -174,6 +174,7 @@ def main() -> int:
                 acc[name] = acc.get(name, 0.0) + ms
         ctx.set_profiling(False)
         # an empty event bracket measures what the two records cost by themselves; take it off
+        acc.pop("depthwise", None)  # a stage of the block workload only
         pair_us = 1e3 * acc.pop("event_pair") / args.steps
         stage_us = {n: max(1e3 * v / args.steps - pair_us, 0.0) for n, v in acc.items()}
         return dt, stage_us, pair_us, x, w

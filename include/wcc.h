@@ -90,6 +90,7 @@ enum {
   WCC_T_POINTWISE,     /* quantise + contraction + dequantise, one kernel              */
   WCC_T_SCATTER_IHAAR, /* scatter + inverse Haar, one kernel                           */
   WCC_T_EVENT_PAIR,    /* an empty bracket: what two event records cost by themselves  */
+  WCC_T_DEPTHWISE,     /* wcc_block_forward only: the depthwise 3x3 kernel             */
   WCC_T_COUNT
 };
 
@@ -174,6 +175,43 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
                        const float *w_scale /*nullable unless I8*/, float alpha_in, float *y,
                        int32_t *idx_out /*nullable*/, float *alpha_out_dev /*nullable*/,
                        void *stream);
+
+/* ==== next row: the inverted residual block the paper timed (appendix "Inference times",
+ * Eq. (inverted)):  y = x + K3_1x1( K_dw( K1_1x1 x ) ), both 1x1 convolutions as WCC layers
+ * with the same levels / keep ratio / quantiser, K_dw a depthwise 3x3 convolution; the
+ * non-linearities are left out, as in the paper's timings. ================================= */
+
+typedef struct {
+  int32_t B, C, expansion;   /* x, y [B, C, H, W]; the middle tensors have C * expansion channels */
+  int32_t H, W, levels;
+  int64_t keep_num, keep_den;
+  int32_t w_dtype;           /* of both 1x1 kernels: w1 [C*expansion, C], w3 [C, C*expansion] */
+  int32_t act_quant_bits;
+} wcc_block_desc;
+
+/* Workspace for wcc_block_forward: the two middle tensors plus the larger of the two layers'
+ * own workspaces.  Pure host function. */
+wcc_status wcc_block_workspace_bytes(const wcc_block_desc *desc, size_t *bytes);
+
+/* K_dw: y[b,c,r,q] = sum_{i,j=0..2} w[c,i,j] * x[b,c,r+i-1,q+j-1], zero outside the plane
+ * (cross-correlation, stride 1, zero padding 1, no bias; the paper names the operator only).
+ * x, y [B,C,H,W] fp32 device, w [C,3,3] fp32 device; x and y must not overlap. */
+wcc_status wcc_depthwise3x3(wcc_ctx *ctx, int32_t B, int32_t C, int32_t H, int32_t W,
+                            const float *x, const float *w, float *y, void *stream);
+
+/* The block.  w1_scale / w3_scale as in wcc_forward (int8 weights only); alpha of each layer is
+ * the largest kept |coefficient| of that layer.  t1_out / t2_out (nullable, [B, C*expansion,
+ * H, W]) receive K1's output and K_dw's output, idx1_out / idx3_out (nullable, [B,k]) the two
+ * index sets: they exist for tests.  Needs a workspace of wcc_block_workspace_bytes. */
+wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const float *x,
+                             const void *w1, const float *w1_scale, const float *w_dw,
+                             const void *w3, const float *w3_scale, float *y,
+                             float *t1_out, float *t2_out, int32_t *idx1_out, int32_t *idx3_out,
+                             void *stream);
+
+/* Which of the block's two layers (0: expand, 1: project) the stage events bracket while
+ * profiling is on (default 1). */
+wcc_status wcc_set_block_profile_layer(wcc_ctx *ctx, int layer);
 
 #ifdef __cplusplus
 }

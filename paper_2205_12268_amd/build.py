@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(CSRC, "libwcc.so")
-SOURCES = ["haar.hip", "select.hip", "gather.hip", "pointwise.hip", "wcc_api.hip"]
+SOURCES = ["haar.hip", "select.hip", "gather.hip", "pointwise.hip", "depthwise.hip", "wcc_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

@@ -519,12 +519,13 @@ __device__ __forceinline__ void wave_lds_fence() {
 // The channel walk of the staged path with NI dense fetches per channel.  mine[i]: the lane's
 // list entries (kInvNone: padding).  row_step: W for lanes inside the plane, 0 for the others
 // (whose dst is the scratch line).
-template <int D, int V, int NI>
+// RES: res + (what dst points at, relative to the output tensor) is added to every stored row.
+template <int D, int V, int NI, bool RES>
 __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane, int64_t k, int n_ch,
                                                 const uint32_t (&mine)[kInvCap / kWave],
                                                 uint32_t *tile, const InvStaged<D, V> &staged,
                                                 const LanePos<D> &p, float *dst, int row_step,
-                                                int64_t dst_step) {
+                                                int64_t dst_step, const float *res) {
   constexpr int R = 1 << D;
   constexpr uint32_t kRank = (1u << kInvRankBits) - 1u;
   float vn[NI];
@@ -538,12 +539,24 @@ __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane,
     const float *nx = plane + (size_t)min(c + 1, n_ch - 1) * k;
 #pragma unroll
     for (int i = 0; i < NI; ++i) vn[i] = nx[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+    float skip[RES ? R : 1][V];
+    if constexpr (RES) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) load_row<V>(res + (size_t)r * row_step, skip[r]);
+    }
     __builtin_amdgcn_sched_barrier(0);
     wave_lds_fence();
     float out[R][V];
     inv_levels<D, V, 1>(out, p, staged);
     wave_lds_fence();
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (RES) {
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < V; ++e) out[r][e] += skip[r][e];
+      res += dst_step;
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * row_step, out[r]);
     dst += dst_step;
@@ -556,13 +569,14 @@ __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane,
 }
 
 // yc [B, C, k] + jmap [B, N] -> y [B, C, H, W].  grid = (ceil(units/4), G, B), block = 256.
-// scratch: 1 KiB that lanes outside the plane may overwrite.
-template <int D, int V>
+// scratch: 1 KiB that lanes outside the plane may overwrite.  RES: y = residual + (the above),
+// residual [B, C, H, W] (the skip connection of Eq. (inverted)); it may be y itself.
+template <int D, int V, bool RES>
 __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restrict__ yc,
                                                             const int32_t *__restrict__ jmap,
-                                                            float *__restrict__ y, Geo g,
-                                                            StripMap m, int C, int Cg, int64_t k,
-                                                            float *scratch) {
+                                                            float *y, Geo g, StripMap m, int C,
+                                                            int Cg, int64_t k, float *scratch,
+                                                            const float *residual) {
   constexpr int R = 1 << D;
   constexpr int NS = slot_count(D, V);
   constexpr bool kStaged = D <= 3;  // the [slot][lane] tiles of four waves fit in LDS
@@ -581,7 +595,8 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
 
   const int32_t *jm = jmap + (size_t)b * g.N;
   const float *plane = yc + ((size_t)b * C + c0) * k;
-  float *dst = y + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+  const size_t first = ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+  float *dst = y + first;
 
   // ranks of this lane's positions (the same for every channel), slot by slot
   InvDirect<D, V> src;
@@ -652,15 +667,16 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
       staged.any[0] = src.any[0];
       staged.any[1] = src.any[1];
       float *to = active ? dst : scratch + lane * V;
+      const float *res = (RES && active) ? residual + first : scratch + lane * V;
       const int row_step = active ? g.W : 0;
       const int64_t dst_step = active ? g.N : 0;
       const int ni = (count + 63) >> 6;
       if (ni <= 4)
-        inv_staged_walk<D, V, 4>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step);
+        inv_staged_walk<D, V, 4, RES>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
       else if (ni <= 8)
-        inv_staged_walk<D, V, 8>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step);
+        inv_staged_walk<D, V, 8, RES>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
       else
-        inv_staged_walk<D, V, 16>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step);
+        inv_staged_walk<D, V, 16, RES>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
       return;
     }
   }
@@ -668,9 +684,20 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
   // plain path
   if (!active) return;
   src.plane = plane;
+  const float *res = RES ? residual + first : nullptr;
   for (int c = c0; c < c1; ++c) {
     float out[R][V];
     inv_levels<D, V, 1>(out, p, src);
+    if constexpr (RES) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        float skip[V];
+        load_row<V>(res + (size_t)r * g.W, skip);
+#pragma unroll
+        for (int e = 0; e < V; ++e) out[r][e] += skip[e];
+      }
+      res += g.N;
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * g.W, out[r]);
     src.plane += k;
@@ -774,13 +801,17 @@ hipError_t keep_launch(const wcc_desc &d, int64_t k, const float *x, const int32
 
 template <int D, int V>
 hipError_t inv_launch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, float *y,
-                      int G, float *scratch, hipStream_t s) {
+                      int G, float *scratch, const float *residual, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_out + G - 1) / G;
   dim3 grid((m.units + 3) / 4, G, d.B);
-  hipLaunchKernelGGL((scatter_ihaar_kernel<D, V>), grid, dim3(256), 0, s, yc, jmap, y, g, m,
-                     d.C_out, Cg, k, scratch);
+  if (residual)
+    hipLaunchKernelGGL((scatter_ihaar_kernel<D, V, true>), grid, dim3(256), 0, s, yc, jmap, y, g, m,
+                       d.C_out, Cg, k, scratch, residual);
+  else
+    hipLaunchKernelGGL((scatter_ihaar_kernel<D, V, false>), grid, dim3(256), 0, s, yc, jmap, y, g, m,
+                       d.C_out, Cg, k, scratch, residual);
   return hipGetLastError();
 }
 
@@ -832,14 +863,14 @@ hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const float *x, const int
 }
 
 hipError_t inv_dispatch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, float *y,
-                        int G, float *scratch, hipStream_t s) {
+                        int G, float *scratch, const float *residual, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
-    case 1: return v4 ? inv_launch<1, 4>(d, k, yc, jmap, y, G, scratch, s)
-                      : inv_launch<1, 2>(d, k, yc, jmap, y, G, scratch, s);
-    case 2: return inv_launch<2, 4>(d, k, yc, jmap, y, G, scratch, s);
-    case 3: return inv_launch<3, 4>(d, k, yc, jmap, y, G, scratch, s);
-    case 4: return inv_launch<4, 4>(d, k, yc, jmap, y, G, scratch, s);
+    case 1: return v4 ? inv_launch<1, 4>(d, k, yc, jmap, y, G, scratch, residual, s)
+                      : inv_launch<1, 2>(d, k, yc, jmap, y, G, scratch, residual, s);
+    case 2: return inv_launch<2, 4>(d, k, yc, jmap, y, G, scratch, residual, s);
+    case 3: return inv_launch<3, 4>(d, k, yc, jmap, y, G, scratch, residual, s);
+    case 4: return inv_launch<4, 4>(d, k, yc, jmap, y, G, scratch, residual, s);
   }
   return hipErrorInvalidValue;
 }
@@ -871,8 +902,8 @@ hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const 
 }
 
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
-                                float *y, float *scratch, hipStream_t s) {
-  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 2048, 8), scratch, s);
+                                float *y, float *scratch, const float *residual, hipStream_t s) {
+  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 2048, 8), scratch, residual, s);
 }
 
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s) {

@@ -12,7 +12,14 @@ struct wcc_ctx {
   bool have_times = false;
   hipEvent_t ev[WCC_T_COUNT][2] = {};
   bool ev_ok = false;
+  bool marked[WCC_T_COUNT] = {};  // stage bracket recorded since profiling was switched on
+  int block_profile_layer = 1;  // which layer of wcc_block_forward the stage events bracket
 };
+
+#define WCC_TRY(expr)                                 \
+  do {                                                \
+    if ((expr) != hipSuccess) return WCC_ERR_HIP;     \
+  } while (0)
 
 namespace wcc {
 namespace {
@@ -73,6 +80,84 @@ WsLayout ws_layout(const wcc_desc &d) {
   L.xc32 = take(B * (size_t)d.C_in * k * 4);
   L.yc = take(B * (size_t)d.C_out * k * 4);
   L.total = off;
+  return L;
+}
+
+
+// One WCC layer (Alg. 1 with the quantiser) on a workspace that starts at `ws`.  residual
+// (nullable, [B, C_out, H, W]) is added to the output by the last kernel.  prof: bracket the
+// stages with the context's events.
+wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc &d, const float *x,
+                      const void *w, const float *w_scale, float alpha_in, float *y,
+                      int32_t *idx_out, float *alpha_out_dev, const float *residual, bool prof,
+                      hipStream_t s) {
+  const int64_t k = k_of(d);
+  const bool quant = d.act_quant_bits == 8;
+
+  float *part = reinterpret_cast<float *>(ws + L.norm_part);
+  float *norm = reinterpret_cast<float *>(ws + L.norm);
+  int32_t *jmap = reinterpret_cast<int32_t *>(ws + L.jmap);
+  int32_t *idx = idx_out ? idx_out : reinterpret_cast<int32_t *>(ws + L.idx);
+  float *slots = reinterpret_cast<float *>(ws + L.alpha);
+  float *xc32 = reinterpret_cast<float *>(ws + L.xc32);
+  float *yc = reinterpret_cast<float *>(ws + L.yc);
+
+  auto mark = [&](int stage, int which) -> hipError_t {
+    if (!prof) return hipSuccess;
+    ctx->marked[stage] = true;
+    return hipEventRecord(ctx->ev[stage][which], s);
+  };
+
+  // A: the transform, first pass: only the channel norms of X_wt leave the chip (the same
+  // kernel clears the selection state)
+  WCC_TRY(mark(WCC_T_HAAR_FWD, 0));
+  WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, L.G,
+                           make_prep(ws, L, slots, quant ? alpha_in : 0.f), s));
+  WCC_TRY(mark(WCC_T_HAAR_FWD, 1));
+  // B: norms, index set I (ascending), rank map for the inverse
+  WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
+  WCC_TRY(launch_select(d, L.G == 1 ? norm : part, L.G, norm, k, ws, L, idx, jmap, s));
+  WCC_TRY(mark(WCC_T_NORM_SELECT, 1));
+  // A again + B': the transform, second pass: X_wt[I] is written straight into its compressed
+  // place (the dropped coefficients never reach memory); alpha = max |kept coefficient|
+  WCC_TRY(mark(WCC_T_GATHER, 0));
+  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !(alpha_in > 0.f)) ? slots : nullptr, s));
+  WCC_TRY(mark(WCC_T_GATHER, 1));
+  // C: Y_wt = Conv(K_1x1, X_wt[I]); the kept coefficients are quantised as they are loaded
+  WCC_TRY(mark(WCC_T_POINTWISE, 0));
+  WCC_TRY(launch_pointwise(d, k, w, w_scale, xc32, true, slots, true, quant ? alpha_out_dev : nullptr,
+                           yc, s));
+  WCC_TRY(mark(WCC_T_POINTWISE, 1));
+  // D + E: Y^0[I] = Y_wt, inverse levels
+  WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 0));
+  WCC_TRY(launch_scatter_ihaar(d, k, yc, jmap, y, reinterpret_cast<float *>(ws + L.scratch), residual, s));
+  WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 1));
+  return WCC_OK;
+}
+
+// The two layers of the inverted residual block as layer descriptors.
+wcc_status block_layers(const wcc_block_desc *bd, wcc_desc &d1, wcc_desc &d3) {
+  if (!bd) return WCC_ERR_NULL;
+  if (bd->C < 1 || bd->expansion < 1 || (int64_t)bd->C * bd->expansion > 65535) return WCC_ERR_SHAPE;
+  d1 = wcc_desc{bd->B, bd->C, bd->C * bd->expansion, bd->H, bd->W, bd->levels, bd->keep_num,
+                bd->keep_den, bd->w_dtype, bd->act_quant_bits};
+  d3 = d1;
+  d3.C_in = d1.C_out;
+  d3.C_out = bd->C;
+  const wcc_status st = check_desc(&d1);
+  return st != WCC_OK ? st : check_desc(&d3);
+}
+
+struct BlockLayout { size_t t1, t2, layer, total; };
+
+BlockLayout block_layout(const wcc_block_desc &bd, const wcc_desc &d1, const wcc_desc &d3) {
+  BlockLayout L{};
+  const size_t mid = align256((size_t)bd.B * d1.C_out * bd.H * bd.W * 4);
+  L.t1 = 0;
+  L.t2 = mid;
+  L.layer = 2 * mid;
+  const size_t a = ws_layout(d1).total, b = ws_layout(d3).total;
+  L.total = L.layer + (a > b ? a : b);
   return L;
 }
 
@@ -147,6 +232,7 @@ wcc_status wcc_set_profiling(wcc_ctx *ctx, int enabled) {
   }
   ctx->profiling = enabled != 0;
   ctx->have_times = false;
+  for (bool &m : ctx->marked) m = false;
   return WCC_OK;
 }
 
@@ -154,16 +240,13 @@ wcc_status wcc_stage_times(wcc_ctx *ctx, float *ms) {
   if (!ctx || !ms) return WCC_ERR_NULL;
   if (!ctx->have_times) return WCC_ERR_UNSUPPORTED;
   for (int i = 0; i < WCC_T_COUNT; ++i) {
+    ms[i] = 0.f;
+    if (!ctx->marked[i]) continue;  // a stage the last calls did not run
     if (hipEventSynchronize(ctx->ev[i][1]) != hipSuccess) return WCC_ERR_HIP;
     if (hipEventElapsedTime(&ms[i], ctx->ev[i][0], ctx->ev[i][1]) != hipSuccess) return WCC_ERR_HIP;
   }
   return WCC_OK;
 }
-
-#define WCC_TRY(expr)                                 \
-  do {                                                \
-    if ((expr) != hipSuccess) return WCC_ERR_HIP;     \
-  } while (0)
 
 wcc_status wcc_haar_fwd(wcc_ctx *ctx, const wcc_desc *desc, const float *x, float *coef,
                         float *norm, void *stream) {
@@ -264,7 +347,8 @@ wcc_status wcc_scatter_ihaar(wcc_ctx *ctx, const wcc_desc *desc, const float *yc
   int32_t *jmap = reinterpret_cast<int32_t *>(static_cast<char *>(ctx->ws) + L.jmap);
   WCC_TRY(launch_jmap_from_idx(idx, desc->B, N, k, jmap, s));
   WCC_TRY(launch_scatter_ihaar(*desc, k, yc, jmap, y,
-                               reinterpret_cast<float *>(static_cast<char *>(ctx->ws) + L.scratch), s));
+                               reinterpret_cast<float *>(static_cast<char *>(ctx->ws) + L.scratch),
+                               nullptr, s));
   return WCC_OK;
 }
 
@@ -279,51 +363,84 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   const WsLayout L = ws_layout(*desc);
   if ((st = need_ws(ctx, L)) != WCC_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  char *ws = static_cast<char *>(ctx->ws);
-  const wcc_desc &d = *desc;
-  const int64_t k = k_of(d);
-  const bool quant = d.act_quant_bits == 8;
-
-  float *part = reinterpret_cast<float *>(ws + L.norm_part);
-  float *norm = reinterpret_cast<float *>(ws + L.norm);
-  int32_t *jmap = reinterpret_cast<int32_t *>(ws + L.jmap);
-  int32_t *idx = idx_out ? idx_out : reinterpret_cast<int32_t *>(ws + L.idx);
-  float *slots = reinterpret_cast<float *>(ws + L.alpha);
-  float *xc32 = reinterpret_cast<float *>(ws + L.xc32);
-  float *yc = reinterpret_cast<float *>(ws + L.yc);
-
   const bool prof = ctx->profiling && ctx->ev_ok;
-  auto mark = [&](int stage, int which) -> hipError_t {
-    return prof ? hipEventRecord(ctx->ev[stage][which], s) : hipSuccess;
-  };
+  st = forward_on(ctx, static_cast<char *>(ctx->ws), L, *desc, x, w, w_scale, alpha_in, y, idx_out,
+                  alpha_out_dev, nullptr, prof, s);
+  if (st != WCC_OK) return st;
+  if (prof) {
+    WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][0], s));
+    WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][1], s));
+    ctx->marked[WCC_T_EVENT_PAIR] = true;
+    ctx->have_times = true;
+  }
+  return WCC_OK;
+}
 
-  // A: the transform, first pass: only the channel norms of X_wt leave the chip (the same
-  // kernel clears the selection state)
-  WCC_TRY(mark(WCC_T_HAAR_FWD, 0));
-  WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, L.G,
-                           make_prep(ws, L, slots, quant ? alpha_in : 0.f), s));
-  WCC_TRY(mark(WCC_T_HAAR_FWD, 1));
-  // B: norms, index set I (ascending), rank map for the inverse
-  WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
-  WCC_TRY(launch_select(d, L.G == 1 ? norm : part, L.G, norm, k, ws, L, idx, jmap, s));
-  WCC_TRY(mark(WCC_T_NORM_SELECT, 1));
-  // A again + B': the transform, second pass: X_wt[I] is written straight into its compressed
-  // place (the dropped coefficients never reach memory); alpha = max |kept coefficient|
-  WCC_TRY(mark(WCC_T_GATHER, 0));
-  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !(alpha_in > 0.f)) ? slots : nullptr, s));
-  WCC_TRY(mark(WCC_T_GATHER, 1));
-  // C: Y_wt = Conv(K_1x1, X_wt[I]); the kept coefficients are quantised as they are loaded
-  WCC_TRY(mark(WCC_T_POINTWISE, 0));
-  WCC_TRY(launch_pointwise(d, k, w, w_scale, xc32, true, slots, true, quant ? alpha_out_dev : nullptr,
-                           yc, s));
-  WCC_TRY(mark(WCC_T_POINTWISE, 1));
-  // D + E: Y^0[I] = Y_wt, inverse levels
-  WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 0));
-  WCC_TRY(launch_scatter_ihaar(d, k, yc, jmap, y, reinterpret_cast<float *>(ws + L.scratch), s));
-  WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 1));
-  WCC_TRY(mark(WCC_T_EVENT_PAIR, 0));
-  WCC_TRY(mark(WCC_T_EVENT_PAIR, 1));
-  if (prof) ctx->have_times = true;
+wcc_status wcc_block_workspace_bytes(const wcc_block_desc *desc, size_t *bytes) {
+  if (!bytes) return WCC_ERR_NULL;
+  wcc_desc d1, d3;
+  const wcc_status st = block_layers(desc, d1, d3);
+  if (st != WCC_OK) return st;
+  *bytes = block_layout(*desc, d1, d3).total;
+  return WCC_OK;
+}
+
+wcc_status wcc_depthwise3x3(wcc_ctx *ctx, int32_t B, int32_t C, int32_t H, int32_t W,
+                            const float *x, const float *w, float *y, void *stream) {
+  if (!ctx || !x || !w || !y) return WCC_ERR_NULL;
+  if (B < 1 || C < 1 || H < 1 || W < 1 || B > 65535 || C > 65535) return WCC_ERR_SHAPE;
+  if ((int64_t)H * W > ((int64_t)1 << 30)) return WCC_ERR_SHAPE;
+  if (misaligned(x) || misaligned(y)) return WCC_ERR_ALIGN;
+  WCC_TRY(launch_depthwise3x3(B, C, H, W, x, w, y, static_cast<hipStream_t>(stream)));
+  return WCC_OK;
+}
+
+wcc_status wcc_set_block_profile_layer(wcc_ctx *ctx, int layer) {
+  if (!ctx) return WCC_ERR_NULL;
+  if (layer != 0 && layer != 1) return WCC_ERR_SHAPE;
+  ctx->block_profile_layer = layer;
+  return WCC_OK;
+}
+
+wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const float *x,
+                             const void *w1, const float *w1_scale, const float *w_dw,
+                             const void *w3, const float *w3_scale, float *y, float *t1_out,
+                             float *t2_out, int32_t *idx1_out, int32_t *idx3_out, void *stream) {
+  if (!ctx || !x || !w1 || !w_dw || !w3 || !y) return WCC_ERR_NULL;
+  wcc_desc d1, d3;
+  wcc_status st = block_layers(desc, d1, d3);
+  if (st != WCC_OK) return st;
+  if (desc->w_dtype == WCC_I8 && (!w1_scale || !w3_scale)) return WCC_ERR_NULL;
+  if (misaligned(x) || misaligned(w1) || misaligned(w3) || misaligned(y) || misaligned(t1_out) ||
+      misaligned(t2_out) || misaligned(idx1_out) || misaligned(idx3_out))
+    return WCC_ERR_ALIGN;
+  const BlockLayout BL = block_layout(*desc, d1, d3);
+  if (!ctx->ws || ctx->ws_bytes < BL.total) return WCC_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char *ws = static_cast<char *>(ctx->ws);
+  float *t1 = t1_out ? t1_out : reinterpret_cast<float *>(ws + BL.t1);
+  float *t2 = t2_out ? t2_out : reinterpret_cast<float *>(ws + BL.t2);
+  const bool prof = ctx->profiling && ctx->ev_ok;
+
+  // K1 (expand), K_dw, K3 (project) with the skip connection added by the last kernel
+  st = forward_on(ctx, ws + BL.layer, ws_layout(d1), d1, x, w1, w1_scale, 0.f, t1, idx1_out, nullptr,
+                  nullptr, prof && ctx->block_profile_layer == 0, s);
+  if (st != WCC_OK) return st;
+  if (prof) WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][0], s));
+  WCC_TRY(launch_depthwise3x3(d3.B, d3.C_in, d3.H, d3.W, t1, w_dw, t2, s));
+  if (prof) {
+    WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][1], s));
+    ctx->marked[WCC_T_DEPTHWISE] = true;
+  }
+  st = forward_on(ctx, ws + BL.layer, ws_layout(d3), d3, t2, w3, w3_scale, 0.f, y, idx3_out, nullptr,
+                  x, prof && ctx->block_profile_layer == 1, s);
+  if (st != WCC_OK) return st;
+  if (prof) {
+    WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][0], s));
+    WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][1], s));
+    ctx->marked[WCC_T_EVENT_PAIR] = true;
+    ctx->have_times = true;
+  }
   return WCC_OK;
 }
 

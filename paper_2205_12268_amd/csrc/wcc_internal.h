@@ -157,7 +157,11 @@ hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const f
                             const void *xc, bool xc_is_f32, const float *alpha, bool alpha_is_slots,
                             float *alpha_out, float *yc, hipStream_t s);
 // scratch: kInvScratchBytes of device memory that the kernel may overwrite with anything
+// residual (nullable): [B, C_out, H, W] added to the result (may be y itself)
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
-                                float *y, float *scratch, hipStream_t s);
+                                float *y, float *scratch, const float *residual, hipStream_t s);
+// depthwise 3x3, stride 1, zero padding 1: x, y [B, C, H, W], w [C, 3, 3]
+hipError_t launch_depthwise3x3(int B, int C, int H, int W, const float *x, const float *w, float *y,
+                               hipStream_t s);
 
 }  // namespace wcc

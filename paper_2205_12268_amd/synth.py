@@ -201,3 +201,64 @@ def make_inputs(cfg: LayerCfg, check: bool = True):
     if check:
         assert_exact_budget(x, cfg.levels)
     return x, make_w(cfg)
+
+
+# --------------------------------------------------------------------------- #
+# the inverted residual block (the workload of the paper's timing table)
+# --------------------------------------------------------------------------- #
+@dataclass(frozen=True)
+class BlockCfg:
+    """x + K3(K_dw(K1 x)): C channels in and out, C * expansion in the middle; both 1x1
+    convolutions are WCC layers with the same levels / keep ratio / quantiser."""
+
+    name: str
+    B: int
+    C: int
+    expansion: int
+    H: int
+    W: int
+    levels: int
+    keep_num: int
+    keep_den: int
+    w_dtype: int
+    act_bits: int
+    sigma: float = 3.0
+    clip_hi: float = 8.0
+    seed: int = SEED_BASE + 0x600
+
+    @property
+    def C_mid(self) -> int:
+        return self.C * self.expansion
+
+    @property
+    def N(self) -> int:
+        return self.H * self.W
+
+    @property
+    def k(self) -> int:
+        return (self.keep_num * self.N + self.keep_den - 1) // self.keep_den
+
+    def layer(self, which: int) -> LayerCfg:
+        """Layer descriptor of the expand (0) or project (1) convolution."""
+        ci, co = (self.C, self.C_mid) if which == 0 else (self.C_mid, self.C)
+        return LayerCfg(f"{self.name}_l{which}", self.B, ci, co, self.H, self.W, self.levels,
+                        self.keep_num, self.keep_den, self.w_dtype, self.act_bits, sigma=self.sigma,
+                        clip_hi=self.clip_hi, seed=self.seed + 17 * which)
+
+
+def block_config(keep_num: int = 1, keep_den: int = 4) -> BlockCfg:
+    """A row of the paper's timing table: 256x256 image, c_in 256, expansion 4, batch 8."""
+    return BlockCfg(f"block_256x256_c256_e4_b8_keep{keep_num}of{keep_den}", 8, 256, 4, 256, 256, 3,
+                    keep_num, keep_den, W_BF16, 8)
+
+
+def make_block_inputs(cfg: BlockCfg):
+    """(x, w1, w_dw, w3): x as in the single-layer workloads (dyadic grid), the two 1x1 kernels
+    in their storage type, the depthwise kernel fp32 [C_mid, 3, 3] (multiples of 2**-8, drawn
+    from N(0, 1/9))."""
+    l0, l1 = cfg.layer(0), cfg.layer(1)
+    x = make_x(l0)
+    assert_exact_budget(x, cfg.levels)
+    rng = np.random.default_rng(cfg.seed ^ 0x5A5A5A)
+    w_dw = (np.rint(rng.standard_normal((cfg.C_mid, 3, 3)) / 3.0 * 256.0) / 256.0).astype(np.float32)
+    return x, make_w(l0), w_dw, make_w(l1)

@@ -15,17 +15,26 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libwcc.so")
 
 F32, BF16, I8 = 0, 1, 2
-STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "event_pair")
+STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "event_pair",
+          "depthwise")
 
 EXPORTS = ("wcc_create", "wcc_destroy", "wcc_workspace_bytes", "wcc_set_workspace", "wcc_k",
            "wcc_status_string", "wcc_set_profiling", "wcc_stage_times", "wcc_haar_fwd",
            "wcc_joint_topk", "wcc_gather_quant", "wcc_pointwise", "wcc_scatter_ihaar",
-           "wcc_forward")
+           "wcc_forward", "wcc_block_workspace_bytes", "wcc_depthwise3x3", "wcc_block_forward",
+           "wcc_set_block_profile_layer")
 
 
 class Desc(C.Structure):
     """Mirror of ``wcc_desc``."""
     _fields_ = [("B", C.c_int32), ("C_in", C.c_int32), ("C_out", C.c_int32), ("H", C.c_int32),
+                ("W", C.c_int32), ("levels", C.c_int32), ("keep_num", C.c_int64),
+                ("keep_den", C.c_int64), ("w_dtype", C.c_int32), ("act_quant_bits", C.c_int32)]
+
+
+class BlockDesc(C.Structure):
+    """Mirror of ``wcc_block_desc``."""
+    _fields_ = [("B", C.c_int32), ("C", C.c_int32), ("expansion", C.c_int32), ("H", C.c_int32),
                 ("W", C.c_int32), ("levels", C.c_int32), ("keep_num", C.c_int64),
                 ("keep_den", C.c_int64), ("w_dtype", C.c_int32), ("act_quant_bits", C.c_int32)]
 
@@ -64,6 +73,11 @@ def lib():
         L.wcc_pointwise.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp]
         L.wcc_scatter_ihaar.argtypes = [vp, dp, vp, vp, vp, vp]
         L.wcc_forward.argtypes = [vp, dp, vp, vp, vp, C.c_float, vp, vp, vp, vp]
+        bp = C.POINTER(BlockDesc)
+        L.wcc_block_workspace_bytes.argtypes = [bp, C.POINTER(C.c_size_t)]
+        L.wcc_depthwise3x3.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp, vp]
+        L.wcc_block_forward.argtypes = [vp, bp] + [vp] * 12
+        L.wcc_set_block_profile_layer.argtypes = [vp, C.c_int]
         for name in EXPORTS:
             if name not in ("wcc_k", "wcc_status_string"):
                 getattr(L, name).restype = C.c_int
@@ -91,6 +105,17 @@ def k_of(desc: Desc) -> int:
 def workspace_bytes(desc: Desc) -> int:
     out = C.c_size_t(0)
     _check(lib().wcc_workspace_bytes(C.byref(desc), C.byref(out)), "wcc_workspace_bytes")
+    return int(out.value)
+
+
+def make_block_desc(B, Cc, expansion, H, W, levels, keep_num, keep_den, w_dtype,
+                    act_quant_bits) -> BlockDesc:
+    return BlockDesc(B, Cc, expansion, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits)
+
+
+def block_workspace_bytes(desc: BlockDesc) -> int:
+    out = C.c_size_t(0)
+    _check(lib().wcc_block_workspace_bytes(C.byref(desc), C.byref(out)), "wcc_block_workspace_bytes")
     return int(out.value)
 
 
@@ -126,8 +151,8 @@ class Context:
         except Exception:
             pass
 
-    def ensure_workspace(self, desc: Desc) -> int:
-        need = workspace_bytes(desc)
+    def ensure_workspace(self, desc) -> int:
+        need = block_workspace_bytes(desc) if isinstance(desc, BlockDesc) else workspace_bytes(desc)
         if self._ws is None or self._ws.numel() < need:
             self._ws = torch.empty(need, dtype=torch.uint8, device=f"cuda:{self.device}")
             _check(lib().wcc_set_workspace(self._h, _ptr(self._ws), self._ws.numel()),
@@ -173,3 +198,19 @@ class Context:
         _check(lib().wcc_forward(self._h, C.byref(desc), _ptr(x), _ptr(w), _ptr(w_scale),
                                  C.c_float(alpha_in), _ptr(y), _ptr(idx_out), _ptr(alpha_out),
                                  _stream()), "wcc_forward")
+
+    # ---- the inverted residual block (next row) ----
+    def wcc_depthwise3x3(self, x, w, y):
+        B, Cc, H, W = x.shape
+        _check(lib().wcc_depthwise3x3(self._h, B, Cc, H, W, _ptr(x), _ptr(w), _ptr(y), _stream()),
+               "wcc_depthwise3x3")
+
+    def wcc_block_forward(self, desc, x, w1, w1_scale, w_dw, w3, w3_scale, y, t1_out=None,
+                          t2_out=None, idx1_out=None, idx3_out=None):
+        _check(lib().wcc_block_forward(self._h, C.byref(desc), _ptr(x), _ptr(w1), _ptr(w1_scale),
+                                       _ptr(w_dw), _ptr(w3), _ptr(w3_scale), _ptr(y), _ptr(t1_out),
+                                       _ptr(t2_out), _ptr(idx1_out), _ptr(idx3_out), _stream()),
+               "wcc_block_forward")
+
+    def set_block_profile_layer(self, layer: int) -> None:
+        _check(lib().wcc_set_block_profile_layer(self._h, int(layer)), "wcc_set_block_profile_layer")

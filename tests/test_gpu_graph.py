@@ -11,7 +11,7 @@ import pytest
 import torch
 
 from paper_2205_12268_amd import synth, wcc
-from util import desc_of, dev, upload_weights
+from tests.util import desc_of, dev, upload_weights
 
 pytestmark = pytest.mark.gpu
 
