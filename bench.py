@@ -91,14 +91,131 @@ def bench_stack(args, synth, run_layer, ctx) -> int:
     return 0
 
 
+def bench_block(args, synth, wcc, torch, np) -> int:
+    """The inverted residual block the paper timed (appendix "Inference times"): 256x256 image,
+    c_in 256, expansion 4, batch 8, one row of its table per keep ratio."""
+    num, den = (int(t) for t in args.keep.split("/"))
+    cfg = synth.block_config(num, den)
+    x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
+    d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
+                            cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+    ctx = wcc.Context(0)
+    ctx.ensure_workspace(d)
+
+    def up(a):
+        a = a.view(np.int16) if a.dtype == np.uint16 else a
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    xd, w1d, w3d, wdd = up(x), up(w1.stored), up(w3.stored), up(w_dw)
+    y = torch.empty_like(xd)
+
+    def step():
+        ctx.wcc_block_forward(d, xd, w1d, None, wdd, w3d, None, y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+
+    # per-kernel device times: the stage events bracket one of the two layers at a time
+    stage_us = {}
+    for layer in (0, 1):
+        ctx.set_block_profile_layer(layer)
+        ctx.set_profiling(True)
+        acc = {}
+        for _ in range(args.steps):
+            step()
+            for name, ms in ctx.stage_times().items():
+                acc[name] = acc.get(name, 0.0) + ms
+        ctx.set_profiling(False)
+        pair = acc.pop("event_pair")
+        for name, v in acc.items():
+            key = name if name == "depthwise" else f"l{layer}_{name}"
+            stage_us[key] = max(1e3 * (v - pair) / args.steps, 0.0)
+    alg = {}
+    for layer in (0, 1):
+        for name, v in algorithmic_bytes(cfg.layer(layer)).items():
+            alg[f"l{layer}_{name}"] = v
+    alg["l1_scatter_ihaar"] += 4 * cfg.B * cfg.C * cfg.N          # the skip connection is read
+    alg["depthwise"] = 8 * cfg.B * cfg.C_mid * cfg.N              # read t1, write t2
+    kernel_of = {"depthwise": "depthwise3x3_kernel"}
+    for layer in (0, 1):
+        for name, kname in STAGE_KERNEL.items():
+            kernel_of[f"l{layer}_{name}"] = kname
+    dom = max(kernel_of, key=lambda n: stage_us[n])
+    achieved = alg[dom] / (stage_us[dom] * 1e-6) / 1e9
+
+    # the dense block on the same GPU (the "standard" column of the paper's table), bf16, from
+    # the framework's library convolutions
+    dense_ms = None
+    try:
+        F = torch.nn.functional
+        xb = xd.to(torch.bfloat16)
+        k1 = torch.from_numpy(w1.values.astype(np.float32)).cuda().to(torch.bfloat16)[:, :, None, None]
+        k3 = torch.from_numpy(w3.values.astype(np.float32)).cuda().to(torch.bfloat16)[:, :, None, None]
+        kd = wdd.to(torch.bfloat16)[:, None]
+
+        def dense():
+            return xb + F.conv2d(F.conv2d(F.conv2d(xb, k1), kd, padding=1, groups=cfg.C_mid), k3)
+
+        for _ in range(3):
+            dense()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            dense()
+        torch.cuda.synchronize()
+        dense_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    except Exception as exc:  # the library convolution is context only
+        print(f"bench.py: dense block baseline skipped ({exc})", file=sys.stderr)
+
+    pix_ch = cfg.B * cfg.N * cfg.C
+    out = {
+        "metric": "WCC layer forward throughput", "value": round(pix_ch / dt / 1e9, 3),
+        "unit": "Gpixel*ch/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": "eager",
+        "config": {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "expansion": cfg.expansion,
+                   "H": cfg.H, "W": cfg.W, "levels": cfg.levels, "keep": f"{num}/{den}",
+                   "act_bits": cfg.act_bits},
+        "roofline": {"bound": "hbm", "kernel": kernel_of[dom], "stage": dom,
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": alg[dom], "kernel_us": round(stage_us[dom], 2)},
+        "stages_us": {n: round(v, 2) for n, v in stage_us.items()},
+        "block_alg_GBs": round(sum(alg.values()) / dt / 1e9, 1),
+        "dense_block_ms": None if dense_ms is None else round(dense_ms, 4),
+        "speedup_vs_dense": None if dense_ms is None else round(dense_ms / (dt * 1e3), 3),
+    }
+    if not args.no_cpu_baseline:
+        from oracle import wcc_ref
+        cores = min(len(os.sched_getaffinity(0)), 16)
+        wcc_ref.set_threads(cores)
+        t1 = time.perf_counter()
+        wcc_ref.block_forward(x[:1], w1.values, None, w_dw, w3.values, None, cfg.levels,
+                              cfg.keep_num, cfg.keep_den, cfg.act_bits)
+        cpu_dt = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": round(cfg.N * cfg.C / cpu_dt / 1e9, 5), "unit": "Gpixel*ch/s",
+                               "cores": cores, "kind": "oracle",
+                               "sample": f"block forward of 1 of the {cfg.B} samples, {cpu_dt:.2f} s"}
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2,
-                    help="single-layer workload 1..4, or 5 = the 16-layer backbone stack")
-    ap.add_argument("--keep", default="1/4", help="kept fraction for --config 5 (num/den)")
+                    help="single-layer workload 1..4, 5 = the 16-layer backbone stack, "
+                         "6 = the inverted residual block of the paper's timing table")
+    ap.add_argument("--keep", default="1/4", help="kept fraction for --config 5 and 6 (num/den)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
                     help="graph: the step is recorded once into a HIP graph and replayed")
@@ -179,6 +296,8 @@ def main() -> int:
         stage_us = {n: max(1e3 * v / args.steps - pair_us, 0.0) for n, v in acc.items()}
         return dt, stage_us, pair_us, x, w
 
+    if args.config == 6:
+        return bench_block(args, synth, wcc, torch, np)
     ctx = wcc.Context(0)
     if args.config == 5:
         return bench_stack(args, synth, run_layer, ctx)

@@ -78,3 +78,86 @@ def test_full_size_forward(ref, n):
     en_ref = np.linalg.norm(yc, axis=2)
     assert rel_l2(en_gpu, en_ref) <= tol
     ctx.close()
+
+
+def test_full_size_block(ref):
+    """The block workload bench.py --config 6 times (256x256, c 256, expansion 4, batch 8,
+    keep 1/4), checked where the oracle can follow: the first layer's index sets in full, K_dw
+    on sampled planes, and the second layer on one sample (valid index set for the fp64 norms
+    of the GPU's own middle tensor, output for that index set)."""
+    cfg = synth.block_config(1, 4)
+    print(f"workload {cfg.name}: generating inputs", flush=True)
+    x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
+    l0, l1 = cfg.layer(0), cfg.layer(1)
+    N, k = cfg.N, cfg.k
+    d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
+                            cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+    ctx = wcc.Context(0)
+    ctx.ensure_workspace(d)
+    xd = dev(x)
+    w1d, _ = upload_weights(w1)
+    w3d, _ = upload_weights(w3)
+    mid = (cfg.B, cfg.C_mid, cfg.H, cfg.W)
+    t1 = torch.empty(mid, dtype=torch.float32, device="cuda")
+    t2 = torch.empty(mid, dtype=torch.float32, device="cuda")
+    y = torch.empty(x.shape, dtype=torch.float32, device="cuda")
+    idx1 = torch.empty((cfg.B, k), dtype=torch.int32, device="cuda")
+    idx3 = torch.empty((cfg.B, k), dtype=torch.int32, device="cuda")
+    print("  gpu block forward", flush=True)
+    ctx.wcc_block_forward(d, xd, w1d, None, dev(w_dw), w3d, None, y, t1, t2, idx1, idx3)
+    torch.cuda.synchronize()
+    y2 = torch.empty_like(y)
+    ctx.wcc_block_forward(d, xd, w1d, None, dev(w_dw), w3d, None, y2)  # middle tensors in the workspace
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    del y2
+
+    print("  oracle: first layer's selection", flush=True)
+    coef = ref.haar_fwd(x, cfg.levels).reshape(cfg.B, cfg.C, N)
+    o_idx1 = ref.topk(ref.channel_norm(coef), k)
+    np.testing.assert_array_equal(idx1.cpu().numpy().astype(np.int64), o_idx1)
+    xc = ref.gather(coef, o_idx1)
+    del coef
+    a1 = float(np.float32(ref.absmax(xc)))
+    print("  oracle: first layer's output on sampled planes", flush=True)
+    xhat = ref.quant_codes(xc, a1, 8)
+    del xc
+    rng = np.random.default_rng(6)
+    planes = {(0, 0), (cfg.B - 1, cfg.C_mid - 1)}
+    while len(planes) < 5:
+        planes.add((int(rng.integers(cfg.B)), int(rng.integers(cfg.C_mid))))
+    for (b, o) in sorted(planes):
+        yc = ref.pointwise(w1.values[o:o + 1], np.array([a1 / 127.0]), xhat[b:b + 1])
+        want = ref.haar_inv(ref.scatter(yc, o_idx1[b:b + 1], N), cfg.H, cfg.W, cfg.levels)[0, 0]
+        got_t1 = t1[b, o].cpu().numpy()
+        assert rel_l2(got_t1, want) <= 1e-2, (b, o)
+        # K_dw on the GPU's own plane
+        want2 = ref.depthwise3x3(got_t1[None, None], w_dw[o:o + 1])[0, 0]
+        assert rel_l2(t2[b, o].cpu().numpy(), want2) <= 1e-6, (b, o)
+    del xhat
+
+    print("  oracle: second layer's alpha over all samples, selection and output on sample 0", flush=True)
+    g_idx3 = idx3.cpu().numpy().astype(np.int64)
+    a3, keep0 = 0.0, None
+    for b in range(cfg.B):
+        cb = ref.haar_fwd(t2[b:b + 1].cpu().numpy().astype(np.float64), cfg.levels).reshape(1, cfg.C_mid, N)
+        xcb = ref.gather(cb, g_idx3[b:b + 1])
+        a3 = max(a3, ref.absmax(xcb))
+        if b == 0:
+            norm0 = ref.channel_norm(cb)[0]
+            keep0 = xcb
+        del cb
+    a3 = float(np.float32(a3))
+    sel = g_idx3[0]
+    assert np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] < N
+    kth = np.sort(norm0)[::-1][k - 1]
+    dropped = np.ones(N, dtype=bool)
+    dropped[sel] = False
+    assert norm0[sel].min() >= kth * (1 - 1e-5) and norm0[dropped].max() <= kth * (1 + 1e-5)
+    yc = ref.pointwise(w3.values, np.full(cfg.C, a3 / 127.0), ref.quant_codes(keep0, a3, 8))
+    want = ref.haar_inv(ref.scatter(yc, g_idx3[0:1], N), cfg.H, cfg.W, cfg.levels)[0]
+    got = y[0].cpu().numpy().astype(np.float64) - x[0].astype(np.float64)
+    err = rel_l2(got, want)
+    print(f"  sample 0 branch rel-L2 = {err:.3e}", flush=True)
+    assert err <= 1e-2
+    ctx.close()
