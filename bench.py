@@ -141,7 +141,8 @@ def bench_block(args, synth, wcc, torch, np) -> int:
         for name, v in algorithmic_bytes(cfg.layer(layer)).items():
             alg[f"l{layer}_{name}"] = v
     alg["l1_scatter_ihaar"] += 4 * cfg.B * cfg.C * cfg.N          # the skip connection is read
-    alg["depthwise"] = 8 * cfg.B * cfg.C_mid * cfg.N              # read t1, write t2
+    # K_dw is folded into the project layer's passes when W % 4 == 0 (its output is never written)
+    alg["depthwise"] = 0 if cfg.W % 4 == 0 else 8 * cfg.B * cfg.C_mid * cfg.N
     kernel_of = {"depthwise": "depthwise3x3_kernel"}
     for layer in (0, 1):
         for name, kname in STAGE_KERNEL.items():

@@ -219,6 +219,116 @@ __device__ __forceinline__ void channel_loop(const float *__restrict__ src, int6
   }
 }
 
+// ---- the same walk with a depthwise 3x3 convolution in front of the transform --------------
+// (the paper's third ingredient: consecutive separable operations fused, so the convolved
+// tensor is never written).  The transform's input tile is K_dw applied to the 2^d + 2 rows
+// x (V + 2) columns around it: cross-correlation, zero padding 1, the same order of
+// multiply-adds as the stand-alone kernel in depthwise.hip, so both give the same bits.
+// The two columns outside a lane's V come from the neighbouring lanes' rows through a lane
+// shuffle; the first and last lane of a wave row take theirs from memory (EDGE) or, where that
+// is the border of the plane, zero.  Every load is issued on every path: rows above / below the
+// plane and edge columns that do not exist are read from a valid address and masked.
+struct DwLane {
+  int row_step;       // W
+  int top_step;       // offset of the row above the strip relative to its first row: -W or 0
+  int bot_step;       // offset of the row below relative to the first row: R*W or (R-1)*W
+  bool top_in, bot_in;
+  bool first, last;   // lane is the first / last of its wave row (or the last one inside the plane)
+  int left_off, right_off;  // EDGE: element offsets of the outside columns (0: none to read)
+};
+
+template <int D, int V>
+__device__ __forceinline__ DwLane dw_lane(const Geo &g, const StripMap &m, const LanePos<D> &p,
+                                          int row0, int col0) {
+  constexpr int R = 1 << D;
+  DwLane q;
+  q.row_step = g.W;
+  q.top_in = row0 > 0;
+  q.bot_in = row0 + R < g.H;
+  q.top_step = q.top_in ? -g.W : 0;
+  q.bot_step = q.bot_in ? R * g.W : (R - 1) * g.W;
+  q.first = p.lc == 0;
+  q.last = p.lc == m.lpr - 1 || col0 + V >= g.W;
+  q.left_off = (q.first && col0 > 0) ? -1 : 0;
+  q.right_off = (q.last && col0 + V < g.W) ? V : 0;
+  return q;
+}
+
+template <int D, int V, bool EDGE, bool PEEL, class Sink, class After>
+__device__ __forceinline__ void channel_loop_dw(const float *__restrict__ src,
+                                                const float *__restrict__ wdw, int64_t N, int n_ch,
+                                                const DwLane &q, const LanePos<D> &p, Sink &sink,
+                                                After &&after) {
+  constexpr int R = 1 << D, RR = R + 2;
+  float raw[2][RR][V];
+  float el[2][EDGE ? RR : 1], er[2][EDGE ? RR : 1];
+  auto row_ptr = [&](const float *plane, int i) -> const float * {
+    return i == 0 ? plane + q.top_step : i == RR - 1 ? plane + q.bot_step
+                                                     : plane + (size_t)(i - 1) * q.row_step;
+  };
+  auto load_tile = [&](int u, int ch) {
+    const float *plane = src + (size_t)min(ch, n_ch - 1) * N;
+#pragma unroll
+    for (int i = 0; i < RR; ++i) {
+      const float *rp = row_ptr(plane, i);
+      load_row<V>(rp, raw[u][i]);
+      if constexpr (EDGE) {
+        el[u][i] = rp[q.left_off];
+        er[u][i] = rp[q.right_off];
+      }
+    }
+  };
+  auto transform = [&](int u, int ch) {
+    float k[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) k[t] = wdw[(size_t)ch * 9 + t];
+    float six[RR][V + 2];
+#pragma unroll
+    for (int i = 0; i < RR; ++i) {
+      const bool in = i == 0 ? q.top_in : i == RR - 1 ? q.bot_in : true;
+#pragma unroll
+      for (int e = 0; e < V; ++e) six[i][e + 1] = in ? raw[u][i][e] : 0.f;
+      float l = __shfl_up(six[i][V], 1, kWave), r = __shfl_down(six[i][1], 1, kWave);
+      if (q.first) l = (EDGE && in && q.left_off != 0) ? el[u][i] : 0.f;
+      if (q.last) r = (EDGE && in && q.right_off != 0) ? er[u][i] : 0.f;
+      six[i][0] = l;
+      six[i][V + 1] = r;
+    }
+    float tile[R][V];
+#pragma unroll
+    for (int o = 0; o < R; ++o) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) tile[o][e] = 0.f;
+#pragma unroll
+      for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+#pragma unroll
+          for (int e = 0; e < V; ++e) tile[o][e] = fmaf(k[i * 3 + j], six[o + i][e + j], tile[o][e]);
+    }
+    fwd_levels<D, V, 1>(tile, p, sink);
+    after(sink);
+  };
+  load_tile(0, 0);
+  auto round = [&](int c) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      load_tile(u ^ 1, c + u + 1);
+      __builtin_amdgcn_sched_barrier(0);  // the loads go out before the arithmetic, not after
+      transform(u, c + u);
+    }
+  };
+  int c = 0;
+  if constexpr (PEEL) {
+    if (1 < n_ch) {
+      round(0);
+      c = 2;
+    }
+  }
+  for (; c + 1 < n_ch; c += 2) round(c);
+  if (c < n_ch) transform(0, c);
+}
+
 // x [B, C, H, W] -> coef [B, C, N]; partial norms over this block's channel group to
 // norm_part [G, B, N] (nullable).  block = 256.
 // SPLIT = false: grid = (ceil(units/4), G, B); each wave of a workgroup takes its own strip unit
@@ -227,12 +337,15 @@ __device__ __forceinline__ void channel_loop(const float *__restrict__ src, int6
 //                of the group's channels each (four times the waves in flight for the same
 //                number of partial-norm planes); their |coefficient| sums meet in LDS and are
 //                added in wave order.
-template <int D, int V, bool SPLIT, bool STORE, int PF>
+// DWM: 0 = x is transformed as it is; 1, 2 = K_dw x is (wdw [C, 3, 3]; 2: the outside columns
+// of a wave row's first and last lane exist and are read).
+template <int D, int V, bool SPLIT, bool STORE, int PF, int DWM = 0>
 __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__ x,
                                                        float *__restrict__ coef,
                                                        float *__restrict__ norm_part, Geo g,
                                                        StripMap m, int C, int Cg, int B,
-                                                       SelectPrep prep) {
+                                                       SelectPrep prep,
+                                                       const float *__restrict__ wdw = nullptr) {
   constexpr int NS = slot_count(D, V);
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int unit = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * 4 + wv;
@@ -258,9 +371,15 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__
     const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
     sink.plane = STORE ? coef + ((size_t)b * C + c0) * g.N : nullptr;
     const int64_t N = g.N;
-    channel_loop<D, V, PF>(src, N, g.W, c1 - c0, p, sink, [N](FwdSink<D, V, STORE> &sk) {
-      if (STORE) sk.plane += N;
-    });
+    if constexpr (DWM == 0) {
+      channel_loop<D, V, PF>(src, N, g.W, c1 - c0, p, sink, [N](FwdSink<D, V, STORE> &sk) {
+        if (STORE) sk.plane += N;
+      });
+    } else {
+      const DwLane q = dw_lane<D, V>(g, m, p, row0, col0);
+      channel_loop_dw<D, V, DWM == 2, false>(src, wdw + (size_t)c0 * 9, N, c1 - c0, q, p, sink,
+                                             [](FwdSink<D, V, STORE> &) {});
+    }
   }
 
   if (norm_part == nullptr) return;
@@ -338,12 +457,13 @@ struct KeepSink {
   }
 };
 
-// grid = (ceil(units/4), G, B), block = 256
-template <int D, int V, int PF>
+// grid = (ceil(units/4), G, B), block = 256.  DWM as in haar_fwd_kernel.
+template <int D, int V, int PF, int DWM = 0>
 __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict__ x,
                                                         const int32_t *__restrict__ jmap,
                                                         float *__restrict__ xc, float *alpha_slots,
-                                                        Geo g, StripMap m, int C, int Cg, int64_t k) {
+                                                        Geo g, StripMap m, int C, int Cg, int64_t k,
+                                                        const float *__restrict__ wdw = nullptr) {
   __shared__ float wmax[4];
   const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int grp = blockIdx.y, b = blockIdx.z;
@@ -390,7 +510,13 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict_
   if (active && c0 < c1) {
     const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
     sink.plane = xc + ((size_t)b * C + c0) * k;
-    channel_loop<D, V, PF>(src, g.N, g.W, c1 - c0, p, sink, [k](KeepSink<D, V> &sk) { sk.plane += k; });
+    if constexpr (DWM == 0) {
+      channel_loop<D, V, PF>(src, g.N, g.W, c1 - c0, p, sink, [k](KeepSink<D, V> &sk) { sk.plane += k; });
+    } else {
+      const DwLane q = dw_lane<D, V>(g, m, p, row0, col0);
+      channel_loop_dw<D, V, DWM == 2, true>(src, wdw + (size_t)c0 * 9, g.N, c1 - c0, q, p, sink,
+                                            [k](KeepSink<D, V> &sk) { sk.plane += k; });
+    }
   }
   if (alpha_slots == nullptr) return;
   float mx = sink.vmax;
@@ -767,35 +893,60 @@ struct Plan {
   int pf;      // prefetch depth in channels (1 or 2)
 };
 
+// does a wave row span less than the plane's width (so that its end lanes have neighbours
+// in memory)?
+bool dw_needs_edges(const StripMap &m) { return m.col_segs > 1 || m.lpr < m.lanes_w; }
+
 template <int D, int V, bool STORE>
 hipError_t fwd_launch(const wcc_desc &d, const float *x, float *coef, float *norm_part, Plan pl,
-                      const SelectPrep &prep, hipStream_t s) {
+                      const SelectPrep &prep, const float *wdw, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_in + pl.G - 1) / pl.G;
   const dim3 grid_split(m.units, pl.G, d.B), grid_flat((m.units + 3) / 4, pl.G, d.B), block(256);
-#define WCC_FWD(SPLIT, PF)                                                                        \
-  hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, STORE, PF>), SPLIT ? grid_split : grid_flat,   \
-                     block, 0, s, x, coef, norm_part, g, m, d.C_in, Cg, d.B, prep)
-  if (pl.split) { if (pl.pf == 2) WCC_FWD(true, 2); else WCC_FWD(true, 1); }
-  else          { if (pl.pf == 2) WCC_FWD(false, 2); else WCC_FWD(false, 1); }
+#define WCC_FWD(SPLIT, PF, DWM)                                                                       \
+  hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, STORE, PF, DWM>), SPLIT ? grid_split : grid_flat,  \
+                     block, 0, s, x, coef, norm_part, g, m, d.C_in, Cg, d.B, prep, wdw)
+  if constexpr (!STORE && V == 4) {
+    if (wdw != nullptr) {  // K_dw in front of the transform (norm-only pass)
+      const bool edges = dw_needs_edges(m);
+      if (pl.split) { if (edges) WCC_FWD(true, 1, 2); else WCC_FWD(true, 1, 1); }
+      else          { if (edges) WCC_FWD(false, 1, 2); else WCC_FWD(false, 1, 1); }
+      return hipGetLastError();
+    }
+  }
+  if (wdw != nullptr) return hipErrorInvalidValue;
+  if (pl.split) { if (pl.pf == 2) WCC_FWD(true, 2, 0); else WCC_FWD(true, 1, 0); }
+  else          { if (pl.pf == 2) WCC_FWD(false, 2, 0); else WCC_FWD(false, 1, 0); }
 #undef WCC_FWD
   return hipGetLastError();
 }
 
 template <int D, int V>
 hipError_t keep_launch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, float *xc,
-                       float *alpha_slots, Plan pl, hipStream_t s) {
+                       float *alpha_slots, Plan pl, const float *wdw, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_in + pl.G - 1) / pl.G;
   dim3 grid((m.units + 3) / 4, pl.G, d.B);
+  if constexpr (V == 4) {
+    if (wdw != nullptr) {  // K_dw in front of the transform
+      if (dw_needs_edges(m))
+        hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 2>), grid, dim3(256), 0, s, x, jmap, xc,
+                           alpha_slots, g, m, d.C_in, Cg, k, wdw);
+      else
+        hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 1>), grid, dim3(256), 0, s, x, jmap, xc,
+                           alpha_slots, g, m, d.C_in, Cg, k, wdw);
+      return hipGetLastError();
+    }
+  }
+  if (wdw != nullptr) return hipErrorInvalidValue;
   if (pl.pf == 2)
-    hipLaunchKernelGGL((haar_keep_kernel<D, V, 2>), grid, dim3(256), 0, s, x, jmap, xc, alpha_slots, g,
-                       m, d.C_in, Cg, k);
+    hipLaunchKernelGGL((haar_keep_kernel<D, V, 2, 0>), grid, dim3(256), 0, s, x, jmap, xc, alpha_slots,
+                       g, m, d.C_in, Cg, k, wdw);
   else
-    hipLaunchKernelGGL((haar_keep_kernel<D, V, 1>), grid, dim3(256), 0, s, x, jmap, xc, alpha_slots, g,
-                       m, d.C_in, Cg, k);
+    hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0>), grid, dim3(256), 0, s, x, jmap, xc, alpha_slots,
+                       g, m, d.C_in, Cg, k, wdw);
   return hipGetLastError();
 }
 
@@ -837,27 +988,27 @@ int forward_groups(const wcc_desc &d) { return groups_for(d, d.C_in, 1024, 16); 
 
 template <bool STORE>
 hipError_t fwd_dispatch(const wcc_desc &d, const float *x, float *coef, float *norm_part, Plan pl,
-                        const SelectPrep &prep, hipStream_t s) {
+                        const SelectPrep &prep, const float *wdw, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
-    case 1: return v4 ? fwd_launch<1, 4, STORE>(d, x, coef, norm_part, pl, prep, s)
-                      : fwd_launch<1, 2, STORE>(d, x, coef, norm_part, pl, prep, s);
-    case 2: return fwd_launch<2, 4, STORE>(d, x, coef, norm_part, pl, prep, s);
-    case 3: return fwd_launch<3, 4, STORE>(d, x, coef, norm_part, pl, prep, s);
-    case 4: return fwd_launch<4, 4, STORE>(d, x, coef, norm_part, pl, prep, s);
+    case 1: return v4 ? fwd_launch<1, 4, STORE>(d, x, coef, norm_part, pl, prep, wdw, s)
+                      : fwd_launch<1, 2, STORE>(d, x, coef, norm_part, pl, prep, wdw, s);
+    case 2: return fwd_launch<2, 4, STORE>(d, x, coef, norm_part, pl, prep, wdw, s);
+    case 3: return fwd_launch<3, 4, STORE>(d, x, coef, norm_part, pl, prep, wdw, s);
+    case 4: return fwd_launch<4, 4, STORE>(d, x, coef, norm_part, pl, prep, wdw, s);
   }
   return hipErrorInvalidValue;
 }
 
 hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, float *xc,
-                         float *alpha_slots, Plan pl, hipStream_t s) {
+                         float *alpha_slots, Plan pl, const float *wdw, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
-    case 1: return v4 ? keep_launch<1, 4>(d, k, x, jmap, xc, alpha_slots, pl, s)
-                      : keep_launch<1, 2>(d, k, x, jmap, xc, alpha_slots, pl, s);
-    case 2: return keep_launch<2, 4>(d, k, x, jmap, xc, alpha_slots, pl, s);
-    case 3: return keep_launch<3, 4>(d, k, x, jmap, xc, alpha_slots, pl, s);
-    case 4: return keep_launch<4, 4>(d, k, x, jmap, xc, alpha_slots, pl, s);
+    case 1: return v4 ? keep_launch<1, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s)
+                      : keep_launch<1, 2>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
+    case 2: return keep_launch<2, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
+    case 3: return keep_launch<3, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
+    case 4: return keep_launch<4, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
   }
   return hipErrorInvalidValue;
 }
@@ -887,18 +1038,20 @@ Plan fwd_plan(const wcc_desc &d, int G) {
 
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
                            const SelectPrep &prep, hipStream_t s) {
-  return fwd_dispatch<true>(d, x, coef, norm_part, fwd_plan(d, G), prep, s);
+  return fwd_dispatch<true>(d, x, coef, norm_part, fwd_plan(d, G), prep, nullptr, s);
 }
 
 hipError_t launch_haar_norm(const wcc_desc &d, const float *x, float *norm_part, int G,
-                            const SelectPrep &prep, hipStream_t s) {
-  return fwd_dispatch<false>(d, x, nullptr, norm_part, fwd_plan(d, G), prep, s);
+                            const SelectPrep &prep, const float *wdw, hipStream_t s) {
+  Plan pl = fwd_plan(d, G);
+  if (wdw) pl.pf = 1;
+  return fwd_dispatch<false>(d, x, nullptr, norm_part, pl, prep, wdw, s);
 }
 
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap,
-                            float *xc, float *alpha_slots, hipStream_t s) {
+                            float *xc, float *alpha_slots, const float *wdw, hipStream_t s) {
   const Plan pl{groups_for(d, d.C_in, 1024, 8), false, 1};
-  return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, s);
+  return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
 }
 
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,

@@ -85,12 +85,13 @@ WsLayout ws_layout(const wcc_desc &d) {
 
 
 // One WCC layer (Alg. 1 with the quantiser) on a workspace that starts at `ws`.  residual
-// (nullable, [B, C_out, H, W]) is added to the output by the last kernel.  prof: bracket the
+// (nullable, [B, C_out, H, W]) is added to the output by the last kernel.  wdw (nullable,
+// [C_in, 3, 3]): the layer's input is K_dw x, convolved on the fly by both transform passes.  prof: bracket the
 // stages with the context's events.
 wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc &d, const float *x,
                       const void *w, const float *w_scale, float alpha_in, float *y,
-                      int32_t *idx_out, float *alpha_out_dev, const float *residual, bool prof,
-                      hipStream_t s) {
+                      int32_t *idx_out, float *alpha_out_dev, const float *residual,
+                      const float *wdw, bool prof, hipStream_t s) {
   const int64_t k = k_of(d);
   const bool quant = d.act_quant_bits == 8;
 
@@ -112,7 +113,7 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
   // kernel clears the selection state)
   WCC_TRY(mark(WCC_T_HAAR_FWD, 0));
   WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, L.G,
-                           make_prep(ws, L, slots, quant ? alpha_in : 0.f), s));
+                           make_prep(ws, L, slots, quant ? alpha_in : 0.f), wdw, s));
   WCC_TRY(mark(WCC_T_HAAR_FWD, 1));
   // B: norms, index set I (ascending), rank map for the inverse
   WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
@@ -121,7 +122,7 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
   // A again + B': the transform, second pass: X_wt[I] is written straight into its compressed
   // place (the dropped coefficients never reach memory); alpha = max |kept coefficient|
   WCC_TRY(mark(WCC_T_GATHER, 0));
-  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !(alpha_in > 0.f)) ? slots : nullptr, s));
+  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !(alpha_in > 0.f)) ? slots : nullptr, wdw, s));
   WCC_TRY(mark(WCC_T_GATHER, 1));
   // C: Y_wt = Conv(K_1x1, X_wt[I]); the kept coefficients are quantised as they are loaded
   WCC_TRY(mark(WCC_T_POINTWISE, 0));
@@ -365,7 +366,7 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool prof = ctx->profiling && ctx->ev_ok;
   st = forward_on(ctx, static_cast<char *>(ctx->ws), L, *desc, x, w, w_scale, alpha_in, y, idx_out,
-                  alpha_out_dev, nullptr, prof, s);
+                  alpha_out_dev, nullptr, nullptr, prof, s);
   if (st != WCC_OK) return st;
   if (prof) {
     WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][0], s));
@@ -424,16 +425,23 @@ wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const flo
 
   // K1 (expand), K_dw, K3 (project) with the skip connection added by the last kernel
   st = forward_on(ctx, ws + BL.layer, ws_layout(d1), d1, x, w1, w1_scale, 0.f, t1, idx1_out, nullptr,
-                  nullptr, prof && ctx->block_profile_layer == 0, s);
+                  nullptr, nullptr, prof && ctx->block_profile_layer == 0, s);
   if (st != WCC_OK) return st;
-  if (prof) WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][0], s));
-  WCC_TRY(launch_depthwise3x3(d3.B, d3.C_in, d3.H, d3.W, t1, w_dw, t2, s));
-  if (prof) {
-    WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][1], s));
-    ctx->marked[WCC_T_DEPTHWISE] = true;
+  // K_dw is folded into the two transform passes of the project layer (its output is never
+  // written) when the width allows; the stand-alone kernel runs otherwise, and when the caller
+  // asks for K_dw's output
+  const bool fold = desc->W % 4 == 0;
+  if (!fold || t2_out) {
+    if (prof) WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][0], s));
+    WCC_TRY(launch_depthwise3x3(d3.B, d3.C_in, d3.H, d3.W, t1, w_dw, t2, s));
+    if (prof) {
+      WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][1], s));
+      ctx->marked[WCC_T_DEPTHWISE] = true;
+    }
   }
-  st = forward_on(ctx, ws + BL.layer, ws_layout(d3), d3, t2, w3, w3_scale, 0.f, y, idx3_out, nullptr,
-                  x, prof && ctx->block_profile_layer == 1, s);
+  st = forward_on(ctx, ws + BL.layer, ws_layout(d3), d3, fold ? t1 : t2, w3, w3_scale, 0.f, y,
+                  idx3_out, nullptr, x, fold ? w_dw : nullptr,
+                  prof && ctx->block_profile_layer == 1, s);
   if (st != WCC_OK) return st;
   if (prof) {
     WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][0], s));

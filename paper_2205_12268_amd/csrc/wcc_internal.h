@@ -127,10 +127,13 @@ int forward_groups(const wcc_desc &d);
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part,
                            int G, const SelectPrep &prep, hipStream_t s);
 // norm-only pass (no coefficient is written) and keep-only pass of the fused layer
+// wdw (nullable, [C_in, 3, 3]): the transform's input is the depthwise 3x3 convolution of x
+// with these kernels, computed on the fly; needs W % 4 == 0
 hipError_t launch_haar_norm(const wcc_desc &d, const float *x, float *norm_part, int G,
-                            const SelectPrep &prep, hipStream_t s);
+                            const SelectPrep &prep, const float *wdw, hipStream_t s);
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap,
-                            float *xc, float *alpha_slots /*nullable*/, hipStream_t s);
+                            float *xc, float *alpha_slots /*nullable*/, const float *wdw /*nullable*/,
+                            hipStream_t s);
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s);
 hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, float *norm, hipStream_t s);
 SelectPrep make_prep(void *ws_base, const WsLayout &L, float *alpha_slots, float alpha_in);

@@ -51,6 +51,11 @@ CASES = [
     synth.BlockCfg("blk_i8_d3", 1, 32, 2, 64, 128, 3, 1, 8, I8, 8, sigma=3.0, seed=synth.SEED_BASE + 0x611),
     synth.BlockCfg("blk_f32_d1", 2, 8, 3, 16, 24, 1, 1, 2, F32, 0, sigma=1.0, seed=synth.SEED_BASE + 0x612),
     synth.BlockCfg("blk_bf16_big_plane", 1, 8, 6, 128, 256, 3, 1, 4, BF16, 8, sigma=3.0, seed=synth.SEED_BASE + 0x613),
+    # rows wider than a wave: the folded K_dw reads its outside columns from memory
+    synth.BlockCfg("blk_bf16_wide", 1, 8, 2, 16, 320, 2, 1, 4, BF16, 8, sigma=2.0, seed=synth.SEED_BASE + 0x614),
+    synth.BlockCfg("blk_i8_wide_d1", 2, 16, 2, 8, 1024, 1, 1, 2, I8, 8, sigma=2.0, seed=synth.SEED_BASE + 0x615),
+    # W % 4 != 0: K_dw stays a kernel of its own
+    synth.BlockCfg("blk_f32_odd_width", 1, 4, 2, 8, 10, 1, 1, 2, F32, 0, sigma=1.0, seed=synth.SEED_BASE + 0x616),
 ]
 
 
