@@ -235,6 +235,9 @@ def main() -> int:
                          "6 = the inverted residual block of the paper's timing table")
     ap.add_argument("--keep", default="1/4", help="kept fraction for --config 5 and 6 (num/den)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--index-list", choices=["select", "prefix"], default="select",
+                    help="prefix: wcc_forward_fixed with the first k positions instead of the joint "
+                         "shrinkage's top-k (single-layer workloads)")
     ap.add_argument("--no-dense-baseline", action="store_true",
                     help="--config 6: skip timing the dense block built from library convolutions")
     ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
@@ -271,7 +274,10 @@ def main() -> int:
         y = torch.empty((cfg.B, cfg.C_out, cfg.H, cfg.W), dtype=torch.float32, device="cuda")
 
         def step():
-            ctx.wcc_forward(d, xd, wd, wsd, 0.0, y)
+            if args.index_list == "prefix":
+                ctx.wcc_forward_fixed(d, xd, wd, wsd, 0.0, None, y)
+            else:
+                ctx.wcc_forward(d, xd, wd, wsd, 0.0, y)
 
         if args.copy_probe:
             probe = torch.empty_like(xd)
@@ -327,6 +333,8 @@ def main() -> int:
     pix_ch = cfg.B * cfg.H * cfg.W * cfg.C_in
     value = pix_ch / dt / 1e9
     alg = algorithmic_bytes(cfg)
+    if args.index_list == "prefix":  # no norm pass, no selection: only the rank map is written
+        alg["haar_fwd"], alg["norm_select"] = 0, 4 * cfg.B * cfg.N
     dom = max(STAGE_KERNEL, key=lambda n: stage_us[n])  # the single kernel that takes longest
     achieved = alg[dom] / (stage_us[dom] * 1e-6) / 1e9
     traffic = read_traffic(os.path.join(ROOT, "profiles"), cfg.name, STAGE_KERNEL[dom])
@@ -346,14 +354,16 @@ def main() -> int:
         "launch": args.launch,
         "config": {"workload": cfg.name, "B": cfg.B, "C_in": cfg.C_in, "C_out": cfg.C_out,
                    "H": cfg.H, "W": cfg.W, "levels": cfg.levels,
-                   "keep": f"{cfg.keep_num}/{cfg.keep_den}", "act_bits": cfg.act_bits},
+                   "keep": f"{cfg.keep_num}/{cfg.keep_den}", "act_bits": cfg.act_bits,
+                   "index_list": args.index_list},
         "roofline": {"bound": "hbm", "kernel": STAGE_KERNEL[dom], "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "algorithmic_bytes": alg[dom],
                      "kernel_us": round(stage_us[dom], 2)},
         "stages_us": {n: round(v, 2) for n, v in stage_us.items()},
         "event_pair_us": round(pair_us, 2),
-        "stages_alg_GBs": {n: round(alg[n] / (stage_us[n] * 1e-6) / 1e9, 1) for n in stage_us},
+        "stages_alg_GBs": {n: round(alg[n] / (stage_us[n] * 1e-6) / 1e9, 1)
+                           for n in stage_us if stage_us[n] > 0},
         "layer_alg_GBs": round(sum(alg.values()) / dt / 1e9, 1),
         "gemm_tflops": round(2.0 * cfg.B * cfg.C_in * cfg.C_out * cfg.k
                              / (stage_us["pointwise"] * 1e-6) / 1e12, 2),

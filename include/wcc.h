@@ -176,6 +176,18 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
                        int32_t *idx_out /*nullable*/, float *alpha_out_dev /*nullable*/,
                        void *stream);
 
+/* ---- variant: the layer with an index list that does not depend on the input ------------
+ * The footnote of the section "Joint hard shrinkage" mentions keeping the upper-left part of
+ * the wavelet transform for any image.  idx [B,k] (strictly ascending per sample, values in
+ * [0,N)) is used as the index set I of every channel; idx = NULL means the first k positions of
+ * the wavelet vector (the coarsest bands first, in the order of `coef` above).  Everything after
+ * the selection is as in wcc_forward (alpha = largest kept |coefficient| unless alpha_in > 0);
+ * the norm pass and the selection are not run. */
+wcc_status wcc_forward_fixed(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const void *w,
+                             const float *w_scale /*nullable unless I8*/, float alpha_in,
+                             const int32_t *idx /*nullable*/, float *y,
+                             float *alpha_out_dev /*nullable*/, void *stream);
+
 /* ==== next row: the inverted residual block the paper timed (appendix "Inference times",
  * Eq. (inverted)):  y = x + K3_1x1( K_dw( K1_1x1 x ) ), both 1x1 convolutions as WCC layers
  * with the same levels / keep ratio / quantiser, K_dw a depthwise 3x3 convolution; the

@@ -190,6 +190,27 @@ def forward(x, w, w_scale, levels: int, keep_num: int, keep_den: int, act_bits: 
     return y, idx, float(alpha.value)
 
 
+def forward_with_list(x, w, w_scale, levels: int, idx, act_bits: int = 0, alpha_in: float = 0.0):
+    """The layer with the index set given instead of selected (the steps of Alg. 1 after the
+    shrinkage's top-k; footnote of the section "Joint hard shrinkage").  idx [B, k] ascending.
+    Returns (y [B,C_out,H,W], alpha)."""
+    x = _d(x)
+    w = _d(w)
+    B, Ci, H, W = x.shape
+    N = H * W
+    idx = np.ascontiguousarray(idx, dtype=np.int64)
+    coef = haar_fwd(x, levels).reshape(B, Ci, N)
+    xc = gather(coef, idx)
+    alpha, sx = 0.0, 1.0
+    if act_bits:
+        alpha = float(np.float32(alpha_in if alpha_in > 0 else absmax(xc)))
+        xc = quant_codes(xc, alpha, act_bits)
+        sx = alpha / float((1 << (act_bits - 1)) - 1)
+    sw = np.ones(w.shape[0]) if w_scale is None else _d(w_scale)
+    yc = pointwise(w, sx * sw, xc)
+    return haar_inv(scatter(yc, idx, N), H, W, levels), alpha
+
+
 def depthwise3x3(x, w):
     """K_dw of Eq. (inverted): x [B, C, H, W], w [C, 3, 3] -> [B, C, H, W] (zero padding 1)."""
     x = _d(x)

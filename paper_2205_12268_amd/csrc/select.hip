@@ -489,7 +489,26 @@ __global__ __launch_bounds__(256) void jmap_scatter_kernel(const int32_t *__rest
   if (q >= 0 && q < N) jmap[(size_t)b * N + q] = (int32_t)j;
 }
 
+// the index list "first k positions" (coarsest bands first): jmap[b][q] = q < k ? q : -1,
+// idx[b][j] = j (idx nullable)
+__global__ __launch_bounds__(256) void jmap_prefix_kernel(int64_t N, int64_t k,
+                                                          int32_t *__restrict__ jmap,
+                                                          int32_t *__restrict__ idx) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int b = blockIdx.y;
+  if (q >= N) return;
+  jmap[(size_t)b * N + q] = q < k ? (int32_t)q : -1;
+  if (idx && q < k) idx[(size_t)b * k + q] = (int32_t)q;
+}
+
 }  // namespace
+
+hipError_t launch_jmap_prefix(int B, int64_t N, int64_t k, int32_t *jmap, int32_t *idx,
+                              hipStream_t s) {
+  hipLaunchKernelGGL(jmap_prefix_kernel, dim3((unsigned)((N + 255) / 256), B), dim3(256), 0, s, N, k,
+                     jmap, idx);
+  return hipGetLastError();
+}
 
 SelectPrep make_prep(void *ws_base, const WsLayout &L, float *alpha_slots, float alpha_in) {
   char *ws = static_cast<char *>(ws_base);

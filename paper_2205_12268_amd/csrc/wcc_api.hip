@@ -84,6 +84,11 @@ WsLayout ws_layout(const wcc_desc &d) {
 }
 
 
+// Where the index set I of a layer comes from.
+enum { kListSelect = 0,  // joint shrinkage: top-k channel norms (Alg. 1)
+       kListPrefix = 1,  // the first k positions of the wavelet vector, whatever the input
+       kListGiven = 2 }; // the caller's list
+
 // One WCC layer (Alg. 1 with the quantiser) on a workspace that starts at `ws`.  residual
 // (nullable, [B, C_out, H, W]) is added to the output by the last kernel.  wdw (nullable,
 // [C_in, 3, 3]): the layer's input is K_dw x, convolved on the fly by both transform passes.  prof: bracket the
@@ -91,7 +96,8 @@ WsLayout ws_layout(const wcc_desc &d) {
 wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc &d, const float *x,
                       const void *w, const float *w_scale, float alpha_in, float *y,
                       int32_t *idx_out, float *alpha_out_dev, const float *residual,
-                      const float *wdw, bool prof, hipStream_t s) {
+                      const float *wdw, bool prof, hipStream_t s, int list = kListSelect,
+                      const int32_t *idx_given = nullptr) {
   const int64_t k = k_of(d);
   const bool quant = d.act_quant_bits == 8;
 
@@ -109,16 +115,27 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
     return hipEventRecord(ctx->ev[stage][which], s);
   };
 
-  // A: the transform, first pass: only the channel norms of X_wt leave the chip (the same
-  // kernel clears the selection state)
-  WCC_TRY(mark(WCC_T_HAAR_FWD, 0));
-  WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, L.G,
-                           make_prep(ws, L, slots, quant ? alpha_in : 0.f), wdw, s));
-  WCC_TRY(mark(WCC_T_HAAR_FWD, 1));
-  // B: norms, index set I (ascending), rank map for the inverse
-  WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
-  WCC_TRY(launch_select(d, L.G == 1 ? norm : part, L.G, norm, k, ws, L, idx, jmap, s));
-  WCC_TRY(mark(WCC_T_NORM_SELECT, 1));
+  if (list == kListSelect) {
+    // A: the transform, first pass: only the channel norms of X_wt leave the chip (the same
+    // kernel clears the selection state)
+    WCC_TRY(mark(WCC_T_HAAR_FWD, 0));
+    WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, L.G,
+                             make_prep(ws, L, slots, quant ? alpha_in : 0.f), wdw, s));
+    WCC_TRY(mark(WCC_T_HAAR_FWD, 1));
+    // B: norms, index set I (ascending), rank map for the inverse
+    WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
+    WCC_TRY(launch_select(d, L.G == 1 ? norm : part, L.G, norm, k, ws, L, idx, jmap, s));
+    WCC_TRY(mark(WCC_T_NORM_SELECT, 1));
+  } else {
+    // a list that does not depend on the input: no norm pass, no selection
+    WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
+    WCC_TRY(launch_alpha_init(slots, quant ? alpha_in : 0.f, s));
+    if (list == kListPrefix)
+      WCC_TRY(launch_jmap_prefix(d.B, (int64_t)d.H * d.W, k, jmap, idx_out, s));
+    else
+      WCC_TRY(launch_jmap_from_idx(idx_given, d.B, (int64_t)d.H * d.W, k, jmap, s));
+    WCC_TRY(mark(WCC_T_NORM_SELECT, 1));
+  }
   // A again + B': the transform, second pass: X_wt[I] is written straight into its compressed
   // place (the dropped coefficients never reach memory); alpha = max |kept coefficient|
   WCC_TRY(mark(WCC_T_GATHER, 0));
@@ -367,6 +384,30 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   const bool prof = ctx->profiling && ctx->ev_ok;
   st = forward_on(ctx, static_cast<char *>(ctx->ws), L, *desc, x, w, w_scale, alpha_in, y, idx_out,
                   alpha_out_dev, nullptr, nullptr, prof, s);
+  if (st != WCC_OK) return st;
+  if (prof) {
+    WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][0], s));
+    WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][1], s));
+    ctx->marked[WCC_T_EVENT_PAIR] = true;
+    ctx->have_times = true;
+  }
+  return WCC_OK;
+}
+
+wcc_status wcc_forward_fixed(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const void *w,
+                             const float *w_scale, float alpha_in, const int32_t *idx, float *y,
+                             float *alpha_out_dev, void *stream) {
+  if (!ctx || !x || !w || !y) return WCC_ERR_NULL;
+  wcc_status st = check_desc(desc);
+  if (st != WCC_OK) return st;
+  if (desc->w_dtype == WCC_I8 && !w_scale) return WCC_ERR_NULL;
+  if (misaligned(x) || misaligned(w) || misaligned(y) || misaligned(idx)) return WCC_ERR_ALIGN;
+  const WsLayout L = ws_layout(*desc);
+  if ((st = need_ws(ctx, L)) != WCC_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool prof = ctx->profiling && ctx->ev_ok;
+  st = forward_on(ctx, static_cast<char *>(ctx->ws), L, *desc, x, w, w_scale, alpha_in, y, nullptr,
+                  alpha_out_dev, nullptr, nullptr, prof, s, idx ? kListGiven : kListPrefix, idx);
   if (st != WCC_OK) return st;
   if (prof) {
     WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][0], s));

@@ -145,6 +145,8 @@ hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, fl
                          int32_t *jmap /*nullable*/, hipStream_t s);
 hipError_t launch_jmap_from_idx(const int32_t *idx, int B, int64_t N, int64_t k, int32_t *jmap,
                                 hipStream_t s);
+// rank map (and index list, nullable) of "the first k positions of every sample"
+hipError_t launch_jmap_prefix(int B, int64_t N, int64_t k, int32_t *jmap, int32_t *idx, hipStream_t s);
 hipError_t launch_alpha_init(float *alpha_slots, float alpha_in, hipStream_t s);
 // alpha_slots nullable: no maximum is taken
 hipError_t launch_gather(const float *coef, const int32_t *idx, int B, int C, int64_t N, int64_t k,

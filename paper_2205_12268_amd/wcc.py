@@ -21,7 +21,7 @@ STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "ev
 EXPORTS = ("wcc_create", "wcc_destroy", "wcc_workspace_bytes", "wcc_set_workspace", "wcc_k",
            "wcc_status_string", "wcc_set_profiling", "wcc_stage_times", "wcc_haar_fwd",
            "wcc_joint_topk", "wcc_gather_quant", "wcc_pointwise", "wcc_scatter_ihaar",
-           "wcc_forward", "wcc_block_workspace_bytes", "wcc_depthwise3x3", "wcc_block_forward",
+           "wcc_forward", "wcc_forward_fixed", "wcc_block_workspace_bytes", "wcc_depthwise3x3", "wcc_block_forward",
            "wcc_set_block_profile_layer")
 
 
@@ -73,6 +73,7 @@ def lib():
         L.wcc_pointwise.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp]
         L.wcc_scatter_ihaar.argtypes = [vp, dp, vp, vp, vp, vp]
         L.wcc_forward.argtypes = [vp, dp, vp, vp, vp, C.c_float, vp, vp, vp, vp]
+        L.wcc_forward_fixed.argtypes = [vp, dp, vp, vp, vp, C.c_float, vp, vp, vp, vp]
         bp = C.POINTER(BlockDesc)
         L.wcc_block_workspace_bytes.argtypes = [bp, C.POINTER(C.c_size_t)]
         L.wcc_depthwise3x3.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp, vp]
@@ -198,6 +199,11 @@ class Context:
         _check(lib().wcc_forward(self._h, C.byref(desc), _ptr(x), _ptr(w), _ptr(w_scale),
                                  C.c_float(alpha_in), _ptr(y), _ptr(idx_out), _ptr(alpha_out),
                                  _stream()), "wcc_forward")
+
+    def wcc_forward_fixed(self, desc, x, w, w_scale, alpha_in, idx, y, alpha_out=None):
+        _check(lib().wcc_forward_fixed(self._h, C.byref(desc), _ptr(x), _ptr(w), _ptr(w_scale),
+                                       C.c_float(alpha_in), _ptr(idx), _ptr(y), _ptr(alpha_out),
+                                       _stream()), "wcc_forward_fixed")
 
     # ---- the inverted residual block (next row) ----
     def wcc_depthwise3x3(self, x, w, y):

@@ -301,3 +301,28 @@ def test_quantiser_codes_on_arbitrary_floats(ref, ctx, alpha_bits):
     ctx.wcc_gather_quant(d, dev(coef), idx, alpha, xc, a)
     assert float(a.item()) == alpha
     np.testing.assert_array_equal(xc.cpu().numpy().astype(np.float64), ref.quant_codes(coef, alpha, 8))
+
+
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[1], SMALL[6], SMALL[12]], ids=lambda c: c.name)
+@pytest.mark.parametrize("kind", ["prefix", "given"])
+def test_forward_with_a_fixed_index_list(ref, ctx, cfg, kind):
+    """wcc_forward_fixed: the first k positions, or a caller's ascending list per sample."""
+    x, w = synth.make_inputs(cfg)
+    d = desc_of(cfg)
+    ctx.ensure_workspace(d)
+    N, k = cfg.N, cfg.k
+    if kind == "prefix":
+        idx = np.tile(np.arange(k, dtype=np.int64), (cfg.B, 1))
+        idx_dev = None
+    else:
+        rng = np.random.default_rng(cfg.seed + 5)
+        idx = np.stack([np.sort(rng.choice(N, k, replace=False)) for _ in range(cfg.B)]).astype(np.int64)
+        idx_dev = dev(idx.astype(np.int32))
+    wd, wsd = upload_weights(w)
+    y = torch.full((cfg.B, cfg.C_out, cfg.H, cfg.W), float("nan"), dtype=torch.float32, device="cuda")
+    alpha = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ctx.wcc_forward_fixed(d, dev(x), wd, wsd, 0.0, idx_dev, y, alpha)
+    want, o_alpha = ref.forward_with_list(x, w.values, w.scale, cfg.levels, idx, cfg.act_bits)
+    if cfg.act_bits:
+        assert float(alpha.item()) == o_alpha
+    assert rel_l2(y.cpu().numpy(), want) <= tol_for(cfg)

@@ -536,3 +536,31 @@ def test_block_structure(ref):
     np.testing.assert_array_equal(y, x + t3)
     assert a1 == want_a1 and a3 == want_a3 and a1 > 0 and a3 > 0
     assert idx1.shape == idx3.shape == (2, 32)
+
+
+# ---- the layer with a given index list ----------------------------------------------------------
+@pytest.mark.parametrize("bits", [0, 8])
+def test_given_list_equals_selected_list_and_dense_conv(ref, bits):
+    x, w = small_problem(41)
+    y, idx, alpha = ref.forward(x, w, None, 2, 1, 4, bits)
+    y2, alpha2 = ref.forward_with_list(x, w, None, 2, idx, bits)
+    np.testing.assert_array_equal(y2, y)  # the list the shrinkage picks: the layer itself
+    assert alpha2 == alpha
+    # the full list, no quantiser: the dense 1x1 convolution
+    N = x.shape[2] * x.shape[3]
+    full = np.tile(np.arange(N), (x.shape[0], 1))
+    y3, _ = ref.forward_with_list(x, w, None, 2, full, 0)
+    np.testing.assert_allclose(y3, np.einsum("oc,bchw->bohw", w, x), rtol=0, atol=1e-13)
+
+
+def test_prefix_list_is_a_low_pass(ref):
+    """Keeping the first n_d positions keeps exactly the coarsest approximation: with K = I the
+    output is the block average of x over 2^d x 2^d pixels, spread back over each block."""
+    rng = np.random.default_rng(42)
+    x = rng.standard_normal((1, 3, 8, 16))
+    d, nd = 2, (8 // 4) * (16 // 4)
+    idx = np.arange(nd)[None, :]
+    y, _ = ref.forward_with_list(x, np.eye(3), None, d, idx, 0)
+    want = x.reshape(1, 3, 2, 4, 4, 4).mean(axis=(3, 5), keepdims=True)
+    want = np.broadcast_to(want, (1, 3, 2, 4, 4, 4)).reshape(1, 3, 8, 16)
+    np.testing.assert_allclose(y, want, rtol=0, atol=1e-13)
