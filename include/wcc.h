@@ -43,7 +43,13 @@
  *   xc    [B, C_in,  k]     fp32 (act_quant_bits = 0) or int8 codes (= 8)
  *   yc    [B, C_out, k]     fp32
  *   w     [C_out, C_in]     fp32 | bf16 | int8 codes (w_dtype)
- *   w_scale [C_out]         fp32   per-output-channel scale of int8 weight codes
+ *   w_scale [C_out]         fp32   per-output-channel scale of int8 / int4 weight codes
+ *   WCC_I4 weights          uint8  [C_out, C_in/2]: two signed 4-bit codes (two's complement,
+ *                                  -7..7) a byte, channel 2i in the low nibble, 2i+1 in the
+ *                                  high one; C_in must be even.  The codes are widened to int8
+ *                                  by a small kernel into the workspace and then take the int8
+ *                                  path (the paper's tables use 4-bit weights with 8-bit
+ *                                  activations).
  */
 #ifndef WCC_H
 #define WCC_H
@@ -69,7 +75,7 @@ typedef enum {
   WCC_ERR_ALIGN = 8        /* a tensor pointer is not 16-byte aligned                     */
 } wcc_status;
 
-typedef enum { WCC_F32 = 0, WCC_BF16 = 1, WCC_I8 = 2 } wcc_dtype;
+typedef enum { WCC_F32 = 0, WCC_BF16 = 1, WCC_I8 = 2, WCC_I4 = 3 } wcc_dtype;
 
 /* One WCC layer: the inputs of the explicit algorithm (feature-map shape,
  * kernel shape, wavelet level d, kept fraction gamma) plus storage types. */

@@ -111,7 +111,24 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
   }
 }
 
+// two signed 4-bit codes a byte (low nibble first) -> int8 codes
+__global__ __launch_bounds__(256) void unpack_i4_kernel(const uint8_t *__restrict__ packed,
+                                                        int8_t *__restrict__ out, int64_t n_bytes) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_bytes) return;
+  const uint32_t v = packed[i];
+  const int lo = (int)(v << 28) >> 28, hi = (int)(v << 24) >> 28;  // sign-extend the nibbles
+  out[2 * i] = (int8_t)lo;
+  out[2 * i + 1] = (int8_t)hi;
+}
+
 }  // namespace
+
+hipError_t launch_unpack_i4(const uint8_t *packed, int8_t *out, int64_t n, hipStream_t s) {
+  const int64_t nb = n / 2;
+  hipLaunchKernelGGL(unpack_i4_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, packed, out, nb);
+  return hipGetLastError();
+}
 
 hipError_t launch_alpha_init(float *alpha_slots, float alpha_in, hipStream_t s) {
   hipLaunchKernelGGL(alpha_init_kernel, dim3(1), dim3(64), 0, s, alpha_slots, alpha_in);

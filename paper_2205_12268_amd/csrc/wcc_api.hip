@@ -35,7 +35,9 @@ wcc_status check_desc(const wcc_desc *d) {
   // grid limits and 32-bit in-plane offsets
   if (d->B > 65535 || d->C_in > 65535 || d->C_out > 65535) return WCC_ERR_SHAPE;
   if ((int64_t)d->H * d->W > ((int64_t)1 << 30)) return WCC_ERR_SHAPE;
-  if (d->w_dtype != WCC_F32 && d->w_dtype != WCC_BF16 && d->w_dtype != WCC_I8) return WCC_ERR_DTYPE;
+  if (d->w_dtype != WCC_F32 && d->w_dtype != WCC_BF16 && d->w_dtype != WCC_I8 && d->w_dtype != WCC_I4)
+    return WCC_ERR_DTYPE;
+  if (d->w_dtype == WCC_I4 && d->C_in % 2) return WCC_ERR_SHAPE;
   if (d->act_quant_bits != 0 && d->act_quant_bits != 8) return WCC_ERR_DTYPE;
   if (d->keep_num < 1 || d->keep_den < 1 || d->keep_num > d->keep_den) return WCC_ERR_KEEP;
   const int64_t N = (int64_t)d->H * d->W;
@@ -50,6 +52,9 @@ int64_t k_of(const wcc_desc &d) {
   const int64_t N = (int64_t)d.H * d.W;
   return (d.keep_num * N + d.keep_den - 1) / d.keep_den;
 }
+
+// integer weight codes with a per-output-channel scale
+bool coded(int w_dtype) { return w_dtype == WCC_I8 || w_dtype == WCC_I4; }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
 
@@ -79,10 +84,25 @@ WsLayout ws_layout(const wcc_desc &d) {
   L.scratch = take(kInvScratchBytes);
   L.xc32 = take(B * (size_t)d.C_in * k * 4);
   L.yc = take(B * (size_t)d.C_out * k * 4);
+  L.w8 = take(d.w_dtype == WCC_I4 ? (size_t)d.C_out * d.C_in : 0);
   L.total = off;
   return L;
 }
 
+
+// The contraction, with 4-bit weight codes widened to int8 in the workspace first.
+hipError_t pointwise_any(char *ws, const WsLayout &L, const wcc_desc &d, int64_t k, const void *w,
+                         const float *w_scale, const void *xc, bool xc_is_f32, const float *alpha,
+                         bool alpha_is_slots, float *alpha_out, float *yc, hipStream_t s) {
+  if (d.w_dtype != WCC_I4)
+    return launch_pointwise(d, k, w, w_scale, xc, xc_is_f32, alpha, alpha_is_slots, alpha_out, yc, s);
+  int8_t *w8 = reinterpret_cast<int8_t *>(ws + L.w8);
+  const hipError_t e = launch_unpack_i4(static_cast<const uint8_t *>(w), w8, (int64_t)d.C_out * d.C_in, s);
+  if (e != hipSuccess) return e;
+  wcc_desc d8 = d;
+  d8.w_dtype = WCC_I8;
+  return launch_pointwise(d8, k, w8, w_scale, xc, xc_is_f32, alpha, alpha_is_slots, alpha_out, yc, s);
+}
 
 // Where the index set I of a layer comes from.
 enum { kListSelect = 0,  // joint shrinkage: top-k channel norms (Alg. 1)
@@ -143,8 +163,8 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
   WCC_TRY(mark(WCC_T_GATHER, 1));
   // C: Y_wt = Conv(K_1x1, X_wt[I]); the kept coefficients are quantised as they are loaded
   WCC_TRY(mark(WCC_T_POINTWISE, 0));
-  WCC_TRY(launch_pointwise(d, k, w, w_scale, xc32, true, slots, true, quant ? alpha_out_dev : nullptr,
-                           yc, s));
+  WCC_TRY(pointwise_any(ws, L, d, k, w, w_scale, xc32, true, slots, true,
+                        quant ? alpha_out_dev : nullptr, yc, s));
   WCC_TRY(mark(WCC_T_POINTWISE, 1));
   // D + E: Y^0[I] = Y_wt, inverse levels
   WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 0));
@@ -344,11 +364,14 @@ wcc_status wcc_pointwise(wcc_ctx *ctx, const wcc_desc *desc, const void *w, cons
   if (!ctx || !w || !xc || !yc) return WCC_ERR_NULL;
   wcc_status st = check_desc(desc);
   if (st != WCC_OK) return st;
-  if (desc->w_dtype == WCC_I8 && !w_scale) return WCC_ERR_NULL;
+  if (coded(desc->w_dtype) && !w_scale) return WCC_ERR_NULL;
   if (desc->act_quant_bits == 8 && !alpha_dev) return WCC_ERR_NULL;
   if (misaligned(w) || misaligned(xc) || misaligned(yc)) return WCC_ERR_ALIGN;
-  WCC_TRY(launch_pointwise(*desc, k_of(*desc), w, w_scale, xc, desc->act_quant_bits == 0, alpha_dev,
-                           false, nullptr, yc, static_cast<hipStream_t>(stream)));
+  const WsLayout L = ws_layout(*desc);
+  if (desc->w_dtype == WCC_I4 && (st = need_ws(ctx, L)) != WCC_OK) return st;
+  WCC_TRY(pointwise_any(static_cast<char *>(ctx->ws), L, *desc, k_of(*desc), w, w_scale, xc,
+                        desc->act_quant_bits == 0, alpha_dev, false, nullptr, yc,
+                        static_cast<hipStream_t>(stream)));
   return WCC_OK;
 }
 
@@ -376,7 +399,7 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   if (!ctx || !x || !w || !y) return WCC_ERR_NULL;
   wcc_status st = check_desc(desc);
   if (st != WCC_OK) return st;
-  if (desc->w_dtype == WCC_I8 && !w_scale) return WCC_ERR_NULL;
+  if (coded(desc->w_dtype) && !w_scale) return WCC_ERR_NULL;
   if (misaligned(x) || misaligned(w) || misaligned(y) || misaligned(idx_out)) return WCC_ERR_ALIGN;
   const WsLayout L = ws_layout(*desc);
   if ((st = need_ws(ctx, L)) != WCC_OK) return st;
@@ -400,7 +423,7 @@ wcc_status wcc_forward_fixed(wcc_ctx *ctx, const wcc_desc *desc, const float *x,
   if (!ctx || !x || !w || !y) return WCC_ERR_NULL;
   wcc_status st = check_desc(desc);
   if (st != WCC_OK) return st;
-  if (desc->w_dtype == WCC_I8 && !w_scale) return WCC_ERR_NULL;
+  if (coded(desc->w_dtype) && !w_scale) return WCC_ERR_NULL;
   if (misaligned(x) || misaligned(w) || misaligned(y) || misaligned(idx)) return WCC_ERR_ALIGN;
   const WsLayout L = ws_layout(*desc);
   if ((st = need_ws(ctx, L)) != WCC_OK) return st;
@@ -452,7 +475,7 @@ wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const flo
   wcc_desc d1, d3;
   wcc_status st = block_layers(desc, d1, d3);
   if (st != WCC_OK) return st;
-  if (desc->w_dtype == WCC_I8 && (!w1_scale || !w3_scale)) return WCC_ERR_NULL;
+  if (coded(desc->w_dtype) && (!w1_scale || !w3_scale)) return WCC_ERR_NULL;
   if (misaligned(x) || misaligned(w1) || misaligned(w3) || misaligned(y) || misaligned(t1_out) ||
       misaligned(t2_out) || misaligned(idx1_out) || misaligned(idx3_out))
     return WCC_ERR_ALIGN;

@@ -39,6 +39,7 @@ struct WsLayout {
   size_t scratch;     // kInvScratchBytes: sink for the stores of lanes outside the plane
   size_t xc32;        // [B, C_in, k] fp32
   size_t yc;          // [B, C_out, k] fp32  (wcc_forward only)
+  size_t w8;          // [C_out, C_in] int8: WCC_I4 weights widened (else empty)
   size_t total;
   int G;              // channel groups of the forward transform
   int nblk;           // select workgroups per sample
@@ -165,6 +166,8 @@ hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const f
 // residual (nullable): [B, C_out, H, W] added to the result (may be y itself)
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
                                 float *y, float *scratch, const float *residual, hipStream_t s);
+// out[i] = the two signed 4-bit codes of packed[i / 2] widened to int8 (n = number of codes, even)
+hipError_t launch_unpack_i4(const uint8_t *packed, int8_t *out, int64_t n, hipStream_t s);
 // depthwise 3x3, stride 1, zero padding 1: x, y [B, C, H, W], w [C, 3, 3]
 hipError_t launch_depthwise3x3(int B, int C, int H, int W, const float *x, const float *w, float *y,
                                hipStream_t s);

@@ -24,7 +24,7 @@ from scipy import ndimage
 GRID_BITS = 6  # activations are multiples of 2**-6
 SEED_BASE = 0x57434300
 
-W_F32, W_BF16, W_I8 = 0, 1, 2
+W_F32, W_BF16, W_I8, W_I4 = 0, 1, 2, 3
 
 
 @dataclass(frozen=True)
@@ -168,7 +168,8 @@ class Weights:
     """1x1 kernel [C_out, C_in] in its storage type.
 
     `stored`  what the library receives: float32 values, bf16 bit patterns
-              (uint16) or int8 codes.
+              (uint16), int8 codes, or 4-bit codes packed two a byte (uint8
+              [C_out, C_in/2], even channel in the low nibble).
     `scale`   float32 [C_out] per-output-channel scale for int8 codes, else None.
     `values`  float64 [C_out, C_in]: the numbers the stored weights stand for
               (codes are *not* multiplied by `scale` here).
@@ -193,6 +194,13 @@ def make_w(cfg: LayerCfg) -> Weights:
         s = (np.abs(w).max(axis=1) / 127.0).astype(np.float32)
         codes = np.clip(np.rint(w / s[:, None].astype(np.float64)), -127, 127).astype(np.int8)
         return Weights(W_I8, codes, s, codes.astype(np.float64))
+    if cfg.w_dtype == W_I4:
+        assert cfg.C_in % 2 == 0
+        s = (np.abs(w).max(axis=1) / 7.0).astype(np.float32)
+        codes = np.clip(np.rint(w / s[:, None].astype(np.float64)), -7, 7).astype(np.int8)
+        nib = codes.astype(np.uint8) & 0x0F                      # two's complement nibbles
+        packed = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+        return Weights(W_I4, np.ascontiguousarray(packed), s, codes.astype(np.float64))
     raise ValueError("unknown weight dtype")
 
 

@@ -14,7 +14,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libwcc.so")
 
-F32, BF16, I8 = 0, 1, 2
+F32, BF16, I8, I4 = 0, 1, 2, 3
 STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "event_pair",
           "depthwise")
 

@@ -13,7 +13,7 @@ from tests.util import desc_of, dev, oracle_scale, rel_l2, tol_for, upload_weigh
 
 pytestmark = pytest.mark.gpu
 
-F32, BF16, I8 = synth.W_F32, synth.W_BF16, synth.W_I8
+F32, BF16, I8, I4 = synth.W_F32, synth.W_BF16, synth.W_I8, synth.W_I4
 
 
 def case(name, B, Ci, Co, H, W, d, num, den, wd, bits, base=2, **kw):
@@ -38,6 +38,9 @@ SMALL = [
     case("wide_k", 1, 96, 160, 64, 128, 2, 1, 2, BF16, 8),             # K > 64: two k tiles; M > 128
     case("i8_wide", 2, 192, 144, 32, 64, 1, 1, 4, I8, 8),
     case("spiky", 2, 32, 32, 64, 128, 3, 1, 8, BF16, 8, base=3),
+    case("i4_weights", 2, 64, 48, 32, 64, 2, 1, 4, I4, 8),              # 4-bit codes, matrix-core path
+    case("i4_ragged", 1, 22, 10, 16, 24, 1, 1, 3, I4, 8),               # C_in % 16 != 0: FMA path
+    case("i4_noquant", 1, 16, 24, 32, 32, 2, 1, 4, I4, 0),
 ]
 
 

@@ -45,6 +45,17 @@ def test_weight_storage_types():
     cfg1 = synth.config(1)
     w1 = synth.make_w(cfg1)
     np.testing.assert_array_equal(np.rint(w1.stored * 1024) / 1024, w1.stored)
+    # 4-bit codes: two a byte, even channel in the low nibble, two's complement, -7..7
+    cfg44 = synth.small(synth.config(4), C_in=16, C_out=8, w_dtype=synth.W_I4)
+    w44 = synth.make_w(cfg44)
+    assert w44.stored.dtype == np.uint8 and w44.stored.shape == (8, 8) and w44.scale.shape == (8,)
+    lo = (w44.stored & 0x0F).astype(np.int16)
+    hi = (w44.stored >> 4).astype(np.int16)
+    lo[lo > 7] -= 16
+    hi[hi > 7] -= 16
+    np.testing.assert_array_equal(lo, w44.values[:, 0::2])
+    np.testing.assert_array_equal(hi, w44.values[:, 1::2])
+    assert np.abs(w44.values).max() == 7 and (w44.values < 0).any()
 
 
 def test_budget_guard_trips():
