@@ -235,6 +235,9 @@ def main() -> int:
                          "6 = the inverted residual block of the paper's timing table")
     ap.add_argument("--keep", default="1/4", help="kept fraction for --config 5 and 6 (num/den)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--alpha", choices=["dynamic", "static"], default="dynamic",
+                    help="static: the clipping parameter is passed in (the value a dynamic call "
+                         "finds), as a learned alpha would be (single-layer workloads)")
     ap.add_argument("--index-list", choices=["select", "prefix"], default="select",
                     help="prefix: wcc_forward_fixed with the first k positions instead of the joint "
                          "shrinkage's top-k (single-layer workloads)")
@@ -273,11 +276,20 @@ def main() -> int:
         wsd = None if w.scale is None else torch.from_numpy(w.scale).cuda()
         y = torch.empty((cfg.B, cfg.C_out, cfg.H, cfg.W), dtype=torch.float32, device="cuda")
 
+        alpha_in = 0.0
+        if args.alpha == "static" and cfg.act_bits:
+            a_dev = torch.zeros(1, dtype=torch.float32, device="cuda")
+            if args.index_list == "prefix":
+                ctx.wcc_forward_fixed(d, xd, wd, wsd, 0.0, None, y, a_dev)
+            else:
+                ctx.wcc_forward(d, xd, wd, wsd, 0.0, y, None, a_dev)
+            alpha_in = float(a_dev.item())
+
         def step():
             if args.index_list == "prefix":
-                ctx.wcc_forward_fixed(d, xd, wd, wsd, 0.0, None, y)
+                ctx.wcc_forward_fixed(d, xd, wd, wsd, alpha_in, None, y)
             else:
-                ctx.wcc_forward(d, xd, wd, wsd, 0.0, y)
+                ctx.wcc_forward(d, xd, wd, wsd, alpha_in, y)
 
         if args.copy_probe:
             probe = torch.empty_like(xd)
@@ -333,6 +345,9 @@ def main() -> int:
     pix_ch = cfg.B * cfg.H * cfg.W * cfg.C_in
     value = pix_ch / dt / 1e9
     alg = algorithmic_bytes(cfg)
+    if args.alpha == "static" and cfg.act_bits:  # kept coefficients travel as int8 codes
+        alg["gather"] -= 3 * cfg.B * cfg.C_in * cfg.k
+        alg["pointwise"] -= 3 * cfg.B * cfg.C_in * cfg.k
     if args.index_list == "prefix":  # no norm pass, no selection: only the rank map is written
         alg["haar_fwd"], alg["norm_select"] = 0, 4 * cfg.B * cfg.N
     dom = max(STAGE_KERNEL, key=lambda n: stage_us[n])  # the single kernel that takes longest
@@ -355,7 +370,7 @@ def main() -> int:
         "config": {"workload": cfg.name, "B": cfg.B, "C_in": cfg.C_in, "C_out": cfg.C_out,
                    "H": cfg.H, "W": cfg.W, "levels": cfg.levels,
                    "keep": f"{cfg.keep_num}/{cfg.keep_den}", "act_bits": cfg.act_bits,
-                   "index_list": args.index_list},
+                   "index_list": args.index_list, "alpha": args.alpha},
         "roofline": {"bound": "hbm", "kernel": STAGE_KERNEL[dom], "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "algorithmic_bytes": alg[dom],

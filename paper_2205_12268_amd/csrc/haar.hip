@@ -431,12 +431,17 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__
 // ---- second pass of the fused layer: transform again, keep only the selected positions ----
 // xc[b, c, jmap[b, q]] = HWT_d(x[b, c])[q] for the kept q; dropped coefficients never reach
 // memory.  Also raises the alpha slots to max |kept coefficient| (nullable).
-template <int D, int V>
+// Q8: the clipping parameter is known beforehand (the caller supplied it), so the kept
+// coefficients leave the chip as signed 8-bit codes (Eq. quantweights) instead of fp32.
+template <int D, int V, bool Q8>
 struct KeepSink {
-  float *plane;  // xc[b, c, :]
+  using Out = std::conditional_t<Q8, int8_t, float>;
+  Out *plane;  // xc[b, c, :]
   int jj[slot_count(D, V)];
   uint64_t any[2];  // wave-uniform: bit s set if some lane keeps slot s
   float vmax;
+  Quant quant;
+  __device__ __forceinline__ explicit KeepSink(float alpha) : quant(alpha) {}
   template <int L, int J>
   __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
                                           bool owner) {
@@ -449,21 +454,27 @@ struct KeepSink {
       if ((any[s >> 6] >> (s & 63)) & 1) {
         const int j = jj[s];
         if (owner && j >= 0) {
-          plane[j] = v[e];
-          vmax = fmaxf(vmax, fabsf(v[e]));
+          if constexpr (Q8) {
+            plane[j] = (int8_t)quant.code(v[e]);
+          } else {
+            plane[j] = v[e];
+            vmax = fmaxf(vmax, fabsf(v[e]));
+          }
         }
       }
     }
   }
 };
 
-// grid = (ceil(units/4), G, B), block = 256.  DWM as in haar_fwd_kernel.
-template <int D, int V, int PF, int DWM = 0>
+// grid = (ceil(units/4), G, B), block = 256.  DWM as in haar_fwd_kernel.  Q8: xc is int8 codes
+// for the clipping parameter q_alpha (> 0), and alpha_slots must be null.
+template <int D, int V, int PF, int DWM, bool Q8>
 __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict__ x,
                                                         const int32_t *__restrict__ jmap,
-                                                        float *__restrict__ xc, float *alpha_slots,
+                                                        void *__restrict__ xc, float *alpha_slots,
                                                         Geo g, StripMap m, int C, int Cg, int64_t k,
-                                                        const float *__restrict__ wdw = nullptr) {
+                                                        const float *__restrict__ wdw,
+                                                        float q_alpha) {
   __shared__ float wmax[4];
   const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int grp = blockIdx.y, b = blockIdx.z;
@@ -472,7 +483,8 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict_
   const bool active = locate<D, V>(m, g, unit, p, row0, col0);
   const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
 
-  KeepSink<D, V> sink;
+  using Sink = KeepSink<D, V, Q8>;
+  Sink sink(Q8 ? q_alpha : 0.f);
   sink.any[0] = sink.any[1] = 0;
   sink.vmax = 0.f;
   const int32_t *jm = jmap + (size_t)b * g.N;
@@ -509,13 +521,13 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict_
 
   if (active && c0 < c1) {
     const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
-    sink.plane = xc + ((size_t)b * C + c0) * k;
+    sink.plane = static_cast<typename Sink::Out *>(xc) + ((size_t)b * C + c0) * k;
     if constexpr (DWM == 0) {
-      channel_loop<D, V, PF>(src, g.N, g.W, c1 - c0, p, sink, [k](KeepSink<D, V> &sk) { sk.plane += k; });
+      channel_loop<D, V, PF>(src, g.N, g.W, c1 - c0, p, sink, [k](Sink &sk) { sk.plane += k; });
     } else {
       const DwLane q = dw_lane<D, V>(g, m, p, row0, col0);
       channel_loop_dw<D, V, DWM == 2, true>(src, wdw + (size_t)c0 * 9, g.N, c1 - c0, q, p, sink,
-                                            [k](KeepSink<D, V> &sk) { sk.plane += k; });
+                                            [k](Sink &sk) { sk.plane += k; });
     }
   }
   if (alpha_slots == nullptr) return;
@@ -923,30 +935,31 @@ hipError_t fwd_launch(const wcc_desc &d, const float *x, float *coef, float *nor
 }
 
 template <int D, int V>
-hipError_t keep_launch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, float *xc,
-                       float *alpha_slots, Plan pl, const float *wdw, hipStream_t s) {
+hipError_t keep_launch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, void *xc,
+                       float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_in + pl.G - 1) / pl.G;
   dim3 grid((m.units + 3) / 4, pl.G, d.B);
+  const bool q8 = q_alpha > 0.f;
+#define WCC_KEEP(PF, DWM)                                                                          \
+  do {                                                                                             \
+    if (q8)                                                                                        \
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, true>), grid, dim3(256), 0, s, x, jmap,  \
+                         xc, nullptr, g, m, d.C_in, Cg, k, wdw, q_alpha);                          \
+    else                                                                                           \
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, false>), grid, dim3(256), 0, s, x, jmap, \
+                         xc, alpha_slots, g, m, d.C_in, Cg, k, wdw, 0.f);                          \
+  } while (0)
   if constexpr (V == 4) {
     if (wdw != nullptr) {  // K_dw in front of the transform
-      if (dw_needs_edges(m))
-        hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 2>), grid, dim3(256), 0, s, x, jmap, xc,
-                           alpha_slots, g, m, d.C_in, Cg, k, wdw);
-      else
-        hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 1>), grid, dim3(256), 0, s, x, jmap, xc,
-                           alpha_slots, g, m, d.C_in, Cg, k, wdw);
+      if (dw_needs_edges(m)) WCC_KEEP(1, 2); else WCC_KEEP(1, 1);
       return hipGetLastError();
     }
   }
   if (wdw != nullptr) return hipErrorInvalidValue;
-  if (pl.pf == 2)
-    hipLaunchKernelGGL((haar_keep_kernel<D, V, 2, 0>), grid, dim3(256), 0, s, x, jmap, xc, alpha_slots,
-                       g, m, d.C_in, Cg, k, wdw);
-  else
-    hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0>), grid, dim3(256), 0, s, x, jmap, xc, alpha_slots,
-                       g, m, d.C_in, Cg, k, wdw);
+  if (pl.pf == 2) WCC_KEEP(2, 0); else WCC_KEEP(1, 0);
+#undef WCC_KEEP
   return hipGetLastError();
 }
 
@@ -1000,15 +1013,15 @@ hipError_t fwd_dispatch(const wcc_desc &d, const float *x, float *coef, float *n
   return hipErrorInvalidValue;
 }
 
-hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, float *xc,
-                         float *alpha_slots, Plan pl, const float *wdw, hipStream_t s) {
+hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, void *xc,
+                         float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
-    case 1: return v4 ? keep_launch<1, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s)
-                      : keep_launch<1, 2>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
-    case 2: return keep_launch<2, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
-    case 3: return keep_launch<3, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
-    case 4: return keep_launch<4, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
+    case 1: return v4 ? keep_launch<1, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s)
+                      : keep_launch<1, 2>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+    case 2: return keep_launch<2, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+    case 3: return keep_launch<3, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+    case 4: return keep_launch<4, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
   }
   return hipErrorInvalidValue;
 }
@@ -1049,9 +1062,10 @@ hipError_t launch_haar_norm(const wcc_desc &d, const float *x, float *norm_part,
 }
 
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap,
-                            float *xc, float *alpha_slots, const float *wdw, hipStream_t s) {
+                            void *xc, float *alpha_slots, const float *wdw, float q_alpha,
+                            hipStream_t s) {
   const Plan pl{groups_for(d, d.C_in, 1024, 8), false, 1};
-  return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, s);
+  return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
 }
 
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,

@@ -159,11 +159,14 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
   // A again + B': the transform, second pass: X_wt[I] is written straight into its compressed
   // place (the dropped coefficients never reach memory); alpha = max |kept coefficient|
   WCC_TRY(mark(WCC_T_GATHER, 0));
-  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !(alpha_in > 0.f)) ? slots : nullptr, wdw, s));
+  // (with the caller's alpha the codes can be decided right there: int8 leaves the chip)
+  const bool codes_now = quant && alpha_in > 0.f && k % 4 == 0;
+  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !(alpha_in > 0.f)) ? slots : nullptr, wdw,
+                           codes_now ? alpha_in : 0.f, s));
   WCC_TRY(mark(WCC_T_GATHER, 1));
   // C: Y_wt = Conv(K_1x1, X_wt[I]); the kept coefficients are quantised as they are loaded
   WCC_TRY(mark(WCC_T_POINTWISE, 0));
-  WCC_TRY(pointwise_any(ws, L, d, k, w, w_scale, xc32, true, slots, true,
+  WCC_TRY(pointwise_any(ws, L, d, k, w, w_scale, xc32, !codes_now, slots, true,
                         quant ? alpha_out_dev : nullptr, yc, s));
   WCC_TRY(mark(WCC_T_POINTWISE, 1));
   // D + E: Y^0[I] = Y_wt, inverse levels

@@ -132,9 +132,10 @@ hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float
 // with these kernels, computed on the fly; needs W % 4 == 0
 hipError_t launch_haar_norm(const wcc_desc &d, const float *x, float *norm_part, int G,
                             const SelectPrep &prep, const float *wdw, hipStream_t s);
+// q_alpha > 0: xc is int8 codes for that clipping parameter (alpha_slots unused); else fp32
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap,
-                            float *xc, float *alpha_slots /*nullable*/, const float *wdw /*nullable*/,
-                            hipStream_t s);
+                            void *xc, float *alpha_slots /*nullable*/, const float *wdw /*nullable*/,
+                            float q_alpha, hipStream_t s);
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s);
 hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, float *norm, hipStream_t s);
 SelectPrep make_prep(void *ws_base, const WsLayout &L, float *alpha_slots, float alpha_in);

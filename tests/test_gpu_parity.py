@@ -329,3 +329,28 @@ def test_forward_with_a_fixed_index_list(ref, ctx, cfg, kind):
     if cfg.act_bits:
         assert float(alpha.item()) == o_alpha
     assert rel_l2(y.cpu().numpy(), want) <= tol_for(cfg)
+
+
+QUANT_CASES = [c for c in SMALL if c.act_bits == 8]
+
+
+@pytest.mark.parametrize("cfg", QUANT_CASES, ids=lambda c: c.name)
+@pytest.mark.parametrize("frac", [0.37, 1.0, 2.5])
+def test_forward_with_the_callers_alpha(ref, ctx, cfg, frac):
+    """alpha_in > 0 (a learned clipping parameter): the keep pass writes int8 codes itself.
+    alpha below, at and above the largest kept coefficient; every shape of the small set."""
+    x, w = synth.make_inputs(cfg)
+    o0 = oracle_stages(ref, cfg, x, w)
+    a_in = float(np.float32(o0["alpha"] * frac))
+    want, idx, alpha = ref.forward(x, w.values, w.scale, cfg.levels, cfg.keep_num, cfg.keep_den,
+                                   act_bits=8, alpha_in=a_in)
+    d = desc_of(cfg)
+    ctx.ensure_workspace(d)
+    wd, wsd = upload_weights(w)
+    y = torch.full((cfg.B, cfg.C_out, cfg.H, cfg.W), float("nan"), dtype=torch.float32, device="cuda")
+    a = torch.zeros(1, dtype=torch.float32, device="cuda")
+    gi = torch.empty((cfg.B, cfg.k), dtype=torch.int32, device="cuda")
+    ctx.wcc_forward(d, dev(x), wd, wsd, a_in, y, gi, a)
+    assert float(a.item()) == alpha == a_in
+    np.testing.assert_array_equal(gi.cpu().numpy().astype(np.int64), idx)
+    assert rel_l2(y.cpu().numpy(), want) <= 1e-2
