@@ -1,0 +1,102 @@
+"""Seeded random small layers: every mix of level count, width class (narrow planes packed
+several strips a wave, rows wider than a wave, widths that are not a multiple of 4), channel
+counts that do and do not fit the matrix-core tiles, keep ratios from almost nothing to
+everything, weight types and quantiser on/off -- each against the oracle through wcc_forward."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2205_12268_amd import synth, wcc
+from tests.util import desc_of, dev, rel_l2, tol_for, upload_weights
+
+pytestmark = pytest.mark.gpu
+
+
+def draw(seed: int) -> synth.LayerCfg:
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.integers(1, 5))
+    s = 1 << d
+    H = s * int(rng.integers(1, max(2, 48 // s)))
+    wide = rng.random() < 0.3
+    W = s * int(rng.integers(1, (640 if wide else 160) // s + 1))
+    if d == 1 and rng.random() < 0.5:
+        W += 2 * int(rng.integers(0, 2))                      # W % 4 == 2 now and then
+    dt = int(rng.choice([synth.W_F32, synth.W_BF16, synth.W_I8, synth.W_I4]))
+    Ci = int(rng.choice([2, 6, 8, 16, 24, 32, 48, 64, 80]))
+    Co = int(rng.choice([1, 3, 8, 20, 32, 64, 96, 130]))
+    den = int(rng.choice([1, 2, 3, 4, 7, 8, 16, 50]))
+    num = int(rng.integers(1, den + 1))
+    bits = 0 if dt == synth.W_F32 and rng.random() < 0.5 else int(rng.choice([0, 8, 8]))
+    return synth.LayerCfg(f"rand{seed}", int(rng.integers(1, 4)), Ci, Co, H, W, d, num, den, dt, bits,
+                          sigma=float(rng.choice([0.0, 1.0, 2.5])), clip_hi=8.0,
+                          seed=synth.SEED_BASE + 0x900 + seed)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = wcc.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_layer(ref, ctx, seed):
+    cfg = draw(seed)
+    print(f"{cfg}", flush=True)
+    x, w = synth.make_inputs(cfg)
+    d = desc_of(cfg)
+    ctx.ensure_workspace(d)
+    wd, wsd = upload_weights(w)
+    y = torch.full((cfg.B, cfg.C_out, cfg.H, cfg.W), float("nan"), dtype=torch.float32, device="cuda")
+    idx = torch.full((cfg.B, cfg.k), -7, dtype=torch.int32, device="cuda")
+    alpha = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ctx.wcc_forward(d, dev(x), wd, wsd, 0.0, y, idx, alpha)
+    want, o_idx, o_alpha = ref.forward(x, w.values, w.scale, cfg.levels, cfg.keep_num, cfg.keep_den,
+                                       act_bits=cfg.act_bits)
+    np.testing.assert_array_equal(idx.cpu().numpy().astype(np.int64), o_idx)
+    if cfg.act_bits:
+        assert float(alpha.item()) == o_alpha
+    got = y.cpu().numpy()
+    assert np.isfinite(got).all()
+    assert rel_l2(got, want) <= tol_for(cfg)
+
+
+def draw_block(seed: int) -> synth.BlockCfg:
+    rng = np.random.default_rng(2000 + seed)
+    d = int(rng.integers(1, 4))
+    s = 1 << d
+    H = s * int(rng.integers(1, max(2, 40 // s)))
+    W = s * int(rng.integers(1, (560 if rng.random() < 0.4 else 128) // s + 1))
+    dt = int(rng.choice([synth.W_F32, synth.W_BF16, synth.W_I8, synth.W_I4]))
+    den = int(rng.choice([1, 2, 4, 8, 5]))
+    bits = 0 if dt == synth.W_F32 else 8
+    return synth.BlockCfg(f"randblk{seed}", int(rng.integers(1, 3)), int(rng.choice([2, 4, 8, 16])),
+                          int(rng.integers(1, 5)), H, W, d, int(rng.integers(1, den + 1)), den, dt, bits,
+                          sigma=float(rng.choice([1.0, 2.0])), seed=synth.SEED_BASE + 0xA00 + seed)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_block(ref, ctx, seed):
+    """x + WCC(K3, K_dw(WCC(K1, x))) end to end against the independent oracle chain.  The
+    second layer's index set may legitimately differ where two fp64 norms are within rounding of
+    each other (its input is not dyadic), so the bar is the output tolerance."""
+    cfg = draw_block(seed)
+    print(f"{cfg}", flush=True)
+    x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
+    d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
+                            cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+    ctx.ensure_workspace(d)
+    w1d, w1s = upload_weights(w1)
+    w3d, w3s = upload_weights(w3)
+    y = torch.full(x.shape, float("nan"), dtype=torch.float32, device="cuda")
+    idx1 = torch.empty((cfg.B, cfg.k), dtype=torch.int32, device="cuda")
+    ctx.wcc_block_forward(d, dev(x), w1d, w1s, dev(w_dw), w3d, w3s, y, None, None, idx1, None)
+    o = ref.block_forward(x, w1.values, w1.scale, w_dw, w3.values, w3.scale, cfg.levels,
+                          cfg.keep_num, cfg.keep_den, cfg.act_bits)
+    np.testing.assert_array_equal(idx1.cpu().numpy().astype(np.int64), o[3])
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    tol = 1e-4 if cfg.w_dtype == synth.W_F32 else 3e-2
+    assert rel_l2(got - x, o[0] - x) <= tol
