@@ -27,17 +27,19 @@ STAGE_KERNEL = {"haar_fwd": "haar_fwd_kernel", "gather": "haar_keep_kernel",
                 "pointwise": "pointwise", "scatter_ihaar": "scatter_ihaar_kernel"}
 
 
-def algorithmic_bytes(cfg) -> dict:
+def algorithmic_bytes(cfg, act_bytes: int = 4) -> dict:
     """Bytes each stage of the fused layer must move per call: what the method itself reads
-    and writes (fp32 activations, int32 positions), not what an implementation adds."""
+    and writes (feature maps of act_bytes per element, fp32 kept coefficients, int32 positions),
+    not what an implementation adds."""
     B, Ci, Co, N, k = cfg.B, cfg.C_in, cfg.C_out, cfg.N, cfg.k
-    bw = {0: 4, 1: 2, 2: 1}[cfg.w_dtype]
+    bw = {0: 4, 1: 2, 2: 1, 3: 0.5}[cfg.w_dtype]
+    a = act_bytes
     return {
-        "haar_fwd": 4 * B * Ci * N + 4 * B * N,                    # read x, write norms
+        "haar_fwd": a * B * Ci * N + 4 * B * N,                    # read x, write norms
         "norm_select": 4 * B * N + 4 * B * k,                      # read norms, write I
-        "gather": 4 * B * Ci * N + 4 * B * k + 4 * B * Ci * k,     # read x and I, write X_wt[I]
+        "gather": a * B * Ci * N + 4 * B * k + 4 * B * Ci * k,     # read x and I, write X_wt[I]
         "pointwise": 4 * B * Ci * k + bw * Ci * Co + 4 * B * Co * k,
-        "scatter_ihaar": 4 * B * Co * k + 4 * B * k + 4 * B * Co * N,
+        "scatter_ihaar": 4 * B * Co * k + 4 * B * k + a * B * Co * N,
     }
 
 
@@ -63,7 +65,7 @@ def bench_stack(args, synth, run_layer, ctx) -> int:
     worst = None
     for cfg in layers:
         dt, stage_us, _, _, _ = run_layer(cfg, ctx)
-        alg = algorithmic_bytes(cfg)
+        alg = algorithmic_bytes(cfg, 2 if args.act == "bf16" else 4)
         total_s += dt
         total_pix += cfg.B * cfg.H * cfg.W * cfg.C_in
         total_alg += sum(alg.values())
@@ -97,8 +99,11 @@ def bench_block(args, synth, wcc, torch, np) -> int:
     num, den = (int(t) for t in args.keep.split("/"))
     cfg = synth.block_config(num, den)
     x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
+    bf16 = args.act == "bf16"
+    if bf16:
+        x = synth.round_to_bf16(x)
     d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
-                            cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+                            cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.BF16 if bf16 else wcc.F32)
     ctx = wcc.Context(0)
     ctx.ensure_workspace(d)
 
@@ -107,6 +112,8 @@ def bench_block(args, synth, wcc, torch, np) -> int:
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
     xd, w1d, w3d, wdd = up(x), up(w1.stored), up(w3.stored), up(w_dw)
+    if bf16:
+        xd = xd.to(torch.bfloat16)
     y = torch.empty_like(xd)
 
     def step():
@@ -137,10 +144,11 @@ def bench_block(args, synth, wcc, torch, np) -> int:
             key = name if name == "depthwise" else f"l{layer}_{name}"
             stage_us[key] = max(1e3 * (v - pair) / args.steps, 0.0)
     alg = {}
+    ab = 2 if bf16 else 4
     for layer in (0, 1):
-        for name, v in algorithmic_bytes(cfg.layer(layer)).items():
+        for name, v in algorithmic_bytes(cfg.layer(layer), ab).items():
             alg[f"l{layer}_{name}"] = v
-    alg["l1_scatter_ihaar"] += 4 * cfg.B * cfg.C * cfg.N          # the skip connection is read
+    alg["l1_scatter_ihaar"] += ab * cfg.B * cfg.C * cfg.N         # the skip connection is read
     # K_dw is folded into the project layer's passes when W % 4 == 0 (its output is never written)
     alg["depthwise"] = 0 if cfg.W % 4 == 0 else 8 * cfg.B * cfg.C_mid * cfg.N
     kernel_of = {"depthwise": "depthwise3x3_kernel"}
@@ -195,7 +203,7 @@ def bench_block(args, synth, wcc, torch, np) -> int:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": "eager",
         "config": {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "expansion": cfg.expansion,
                    "H": cfg.H, "W": cfg.W, "levels": cfg.levels, "keep": f"{num}/{den}",
-                   "act_bits": cfg.act_bits},
+                   "act_bits": cfg.act_bits, "act": args.act},
         "roofline": {"bound": "hbm", "kernel": kernel_of[dom], "stage": dom,
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
@@ -238,6 +246,9 @@ def main() -> int:
     ap.add_argument("--alpha", choices=["dynamic", "static"], default="dynamic",
                     help="static: the clipping parameter is passed in (the value a dynamic call "
                          "finds), as a learned alpha would be (single-layer workloads)")
+    ap.add_argument("--act", choices=["f32", "bf16"], default="f32",
+                    help="storage type of the feature maps x and y (bf16: a bandwidth variant; the "
+                         "metric is quoted on f32)")
     ap.add_argument("--index-list", choices=["select", "prefix"], default="select",
                     help="prefix: wcc_forward_fixed with the first k positions instead of the joint "
                          "shrinkage's top-k (single-layer workloads)")
@@ -267,14 +278,20 @@ def main() -> int:
     def run_layer(cfg, ctx):
         """Times args.steps forwards of one layer; returns (seconds per step, stage us, event pair us, x, w)."""
         x, w = synth.make_inputs(cfg)
+        bf16 = args.act == "bf16"
+        if bf16:
+            x = synth.round_to_bf16(x)
         d = wcc.make_desc(cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
-                          cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+                          cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.BF16 if bf16 else wcc.F32)
         ctx.ensure_workspace(d)
         xd = torch.from_numpy(x).cuda()
+        if bf16:
+            xd = xd.to(torch.bfloat16)
         stored = w.stored.view(np.int16) if w.stored.dtype == np.uint16 else w.stored
         wd = torch.from_numpy(np.ascontiguousarray(stored)).cuda()
         wsd = None if w.scale is None else torch.from_numpy(w.scale).cuda()
-        y = torch.empty((cfg.B, cfg.C_out, cfg.H, cfg.W), dtype=torch.float32, device="cuda")
+        y = torch.empty((cfg.B, cfg.C_out, cfg.H, cfg.W), device="cuda",
+                        dtype=torch.bfloat16 if bf16 else torch.float32)
 
         alpha_in = 0.0
         if args.alpha == "static" and cfg.act_bits:
@@ -344,7 +361,7 @@ def main() -> int:
 
     pix_ch = cfg.B * cfg.H * cfg.W * cfg.C_in
     value = pix_ch / dt / 1e9
-    alg = algorithmic_bytes(cfg)
+    alg = algorithmic_bytes(cfg, 2 if args.act == "bf16" else 4)
     if args.alpha == "static" and cfg.act_bits:  # kept coefficients travel as int8 codes
         alg["gather"] -= 3 * cfg.B * cfg.C_in * cfg.k
         alg["pointwise"] -= 3 * cfg.B * cfg.C_in * cfg.k
@@ -370,7 +387,7 @@ def main() -> int:
         "config": {"workload": cfg.name, "B": cfg.B, "C_in": cfg.C_in, "C_out": cfg.C_out,
                    "H": cfg.H, "W": cfg.W, "levels": cfg.levels,
                    "keep": f"{cfg.keep_num}/{cfg.keep_den}", "act_bits": cfg.act_bits,
-                   "index_list": args.index_list, "alpha": args.alpha},
+                   "index_list": args.index_list, "alpha": args.alpha, "act": args.act},
         "roofline": {"bound": "hbm", "kernel": STAGE_KERNEL[dom], "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "algorithmic_bytes": alg[dom],

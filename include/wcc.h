@@ -29,8 +29,8 @@
  *
  * Layouts (all row-major, last index contiguous); N = H*W, n_l = (H>>l)*(W>>l)
  * ---------------------------------------------------------------------------
- *   x     [B, C_in,  H, W]  fp32   input feature map
- *   y     [B, C_out, H, W]  fp32   output feature map
+ *   x     [B, C_in,  H, W]  fp32   input feature map   (bf16 if act_dtype = WCC_BF16,
+ *   y     [B, C_out, H, W]  fp32   output feature map   fused calls only)
  *   coef  [B, C,     N]     fp32   wavelet vector of every channel.  Position q
  *                                  ("linear index") follows the concatenation of
  *                                  Eq. (wavelet_transform) for d = levels:
@@ -86,6 +86,12 @@ typedef struct {
                                  k = ceil(keep_num*H*W/keep_den) in integer arithmetic      */
   int32_t w_dtype;            /* wcc_dtype of w                                             */
   int32_t act_quant_bits;     /* 0: kept coefficients stay fp32; 8: signed 8-bit codes      */
+  int32_t act_dtype;          /* storage type of x and y: WCC_F32 (0, the default) or
+                                 WCC_BF16.  bf16 feature maps are read exactly and written
+                                 rounded to nearest even; all arithmetic stays fp32.  Only the
+                                 fused calls (wcc_forward, wcc_forward_fixed,
+                                 wcc_block_forward) take bf16; the stage calls return
+                                 WCC_ERR_UNSUPPORTED for it                                   */
 } wcc_desc;
 
 /* Stages whose device time wcc_forward can record (wcc_set_profiling). */
@@ -177,8 +183,8 @@ wcc_status wcc_scatter_ihaar(wcc_ctx *ctx, const wcc_desc *desc, const float *yc
 /* ---- the whole layer (Alg. 1 with the quantiser between shrinkage and convolution) ------
  * y = H^T T^T K T H x.  Intermediates live in the workspace.  Results are those of the five
  * calls above run in sequence.  idx_out ([B,k]) and alpha_out_dev (1 float) are optional. */
-wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const void *w,
-                       const float *w_scale /*nullable unless I8*/, float alpha_in, float *y,
+wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const void *x, const void *w,
+                       const float *w_scale /*nullable unless I8*/, float alpha_in, void *y,
                        int32_t *idx_out /*nullable*/, float *alpha_out_dev /*nullable*/,
                        void *stream);
 
@@ -189,9 +195,9 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
  * the wavelet vector (the coarsest bands first, in the order of `coef` above).  Everything after
  * the selection is as in wcc_forward (alpha = largest kept |coefficient| unless alpha_in > 0);
  * the norm pass and the selection are not run. */
-wcc_status wcc_forward_fixed(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const void *w,
+wcc_status wcc_forward_fixed(wcc_ctx *ctx, const wcc_desc *desc, const void *x, const void *w,
                              const float *w_scale /*nullable unless I8*/, float alpha_in,
-                             const int32_t *idx /*nullable*/, float *y,
+                             const int32_t *idx /*nullable*/, void *y,
                              float *alpha_out_dev /*nullable*/, void *stream);
 
 /* ==== next row: the inverted residual block the paper timed (appendix "Inference times",
@@ -205,6 +211,8 @@ typedef struct {
   int64_t keep_num, keep_den;
   int32_t w_dtype;           /* of both 1x1 kernels: w1 [C*expansion, C], w3 [C, C*expansion] */
   int32_t act_quant_bits;
+  int32_t act_dtype;         /* storage type of x, y and the middle tensor (see wcc_desc);
+                                WCC_BF16 needs W % 4 == 0 and t2_out = NULL                  */
 } wcc_block_desc;
 
 /* Workspace for wcc_block_forward: the two middle tensors plus the larger of the two layers'
@@ -221,10 +229,10 @@ wcc_status wcc_depthwise3x3(wcc_ctx *ctx, int32_t B, int32_t C, int32_t H, int32
  * the largest kept |coefficient| of that layer.  t1_out / t2_out (nullable, [B, C*expansion,
  * H, W]) receive K1's output and K_dw's output, idx1_out / idx3_out (nullable, [B,k]) the two
  * index sets: they exist for tests.  Needs a workspace of wcc_block_workspace_bytes. */
-wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const float *x,
+wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const void *x,
                              const void *w1, const float *w1_scale, const float *w_dw,
-                             const void *w3, const float *w3_scale, float *y,
-                             float *t1_out, float *t2_out, int32_t *idx1_out, int32_t *idx3_out,
+                             const void *w3, const float *w3_scale, void *y,
+                             void *t1_out, float *t2_out, int32_t *idx1_out, int32_t *idx3_out,
                              void *stream);
 
 /* Which of the block's two layers (0: expand, 1: project) the stage events bracket while

@@ -147,6 +147,37 @@ __device__ __forceinline__ void store_row(float *dst, const float (&src)[V]) {
   if constexpr (V == 4) { t.z = src[2]; t.w = src[3]; }
   *reinterpret_cast<T *>(dst) = t;
 }
+__device__ __forceinline__ float load_one(const float *src) { return *src; }
+
+// The same for activations stored as bf16 (bit patterns in uint16): widening is exact, narrowing
+// rounds to nearest even.
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
+__device__ __forceinline__ uint32_t to_bf16(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+template <int V>
+__device__ __forceinline__ void load_row(const bf16_t *src, float (&dst)[V]) {
+  if constexpr (V == 4) {
+    const uint2 t = *reinterpret_cast<const uint2 *>(src);
+    dst[0] = bf16_lo(t.x); dst[1] = bf16_hi(t.x); dst[2] = bf16_lo(t.y); dst[3] = bf16_hi(t.y);
+  } else {
+    const uint32_t t = *reinterpret_cast<const uint32_t *>(src);
+    dst[0] = bf16_lo(t); dst[1] = bf16_hi(t);
+  }
+}
+template <int V>
+__device__ __forceinline__ void store_row(bf16_t *dst, const float (&src)[V]) {
+  const uint32_t a = to_bf16(src[0]) | (to_bf16(src[1]) << 16);
+  if constexpr (V == 4) {
+    const uint32_t b = to_bf16(src[2]) | (to_bf16(src[3]) << 16);
+    *reinterpret_cast<uint2 *>(dst) = make_uint2(a, b);
+  } else {
+    *reinterpret_cast<uint32_t *>(dst) = a;
+  }
+}
+__device__ __forceinline__ float load_one(const bf16_t *src) { return __uint_as_float((uint32_t)*src << 16); }
 
 // How waves tile one plane.
 struct StripMap {
@@ -186,15 +217,15 @@ __device__ __forceinline__ bool locate(const StripMap &m, const Geo &g, int unit
 // has to drain the prefetch as well (the counter is in order).  A prefetch past the last
 // channel reads the last channel again (a cache hit); the at most PF channels left after the
 // main loop are already in registers.
-template <int D, int V, int PF, class Sink, class After>
-__device__ __forceinline__ void channel_loop(const float *__restrict__ src, int64_t N, int W,
+template <int D, int V, int PF, class XT, class Sink, class After>
+__device__ __forceinline__ void channel_loop(const XT *__restrict__ src, int64_t N, int W,
                                              int n_ch, const LanePos<D> &p, Sink &sink,
                                              After &&after) {
   constexpr int R = 1 << D;
   float buf[PF + 1][R][V];
 #pragma unroll
   for (int u = 0; u < PF; ++u) {
-    const float *nx = src + (size_t)min(u, n_ch - 1) * N;
+    const XT *nx = src + (size_t)min(u, n_ch - 1) * N;
 #pragma unroll
     for (int r = 0; r < R; ++r) load_row<V>(nx + (size_t)r * W, buf[u][r]);
   }
@@ -202,7 +233,7 @@ __device__ __forceinline__ void channel_loop(const float *__restrict__ src, int6
   for (; c + PF < n_ch; c += PF + 1) {
 #pragma unroll
     for (int u = 0; u <= PF; ++u) {
-      const float *nx = src + (size_t)min(c + u + PF, n_ch - 1) * N;
+      const XT *nx = src + (size_t)min(c + u + PF, n_ch - 1) * N;
 #pragma unroll
       for (int r = 0; r < R; ++r) load_row<V>(nx + (size_t)r * W, buf[(u + PF) % (PF + 1)][r]);
       __builtin_amdgcn_sched_barrier(0);  // the loads go out before the arithmetic, not after
@@ -254,27 +285,27 @@ __device__ __forceinline__ DwLane dw_lane(const Geo &g, const StripMap &m, const
   return q;
 }
 
-template <int D, int V, bool EDGE, bool PEEL, class Sink, class After>
-__device__ __forceinline__ void channel_loop_dw(const float *__restrict__ src,
+template <int D, int V, bool EDGE, bool PEEL, class XT, class Sink, class After>
+__device__ __forceinline__ void channel_loop_dw(const XT *__restrict__ src,
                                                 const float *__restrict__ wdw, int64_t N, int n_ch,
                                                 const DwLane &q, const LanePos<D> &p, Sink &sink,
                                                 After &&after) {
   constexpr int R = 1 << D, RR = R + 2;
   float raw[2][RR][V];
   float el[2][EDGE ? RR : 1], er[2][EDGE ? RR : 1];
-  auto row_ptr = [&](const float *plane, int i) -> const float * {
+  auto row_ptr = [&](const XT *plane, int i) -> const XT * {
     return i == 0 ? plane + q.top_step : i == RR - 1 ? plane + q.bot_step
                                                      : plane + (size_t)(i - 1) * q.row_step;
   };
   auto load_tile = [&](int u, int ch) {
-    const float *plane = src + (size_t)min(ch, n_ch - 1) * N;
+    const XT *plane = src + (size_t)min(ch, n_ch - 1) * N;
 #pragma unroll
     for (int i = 0; i < RR; ++i) {
-      const float *rp = row_ptr(plane, i);
+      const XT *rp = row_ptr(plane, i);
       load_row<V>(rp, raw[u][i]);
       if constexpr (EDGE) {
-        el[u][i] = rp[q.left_off];
-        er[u][i] = rp[q.right_off];
+        el[u][i] = load_one(rp + q.left_off);
+        er[u][i] = load_one(rp + q.right_off);
       }
     }
   };
@@ -339,13 +370,14 @@ __device__ __forceinline__ void channel_loop_dw(const float *__restrict__ src,
 //                added in wave order.
 // DWM: 0 = x is transformed as it is; 1, 2 = K_dw x is (wdw [C, 3, 3]; 2: the outside columns
 // of a wave row's first and last lane exist and are read).
-template <int D, int V, bool SPLIT, bool STORE, int PF, int DWM = 0>
-__global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__ x,
+// XT: float or bf16_t, the storage type of x.
+template <int D, int V, bool SPLIT, bool STORE, int PF, int DWM, class XT>
+__global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
                                                        float *__restrict__ coef,
                                                        float *__restrict__ norm_part, Geo g,
                                                        StripMap m, int C, int Cg, int B,
                                                        SelectPrep prep,
-                                                       const float *__restrict__ wdw = nullptr) {
+                                                       const float *__restrict__ wdw) {
   constexpr int NS = slot_count(D, V);
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int unit = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * 4 + wv;
@@ -368,7 +400,7 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const float *__restrict__
   for (int s = 0; s < NS; ++s) sink.acc[s] = 0.f;
 
   if (p.active && c0 < c1) {
-    const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+    const XT *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
     sink.plane = STORE ? coef + ((size_t)b * C + c0) * g.N : nullptr;
     const int64_t N = g.N;
     if constexpr (DWM == 0) {
@@ -468,8 +500,8 @@ struct KeepSink {
 
 // grid = (ceil(units/4), G, B), block = 256.  DWM as in haar_fwd_kernel.  Q8: xc is int8 codes
 // for the clipping parameter q_alpha (> 0), and alpha_slots must be null.
-template <int D, int V, int PF, int DWM, bool Q8>
-__global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict__ x,
+template <int D, int V, int PF, int DWM, bool Q8, class XT>
+__global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x,
                                                         const int32_t *__restrict__ jmap,
                                                         void *__restrict__ xc, float *alpha_slots,
                                                         Geo g, StripMap m, int C, int Cg, int64_t k,
@@ -520,7 +552,7 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const float *__restrict_
     if (__ballot(sink.jj[s] >= 0) != 0) sink.any[s >> 6] |= (uint64_t)1 << (s & 63);
 
   if (active && c0 < c1) {
-    const float *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+    const XT *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
     sink.plane = static_cast<typename Sink::Out *>(xc) + ((size_t)b * C + c0) * k;
     if constexpr (DWM == 0) {
       channel_loop<D, V, PF>(src, g.N, g.W, c1 - c0, p, sink, [k](Sink &sk) { sk.plane += k; });
@@ -658,12 +690,12 @@ __device__ __forceinline__ void wave_lds_fence() {
 // list entries (kInvNone: padding).  row_step: W for lanes inside the plane, 0 for the others
 // (whose dst is the scratch line).
 // RES: res + (what dst points at, relative to the output tensor) is added to every stored row.
-template <int D, int V, int NI, bool RES>
+template <int D, int V, int NI, bool RES, class YT>
 __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane, int64_t k, int n_ch,
                                                 const uint32_t (&mine)[kInvCap / kWave],
                                                 uint32_t *tile, const InvStaged<D, V> &staged,
-                                                const LanePos<D> &p, float *dst, int row_step,
-                                                int64_t dst_step, const float *res) {
+                                                const LanePos<D> &p, YT *dst, int row_step,
+                                                int64_t dst_step, const YT *res) {
   constexpr int R = 1 << D;
   constexpr uint32_t kRank = (1u << kInvRankBits) - 1u;
   float vn[NI];
@@ -709,12 +741,13 @@ __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane,
 // yc [B, C, k] + jmap [B, N] -> y [B, C, H, W].  grid = (ceil(units/4), G, B), block = 256.
 // scratch: 1 KiB that lanes outside the plane may overwrite.  RES: y = residual + (the above),
 // residual [B, C, H, W] (the skip connection of Eq. (inverted)); it may be y itself.
-template <int D, int V, bool RES>
+// YT: float or bf16_t, the storage type of y and of the residual.
+template <int D, int V, bool RES, class YT>
 __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restrict__ yc,
                                                             const int32_t *__restrict__ jmap,
-                                                            float *y, Geo g, StripMap m, int C,
+                                                            YT *y, Geo g, StripMap m, int C,
                                                             int Cg, int64_t k, float *scratch,
-                                                            const float *residual) {
+                                                            const YT *residual) {
   constexpr int R = 1 << D;
   constexpr int NS = slot_count(D, V);
   constexpr bool kStaged = D <= 3;  // the [slot][lane] tiles of four waves fit in LDS
@@ -734,7 +767,7 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
   const int32_t *jm = jmap + (size_t)b * g.N;
   const float *plane = yc + ((size_t)b * C + c0) * k;
   const size_t first = ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
-  float *dst = y + first;
+  YT *dst = y + first;
 
   // ranks of this lane's positions (the same for every channel), slot by slot
   InvDirect<D, V> src;
@@ -804,17 +837,18 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
       staged.cell = reinterpret_cast<const float *>(tile) + lane;
       staged.any[0] = src.any[0];
       staged.any[1] = src.any[1];
-      float *to = active ? dst : scratch + lane * V;
-      const float *res = (RES && active) ? residual + first : scratch + lane * V;
+      YT *sink_line = reinterpret_cast<YT *>(scratch) + lane * V;
+      YT *to = active ? dst : sink_line;
+      const YT *res = (RES && active) ? residual + first : sink_line;
       const int row_step = active ? g.W : 0;
       const int64_t dst_step = active ? g.N : 0;
       const int ni = (count + 63) >> 6;
       if (ni <= 4)
-        inv_staged_walk<D, V, 4, RES>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 4, RES, YT>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
       else if (ni <= 8)
-        inv_staged_walk<D, V, 8, RES>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 8, RES, YT>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
       else
-        inv_staged_walk<D, V, 16, RES>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 16, RES, YT>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
       return;
     }
   }
@@ -822,7 +856,7 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
   // plain path
   if (!active) return;
   src.plane = plane;
-  const float *res = RES ? residual + first : nullptr;
+  const YT *res = RES ? residual + first : nullptr;
   for (int c = c0; c < c1; ++c) {
     float out[R][V];
     inv_levels<D, V, 1>(out, p, src);
@@ -905,20 +939,26 @@ struct Plan {
   int pf;      // prefetch depth in channels (1 or 2)
 };
 
+// x is fp32, or bf16 when the layer's activations are stored that way (fused calls only)
+template <int D, int V, bool STORE>
+hipError_t fwd_launch(const wcc_desc &d, const void *x, float *coef, float *norm_part, Plan pl,
+                      const SelectPrep &prep, const float *wdw, hipStream_t s);
+
 // does a wave row span less than the plane's width (so that its end lanes have neighbours
 // in memory)?
 bool dw_needs_edges(const StripMap &m) { return m.col_segs > 1 || m.lpr < m.lanes_w; }
 
-template <int D, int V, bool STORE>
-hipError_t fwd_launch(const wcc_desc &d, const float *x, float *coef, float *norm_part, Plan pl,
-                      const SelectPrep &prep, const float *wdw, hipStream_t s) {
+template <int D, int V, bool STORE, class XT>
+hipError_t fwd_launch_t(const wcc_desc &d, const XT *x, float *coef, float *norm_part, Plan pl,
+                        const SelectPrep &prep, const float *wdw, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_in + pl.G - 1) / pl.G;
   const dim3 grid_split(m.units, pl.G, d.B), grid_flat((m.units + 3) / 4, pl.G, d.B), block(256);
 #define WCC_FWD(SPLIT, PF, DWM)                                                                       \
-  hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, STORE, PF, DWM>), SPLIT ? grid_split : grid_flat,  \
-                     block, 0, s, x, coef, norm_part, g, m, d.C_in, Cg, d.B, prep, wdw)
+  hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, STORE, PF, DWM, XT>),                              \
+                     SPLIT ? grid_split : grid_flat, block, 0, s, x, coef, norm_part, g, m, d.C_in,   \
+                     Cg, d.B, prep, wdw)
   if constexpr (!STORE && V == 4) {
     if (wdw != nullptr) {  // K_dw in front of the transform (norm-only pass)
       const bool edges = dw_needs_edges(m);
@@ -934,9 +974,19 @@ hipError_t fwd_launch(const wcc_desc &d, const float *x, float *coef, float *nor
   return hipGetLastError();
 }
 
-template <int D, int V>
-hipError_t keep_launch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, void *xc,
-                       float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
+template <int D, int V, bool STORE>
+hipError_t fwd_launch(const wcc_desc &d, const void *x, float *coef, float *norm_part, Plan pl,
+                      const SelectPrep &prep, const float *wdw, hipStream_t s) {
+  if constexpr (!STORE) {
+    if (d.act_dtype == WCC_BF16)
+      return fwd_launch_t<D, V, STORE>(d, static_cast<const bf16_t *>(x), coef, norm_part, pl, prep, wdw, s);
+  }
+  return fwd_launch_t<D, V, STORE>(d, static_cast<const float *>(x), coef, norm_part, pl, prep, wdw, s);
+}
+
+template <int D, int V, class XT>
+hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_t *jmap, void *xc,
+                         float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_in + pl.G - 1) / pl.G;
@@ -945,11 +995,11 @@ hipError_t keep_launch(const wcc_desc &d, int64_t k, const float *x, const int32
 #define WCC_KEEP(PF, DWM)                                                                          \
   do {                                                                                             \
     if (q8)                                                                                        \
-      hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, true>), grid, dim3(256), 0, s, x, jmap,  \
-                         xc, nullptr, g, m, d.C_in, Cg, k, wdw, q_alpha);                          \
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, true, XT>), grid, dim3(256), 0, s, x,   \
+                         jmap, xc, nullptr, g, m, d.C_in, Cg, k, wdw, q_alpha);                    \
     else                                                                                           \
-      hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, false>), grid, dim3(256), 0, s, x, jmap, \
-                         xc, alpha_slots, g, m, d.C_in, Cg, k, wdw, 0.f);                          \
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, false, XT>), grid, dim3(256), 0, s, x,  \
+                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, k, wdw, 0.f);                    \
   } while (0)
   if constexpr (V == 4) {
     if (wdw != nullptr) {  // K_dw in front of the transform
@@ -964,18 +1014,27 @@ hipError_t keep_launch(const wcc_desc &d, int64_t k, const float *x, const int32
 }
 
 template <int D, int V>
-hipError_t inv_launch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, float *y,
-                      int G, float *scratch, const float *residual, hipStream_t s) {
+hipError_t keep_launch(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap, void *xc,
+                       float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
+  if (d.act_dtype == WCC_BF16)
+    return keep_launch_t<D, V>(d, k, static_cast<const bf16_t *>(x), jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+  return keep_launch_t<D, V>(d, k, static_cast<const float *>(x), jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+}
+
+template <int D, int V>
+hipError_t inv_launch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, void *y,
+                      int G, float *scratch, const void *residual, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_out + G - 1) / G;
   dim3 grid((m.units + 3) / 4, G, d.B);
-  if (residual)
-    hipLaunchKernelGGL((scatter_ihaar_kernel<D, V, true>), grid, dim3(256), 0, s, yc, jmap, y, g, m,
-                       d.C_out, Cg, k, scratch, residual);
-  else
-    hipLaunchKernelGGL((scatter_ihaar_kernel<D, V, false>), grid, dim3(256), 0, s, yc, jmap, y, g, m,
-                       d.C_out, Cg, k, scratch, residual);
+#define WCC_INV(RES, YT)                                                                          \
+  hipLaunchKernelGGL((scatter_ihaar_kernel<D, V, RES, YT>), grid, dim3(256), 0, s, yc, jmap,      \
+                     static_cast<YT *>(y), g, m, d.C_out, Cg, k, scratch,                         \
+                     static_cast<const YT *>(residual))
+  if (d.act_dtype == WCC_BF16) { if (residual) WCC_INV(true, bf16_t); else WCC_INV(false, bf16_t); }
+  else                         { if (residual) WCC_INV(true, float); else WCC_INV(false, float); }
+#undef WCC_INV
   return hipGetLastError();
 }
 
@@ -1000,7 +1059,7 @@ int groups_for(const wcc_desc &d, int C, int64_t want_waves, int min_ch) {
 int forward_groups(const wcc_desc &d) { return groups_for(d, d.C_in, 1024, 16); }
 
 template <bool STORE>
-hipError_t fwd_dispatch(const wcc_desc &d, const float *x, float *coef, float *norm_part, Plan pl,
+hipError_t fwd_dispatch(const wcc_desc &d, const void *x, float *coef, float *norm_part, Plan pl,
                         const SelectPrep &prep, const float *wdw, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
@@ -1013,7 +1072,7 @@ hipError_t fwd_dispatch(const wcc_desc &d, const float *x, float *coef, float *n
   return hipErrorInvalidValue;
 }
 
-hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap, void *xc,
+hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap, void *xc,
                          float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
@@ -1026,8 +1085,8 @@ hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const float *x, const int
   return hipErrorInvalidValue;
 }
 
-hipError_t inv_dispatch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, float *y,
-                        int G, float *scratch, const float *residual, hipStream_t s) {
+hipError_t inv_dispatch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, void *y,
+                        int G, float *scratch, const void *residual, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
     case 1: return v4 ? inv_launch<1, 4>(d, k, yc, jmap, y, G, scratch, residual, s)
@@ -1054,14 +1113,14 @@ hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float
   return fwd_dispatch<true>(d, x, coef, norm_part, fwd_plan(d, G), prep, nullptr, s);
 }
 
-hipError_t launch_haar_norm(const wcc_desc &d, const float *x, float *norm_part, int G,
+hipError_t launch_haar_norm(const wcc_desc &d, const void *x, float *norm_part, int G,
                             const SelectPrep &prep, const float *wdw, hipStream_t s) {
   Plan pl = fwd_plan(d, G);
   if (wdw) pl.pf = 1;
   return fwd_dispatch<false>(d, x, nullptr, norm_part, pl, prep, wdw, s);
 }
 
-hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap,
+hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap,
                             void *xc, float *alpha_slots, const float *wdw, float q_alpha,
                             hipStream_t s) {
   const Plan pl{groups_for(d, d.C_in, 1024, 8), false, 1};
@@ -1069,7 +1128,7 @@ hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const 
 }
 
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
-                                float *y, float *scratch, const float *residual, hipStream_t s) {
+                                void *y, float *scratch, const void *residual, hipStream_t s) {
   return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 2048, 8), scratch, residual, s);
 }
 

@@ -39,6 +39,7 @@ wcc_status check_desc(const wcc_desc *d) {
     return WCC_ERR_DTYPE;
   if (d->w_dtype == WCC_I4 && d->C_in % 2) return WCC_ERR_SHAPE;
   if (d->act_quant_bits != 0 && d->act_quant_bits != 8) return WCC_ERR_DTYPE;
+  if (d->act_dtype != WCC_F32 && d->act_dtype != WCC_BF16) return WCC_ERR_DTYPE;
   if (d->keep_num < 1 || d->keep_den < 1 || d->keep_num > d->keep_den) return WCC_ERR_KEEP;
   const int64_t N = (int64_t)d->H * d->W;
   // keep_num * N must not overflow
@@ -113,9 +114,9 @@ enum { kListSelect = 0,  // joint shrinkage: top-k channel norms (Alg. 1)
 // (nullable, [B, C_out, H, W]) is added to the output by the last kernel.  wdw (nullable,
 // [C_in, 3, 3]): the layer's input is K_dw x, convolved on the fly by both transform passes.  prof: bracket the
 // stages with the context's events.
-wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc &d, const float *x,
-                      const void *w, const float *w_scale, float alpha_in, float *y,
-                      int32_t *idx_out, float *alpha_out_dev, const float *residual,
+wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc &d, const void *x,
+                      const void *w, const float *w_scale, float alpha_in, void *y,
+                      int32_t *idx_out, float *alpha_out_dev, const void *residual,
                       const float *wdw, bool prof, hipStream_t s, int list = kListSelect,
                       const int32_t *idx_given = nullptr) {
   const int64_t k = k_of(d);
@@ -181,7 +182,7 @@ wcc_status block_layers(const wcc_block_desc *bd, wcc_desc &d1, wcc_desc &d3) {
   if (!bd) return WCC_ERR_NULL;
   if (bd->C < 1 || bd->expansion < 1 || (int64_t)bd->C * bd->expansion > 65535) return WCC_ERR_SHAPE;
   d1 = wcc_desc{bd->B, bd->C, bd->C * bd->expansion, bd->H, bd->W, bd->levels, bd->keep_num,
-                bd->keep_den, bd->w_dtype, bd->act_quant_bits};
+                bd->keep_den, bd->w_dtype, bd->act_quant_bits, bd->act_dtype};
   d3 = d1;
   d3.C_in = d1.C_out;
   d3.C_out = bd->C;
@@ -294,6 +295,7 @@ wcc_status wcc_haar_fwd(wcc_ctx *ctx, const wcc_desc *desc, const float *x, floa
   if (!ctx || !x || !coef) return WCC_ERR_NULL;
   wcc_status st = check_desc(desc);
   if (st != WCC_OK) return st;
+  if (desc->act_dtype != WCC_F32) return WCC_ERR_UNSUPPORTED;  // fp32 feature maps only here
   if (misaligned(x) || misaligned(coef) || misaligned(norm)) return WCC_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const WsLayout L = ws_layout(*desc);
@@ -383,6 +385,7 @@ wcc_status wcc_scatter_ihaar(wcc_ctx *ctx, const wcc_desc *desc, const float *yc
   if (!ctx || !yc || !idx || !y) return WCC_ERR_NULL;
   wcc_status st = check_desc(desc);
   if (st != WCC_OK) return st;
+  if (desc->act_dtype != WCC_F32) return WCC_ERR_UNSUPPORTED;  // fp32 feature maps only here
   if (misaligned(yc) || misaligned(idx) || misaligned(y)) return WCC_ERR_ALIGN;
   const WsLayout L = ws_layout(*desc);
   if ((st = need_ws(ctx, L)) != WCC_OK) return st;
@@ -396,8 +399,8 @@ wcc_status wcc_scatter_ihaar(wcc_ctx *ctx, const wcc_desc *desc, const float *yc
   return WCC_OK;
 }
 
-wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const void *w,
-                       const float *w_scale, float alpha_in, float *y, int32_t *idx_out,
+wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const void *x, const void *w,
+                       const float *w_scale, float alpha_in, void *y, int32_t *idx_out,
                        float *alpha_out_dev, void *stream) {
   if (!ctx || !x || !w || !y) return WCC_ERR_NULL;
   wcc_status st = check_desc(desc);
@@ -420,8 +423,8 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const
   return WCC_OK;
 }
 
-wcc_status wcc_forward_fixed(wcc_ctx *ctx, const wcc_desc *desc, const float *x, const void *w,
-                             const float *w_scale, float alpha_in, const int32_t *idx, float *y,
+wcc_status wcc_forward_fixed(wcc_ctx *ctx, const wcc_desc *desc, const void *x, const void *w,
+                             const float *w_scale, float alpha_in, const int32_t *idx, void *y,
                              float *alpha_out_dev, void *stream) {
   if (!ctx || !x || !w || !y) return WCC_ERR_NULL;
   wcc_status st = check_desc(desc);
@@ -470,9 +473,9 @@ wcc_status wcc_set_block_profile_layer(wcc_ctx *ctx, int layer) {
   return WCC_OK;
 }
 
-wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const float *x,
+wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const void *x,
                              const void *w1, const float *w1_scale, const float *w_dw,
-                             const void *w3, const float *w3_scale, float *y, float *t1_out,
+                             const void *w3, const float *w3_scale, void *y, void *t1_out,
                              float *t2_out, int32_t *idx1_out, int32_t *idx3_out, void *stream) {
   if (!ctx || !x || !w1 || !w_dw || !w3 || !y) return WCC_ERR_NULL;
   wcc_desc d1, d3;
@@ -486,7 +489,7 @@ wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const flo
   if (!ctx->ws || ctx->ws_bytes < BL.total) return WCC_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   char *ws = static_cast<char *>(ctx->ws);
-  float *t1 = t1_out ? t1_out : reinterpret_cast<float *>(ws + BL.t1);
+  void *t1 = t1_out ? t1_out : static_cast<void *>(ws + BL.t1);
   float *t2 = t2_out ? t2_out : reinterpret_cast<float *>(ws + BL.t2);
   const bool prof = ctx->profiling && ctx->ev_ok;
 
@@ -498,15 +501,16 @@ wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const flo
   // written) when the width allows; the stand-alone kernel runs otherwise, and when the caller
   // asks for K_dw's output
   const bool fold = desc->W % 4 == 0;
+  if (desc->act_dtype != WCC_F32 && (!fold || t2_out)) return WCC_ERR_UNSUPPORTED;
   if (!fold || t2_out) {
     if (prof) WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][0], s));
-    WCC_TRY(launch_depthwise3x3(d3.B, d3.C_in, d3.H, d3.W, t1, w_dw, t2, s));
+    WCC_TRY(launch_depthwise3x3(d3.B, d3.C_in, d3.H, d3.W, static_cast<const float *>(t1), w_dw, t2, s));
     if (prof) {
       WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][1], s));
       ctx->marked[WCC_T_DEPTHWISE] = true;
     }
   }
-  st = forward_on(ctx, ws + BL.layer, ws_layout(d3), d3, fold ? t1 : t2, w3, w3_scale, 0.f, y,
+  st = forward_on(ctx, ws + BL.layer, ws_layout(d3), d3, fold ? t1 : static_cast<void *>(t2), w3, w3_scale, 0.f, y,
                   idx3_out, nullptr, x, fold ? w_dw : nullptr,
                   prof && ctx->block_profile_layer == 1, s);
   if (st != WCC_OK) return st;

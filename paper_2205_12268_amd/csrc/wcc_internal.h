@@ -9,6 +9,7 @@
 namespace wcc {
 
 constexpr int kWave = 64;          // CDNA wavefront width
+using bf16_t = uint16_t;           // a bf16 bit pattern in memory
 constexpr int kMaxLevels = 4;      // register-resident strip transform up to 16 rows per lane
 constexpr int kRadixBins = 2048;   // 11 + 11 + 10 bit radix select
 constexpr int kSelectChunk = 1024; // keys per workgroup in the select kernels
@@ -130,10 +131,11 @@ hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float
 // norm-only pass (no coefficient is written) and keep-only pass of the fused layer
 // wdw (nullable, [C_in, 3, 3]): the transform's input is the depthwise 3x3 convolution of x
 // with these kernels, computed on the fly; needs W % 4 == 0
-hipError_t launch_haar_norm(const wcc_desc &d, const float *x, float *norm_part, int G,
+// (x: fp32, or bf16 if d.act_dtype says so; the same for y and residual further down)
+hipError_t launch_haar_norm(const wcc_desc &d, const void *x, float *norm_part, int G,
                             const SelectPrep &prep, const float *wdw, hipStream_t s);
 // q_alpha > 0: xc is int8 codes for that clipping parameter (alpha_slots unused); else fp32
-hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const float *x, const int32_t *jmap,
+hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap,
                             void *xc, float *alpha_slots /*nullable*/, const float *wdw /*nullable*/,
                             float q_alpha, hipStream_t s);
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s);
@@ -166,7 +168,7 @@ hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const f
 // scratch: kInvScratchBytes of device memory that the kernel may overwrite with anything
 // residual (nullable): [B, C_out, H, W] added to the result (may be y itself)
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
-                                float *y, float *scratch, const float *residual, hipStream_t s);
+                                void *y, float *scratch, const void *residual, hipStream_t s);
 // out[i] = the two signed 4-bit codes of packed[i / 2] widened to int8 (n = number of codes, even)
 hipError_t launch_unpack_i4(const uint8_t *packed, int8_t *out, int64_t n, hipStream_t s);
 // depthwise 3x3, stride 1, zero padding 1: x, y [B, C, H, W], w [C, 3, 3]

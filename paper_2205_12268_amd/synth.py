@@ -163,6 +163,12 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << 16).view(np.float32)
 
 
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """float32 array of the bf16-representable numbers nearest to `a` (ties to even): feature
+    maps for layers whose activations are stored as bf16.  Dyadic inputs stay dyadic."""
+    return bf16_bits_to_f32(_round_to_bf16_bits(np.asarray(a, dtype=np.float32)))
+
+
 @dataclass
 class Weights:
     """1x1 kernel [C_out, C_in] in its storage type.

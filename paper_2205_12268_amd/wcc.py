@@ -29,14 +29,16 @@ class Desc(C.Structure):
     """Mirror of ``wcc_desc``."""
     _fields_ = [("B", C.c_int32), ("C_in", C.c_int32), ("C_out", C.c_int32), ("H", C.c_int32),
                 ("W", C.c_int32), ("levels", C.c_int32), ("keep_num", C.c_int64),
-                ("keep_den", C.c_int64), ("w_dtype", C.c_int32), ("act_quant_bits", C.c_int32)]
+                ("keep_den", C.c_int64), ("w_dtype", C.c_int32), ("act_quant_bits", C.c_int32),
+                ("act_dtype", C.c_int32)]
 
 
 class BlockDesc(C.Structure):
     """Mirror of ``wcc_block_desc``."""
     _fields_ = [("B", C.c_int32), ("C", C.c_int32), ("expansion", C.c_int32), ("H", C.c_int32),
                 ("W", C.c_int32), ("levels", C.c_int32), ("keep_num", C.c_int64),
-                ("keep_den", C.c_int64), ("w_dtype", C.c_int32), ("act_quant_bits", C.c_int32)]
+                ("keep_den", C.c_int64), ("w_dtype", C.c_int32), ("act_quant_bits", C.c_int32),
+                ("act_dtype", C.c_int32)]
 
 
 class WccError(RuntimeError):
@@ -95,8 +97,9 @@ def _check(status: int, where: str) -> None:
         raise WccError(status, where)
 
 
-def make_desc(B, C_in, C_out, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits) -> Desc:
-    return Desc(B, C_in, C_out, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits)
+def make_desc(B, C_in, C_out, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits,
+              act_dtype=F32) -> Desc:
+    return Desc(B, C_in, C_out, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits, act_dtype)
 
 
 def k_of(desc: Desc) -> int:
@@ -110,8 +113,9 @@ def workspace_bytes(desc: Desc) -> int:
 
 
 def make_block_desc(B, Cc, expansion, H, W, levels, keep_num, keep_den, w_dtype,
-                    act_quant_bits) -> BlockDesc:
-    return BlockDesc(B, Cc, expansion, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits)
+                    act_quant_bits, act_dtype=F32) -> BlockDesc:
+    return BlockDesc(B, Cc, expansion, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits,
+                     act_dtype)
 
 
 def block_workspace_bytes(desc: BlockDesc) -> int:
