@@ -179,6 +179,34 @@ __device__ __forceinline__ void store_row(bf16_t *dst, const float (&src)[V]) {
 }
 __device__ __forceinline__ float load_one(const bf16_t *src) { return __uint_as_float((uint32_t)*src << 16); }
 
+// What a lane loads of one row, kept as it arrives: the widening of bf16 happens when the
+// values are used, not where the load is issued (a conversion next to the load would wait for it
+// and undo the prefetch).
+template <int V, class T> struct Row;
+template <int V> struct Row<V, float> {
+  float v[V];
+  __device__ __forceinline__ void load(const float *src) { load_row<V>(src, v); }
+  __device__ __forceinline__ void get(float (&d)[V]) const {
+#pragma unroll
+    for (int e = 0; e < V; ++e) d[e] = v[e];
+  }
+};
+template <int V> struct Row<V, bf16_t> {
+  uint32_t w[V / 2];
+  __device__ __forceinline__ void load(const bf16_t *src) {
+    if constexpr (V == 4) {
+      const uint2 t = *reinterpret_cast<const uint2 *>(src);
+      w[0] = t.x; w[1] = t.y;
+    } else {
+      w[0] = *reinterpret_cast<const uint32_t *>(src);
+    }
+  }
+  __device__ __forceinline__ void get(float (&d)[V]) const {
+#pragma unroll
+    for (int e = 0; e < V / 2; ++e) { d[2 * e] = bf16_lo(w[e]); d[2 * e + 1] = bf16_hi(w[e]); }
+  }
+};
+
 // How waves tile one plane.
 struct StripMap {
   int lpr;        // lanes per strip row (power of two <= 64)
@@ -222,12 +250,12 @@ __device__ __forceinline__ void channel_loop(const XT *__restrict__ src, int64_t
                                              int n_ch, const LanePos<D> &p, Sink &sink,
                                              After &&after) {
   constexpr int R = 1 << D;
-  float buf[PF + 1][R][V];
+  Row<V, XT> buf[PF + 1][R];
 #pragma unroll
   for (int u = 0; u < PF; ++u) {
     const XT *nx = src + (size_t)min(u, n_ch - 1) * N;
 #pragma unroll
-    for (int r = 0; r < R; ++r) load_row<V>(nx + (size_t)r * W, buf[u][r]);
+    for (int r = 0; r < R; ++r) buf[u][r].load(nx + (size_t)r * W);
   }
   int c = 0;
   for (; c + PF < n_ch; c += PF + 1) {
@@ -235,16 +263,22 @@ __device__ __forceinline__ void channel_loop(const XT *__restrict__ src, int64_t
     for (int u = 0; u <= PF; ++u) {
       const XT *nx = src + (size_t)min(c + u + PF, n_ch - 1) * N;
 #pragma unroll
-      for (int r = 0; r < R; ++r) load_row<V>(nx + (size_t)r * W, buf[(u + PF) % (PF + 1)][r]);
+      for (int r = 0; r < R; ++r) buf[(u + PF) % (PF + 1)][r].load(nx + (size_t)r * W);
       __builtin_amdgcn_sched_barrier(0);  // the loads go out before the arithmetic, not after
-      fwd_levels<D, V, 1>(buf[u], p, sink);
+      float in[R][V];
+#pragma unroll
+      for (int r = 0; r < R; ++r) buf[u][r].get(in[r]);
+      fwd_levels<D, V, 1>(in, p, sink);
       after(sink);
     }
   }
 #pragma unroll
   for (int u = 0; u < PF; ++u) {
     if (c + u < n_ch) {
-      fwd_levels<D, V, 1>(buf[u], p, sink);
+      float in[R][V];
+#pragma unroll
+      for (int r = 0; r < R; ++r) buf[u][r].get(in[r]);
+      fwd_levels<D, V, 1>(in, p, sink);
       after(sink);
     }
   }
@@ -291,8 +325,8 @@ __device__ __forceinline__ void channel_loop_dw(const XT *__restrict__ src,
                                                 const DwLane &q, const LanePos<D> &p, Sink &sink,
                                                 After &&after) {
   constexpr int R = 1 << D, RR = R + 2;
-  float raw[2][RR][V];
-  float el[2][EDGE ? RR : 1], er[2][EDGE ? RR : 1];
+  Row<V, XT> raw[2][RR];
+  XT el[2][EDGE ? RR : 1], er[2][EDGE ? RR : 1];  // outside columns, as stored
   auto row_ptr = [&](const XT *plane, int i) -> const XT * {
     return i == 0 ? plane + q.top_step : i == RR - 1 ? plane + q.bot_step
                                                      : plane + (size_t)(i - 1) * q.row_step;
@@ -302,10 +336,10 @@ __device__ __forceinline__ void channel_loop_dw(const XT *__restrict__ src,
 #pragma unroll
     for (int i = 0; i < RR; ++i) {
       const XT *rp = row_ptr(plane, i);
-      load_row<V>(rp, raw[u][i]);
+      raw[u][i].load(rp);
       if constexpr (EDGE) {
-        el[u][i] = load_one(rp + q.left_off);
-        er[u][i] = load_one(rp + q.right_off);
+        el[u][i] = rp[q.left_off];
+        er[u][i] = rp[q.right_off];
       }
     }
   };
@@ -317,11 +351,13 @@ __device__ __forceinline__ void channel_loop_dw(const XT *__restrict__ src,
 #pragma unroll
     for (int i = 0; i < RR; ++i) {
       const bool in = i == 0 ? q.top_in : i == RR - 1 ? q.bot_in : true;
+      float own[V];
+      raw[u][i].get(own);
 #pragma unroll
-      for (int e = 0; e < V; ++e) six[i][e + 1] = in ? raw[u][i][e] : 0.f;
+      for (int e = 0; e < V; ++e) six[i][e + 1] = in ? own[e] : 0.f;
       float l = __shfl_up(six[i][V], 1, kWave), r = __shfl_down(six[i][1], 1, kWave);
-      if (q.first) l = (EDGE && in && q.left_off != 0) ? el[u][i] : 0.f;
-      if (q.last) r = (EDGE && in && q.right_off != 0) ? er[u][i] : 0.f;
+      if (q.first) l = (EDGE && in && q.left_off != 0) ? load_one(&el[u][i]) : 0.f;
+      if (q.last) r = (EDGE && in && q.right_off != 0) ? load_one(&er[u][i]) : 0.f;
       six[i][0] = l;
       six[i][V + 1] = r;
     }
