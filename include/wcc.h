@@ -134,7 +134,7 @@ wcc_status wcc_stage_times(wcc_ctx *ctx, float *ms /*[host], WCC_T_COUNT floats*
  * coef[b,c,:] = HWT_d(x[b,c,:,:]) for the C_in channels of desc; one level maps each 2x2
  * block [[a,b],[c,d]] to y1=(a+b+c+d)/2, y2=(a-b+c-d)/2, y3=(a+b-c-d)/2, y4=(a-b-c+d)/2 and
  * recurses on y1.  If norm != NULL it also receives norm[b,q] = sum_c |coef[b,c,q]| (the
- * "vector norm along the channel dimension" of Alg. 1, read as L1; channel partial sums are
+ * per-position norm over channels that Alg. 1 ranks by, read as L1; channel partial sums are
  * combined in a fixed order, so the result does not vary from run to run).
  * x is not modified.  Needs the workspace when norm != NULL. */
 wcc_status wcc_haar_fwd(wcc_ctx *ctx, const wcc_desc *desc, const float *x, float *coef,

@@ -66,7 +66,7 @@ void wcc_ref_set_threads(int n) {
 #endif
 }
 
-/* k = ceil(num * N / den)  (Alg. 1: "top ceil(gamma n_w n_h) vectors"). */
+/* k = ceil(num * N / den): the size of the index set I of Alg. 1, gamma = num/den. */
 int64_t wcc_ref_k(int64_t N, int64_t num, int64_t den) {
   return (num * N + den - 1) / den;
 }
@@ -172,7 +172,7 @@ int wcc_ref_haar_inv(const double *y, int64_t planes, int64_t H, int64_t W, int 
   return fail ? -1 : 0;
 }
 
-/* ---- channel norm (Alg. 1: "vector norm along the channel dimension") ---- */
+/* ---- channel norm (Alg. 1: one norm per position, taken over the channels) ---- */
 /* coef [B, C, N] -> norm [B, N], L1, channels added in increasing order. */
 void wcc_ref_channel_norm(const double *coef, int64_t B, int64_t C, int64_t N, double *norm) {
 #pragma omp parallel for schedule(static)

@@ -1,5 +1,5 @@
-// Multi-level Haar analysis / synthesis for gfx950 (Eq. HaarKernel, Eq. wavelet_transform;
-// "transposed operations in the opposite order" for the inverse), with the channel L1 norm
+// Multi-level Haar analysis / synthesis for gfx950 (Eq. HaarKernel, Eq. wavelet_transform; the
+// inverse undoes the levels last to first with the transposed kernels), with the channel L1 norm
 // of Alg. 1 fused into the analysis and the zero filling T^T fused into the synthesis.
 //
 // Design.  A d-level Haar transform is local to 2^d x 2^d pixel blocks, so the whole

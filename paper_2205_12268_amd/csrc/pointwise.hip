@@ -1,5 +1,5 @@
 // The 1x1 convolution on the compressed signal (Eq. WCC: K_1x1 applied between T and T^T;
-// "y_i = sum_j k_ij x_j" with x_j the length-k compressed channel vectors): per sample a
+// output channel i is sum_j k_ij x_j over the length-k compressed channel vectors x_j): per sample a
 // [C_out x C_in] . [C_in x k] contraction, k contiguous in memory on both sides.
 //
 // Matrix-core kernel (int8 activation codes):

@@ -1,4 +1,5 @@
-// Joint shrinkage (Alg. 1: "indices of the top ceil(gamma n_w n_h) vectors by norm"):
+// Joint shrinkage (Alg. 1: the index set I holds the k = ceil(gamma n_w n_h) positions whose
+// channel vectors have the largest norm):
 // per sample, the k largest of N non-negative fp32 norms, ties toward the lower position,
 // emitted in ascending position order.
 //
