@@ -103,7 +103,8 @@ def bench_block(args, synth, wcc, torch, np) -> int:
     if bf16:
         x = synth.round_to_bf16(x)
     d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
-                            cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.BF16 if bf16 else wcc.F32)
+                            cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.BF16 if bf16 else wcc.F32,
+                            wcc.NORM_L2 if args.norm == "l2" else wcc.NORM_L1)
     ctx = wcc.Context(0)
     ctx.ensure_workspace(d)
 
@@ -203,7 +204,7 @@ def bench_block(args, synth, wcc, torch, np) -> int:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": "eager",
         "config": {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "expansion": cfg.expansion,
                    "H": cfg.H, "W": cfg.W, "levels": cfg.levels, "keep": f"{num}/{den}",
-                   "act_bits": cfg.act_bits, "act": args.act},
+                   "act_bits": cfg.act_bits, "act": args.act, "norm": args.norm},
         "roofline": {"bound": "hbm", "kernel": kernel_of[dom], "stage": dom,
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
@@ -249,6 +250,9 @@ def main() -> int:
     ap.add_argument("--act", choices=["f32", "bf16"], default="f32",
                     help="storage type of the feature maps x and y (bf16: a bandwidth variant; the "
                          "metric is quoted on f32)")
+    ap.add_argument("--norm", choices=["l1", "l2"], default="l1",
+                    help="l2: positions ranked by the sum of squares over channels (a variant; the "
+                         "metric is quoted on l1)")
     ap.add_argument("--index-list", choices=["select", "prefix"], default="select",
                     help="prefix: wcc_forward_fixed with the first k positions instead of the joint "
                          "shrinkage's top-k (single-layer workloads)")
@@ -282,7 +286,8 @@ def main() -> int:
         if bf16:
             x = synth.round_to_bf16(x)
         d = wcc.make_desc(cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
-                          cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.BF16 if bf16 else wcc.F32)
+                          cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.BF16 if bf16 else wcc.F32,
+                          wcc.NORM_L2 if args.norm == "l2" else wcc.NORM_L1)
         ctx.ensure_workspace(d)
         xd = torch.from_numpy(x).cuda()
         if bf16:
@@ -387,7 +392,8 @@ def main() -> int:
         "config": {"workload": cfg.name, "B": cfg.B, "C_in": cfg.C_in, "C_out": cfg.C_out,
                    "H": cfg.H, "W": cfg.W, "levels": cfg.levels,
                    "keep": f"{cfg.keep_num}/{cfg.keep_den}", "act_bits": cfg.act_bits,
-                   "index_list": args.index_list, "alpha": args.alpha, "act": args.act},
+                   "index_list": args.index_list, "alpha": args.alpha, "act": args.act,
+                   "norm": args.norm},
         "roofline": {"bound": "hbm", "kernel": STAGE_KERNEL[dom], "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "algorithmic_bytes": alg[dom],

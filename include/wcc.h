@@ -38,7 +38,7 @@
  *                                    | y4^(d-1) | ... | y2^1 | y3^1 | y4^1 ],
  *                                  band j (1..3 -> y2..y4) of level l at offset
  *                                  j*n_l, each band row-major (H>>l) x (W>>l).
- *   norm  [B, N]            fp32   L1 norm over channels of coef at each position
+ *   norm  [B, N]            fp32   norm over channels of coef at each position (desc.norm)
  *   idx   [B, k]            int32  kept positions of each sample, strictly ascending
  *   xc    [B, C_in,  k]     fp32 (act_quant_bits = 0) or int8 codes (= 8)
  *   yc    [B, C_out, k]     fp32
@@ -77,6 +77,11 @@ typedef enum {
 
 typedef enum { WCC_F32 = 0, WCC_BF16 = 1, WCC_I8 = 2, WCC_I4 = 3 } wcc_dtype;
 
+/* Which norm over the channels ranks the positions (Alg. 1 names none): the sum of absolute
+ * values, or the sum of squares -- the Euclidean norm without its square root, which orders
+ * the positions the same way. */
+typedef enum { WCC_NORM_L1 = 0, WCC_NORM_L2 = 1 } wcc_norm;
+
 /* One WCC layer: the inputs of the explicit algorithm (feature-map shape,
  * kernel shape, wavelet level d, kept fraction gamma) plus storage types. */
 typedef struct {
@@ -92,6 +97,9 @@ typedef struct {
                                  fused calls (wcc_forward, wcc_forward_fixed,
                                  wcc_block_forward) take bf16; the stage calls return
                                  WCC_ERR_UNSUPPORTED for it                                   */
+  int32_t norm;               /* wcc_norm: WCC_NORM_L1 (0, the default) or WCC_NORM_L2.  With
+                                 WCC_NORM_L2 every norm tensor holds sum_c coef^2 (partial sums
+                                 combined in a fixed order) and feature maps must be fp32     */
 } wcc_desc;
 
 /* Stages whose device time wcc_forward can record (wcc_set_profiling). */
@@ -134,8 +142,9 @@ wcc_status wcc_stage_times(wcc_ctx *ctx, float *ms /*[host], WCC_T_COUNT floats*
  * coef[b,c,:] = HWT_d(x[b,c,:,:]) for the C_in channels of desc; one level maps each 2x2
  * block [[a,b],[c,d]] to y1=(a+b+c+d)/2, y2=(a-b+c-d)/2, y3=(a+b-c-d)/2, y4=(a-b-c+d)/2 and
  * recurses on y1.  If norm != NULL it also receives norm[b,q] = sum_c |coef[b,c,q]| (the
- * per-position norm over channels that Alg. 1 ranks by, read as L1; channel partial sums are
- * combined in a fixed order, so the result does not vary from run to run).
+ * per-position norm over channels that Alg. 1 ranks by, read as L1), or sum_c coef[b,c,q]^2
+ * with desc.norm = WCC_NORM_L2; channel partial sums are combined in a fixed order, so the
+ * result does not vary from run to run.
  * x is not modified.  Needs the workspace when norm != NULL. */
 wcc_status wcc_haar_fwd(wcc_ctx *ctx, const wcc_desc *desc, const float *x, float *coef,
                         float *norm /*nullable*/, void *stream);
@@ -213,6 +222,7 @@ typedef struct {
   int32_t act_quant_bits;
   int32_t act_dtype;         /* storage type of x, y and the middle tensor (see wcc_desc);
                                 WCC_BF16 needs W % 4 == 0 and t2_out = NULL                  */
+  int32_t norm;              /* wcc_norm of both layers (see wcc_desc)                       */
 } wcc_block_desc;
 
 /* Workspace for wcc_block_forward: the two middle tensors plus the larger of the two layers'

@@ -186,6 +186,21 @@ void wcc_ref_channel_norm(const double *coef, int64_t B, int64_t C, int64_t N, d
   }
 }
 
+/* The other common reading of the norm Alg. 1 leaves unnamed: Euclidean.  The square root is
+ * left out (it does not change the order of non-negative numbers):
+ * coef [B, C, N] -> norm [B, N] = sum_c coef^2, channels added in increasing order. */
+void wcc_ref_channel_norm_sq(const double *coef, int64_t B, int64_t C, int64_t N, double *norm) {
+#pragma omp parallel for schedule(static)
+  for (int64_t b = 0; b < B; ++b) {
+    double *s = norm + b * N;
+    for (int64_t q = 0; q < N; ++q) s[q] = 0.0;
+    for (int64_t c = 0; c < C; ++c) {
+      const double *v = coef + (b * C + c) * N;
+      for (int64_t q = 0; q < N; ++q) s[q] += v[q] * v[q];
+    }
+  }
+}
+
 /* ---- joint top-k (Alg. 1: index set I) by a full sort ---- */
 typedef struct {
   double s;

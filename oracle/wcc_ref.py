@@ -33,6 +33,8 @@ def lib():
         L.wcc_ref_haar_inv.argtypes = [_pd, _i64, _i64, _i64, C.c_int, _pd]
         L.wcc_ref_channel_norm.restype = None
         L.wcc_ref_channel_norm.argtypes = [_pd, _i64, _i64, _i64, _pd]
+        L.wcc_ref_channel_norm_sq.restype = None
+        L.wcc_ref_channel_norm_sq.argtypes = [_pd, _i64, _i64, _i64, _pd]
         L.wcc_ref_topk.restype = C.c_int
         L.wcc_ref_topk.argtypes = [_pd, _i64, _i64, _i64, _pi]
         L.wcc_ref_gather.restype = None
@@ -106,12 +108,13 @@ def haar_inv(y, H: int, W: int, levels: int):
     return x
 
 
-def channel_norm(coef):
-    """coef [B, C, N] -> [B, N]."""
+def channel_norm(coef, norm: str = "l1"):
+    """coef [B, C, N] -> [B, N]: sum over channels of |coef| ("l1") or of coef^2 ("l2")."""
     coef = _d(coef)
     B, Cc, N = coef.shape
     out = np.empty((B, N), dtype=np.float64)
-    lib().wcc_ref_channel_norm(_p(coef), B, Cc, N, _p(out))
+    fn = {"l1": lib().wcc_ref_channel_norm, "l2": lib().wcc_ref_channel_norm_sq}[norm]
+    fn(_p(coef), B, Cc, N, _p(out))
     return out
 
 
@@ -170,11 +173,17 @@ def pointwise(w, out_scale, xc):
 
 
 def forward(x, w, w_scale, levels: int, keep_num: int, keep_den: int, act_bits: int = 0,
-            alpha_in: float = 0.0):
-    """Whole layer.  Returns (y [B,C_out,H,W], idx [B,k], alpha)."""
+            alpha_in: float = 0.0, norm: str = "l1"):
+    """Whole layer.  Returns (y [B,C_out,H,W], idx [B,k], alpha).  norm = "l2": the positions
+    are ranked by the sum of squares over channels; the steps are then taken one by one."""
     x = _d(x)
     w = _d(w)
     B, Ci, H, W = x.shape
+    if norm != "l1":
+        coef = haar_fwd(x, levels).reshape(B, Ci, H * W)
+        idx = topk(channel_norm(coef, norm), k_of(H * W, keep_num, keep_den))
+        y, alpha = forward_with_list(x, w, w_scale, levels, idx, act_bits, alpha_in)
+        return y, idx, alpha
     Co = w.shape[0]
     assert w.shape == (Co, Ci)
     sc = None if w_scale is None else _d(w_scale)
@@ -224,15 +233,15 @@ def depthwise3x3(x, w):
 
 
 def block_forward(x, w1, w1_scale, w_dw, w3, w3_scale, levels: int, keep_num: int, keep_den: int,
-                  act_bits: int = 0):
+                  act_bits: int = 0, norm: str = "l1"):
     """The inverted residual block of Eq. (inverted) with both 1x1 convolutions as WCC layers
     (activations left out, as in the paper's timings):
     x + WCC(K3, K_dw(WCC(K1, x))).  Returns (y, t1, t2, idx1, idx3, alpha1, alpha3) where
     t1 = WCC(K1, x) and t2 = K_dw t1."""
     x = _d(x)
-    t1, idx1, a1 = forward(x, w1, w1_scale, levels, keep_num, keep_den, act_bits)
+    t1, idx1, a1 = forward(x, w1, w1_scale, levels, keep_num, keep_den, act_bits, norm=norm)
     t2 = depthwise3x3(t1, w_dw)
-    t3, idx3, a3 = forward(t2, w3, w3_scale, levels, keep_num, keep_den, act_bits)
+    t3, idx3, a3 = forward(t2, w3, w3_scale, levels, keep_num, keep_den, act_bits, norm=norm)
     return x + t3, t1, t2, idx1, idx3, a1, a3
 
 

@@ -69,7 +69,8 @@ struct LanePos {
 
 // ---- analysis ---------------------------------------------------------------------------
 // STORE = false: only the |coefficient| sums are kept (the norm-only pass of the fused layer).
-template <int D, int V, bool STORE>
+// SQ: the sums are of squared coefficients (one fused multiply-add each) instead.
+template <int D, int V, bool STORE, bool SQ = false>
 struct FwdSink {
   float *plane;  // wavelet vector of the current (b, c)
   float acc[slot_count(D, V)];
@@ -79,7 +80,10 @@ struct FwdSink {
     constexpr int CV = cols_at(V, L);
     constexpr int base = slot_base(D, V, L, J);
 #pragma unroll
-    for (int e = 0; e < CV; ++e) acc[base + i * CV + e] += fabsf(v[e]);
+    for (int e = 0; e < CV; ++e) {
+      float &a = acc[base + i * CV + e];
+      a = SQ ? fmaf(v[e], v[e], a) : a + fabsf(v[e]);
+    }
     if (!STORE || !owner) return;
     float *dst = plane + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
     if constexpr (CV == 2) {
@@ -406,8 +410,8 @@ __device__ __forceinline__ void channel_loop_dw(const XT *__restrict__ src,
 //                added in wave order.
 // DWM: 0 = x is transformed as it is; 1, 2 = K_dw x is (wdw [C, 3, 3]; 2: the outside columns
 // of a wave row's first and last lane exist and are read).
-// XT: float or bf16_t, the storage type of x.
-template <int D, int V, bool SPLIT, bool STORE, int PF, int DWM, class XT>
+// XT: float or bf16_t, the storage type of x.  SQ: sums of squares instead of absolute values.
+template <int D, int V, bool SPLIT, bool STORE, int PF, int DWM, class XT, bool SQ = false>
 __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
                                                        float *__restrict__ coef,
                                                        float *__restrict__ norm_part, Geo g,
@@ -431,7 +435,7 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
     c1 = min(c1, c0 + Cw);
   }
 
-  FwdSink<D, V, STORE> sink;
+  FwdSink<D, V, STORE, SQ> sink;
 #pragma unroll
   for (int s = 0; s < NS; ++s) sink.acc[s] = 0.f;
 
@@ -440,13 +444,13 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
     sink.plane = STORE ? coef + ((size_t)b * C + c0) * g.N : nullptr;
     const int64_t N = g.N;
     if constexpr (DWM == 0) {
-      channel_loop<D, V, PF>(src, N, g.W, c1 - c0, p, sink, [N](FwdSink<D, V, STORE> &sk) {
+      channel_loop<D, V, PF>(src, N, g.W, c1 - c0, p, sink, [N](FwdSink<D, V, STORE, SQ> &sk) {
         if (STORE) sk.plane += N;
       });
     } else {
       const DwLane q = dw_lane<D, V>(g, m, p, row0, col0);
       channel_loop_dw<D, V, DWM == 2, false>(src, wdw + (size_t)c0 * 9, N, c1 - c0, q, p, sink,
-                                             [](FwdSink<D, V, STORE> &) {});
+                                             [](FwdSink<D, V, STORE, SQ> &) {});
     }
   }
 
@@ -928,7 +932,9 @@ __global__ __launch_bounds__(256) void norm_reduce_kernel(const float *__restric
   norm[i] = s;
 }
 
-// norm[b, q] = sum_c |coef[b, c, q]|, channels in increasing order.  grid = (ceil(N/4/256), B)
+// norm[b, q] = sum_c |coef[b, c, q]| (SQ: sum_c coef^2), channels in increasing order.
+// grid = (ceil(N/4/256), B)
+template <bool SQ>
 __global__ __launch_bounds__(256) void channel_norm_kernel(const float *__restrict__ coef, int C,
                                                            int64_t N, float *__restrict__ norm) {
   const int64_t i4 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -938,7 +944,12 @@ __global__ __launch_bounds__(256) void channel_norm_kernel(const float *__restri
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int c = 0; c < C; ++c) {
     const float4 t = p[(size_t)c * (N / 4)];
-    s.x += fabsf(t.x); s.y += fabsf(t.y); s.z += fabsf(t.z); s.w += fabsf(t.w);
+    if constexpr (SQ) {
+      s.x = fmaf(t.x, t.x, s.x); s.y = fmaf(t.y, t.y, s.y);
+      s.z = fmaf(t.z, t.z, s.z); s.w = fmaf(t.w, t.w, s.w);
+    } else {
+      s.x += fabsf(t.x); s.y += fabsf(t.y); s.z += fabsf(t.z); s.w += fabsf(t.w);
+    }
   }
   reinterpret_cast<float4 *>(norm + (size_t)b * N)[i4] = s;
 }
@@ -995,6 +1006,28 @@ hipError_t fwd_launch_t(const wcc_desc &d, const XT *x, float *coef, float *norm
   hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, STORE, PF, DWM, XT>),                              \
                      SPLIT ? grid_split : grid_flat, block, 0, s, x, coef, norm_part, g, m, d.C_in,   \
                      Cg, d.B, prep, wdw)
+  if (d.norm == WCC_NORM_L2) {
+    // sums of squares: the norm-only pass over fp32 maps, prefetch depth 1
+    if constexpr (!STORE && std::is_same<XT, float>::value) {
+#define WCC_FWD_SQ(SPLIT, DWM)                                                                        \
+  hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, false, 1, DWM, float, true>),                      \
+                     SPLIT ? grid_split : grid_flat, block, 0, s, x, coef, norm_part, g, m, d.C_in,   \
+                     Cg, d.B, prep, wdw)
+      if (wdw != nullptr) {
+        if constexpr (V == 4) {
+          const bool edges = dw_needs_edges(m);
+          if (pl.split) { if (edges) WCC_FWD_SQ(true, 2); else WCC_FWD_SQ(true, 1); }
+          else          { if (edges) WCC_FWD_SQ(false, 2); else WCC_FWD_SQ(false, 1); }
+          return hipGetLastError();
+        }
+        return hipErrorInvalidValue;
+      }
+      if (pl.split) WCC_FWD_SQ(true, 0); else WCC_FWD_SQ(false, 0);
+#undef WCC_FWD_SQ
+      return hipGetLastError();
+    }
+    return hipErrorInvalidValue;
+  }
   if constexpr (!STORE && V == 4) {
     if (wdw != nullptr) {  // K_dw in front of the transform (norm-only pass)
       const bool edges = dw_needs_edges(m);
@@ -1175,10 +1208,13 @@ hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *
   return hipGetLastError();
 }
 
-hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, float *norm,
-                               hipStream_t s) {
+hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, bool squares,
+                               float *norm, hipStream_t s) {
   dim3 grid((unsigned)((N / 4 + 255) / 256), B);
-  hipLaunchKernelGGL(channel_norm_kernel, grid, dim3(256), 0, s, coef, C, N, norm);
+  if (squares)
+    hipLaunchKernelGGL(channel_norm_kernel<true>, grid, dim3(256), 0, s, coef, C, N, norm);
+  else
+    hipLaunchKernelGGL(channel_norm_kernel<false>, grid, dim3(256), 0, s, coef, C, N, norm);
   return hipGetLastError();
 }
 

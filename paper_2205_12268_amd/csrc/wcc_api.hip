@@ -40,6 +40,8 @@ wcc_status check_desc(const wcc_desc *d) {
   if (d->w_dtype == WCC_I4 && d->C_in % 2) return WCC_ERR_SHAPE;
   if (d->act_quant_bits != 0 && d->act_quant_bits != 8) return WCC_ERR_DTYPE;
   if (d->act_dtype != WCC_F32 && d->act_dtype != WCC_BF16) return WCC_ERR_DTYPE;
+  if (d->norm != WCC_NORM_L1 && d->norm != WCC_NORM_L2) return WCC_ERR_DTYPE;
+  if (d->norm == WCC_NORM_L2 && d->act_dtype != WCC_F32) return WCC_ERR_UNSUPPORTED;
   if (d->keep_num < 1 || d->keep_den < 1 || d->keep_num > d->keep_den) return WCC_ERR_KEEP;
   const int64_t N = (int64_t)d->H * d->W;
   // keep_num * N must not overflow
@@ -182,7 +184,7 @@ wcc_status block_layers(const wcc_block_desc *bd, wcc_desc &d1, wcc_desc &d3) {
   if (!bd) return WCC_ERR_NULL;
   if (bd->C < 1 || bd->expansion < 1 || (int64_t)bd->C * bd->expansion > 65535) return WCC_ERR_SHAPE;
   d1 = wcc_desc{bd->B, bd->C, bd->C * bd->expansion, bd->H, bd->W, bd->levels, bd->keep_num,
-                bd->keep_den, bd->w_dtype, bd->act_quant_bits, bd->act_dtype};
+                bd->keep_den, bd->w_dtype, bd->act_quant_bits, bd->act_dtype, bd->norm};
   d3 = d1;
   d3.C_in = d1.C_out;
   d3.C_out = bd->C;
@@ -300,8 +302,13 @@ wcc_status wcc_haar_fwd(wcc_ctx *ctx, const wcc_desc *desc, const float *x, floa
   hipStream_t s = static_cast<hipStream_t>(stream);
   const WsLayout L = ws_layout(*desc);
   const SelectPrep no_prep{nullptr, nullptr, 0.f};
-  if (!norm) {
-    WCC_TRY(launch_haar_fwd(*desc, x, coef, nullptr, L.G, no_prep, s));
+  if (!norm || desc->norm == WCC_NORM_L2) {
+    // (sums of squares are taken from the stored coefficients in a pass of their own)
+    wcc_desc plain = *desc;
+    plain.norm = WCC_NORM_L1;
+    WCC_TRY(launch_haar_fwd(plain, x, coef, nullptr, L.G, no_prep, s));
+    if (norm)
+      WCC_TRY(launch_channel_norm(coef, desc->B, desc->C_in, (int64_t)desc->H * desc->W, true, norm, s));
     return WCC_OK;
   }
   if ((st = need_ws(ctx, L)) != WCC_OK) return st;
@@ -328,7 +335,8 @@ wcc_status wcc_joint_topk(wcc_ctx *ctx, const wcc_desc *desc, const float *coef,
   char *ws = static_cast<char *>(ctx->ws);
   if (!norm) {
     float *nw = reinterpret_cast<float *>(ws + L.norm);
-    WCC_TRY(launch_channel_norm(coef, desc->B, desc->C_in, (int64_t)desc->H * desc->W, nw, s));
+    WCC_TRY(launch_channel_norm(coef, desc->B, desc->C_in, (int64_t)desc->H * desc->W,
+                                desc->norm == WCC_NORM_L2, nw, s));
     norm = nw;
   }
   const int64_t k = k_of(*desc);

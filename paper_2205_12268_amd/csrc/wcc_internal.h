@@ -139,7 +139,8 @@ hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const i
                             void *xc, float *alpha_slots /*nullable*/, const float *wdw /*nullable*/,
                             float q_alpha, hipStream_t s);
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s);
-hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, float *norm, hipStream_t s);
+hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, bool squares, float *norm,
+                               hipStream_t s);
 SelectPrep make_prep(void *ws_base, const WsLayout &L, float *alpha_slots, float alpha_in);
 hipError_t launch_select_init(const SelectPrep &p, int B, hipStream_t s);
 // G > 1: norm_or_part is [G, B, N] partial norms, reduced into norm_out on the fly;

@@ -15,6 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libwcc.so")
 
 F32, BF16, I8, I4 = 0, 1, 2, 3
+NORM_L1, NORM_L2 = 0, 1
 STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "event_pair",
           "depthwise")
 
@@ -30,7 +31,7 @@ class Desc(C.Structure):
     _fields_ = [("B", C.c_int32), ("C_in", C.c_int32), ("C_out", C.c_int32), ("H", C.c_int32),
                 ("W", C.c_int32), ("levels", C.c_int32), ("keep_num", C.c_int64),
                 ("keep_den", C.c_int64), ("w_dtype", C.c_int32), ("act_quant_bits", C.c_int32),
-                ("act_dtype", C.c_int32)]
+                ("act_dtype", C.c_int32), ("norm", C.c_int32)]
 
 
 class BlockDesc(C.Structure):
@@ -38,7 +39,7 @@ class BlockDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("C", C.c_int32), ("expansion", C.c_int32), ("H", C.c_int32),
                 ("W", C.c_int32), ("levels", C.c_int32), ("keep_num", C.c_int64),
                 ("keep_den", C.c_int64), ("w_dtype", C.c_int32), ("act_quant_bits", C.c_int32),
-                ("act_dtype", C.c_int32)]
+                ("act_dtype", C.c_int32), ("norm", C.c_int32)]
 
 
 class WccError(RuntimeError):
@@ -98,8 +99,9 @@ def _check(status: int, where: str) -> None:
 
 
 def make_desc(B, C_in, C_out, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits,
-              act_dtype=F32) -> Desc:
-    return Desc(B, C_in, C_out, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits, act_dtype)
+              act_dtype=F32, norm=NORM_L1) -> Desc:
+    return Desc(B, C_in, C_out, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits, act_dtype,
+                norm)
 
 
 def k_of(desc: Desc) -> int:
@@ -113,9 +115,9 @@ def workspace_bytes(desc: Desc) -> int:
 
 
 def make_block_desc(B, Cc, expansion, H, W, levels, keep_num, keep_den, w_dtype,
-                    act_quant_bits, act_dtype=F32) -> BlockDesc:
+                    act_quant_bits, act_dtype=F32, norm=NORM_L1) -> BlockDesc:
     return BlockDesc(B, Cc, expansion, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits,
-                     act_dtype)
+                     act_dtype, norm)
 
 
 def block_workspace_bytes(desc: BlockDesc) -> int:

@@ -51,6 +51,7 @@ def test_k_and_workspace_are_pure_host_functions():
     (dict(H=12, levels=3), 2), (dict(levels=0), 2), (dict(levels=5), 2), (dict(B=0), 2),
     (dict(W=6, levels=2), 2), (dict(w_dtype=7), 3), (dict(act_quant_bits=4), 3),
     (dict(keep_num=0), 4), (dict(keep_num=3, keep_den=2), 4), (dict(keep_den=0), 4),
+    (dict(norm=2), 3), (dict(norm=wcc.NORM_L2, act_dtype=wcc.BF16), 6),
 ])
 def test_descriptor_errors(kw, status):
     base = dict(B=1, C_in=4, C_out=4, H=16, W=16, levels=2, keep_num=1, keep_den=4,

@@ -171,6 +171,57 @@ def test_channel_norm_is_l1(ref):
     np.testing.assert_allclose(ref.channel_norm(c), np.linalg.norm(c, ord=1, axis=1), atol=1e-14)
 
 
+def test_channel_norm_l2_is_the_squared_euclidean_norm(ref):
+    rng = np.random.default_rng(3)
+    c = rng.standard_normal((3, 5, 40))
+    np.testing.assert_allclose(ref.channel_norm(c, "l2"), np.linalg.norm(c, ord=2, axis=1) ** 2,
+                               rtol=1e-13)
+    # a 3-4-5 triangle: L1 = 7, squared L2 = 25
+    c = np.zeros((1, 2, 4))
+    c[0, :, 1] = [3.0, -4.0]
+    np.testing.assert_array_equal(ref.channel_norm(c, "l2")[0], [0.0, 25.0, 0.0, 0.0])
+    np.testing.assert_array_equal(ref.channel_norm(c, "l1")[0], [0.0, 7.0, 0.0, 0.0])
+
+
+def test_l1_and_l2_rank_differently_where_they_should(ref):
+    """One pixel per 2x2 block is set so that every wavelet coefficient of the block has the
+    magnitude pixel/2 (one level, orthonormal 2x2 kernels).  Block A carries (3, 3) over the two
+    channels, block B (5, 0): L1 prefers A (3 > 2.5), L2 prefers B (4.5 < 6.25)."""
+    x = np.zeros((1, 2, 2, 4))
+    x[0, :, 0, 0] = [3.0, 3.0]     # block A = columns 0..1
+    x[0, :, 0, 2] = [5.0, 0.0]     # block B = columns 2..3
+    w = np.eye(2)
+    coef = ref.haar_fwd(x, 1).reshape(1, 2, 8)
+    # N = 8 positions: 4 bands x 2 blocks; the block's column inside each band is 0 (A) or 1 (B)
+    _, idx1, _ = ref.forward(x, w, None, 1, 1, 2)
+    _, idx2, _ = ref.forward(x, w, None, 1, 1, 2, norm="l2")
+    np.testing.assert_array_equal(idx1[0], [0, 2, 4, 6])
+    np.testing.assert_array_equal(idx2[0], [1, 3, 5, 7])
+    np.testing.assert_allclose(np.abs(coef[0, :, 0]), [1.5, 1.5])
+    np.testing.assert_allclose(np.abs(coef[0, :, 1]), [2.5, 0.0])
+    # with every position kept the norm no longer matters
+    ya, _, _ = ref.forward(x, w, None, 1, 1, 1)
+    yb, _, _ = ref.forward(x, w, None, 1, 1, 1, norm="l2")
+    np.testing.assert_array_equal(ya, yb)
+    np.testing.assert_allclose(ya, x, atol=1e-15)
+
+
+def test_l2_layer_equals_stage_composition(ref):
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal((2, 6, 8, 16))
+    w = rng.standard_normal((5, 6))
+    y, idx, _ = ref.forward(x, w, None, 2, 1, 4, norm="l2")
+    coef = ref.haar_fwd(x, 2).reshape(2, 6, 128)
+    s = (coef ** 2).sum(axis=1)
+    for b in range(2):
+        order = np.lexsort((np.arange(128), -s[b]))[:32]
+        assert sorted(order) == list(idx[b])
+    z = np.zeros((2, 5, 128))
+    for b in range(2):
+        z[b][:, idx[b]] = w @ coef[b][:, idx[b]]
+    np.testing.assert_allclose(y, ref.haar_inv(z, 8, 16, 2), atol=1e-12)
+
+
 def test_topk_brute_force_tiny(ref):
     rng = np.random.default_rng(23)
     for trial in range(30):
