@@ -983,7 +983,6 @@ StripMap make_map(const wcc_desc &d, int V) {
 struct Plan {
   int G;       // channel groups (grid.y)
   bool split;  // forward/norm pass only: the 4 waves of a workgroup split a group's channels
-  int pf;      // prefetch depth in channels (1 or 2)
 };
 
 // x is fp32, or bf16 when the layer's activations are stored that way (fused calls only)
@@ -1037,8 +1036,8 @@ hipError_t fwd_launch_t(const wcc_desc &d, const XT *x, float *coef, float *norm
     }
   }
   if (wdw != nullptr) return hipErrorInvalidValue;
-  if (pl.split) { if (pl.pf == 2) WCC_FWD(true, 2, 0); else WCC_FWD(true, 1, 0); }
-  else          { if (pl.pf == 2) WCC_FWD(false, 2, 0); else WCC_FWD(false, 1, 0); }
+  // (a prefetch depth of two channels was measured on every workload and never paid)
+  if (pl.split) WCC_FWD(true, 1, 0); else WCC_FWD(false, 1, 0);
 #undef WCC_FWD
   return hipGetLastError();
 }
@@ -1077,7 +1076,7 @@ hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_
     }
   }
   if (wdw != nullptr) return hipErrorInvalidValue;
-  if (pl.pf == 2) WCC_KEEP(2, 0); else WCC_KEEP(1, 0);
+  WCC_KEEP(1, 0);
 #undef WCC_KEEP
   return hipGetLastError();
 }
@@ -1174,7 +1173,7 @@ Plan fwd_plan(const wcc_desc &d, int G) {
   const int Cg = (d.C_in + G - 1) / G;
   const StripMap m = make_map(d, (d.W % 4 == 0) ? 4 : 2);
   const int64_t waves = (int64_t)m.units * d.B * G;
-  return Plan{G, waves < 1024 && Cg >= 8, 1};
+  return Plan{G, waves < 1024 && Cg >= 8};
 }
 
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
@@ -1184,15 +1183,14 @@ hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float
 
 hipError_t launch_haar_norm(const wcc_desc &d, const void *x, float *norm_part, int G,
                             const SelectPrep &prep, const float *wdw, hipStream_t s) {
-  Plan pl = fwd_plan(d, G);
-  if (wdw) pl.pf = 1;
+  const Plan pl = fwd_plan(d, G);
   return fwd_dispatch<false>(d, x, nullptr, norm_part, pl, prep, wdw, s);
 }
 
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap,
                             void *xc, float *alpha_slots, const float *wdw, float q_alpha,
                             hipStream_t s) {
-  const Plan pl{groups_for(d, d.C_in, 1024, 8), false, 1};
+  const Plan pl{groups_for(d, d.C_in, 1024, 8), false};
   return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
 }
 
