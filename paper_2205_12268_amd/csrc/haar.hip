@@ -153,6 +153,36 @@ __device__ __forceinline__ void store_row(float *dst, const float (&src)[V]) {
 }
 __device__ __forceinline__ float load_one(const float *src) { return *src; }
 
+// Streaming variants: the access carries the non-temporal hint, so it does not claim lines in
+// the memory-side cache.  Used for tensors much larger than that cache that are read or written
+// once: without the hint the output of the inverse transform fills the cache with dirty lines
+// whose write-back the next reader of anything pays for.
+typedef float stream_f4 __attribute__((ext_vector_type(4)));
+typedef float stream_f2 __attribute__((ext_vector_type(2)));
+typedef uint32_t stream_u2 __attribute__((ext_vector_type(2)));
+template <int V>
+__device__ __forceinline__ void load_row_stream(const float *src, float (&dst)[V]) {
+  if constexpr (V == 4) {
+    const stream_f4 t = __builtin_nontemporal_load(reinterpret_cast<const stream_f4 *>(src));
+    dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w;
+  } else {
+    const stream_f2 t = __builtin_nontemporal_load(reinterpret_cast<const stream_f2 *>(src));
+    dst[0] = t.x; dst[1] = t.y;
+  }
+}
+template <int V>
+__device__ __forceinline__ void store_row_stream(float *dst, const float (&src)[V]) {
+  if constexpr (V == 4) {
+    stream_f4 t;
+    t.x = src[0]; t.y = src[1]; t.z = src[2]; t.w = src[3];
+    __builtin_nontemporal_store(t, reinterpret_cast<stream_f4 *>(dst));
+  } else {
+    stream_f2 t;
+    t.x = src[0]; t.y = src[1];
+    __builtin_nontemporal_store(t, reinterpret_cast<stream_f2 *>(dst));
+  }
+}
+
 // The same for activations stored as bf16 (bit patterns in uint16): widening is exact, narrowing
 // rounds to nearest even.
 __device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
@@ -182,6 +212,28 @@ __device__ __forceinline__ void store_row(bf16_t *dst, const float (&src)[V]) {
   }
 }
 __device__ __forceinline__ float load_one(const bf16_t *src) { return __uint_as_float((uint32_t)*src << 16); }
+template <int V>
+__device__ __forceinline__ void load_row_stream(const bf16_t *src, float (&dst)[V]) {
+  if constexpr (V == 4) {
+    const stream_u2 t = __builtin_nontemporal_load(reinterpret_cast<const stream_u2 *>(src));
+    dst[0] = bf16_lo(t.x); dst[1] = bf16_hi(t.x); dst[2] = bf16_lo(t.y); dst[3] = bf16_hi(t.y);
+  } else {
+    const uint32_t t = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src));
+    dst[0] = bf16_lo(t); dst[1] = bf16_hi(t);
+  }
+}
+template <int V>
+__device__ __forceinline__ void store_row_stream(bf16_t *dst, const float (&src)[V]) {
+  const uint32_t a = to_bf16(src[0]) | (to_bf16(src[1]) << 16);
+  if constexpr (V == 4) {
+    stream_u2 t;
+    t.x = a;
+    t.y = to_bf16(src[2]) | (to_bf16(src[3]) << 16);
+    __builtin_nontemporal_store(t, reinterpret_cast<stream_u2 *>(dst));
+  } else {
+    __builtin_nontemporal_store(a, reinterpret_cast<uint32_t *>(dst));
+  }
+}
 
 // What a lane loads of one row, kept as it arrives: the widening of bf16 happens when the
 // values are used, not where the load is issued (a conversion next to the load would wait for it
@@ -189,7 +241,10 @@ __device__ __forceinline__ float load_one(const bf16_t *src) { return __uint_as_
 template <int V, class T> struct Row;
 template <int V> struct Row<V, float> {
   float v[V];
-  __device__ __forceinline__ void load(const float *src) { load_row<V>(src, v); }
+  template <bool NT = false>
+  __device__ __forceinline__ void load(const float *src) {
+    if constexpr (NT) load_row_stream<V>(src, v); else load_row<V>(src, v);
+  }
   __device__ __forceinline__ void get(float (&d)[V]) const {
 #pragma unroll
     for (int e = 0; e < V; ++e) d[e] = v[e];
@@ -197,12 +252,19 @@ template <int V> struct Row<V, float> {
 };
 template <int V> struct Row<V, bf16_t> {
   uint32_t w[V / 2];
+  template <bool NT = false>
   __device__ __forceinline__ void load(const bf16_t *src) {
     if constexpr (V == 4) {
-      const uint2 t = *reinterpret_cast<const uint2 *>(src);
-      w[0] = t.x; w[1] = t.y;
+      if constexpr (NT) {
+        const stream_u2 t = __builtin_nontemporal_load(reinterpret_cast<const stream_u2 *>(src));
+        w[0] = t.x; w[1] = t.y;
+      } else {
+        const uint2 t = *reinterpret_cast<const uint2 *>(src);
+        w[0] = t.x; w[1] = t.y;
+      }
     } else {
-      w[0] = *reinterpret_cast<const uint32_t *>(src);
+      w[0] = NT ? __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src))
+                : *reinterpret_cast<const uint32_t *>(src);
     }
   }
   __device__ __forceinline__ void get(float (&d)[V]) const {
@@ -249,7 +311,7 @@ __device__ __forceinline__ bool locate(const StripMap &m, const Geo &g, int unit
 // has to drain the prefetch as well (the counter is in order).  A prefetch past the last
 // channel reads the last channel again (a cache hit); the at most PF channels left after the
 // main loop are already in registers.
-template <int D, int V, int PF, class XT, class Sink, class After>
+template <int D, int V, int PF, bool NT, class XT, class Sink, class After>
 __device__ __forceinline__ void channel_loop(const XT *__restrict__ src, int64_t N, int W,
                                              int n_ch, const LanePos<D> &p, Sink &sink,
                                              After &&after) {
@@ -259,7 +321,7 @@ __device__ __forceinline__ void channel_loop(const XT *__restrict__ src, int64_t
   for (int u = 0; u < PF; ++u) {
     const XT *nx = src + (size_t)min(u, n_ch - 1) * N;
 #pragma unroll
-    for (int r = 0; r < R; ++r) buf[u][r].load(nx + (size_t)r * W);
+    for (int r = 0; r < R; ++r) buf[u][r].template load<NT>(nx + (size_t)r * W);
   }
   int c = 0;
   for (; c + PF < n_ch; c += PF + 1) {
@@ -267,7 +329,7 @@ __device__ __forceinline__ void channel_loop(const XT *__restrict__ src, int64_t
     for (int u = 0; u <= PF; ++u) {
       const XT *nx = src + (size_t)min(c + u + PF, n_ch - 1) * N;
 #pragma unroll
-      for (int r = 0; r < R; ++r) buf[(u + PF) % (PF + 1)][r].load(nx + (size_t)r * W);
+      for (int r = 0; r < R; ++r) buf[(u + PF) % (PF + 1)][r].template load<NT>(nx + (size_t)r * W);
       __builtin_amdgcn_sched_barrier(0);  // the loads go out before the arithmetic, not after
       float in[R][V];
 #pragma unroll
@@ -323,7 +385,7 @@ __device__ __forceinline__ DwLane dw_lane(const Geo &g, const StripMap &m, const
   return q;
 }
 
-template <int D, int V, bool EDGE, bool PEEL, class XT, class Sink, class After>
+template <int D, int V, bool EDGE, bool PEEL, bool NT, class XT, class Sink, class After>
 __device__ __forceinline__ void channel_loop_dw(const XT *__restrict__ src,
                                                 const float *__restrict__ wdw, int64_t N, int n_ch,
                                                 const DwLane &q, const LanePos<D> &p, Sink &sink,
@@ -340,7 +402,7 @@ __device__ __forceinline__ void channel_loop_dw(const XT *__restrict__ src,
 #pragma unroll
     for (int i = 0; i < RR; ++i) {
       const XT *rp = row_ptr(plane, i);
-      raw[u][i].load(rp);
+      raw[u][i].template load<NT>(rp);
       if constexpr (EDGE) {
         el[u][i] = rp[q.left_off];
         er[u][i] = rp[q.right_off];
@@ -411,7 +473,8 @@ __device__ __forceinline__ void channel_loop_dw(const XT *__restrict__ src,
 // DWM: 0 = x is transformed as it is; 1, 2 = K_dw x is (wdw [C, 3, 3]; 2: the outside columns
 // of a wave row's first and last lane exist and are read).
 // XT: float or bf16_t, the storage type of x.  SQ: sums of squares instead of absolute values.
-template <int D, int V, bool SPLIT, bool STORE, int PF, int DWM, class XT, bool SQ = false>
+template <int D, int V, bool SPLIT, bool STORE, int PF, int DWM, class XT, bool SQ = false,
+          bool NT = false>
 __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
                                                        float *__restrict__ coef,
                                                        float *__restrict__ norm_part, Geo g,
@@ -444,12 +507,12 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
     sink.plane = STORE ? coef + ((size_t)b * C + c0) * g.N : nullptr;
     const int64_t N = g.N;
     if constexpr (DWM == 0) {
-      channel_loop<D, V, PF>(src, N, g.W, c1 - c0, p, sink, [N](FwdSink<D, V, STORE, SQ> &sk) {
+      channel_loop<D, V, PF, NT>(src, N, g.W, c1 - c0, p, sink, [N](FwdSink<D, V, STORE, SQ> &sk) {
         if (STORE) sk.plane += N;
       });
     } else {
       const DwLane q = dw_lane<D, V>(g, m, p, row0, col0);
-      channel_loop_dw<D, V, DWM == 2, false>(src, wdw + (size_t)c0 * 9, N, c1 - c0, q, p, sink,
+      channel_loop_dw<D, V, DWM == 2, false, NT>(src, wdw + (size_t)c0 * 9, N, c1 - c0, q, p, sink,
                                              [](FwdSink<D, V, STORE, SQ> &) {});
     }
   }
@@ -540,7 +603,7 @@ struct KeepSink {
 
 // grid = (ceil(units/4), G, B), block = 256.  DWM as in haar_fwd_kernel.  Q8: xc is int8 codes
 // for the clipping parameter q_alpha (> 0), and alpha_slots must be null.
-template <int D, int V, int PF, int DWM, bool Q8, class XT>
+template <int D, int V, int PF, int DWM, bool Q8, class XT, bool NT = false>
 __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x,
                                                         const int32_t *__restrict__ jmap,
                                                         void *__restrict__ xc, float *alpha_slots,
@@ -595,10 +658,10 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
     const XT *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
     sink.plane = static_cast<typename Sink::Out *>(xc) + ((size_t)b * C + c0) * k;
     if constexpr (DWM == 0) {
-      channel_loop<D, V, PF>(src, g.N, g.W, c1 - c0, p, sink, [k](Sink &sk) { sk.plane += k; });
+      channel_loop<D, V, PF, NT>(src, g.N, g.W, c1 - c0, p, sink, [k](Sink &sk) { sk.plane += k; });
     } else {
       const DwLane q = dw_lane<D, V>(g, m, p, row0, col0);
-      channel_loop_dw<D, V, DWM == 2, true>(src, wdw + (size_t)c0 * 9, g.N, c1 - c0, q, p, sink,
+      channel_loop_dw<D, V, DWM == 2, true, false>(src, wdw + (size_t)c0 * 9, g.N, c1 - c0, q, p, sink,
                                             [k](Sink &sk) { sk.plane += k; });
     }
   }
@@ -752,7 +815,7 @@ __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane,
     float skip[RES ? R : 1][V];
     if constexpr (RES) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) load_row<V>(res + (size_t)r * row_step, skip[r]);
+      for (int r = 0; r < R; ++r) load_row_stream<V>(res + (size_t)r * row_step, skip[r]);
     }
     __builtin_amdgcn_sched_barrier(0);
     wave_lds_fence();
@@ -768,7 +831,7 @@ __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane,
       res += dst_step;
     }
 #pragma unroll
-    for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * row_step, out[r]);
+    for (int r = 0; r < R; ++r) store_row_stream<V>(dst + (size_t)r * row_step, out[r]);
     dst += dst_step;
   };
   // The first channel stands outside the loop: at the loop head the outstanding memory
@@ -904,14 +967,14 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         float skip[V];
-        load_row<V>(res + (size_t)r * g.W, skip);
+        load_row_stream<V>(res + (size_t)r * g.W, skip);
 #pragma unroll
         for (int e = 0; e < V; ++e) out[r][e] += skip[e];
       }
       res += g.N;
     }
 #pragma unroll
-    for (int r = 0; r < R; ++r) store_row<V>(dst + (size_t)r * g.W, out[r]);
+    for (int r = 0; r < R; ++r) store_row_stream<V>(dst + (size_t)r * g.W, out[r]);
     src.plane += k;
     dst += g.N;
   }
@@ -983,6 +1046,7 @@ StripMap make_map(const wcc_desc &d, int V) {
 struct Plan {
   int G;       // channel groups (grid.y)
   bool split;  // forward/norm pass only: the 4 waves of a workgroup split a group's channels
+  bool stream; // x is read with streaming loads (maps far larger than the memory-side cache)
 };
 
 // x is fp32, or bf16 when the layer's activations are stored that way (fused calls only)
@@ -1026,6 +1090,23 @@ hipError_t fwd_launch_t(const wcc_desc &d, const XT *x, float *coef, float *norm
       return hipGetLastError();
     }
     return hipErrorInvalidValue;
+  }
+  if constexpr (!STORE) {
+    if (pl.stream && !pl.split) {  // an input far larger than the memory-side cache, read once
+#define WCC_FWD_NT(DWM)                                                                               \
+  hipLaunchKernelGGL((haar_fwd_kernel<D, V, false, false, 1, DWM, XT, false, true>), grid_flat,       \
+                     block, 0, s, x, coef, norm_part, g, m, d.C_in, Cg, d.B, prep, wdw)
+      if (wdw != nullptr) {
+        if constexpr (V == 4) {
+          if (dw_needs_edges(m)) WCC_FWD_NT(2); else WCC_FWD_NT(1);
+          return hipGetLastError();
+        }
+        return hipErrorInvalidValue;
+      }
+      WCC_FWD_NT(0);
+#undef WCC_FWD_NT
+      return hipGetLastError();
+    }
   }
   if constexpr (!STORE && V == 4) {
     if (wdw != nullptr) {  // K_dw in front of the transform (norm-only pass)
@@ -1076,6 +1157,15 @@ hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_
     }
   }
   if (wdw != nullptr) return hipErrorInvalidValue;
+  if (pl.stream) {
+    if (q8)
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0, true, XT, true>), grid, dim3(256), 0, s, x,
+                         jmap, xc, nullptr, g, m, d.C_in, Cg, k, wdw, q_alpha);
+    else
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0, false, XT, true>), grid, dim3(256), 0, s, x,
+                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, k, wdw, 0.f);
+    return hipGetLastError();
+  }
   WCC_KEEP(1, 0);
 #undef WCC_KEEP
   return hipGetLastError();
@@ -1169,11 +1259,18 @@ hipError_t inv_dispatch(const wcc_desc &d, int64_t k, const float *yc, const int
 // G is fixed by the workspace layout (one partial-norm plane per group).  On small layers,
 // where even the groups leave fewer than 1024 waves, the four waves of a workgroup split a
 // group's channels (if each still gets >= 2).
+// The memory-side cache holds 256 MB.  An input that fits is read by the second transform pass
+// from there, so it is loaded the ordinary way; one that does not is streamed past the cache.
+bool streams(const wcc_desc &d) {
+  const int64_t bytes = (int64_t)d.B * d.C_in * d.H * d.W * (d.act_dtype == WCC_BF16 ? 2 : 4);
+  return bytes > ((int64_t)256 << 20);
+}
+
 Plan fwd_plan(const wcc_desc &d, int G) {
   const int Cg = (d.C_in + G - 1) / G;
   const StripMap m = make_map(d, (d.W % 4 == 0) ? 4 : 2);
   const int64_t waves = (int64_t)m.units * d.B * G;
-  return Plan{G, waves < 1024 && Cg >= 8};
+  return Plan{G, waves < 1024 && Cg >= 8, streams(d)};
 }
 
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
@@ -1190,7 +1287,7 @@ hipError_t launch_haar_norm(const wcc_desc &d, const void *x, float *norm_part, 
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap,
                             void *xc, float *alpha_slots, const float *wdw, float q_alpha,
                             hipStream_t s) {
-  const Plan pl{groups_for(d, d.C_in, 1024, 8), false};
+  const Plan pl{groups_for(d, d.C_in, 1024, 8), false, streams(d)};
   return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
 }
 
