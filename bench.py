@@ -250,6 +250,9 @@ def main() -> int:
     ap.add_argument("--act", choices=["f32", "bf16"], default="f32",
                     help="storage type of the feature maps x and y (bf16: a bandwidth variant; the "
                          "metric is quoted on f32)")
+    ap.add_argument("--cold-input", action="store_true",
+                    help="single-layer workloads: also time steps whose input was evicted from the "
+                         "memory-side cache beforehand (reported as cold_input_ms_per_step)")
     ap.add_argument("--norm", choices=["l1", "l2"], default="l1",
                     help="l2: positions ranked by the sum of squares over channels (a variant; the "
                          "metric is quoted on l1)")
@@ -341,6 +344,22 @@ def main() -> int:
             timed()
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / args.steps
+        if args.cold_input:
+            # the loop above finds a small x still in the 256 MB memory-side cache from the
+            # step before; here 512 MB of other data are read in between (untimed), so every
+            # step fetches x from HBM, as after a producer that did not leave it in the cache
+            other = torch.ones(128 << 20, dtype=torch.float32, device="cuda")
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            cold = []
+            for _ in range(min(args.steps, 30)):
+                other.sum()
+                e0.record()
+                step()
+                e1.record()
+                e1.synchronize()
+                cold.append(e0.elapsed_time(e1))
+            run_layer.cold_ms = float(np.median(cold))
+            del other
         # per-stage device time: the same K steps again with the library's HIP events switched
         # on (they bracket each stage on the stream the kernels run on)
         ctx.set_profiling(True)
@@ -407,6 +426,8 @@ def main() -> int:
                              / (stage_us["pointwise"] * 1e-6) / 1e12, 2),
     }
 
+    if args.cold_input:
+        out["cold_input_ms_per_step"] = round(run_layer.cold_ms, 5)
     if not args.no_cpu_baseline:
         from oracle import wcc_ref
         cores = min(len(os.sched_getaffinity(0)), 16)
