@@ -29,6 +29,8 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((__vector_size__(4 * sizeof(int)))) int intx4;
 typedef __attribute__((__vector_size__(16 * sizeof(int)))) int intx16;
 
@@ -84,7 +86,7 @@ template <int BM, int BN, int NPF, bool F32, bool I8W>
 __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
     const void *__restrict__ w, const float *__restrict__ w_scale, const void *__restrict__ xq,
     const float *__restrict__ alpha, bool slots, float *alpha_out, float *__restrict__ yc, int M,
-    int K, int64_t k) {
+    int K, int64_t k, bool stream_out) {
   constexpr int T = 2 * BM;
   constexpr int NB = BN / 32;                // 32-column blocks of the tile: 4 or 2
   constexpr int NG = BN / 4;                 // groups of four positions
@@ -226,8 +228,18 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
 #pragma unroll
       for (int i = 0; i < NB; ++i) v[i] = I8W ? (float)acci[i][r] * sc : accf[i][r] * sc;
       float *dst = yc + ((size_t)b * M + m) * k + n;
-      if constexpr (NB == 4) *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-      else *reinterpret_cast<float2 *>(dst) = make_float2(v[0], v[1]);
+      if (stream_out) {  // (wave-uniform) an output that no cache will hold for its reader
+        if constexpr (NB == 4) {
+          floatx4 o = {v[0], v[1], v[2], v[3]};
+          __builtin_nontemporal_store(o, reinterpret_cast<floatx4 *>(dst));
+        } else {
+          floatx2 o = {v[0], v[1]};
+          __builtin_nontemporal_store(o, reinterpret_cast<floatx2 *>(dst));
+        }
+      } else {
+        if constexpr (NB == 4) *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        else *reinterpret_cast<float2 *>(dst) = make_float2(v[0], v[1]);
+      }
     }
   }
 }
@@ -237,12 +249,15 @@ hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float 
                        const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
                        float *yc, hipStream_t s) {
   dim3 grid((unsigned)((k + BN - 1) / BN), (d.C_out + BM - 1) / BM, d.B), block(2 * BM);
+  // The inverse transform reads yc next.  Up to about twice the 256 MB memory-side cache it is
+  // better left there (measured); beyond that the output is streamed past it.
+  const bool stream_out = (int64_t)d.B * d.C_out * k * 4 > ((int64_t)512 << 20);
   if (f32)
     hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, NPF, true, I8W>), grid, block, 0, s, w, w_scale,
-                       xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k);
+                       xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k, stream_out);
   else
     hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, NPF, false, I8W>), grid, block, 0, s, w, w_scale,
-                       xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k);
+                       xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k, stream_out);
   return hipGetLastError();
 }
 
