@@ -268,8 +268,8 @@ def main() -> int:
                          "kernel of known size, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (see DESIGN.md, "
-              "'More than one GPU')", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path is per image, so "
+              "more GPUs would each take a share of the batch)", file=sys.stderr)
         return 2
 
     import numpy as np
