@@ -9,10 +9,11 @@
 // At the layer's shapes the contraction is bound by HBM (a few tens of flop per byte), so the
 // kernel is built around the activation stream: a workgroup owns BM = 128 or 256 output rows
 // (all of C_out when it fits, so every activation is read and quantised once) and BN = 128
-// positions; each thread loads its share of up to 256 channels' worth of the [C_in x BN]
-// activation tile up front (one exposure to memory latency), quantises it in registers,
-// transposes 4(n) x CPT(c) patches into LDS, and the waves (wave w owns rows 32w..32w+31 and
-// all BN columns) run the MFMAs 64 channels at a time.  The n rows are stored permuted
+// positions; each thread loads its share of a 64-channel chunk of the [C_in x BN] activation
+// tile (NPF chunks could go out together; more than one was measured at every shape and never
+// paid: it costs registers, and with them the second workgroup on the compute unit),
+// quantises it in registers, transposes 4(n) x CPT(c) patches into LDS, and the waves (wave w
+// owns rows 32w..32w+31 and all BN columns) run the MFMAs 64 channels at a time.  The n rows are stored permuted
 // (row (n%NB)*32 + n/NB, NB = BN/32) so that MFMA column c of column block i is n = NB*c + i:
 // after the NB column blocks a lane holds NB adjacent n of one output row and stores them as
 // one 16- or 8-byte word.  Layers whose kept signal is short would leave most of the chip
@@ -262,31 +263,20 @@ hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float 
 }
 
 // Tile choice.  Large tiles first (BM = 256 when C_out needs it: every activation is then read
-// once), as long as they give every compute unit a workgroup; otherwise smaller ones.  The
-// loads of up to four chunks go out together when C_in is that deep and the registers allow.
+// once), as long as they give every compute unit a workgroup; otherwise smaller ones.
 template <bool I8W>
 hipError_t mfma_dispatch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
                          const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
                          float *yc, hipStream_t s) {
 #define WCC_MFMA(BM_, BN_, NPF_) \
   return mfma_launch<BM_, BN_, NPF_, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s)
-  const int nchunks = (d.C_in + BK - 1) / BK;
   const int64_t want = 256;  // compute units
   auto wgs = [&](int bm, int bn) {
     return ((k + bn - 1) / bn) * ((d.C_out + bm - 1) / bm) * (int64_t)d.B;
   };
-  if (d.C_out > 128 && wgs(256, 128) >= want) {
-    if (nchunks >= 4) WCC_MFMA(256, 128, 4);
-    if (nchunks >= 2) WCC_MFMA(256, 128, 2);
-    WCC_MFMA(256, 128, 1);
-  }
+  if (d.C_out > 128 && wgs(256, 128) >= want) WCC_MFMA(256, 128, 1);
   if (d.C_out <= 128 && wgs(128, 128) >= want) WCC_MFMA(128, 128, 1);
-  if (d.C_out > 64 && wgs(128, 64) >= want) {
-    if (nchunks >= 4) WCC_MFMA(128, 64, 4);
-    if (nchunks >= 2) WCC_MFMA(128, 64, 2);
-    WCC_MFMA(128, 64, 1);
-  }
-  if (nchunks >= 2) WCC_MFMA(64, 64, 2);
+  if (d.C_out > 64 && wgs(128, 64) >= want) WCC_MFMA(128, 64, 1);
   WCC_MFMA(64, 64, 1);
 #undef WCC_MFMA
 }
