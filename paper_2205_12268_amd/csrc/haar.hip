@@ -563,6 +563,14 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
   if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
 }
 
+// LDS traffic of one wave with itself: the hardware runs a wave's LDS instructions in order;
+// this keeps the compiler from moving them across
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // ---- second pass of the fused layer: transform again, keep only the selected positions ----
 // xc[b, c, jmap[b, q]] = HWT_d(x[b, c])[q] for the kept q; dropped coefficients never reach
 // memory.  Also raises the alpha slots to max |kept coefficient| (nullable).
@@ -571,33 +579,89 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
 template <int D, int V, bool Q8>
 struct KeepSink {
   using Out = std::conditional_t<Q8, int8_t, float>;
-  Out *plane;  // xc[b, c, :]
-  int jj[slot_count(D, V)];
-  uint64_t any[2];  // wave-uniform: bit s set if some lane keeps slot s
+  // Every slot is stored through a buffer descriptor of the channel's compressed vector, with
+  // the byte offset of the slot's rank, or an offset beyond the vector for a position that is
+  // not kept: the hardware drops such a lane's store.  No store sits behind a branch, so the
+  // number of stores per channel is fixed and the wait for the prefetched rows of the next
+  // channel does not have to drain them (loads and stores retire through one counter); and no
+  // slot needs a 64-bit address or a saved lane mask, which halves the kernel's registers.
+  static constexpr uint32_t kDropped = 0xFFFFFFFFu;
+  __amdgpu_buffer_rsrc_t xc_c;     // xc[b, c, :]
+  uint32_t at[slot_count(D, V)];   // byte offset of the slot's rank, or kDropped
   float vmax;
   Quant quant;
   __device__ __forceinline__ explicit KeepSink(float alpha) : quant(alpha) {}
+  // plane: xc[b, c, :] (wave-uniform), k elements
+  __device__ __forceinline__ void aim(Out *plane, int64_t k) {
+    xc_c = __builtin_amdgcn_make_buffer_rsrc(plane, 0, (int)(uint32_t)(k * (int64_t)sizeof(Out)),
+                                             0x00020000 /* raw dwords, no swizzle */);
+  }
   template <int L, int J>
   __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
                                           bool owner) {
     constexpr int CV = cols_at(V, L);
     constexpr int base = slot_base(D, V, L, J);
     (void)p;
+    (void)owner;  // (at[] is kDropped for the lanes that do not own the value)
 #pragma unroll
     for (int e = 0; e < CV; ++e) {
       const int s = base + i * CV + e;
-      if ((any[s >> 6] >> (s & 63)) & 1) {
-        const int j = jj[s];
-        if (owner && j >= 0) {
-          if constexpr (Q8) {
-            plane[j] = (int8_t)quant.code(v[e]);
-          } else {
-            plane[j] = v[e];
-            vmax = fmaxf(vmax, fabsf(v[e]));
-          }
-        }
+      if constexpr (Q8) {
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)quant.code(v[e]), xc_c, at[s], 0, 0);
+      } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[e]), xc_c, at[s], 0, 0);
+        vmax = fmaxf(vmax, at[s] != kDropped ? fabsf(v[e]) : 0.f);
       }
     }
+  }
+};
+
+// The same sink for a strip that keeps few of its positions.  One sparse store per slot costs
+// the memory pipeline an instruction each, whatever the number of lanes that keep something
+// (measured: the stores were a third of the pass).  Here every lane drops its values into an LDS
+// tile laid out [slot][lane]; after the last level the wave goes through the strip's packed list
+// of kept positions (64 entries a row, built once, the same for every channel), picks each
+// entry's value from the tile and stores NI dense rows instead of one row per slot.
+template <int D, int V, bool Q8, int NI>
+struct KeepStagedSink {
+  using Out = std::conditional_t<Q8, int8_t, float>;
+  static constexpr uint32_t kDropped = 0xFFFFFFFFu;
+  __amdgpu_buffer_rsrc_t xc_c;  // xc[b, c, :]
+  uint32_t *tile;               // [slot][lane]
+  int lane;
+  uint32_t cell[NI];            // tile index of the entry's position
+  uint32_t at[NI];              // byte offset of the entry's rank, or kDropped (list padding)
+  float vmax;
+  Quant quant;
+  __device__ __forceinline__ explicit KeepStagedSink(float alpha) : quant(alpha) {}
+  __device__ __forceinline__ void aim(Out *plane, int64_t k) {
+    xc_c = __builtin_amdgcn_make_buffer_rsrc(plane, 0, (int)(uint32_t)(k * (int64_t)sizeof(Out)),
+                                             0x00020000 /* raw dwords, no swizzle */);
+  }
+  template <int L, int J>
+  __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
+                                          bool owner) {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+    (void)p;
+    (void)owner;  // (a value a lane does not own is in no list)
+#pragma unroll
+    for (int e = 0; e < CV; ++e) tile[(base + i * CV + e) * kWave + lane] = __float_as_uint(v[e]);
+  }
+  // once per channel, after the last level
+  __device__ __forceinline__ void flush() {
+    wave_lds_fence();
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const float v = __uint_as_float(tile[cell[i]]);
+      if constexpr (Q8) {
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)quant.code(v), xc_c, at[i], 0, 0);
+      } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), xc_c, at[i], 0, 0);
+        vmax = fmaxf(vmax, at[i] != kDropped ? fabsf(v) : 0.f);
+      }
+    }
+    wave_lds_fence();
   }
 };
 
@@ -620,8 +684,6 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
 
   using Sink = KeepSink<D, V, Q8>;
   Sink sink(Q8 ? q_alpha : 0.f);
-  sink.any[0] = sink.any[1] = 0;
-  sink.vmax = 0.f;
   const int32_t *jm = jmap + (size_t)b * g.N;
   auto fetch = [&](auto Lc, auto Jc) {
     constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
@@ -635,7 +697,7 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
         const int s = base + i * CV + e;
         int j = -1;
         if (active && owner) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
-        sink.jj[s] = j;
+        sink.at[s] = (uint32_t)j;  // (turned into a byte offset below, once all loads are out)
       }
   };
   auto each_level = [&](auto Lc) {
@@ -649,24 +711,89 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
   if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
   if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
   if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
-  // (all map loads are in flight before the first vote waits for one)
-#pragma unroll
-  for (int s = 0; s < slot_count(D, V); ++s)
-    if (__ballot(sink.jj[s] >= 0) != 0) sink.any[s >> 6] |= (uint64_t)1 << (s & 63);
-
-  if (active && c0 < c1) {
-    const XT *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
-    sink.plane = static_cast<typename Sink::Out *>(xc) + ((size_t)b * C + c0) * k;
+  using Out = typename Sink::Out;
+  const XT *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+  Out *plane = static_cast<Out *>(xc) + ((size_t)b * C + c0) * k;
+  // walks the group's channels with whichever sink; returns its max |kept coefficient|
+  auto walk = [&](auto &sk, auto &&next_channel) {
+    sk.vmax = 0.f;
+    sk.aim(plane, k);
     if constexpr (DWM == 0) {
-      channel_loop<D, V, PF, NT>(src, g.N, g.W, c1 - c0, p, sink, [k](Sink &sk) { sk.plane += k; });
+      channel_loop<D, V, PF, NT>(src, g.N, g.W, c1 - c0, p, sk, next_channel);
     } else {
       const DwLane q = dw_lane<D, V>(g, m, p, row0, col0);
-      channel_loop_dw<D, V, DWM == 2, true, false>(src, wdw + (size_t)c0 * 9, g.N, c1 - c0, q, p, sink,
-                                            [k](Sink &sk) { sk.plane += k; });
+      channel_loop_dw<D, V, DWM == 2, true, false>(src, wdw + (size_t)c0 * 9, g.N, c1 - c0, q, p, sk,
+                                                   next_channel);
+    }
+    return sk.vmax;
+  };
+
+  float mx = 0.f;
+  bool done = false;
+  // Dense stores pay where a strip keeps at most half of its slots' worth of positions.  (With
+  // K_dw folded in the kernel is bound by its arithmetic and registers; there the staging
+  // measured 5-10 % slower than one store per slot.)
+  constexpr int NS = slot_count(D, V);
+  constexpr bool kStaged = V == 4 && (D == 2 || D == 3) && DWM == 0;
+  if constexpr (kStaged) {
+    __shared__ uint32_t tiles[4][NS * kWave];
+    constexpr int kRankBits = 20;  // list entry = rank | tile index << 20
+    int count = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) count += __popcll(__ballot((int)sink.at[s] >= 0));
+    const int ni = (count + kWave - 1) / kWave;
+    const bool whole = __ballot(active) == ~(uint64_t)0;  // (a ragged wave takes the plain path)
+    if (whole && c0 < c1 && ni <= NS / 2 && k <= ((int64_t)1 << kRankBits)) {
+      const int lane = threadIdx.x & (kWave - 1);
+      uint32_t *tile = tiles[threadIdx.x >> 6];
+      // pack (rank, tile index): slot-major, then lane (a band row's kept positions have
+      // consecutive ranks).  The tile is scratch for the list before it becomes the staging area.
+      int running = 0;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const int j = (int)sink.at[s];
+        const uint64_t kept = __ballot(j >= 0);
+        const int to = running + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
+        if (j >= 0) tile[to] = (uint32_t)j | ((uint32_t)(s * kWave + lane) << kRankBits);
+        running += __popcll(kept);
+      }
+      wave_lds_fence();
+      auto run = [&](auto ni_c) {
+        constexpr int NI = decltype(ni_c)::value;
+        KeepStagedSink<D, V, Q8, NI> st(Q8 ? q_alpha : 0.f);
+        st.tile = tile;
+        st.lane = lane;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+          const int e = lane + kWave * i;
+          const uint32_t packed = e < count ? tile[e] : 0u;
+          st.cell[i] = e < count ? packed >> kRankBits : (uint32_t)lane;
+          st.at[i] = e < count ? (packed & ((1u << kRankBits) - 1u)) * (uint32_t)sizeof(Out) : Sink::kDropped;
+        }
+        wave_lds_fence();
+        mx = walk(st, [&plane, k](auto &sk) {
+          sk.flush();
+          plane += k;
+          sk.aim(plane, k);
+        });
+      };
+      if (ni <= 4) run(std::integral_constant<int, 4>{});
+      else if (ni <= 8) run(std::integral_constant<int, 8>{});
+      else run(std::integral_constant<int, 16>{});
+      done = true;
     }
   }
+  if (!done && active && c0 < c1) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      sink.at[s] = (int)sink.at[s] >= 0 ? sink.at[s] * (uint32_t)sizeof(Out) : Sink::kDropped;
+    mx = walk(sink, [&plane, k](Sink &sk) {
+      plane += k;
+      sk.aim(plane, k);
+    });
+  }
   if (alpha_slots == nullptr) return;
-  float mx = sink.vmax;
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
   if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = mx;
@@ -779,14 +906,6 @@ __device__ __forceinline__ void inv_levels(float (&out)[rows_at(D, L - 1)][cols_
       }
     }
   }
-}
-
-// LDS traffic of one wave with itself: the hardware runs a wave's LDS instructions in order;
-// this keeps the compiler from moving them across
-__device__ __forceinline__ void wave_lds_fence() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // The channel walk of the staged path with NI dense fetches per channel.  mine[i]: the lane's
