@@ -4,8 +4,11 @@
   python -m paper_2205_12268_amd.profsum traffic <fetch>/..._counter_collection.csv \\
          <write>/..._counter_collection.csv <copy_bytes>
 
+  python -m paper_2205_12268_amd.profsum traffic_scaled <fetch csv> <write csv> <fs> <ws>
+
 `traffic` scales FETCH_SIZE and WRITE_SIZE (KiB per dispatch) by what the same counters read
-for the plain copy kernel of known size that `bench.py --copy-probe` runs in the same process.
+for the plain copy kernel of known size that `bench.py --copy-probe` runs in the same process;
+`traffic_scaled` takes the two factors as given (for a workload that has no copy probe).
 """
 from __future__ import annotations
 
@@ -54,10 +57,23 @@ def traffic(fetch_csv: str, write_csv: str, copy_bytes: float) -> str:
     return "\n".join(out)
 
 
+def traffic_scaled(fetch_csv: str, write_csv: str, fs: float, ws: float) -> str:
+    f = _mean_counter(fetch_csv, "FETCH_SIZE")
+    w = _mean_counter(write_csv, "WRITE_SIZE")
+    out = [f"# FETCH_SIZE scale {fs:.4f}, WRITE_SIZE scale {ws:.4f} (as calibrated for the single layers)",
+           f"# {'kernel':56s} {'fetch_bytes':>14s} {'write_bytes':>14s} {'total_bytes':>14s}"]
+    for k in f:
+        fb, wb = f[k] * 1024 * fs, w.get(k, 0.0) * 1024 * ws
+        out.append(f"{k:58s} {fb:14.0f} {wb:14.0f} {fb + wb:14.0f}")
+    return "\n".join(out)
+
+
 if __name__ == "__main__":
     if sys.argv[1] == "stats":
         print(stats(sys.argv[2]))
     elif sys.argv[1] == "traffic":
         print(traffic(sys.argv[2], sys.argv[3], float(sys.argv[4])))
+    elif sys.argv[1] == "traffic_scaled":
+        print(traffic_scaled(sys.argv[2], sys.argv[3], float(sys.argv[4]), float(sys.argv[5])))
     else:
         sys.exit(__doc__)
