@@ -1333,7 +1333,15 @@ int groups_for(const wcc_desc &d, int C, int64_t want_waves, int min_ch) {
 // channels a group that is at most 1/16 of the transform's own traffic.  Measured on gfx950:
 // about a thousand waves, each walking as many channels as possible, stream best; more
 // groups only pay when a layer has fewer strips than that.
-int forward_groups(const wcc_desc &d) { return groups_for(d, d.C_in, 1024, 16); }
+//
+// With K_dw folded in and bf16 feature maps the passes are bound by their arithmetic, not by
+// bytes: there four times the waves pay (measured on the block: norm pass 300 -> 227 us, keep
+// pass 492 -> 378 us), where with fp32 maps they cost 3-5 %.
+bool arithmetic_bound(const wcc_desc &d, bool folded_dw) { return folded_dw && d.act_dtype == WCC_BF16; }
+
+int forward_groups(const wcc_desc &d, bool folded_dw) {
+  return groups_for(d, d.C_in, arithmetic_bound(d, folded_dw) ? 4096 : 1024, 16);
+}
 
 template <bool STORE>
 hipError_t fwd_dispatch(const wcc_desc &d, const void *x, float *coef, float *norm_part, Plan pl,
@@ -1406,7 +1414,8 @@ hipError_t launch_haar_norm(const wcc_desc &d, const void *x, float *norm_part, 
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap,
                             void *xc, float *alpha_slots, const float *wdw, float q_alpha,
                             hipStream_t s) {
-  const Plan pl{groups_for(d, d.C_in, 1024, 8), false, streams(d)};
+  const Plan pl{groups_for(d, d.C_in, arithmetic_bound(d, wdw != nullptr) ? 4096 : 1024, 8), false,
+                streams(d)};
   return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
 }
 

@@ -68,10 +68,10 @@ wcc_status need_ws(const wcc_ctx *ctx, const WsLayout &L) {
 
 }  // namespace
 
-WsLayout ws_layout(const wcc_desc &d) {
+WsLayout ws_layout(const wcc_desc &d, bool folded_dw) {
   WsLayout L{};
   const size_t N = (size_t)d.H * d.W, B = d.B, k = (size_t)k_of(d);
-  L.G = forward_groups(d);
+  L.G = forward_groups(d, folded_dw);
   L.nblk = (int)((N + kSelectChunk - 1) / kSelectChunk);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
@@ -200,7 +200,7 @@ BlockLayout block_layout(const wcc_block_desc &bd, const wcc_desc &d1, const wcc
   L.t1 = 0;
   L.t2 = mid;
   L.layer = 2 * mid;
-  const size_t a = ws_layout(d1).total, b = ws_layout(d3).total;
+  const size_t a = ws_layout(d1).total, b = ws_layout(d3, bd.W % 4 == 0).total;
   L.total = L.layer + (a > b ? a : b);
   return L;
 }
@@ -518,7 +518,7 @@ wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const voi
       ctx->marked[WCC_T_DEPTHWISE] = true;
     }
   }
-  st = forward_on(ctx, ws + BL.layer, ws_layout(d3), d3, fold ? t1 : static_cast<void *>(t2), w3, w3_scale, 0.f, y,
+  st = forward_on(ctx, ws + BL.layer, ws_layout(d3, fold), d3, fold ? t1 : static_cast<void *>(t2), w3, w3_scale, 0.f, y,
                   idx3_out, nullptr, x, fold ? w_dw : nullptr,
                   prof && ctx->block_profile_layer == 1, s);
   if (st != WCC_OK) return st;

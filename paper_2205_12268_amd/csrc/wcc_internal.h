@@ -122,8 +122,9 @@ struct Quant {
   __device__ __forceinline__ int code(float v) const { return (int)level(v); }
 };
 
-WsLayout ws_layout(const wcc_desc &d);
-int forward_groups(const wcc_desc &d);
+// folded_dw: the layer's input is K_dw x, convolved on the fly by the transform passes
+WsLayout ws_layout(const wcc_desc &d, bool folded_dw = false);
+int forward_groups(const wcc_desc &d, bool folded_dw);
 
 // launchers (each returns hipGetLastError() after its launches)
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part,
