@@ -13,7 +13,9 @@
 // tile (NPF chunks could go out together; more than one was measured at every shape and never
 // paid: it costs registers, and with them the second workgroup on the compute unit),
 // quantises it in registers, transposes 4(n) x CPT(c) patches into LDS, and the waves (wave w
-// owns rows 32w..32w+31 and all BN columns) run the MFMAs 64 channels at a time.  The n rows are stored permuted
+// owns rows 32w..32w+31 and all BN columns) run the MFMAs 64 channels at a time.  As soon as
+// a chunk's registers are in LDS the next chunk's loads (activations and weights) are issued,
+// so they travel while the MFMAs of this chunk run.  The n rows are stored permuted
 // (row (n%NB)*32 + n/NB, NB = BN/32) so that MFMA column c of column block i is n = NB*c + i:
 // after the NB column blocks a lane holds NB adjacent n of one output row and stores them as
 // one 16- or 8-byte word.  Layers whose kept signal is short would leave most of the chip
@@ -167,26 +169,24 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   // this thread's four positions in channel kq * CPT of chunk 0
   const bool n_in = n0 + 4 * g < k;
   const char *xp = static_cast<const char *>(xb) + ((size_t)(kq * CPT) * k + n0 + 4 * g) * (F32 ? 4 : 1);
-  float al = 0.f;
+  static_assert(NPF == 1, "one chunk of activations in flight");
   load_w(0);
-  for (int kc0 = 0; kc0 < nchunks; kc0 += NPF) {
-    // every load of the next NPF chunks goes out before anything waits on one
-#pragma unroll
-    for (int u = 0; u < NPF; ++u)
-      if (kc0 + u < nchunks)
-        raw[u].load(xp + (size_t)(kc0 + u) * BK * k * (F32 ? 4 : 1), K, k, (kc0 + u) * BK + kq * CPT, n_in);
-    if (kc0 == 0) al = load_alpha(alpha, slots, alpha_out);
-    const Quant quant(al);
-#pragma unroll
-    for (int u = 0; u < NPF; ++u) {
-      if (kc0 + u >= nchunks) break;
-      if (quant.fast) stage_patch(raw[u], quant, std::true_type{});
-      else stage_patch(raw[u], quant, std::false_type{});
+  raw[0].load(xp, K, k, kq * CPT, n_in);
+  const float al = load_alpha(alpha, slots, alpha_out);
+  const Quant quant(al);
+  for (int kc = 0; kc < nchunks; ++kc) {
+    {
+      if (quant.fast) stage_patch(raw[0], quant, std::true_type{});
+      else stage_patch(raw[0], quant, std::false_type{});
 #pragma unroll
       for (int q = 0; q < APT; ++q)
         *reinterpret_cast<uint4 *>(&As[a_row * LDR + a_half * (BK / 2) * ESZ + q * 16]) = wreg[q];
       __syncthreads();
-      if (kc0 + u + 1 < nchunks) load_w(kc0 + u + 1);
+      // both register tiles are in LDS now: the next chunk travels while this one is multiplied
+      if (kc + 1 < nchunks) {
+        load_w(kc + 1);
+        raw[0].load(xp + (size_t)(kc + 1) * BK * k * (F32 ? 4 : 1), K, k, (kc + 1) * BK + kq * CPT, n_in);
+      }
       const int fr = lane & 31, half = lane >> 5;
       if constexpr (I8W) {
 #pragma unroll
