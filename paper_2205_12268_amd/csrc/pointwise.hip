@@ -101,7 +101,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDR];
   __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * LDR];
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
-  const int b = blockIdx.z, m0 = blockIdx.y * BM;
+  const int b = blockIdx.z;
   const int64_t n0 = (int64_t)blockIdx.x * BN;
   const void *xb = static_cast<const char *>(xq) + (size_t)b * K * k * (F32 ? 4 : 1);
   const unsigned char *wb = static_cast<const unsigned char *>(w);
@@ -109,6 +109,12 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   const int g = t % NG, kq = t / NG;         // activation loader: n group (4 n), channel group
   const int nchunks = (K + BK - 1) / BK;
 
+  const float al = load_alpha(alpha, slots, alpha_out);
+  const Quant quant(al);
+  // A workgroup takes the row tiles blockIdx.y, blockIdx.y + gridDim.y, ...: with one workgroup
+  // per column tile (gridDim.y = 1) the stores of a row tile drain while the next one is being
+  // computed, instead of holding the compute unit until they are out.
+  for (int m0 = blockIdx.y * BM; m0 < M; m0 += gridDim.y * BM) {
   floatx16 accf[NB];
   intx16 acci[NB];
 #pragma unroll
@@ -172,8 +178,6 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   static_assert(NPF == 1, "one chunk of activations in flight");
   load_w(0);
   raw[0].load(xp, K, k, kq * CPT, n_in);
-  const float al = load_alpha(alpha, slots, alpha_out);
-  const Quant quant(al);
   for (int kc = 0; kc < nchunks; ++kc) {
     {
       if (quant.fast) stage_patch(raw[0], quant, std::true_type{});
@@ -219,7 +223,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   // epilogue: acc[i][r] is row (r/4)*8 + (lane/32)*4 + r%4, column NB*(lane%32) + i
   const float sx = al / 127.f;
   const int64_t n = n0 + NB * (lane & 31);
-  if (n >= k) return;  // k % 4 == 0: a lane's NB positions are all inside or all outside
+  if (n < k) {  // k % 4 == 0: a lane's NB positions are all inside or all outside
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int m = m0 + wv * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
@@ -243,6 +247,8 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
       }
     }
   }
+  }  // positions inside the signal
+  }  // row tiles
 }
 
 template <int BM, int BN, int NPF, bool I8W>
@@ -250,6 +256,8 @@ hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float 
                        const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
                        float *yc, hipStream_t s) {
   dim3 grid((unsigned)((k + BN - 1) / BN), (d.C_out + BM - 1) / BM, d.B), block(2 * BM);
+  // several row tiles: one workgroup walks them all where the column tiles alone fill the chip
+  if (grid.y > 1 && (int64_t)grid.x * grid.z >= 2 * 256) grid.y = 1;
   // The inverse transform reads yc next.  Up to about twice the 256 MB memory-side cache it is
   // better left there (measured); beyond that the output is streamed past it.
   const bool stream_out = (int64_t)d.B * d.C_out * k * 4 > ((int64_t)512 << 20);
