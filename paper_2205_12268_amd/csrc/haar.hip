@@ -743,7 +743,7 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
     for (int s = 0; s < NS; ++s) count += __popcll(__ballot((int)sink.at[s] >= 0));
     const int ni = (count + kWave - 1) / kWave;
     const bool whole = __ballot(active) == ~(uint64_t)0;  // (a ragged wave takes the plain path)
-    if (whole && c0 < c1 && ni <= NS / 2 && k <= ((int64_t)1 << kRankBits)) {
+    if (whole && c0 < c1 && ni <= NS / 2 && ni <= 16 && k <= ((int64_t)1 << kRankBits)) {
       const int lane = threadIdx.x & (kWave - 1);
       uint32_t *tile = tiles[threadIdx.x >> 6];
       // pack (rank, tile index): slot-major, then lane (a band row's kept positions have
@@ -780,7 +780,7 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
       };
       if (ni <= 4) run(std::integral_constant<int, 4>{});
       else if (ni <= 8) run(std::integral_constant<int, 8>{});
-      else run(std::integral_constant<int, 16>{});
+      else run(std::integral_constant<int, 16>{});  // (ni <= 16 is part of the condition above)
       done = true;
     }
   }

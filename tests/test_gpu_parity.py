@@ -41,6 +41,9 @@ SMALL = [
     case("i4_weights", 2, 64, 48, 32, 64, 2, 1, 4, I4, 8),              # 4-bit codes, matrix-core path
     case("i4_ragged", 1, 22, 10, 16, 24, 1, 1, 3, I4, 8),               # C_in % 16 != 0: FMA path
     case("i4_noquant", 1, 16, 24, 32, 32, 2, 1, 4, I4, 0),
+    # strips that keep 1025..1088 of their 2048 positions: one more list row than the dense keep
+    # pass packs, so these strips must take the one-store-per-slot route
+    case("d3_half_kept", 2, 8, 8, 24, 336, 3, 1, 2, BF16, 8),
 ]
 
 
