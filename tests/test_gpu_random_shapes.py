@@ -1,7 +1,8 @@
 """Seeded random small layers: every mix of level count, width class (narrow planes packed
 several strips a wave, rows wider than a wave, widths that are not a multiple of 4), channel
 counts that do and do not fit the matrix-core tiles, keep ratios from almost nothing to
-everything, weight types and quantiser on/off -- each against the oracle through wcc_forward."""
+everything, weight types and quantiser on/off -- each against the oracle through wcc_forward;
+and a second family of wide planes at keep ratios around one half and above."""
 from __future__ import annotations
 
 import numpy as np
@@ -61,6 +62,45 @@ def test_random_layer(ref, ctx, seed):
     got = y.cpu().numpy()
     assert np.isfinite(got).all()
     assert rel_l2(got, want) <= tol_for(cfg)
+
+
+def draw_dense(seed: int) -> synth.LayerCfg:
+    """Wide planes at keep ratios around and above one half: strips near and beyond what the
+    packed position lists of the keep pass and of the inverse hold."""
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([2, 3, 3]))
+    s = 1 << d
+    H = s * int(rng.integers(1, 5))
+    W = (int(rng.choice([256, 264, 320, 512, 520, 768, 1024, 136, 72, 1032])) // s) * s
+    num, den = [(1, 2), (5, 8), (3, 4), (7, 8), (1, 1), (3, 8), (1, 4), (9, 16), (17, 32),
+                (15, 32)][int(rng.integers(0, 10))]
+    dt = int(rng.choice([synth.W_F32, synth.W_BF16, synth.W_I8, synth.W_I4]))
+    bits = 0 if dt == synth.W_F32 and rng.random() < 0.5 else int(rng.choice([0, 8, 8]))
+    return synth.LayerCfg(f"dense{seed}", int(rng.integers(1, 3)), int(rng.choice([4, 8, 16])),
+                          int(rng.choice([4, 8, 20])), H, W, d, num, den, dt, bits,
+                          sigma=float(rng.choice([0.0, 1.0, 2.5])), clip_hi=8.0,
+                          seed=synth.SEED_BASE + 0xB00 + seed)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_dense_layer(ref, ctx, seed):
+    cfg = draw_dense(seed)
+    print(f"{cfg}", flush=True)
+    x, w = synth.make_inputs(cfg)
+    d = desc_of(cfg)
+    ctx.ensure_workspace(d)
+    wd, wsd = upload_weights(w)
+    y = torch.full((cfg.B, cfg.C_out, cfg.H, cfg.W), float("nan"), dtype=torch.float32, device="cuda")
+    idx = torch.full((cfg.B, cfg.k), -7, dtype=torch.int32, device="cuda")
+    alpha = torch.zeros(1, dtype=torch.float32, device="cuda")
+    a_in = 3.0 if (cfg.act_bits and seed % 3 == 0) else 0.0   # every third one with a caller's alpha
+    ctx.wcc_forward(d, dev(x), wd, wsd, a_in, y, idx, alpha)
+    want, o_idx, o_alpha = ref.forward(x, w.values, w.scale, cfg.levels, cfg.keep_num, cfg.keep_den,
+                                       act_bits=cfg.act_bits, alpha_in=a_in)
+    np.testing.assert_array_equal(idx.cpu().numpy().astype(np.int64), o_idx)
+    if cfg.act_bits:
+        assert float(alpha.item()) == o_alpha
+    assert rel_l2(y.cpu().numpy(), want) <= tol_for(cfg)
 
 
 def draw_block(seed: int) -> synth.BlockCfg:
