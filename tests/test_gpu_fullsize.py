@@ -44,6 +44,12 @@ def test_full_size_forward(ref, n):
     idx2 = torch.empty_like(idx)
     ctx.wcc_forward(d, xd, wd, wsd, 0.0, y2, idx2, None)
     assert torch.equal(idx, idx2) and torch.equal(y, y2)
+    if cfg.act_bits:
+        # the same alpha handed in by the caller: the keep pass decides the codes itself (int8
+        # leaves the chip); same codes, so the same output bit for bit
+        y2.fill_(float("nan"))
+        ctx.wcc_forward(d, xd, wd, wsd, float(alpha.item()), y2, idx2, None)
+        assert torch.equal(idx, idx2) and torch.equal(y, y2)
     del y2, idx2
 
     print("  oracle: transform, norms, selection", flush=True)
