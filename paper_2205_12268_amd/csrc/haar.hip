@@ -1195,16 +1195,22 @@ hipError_t fwd_launch_t(const wcc_desc &d, const XT *x, float *coef, float *norm
   hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, false, 1, DWM, float, true>),                      \
                      SPLIT ? grid_split : grid_flat, block, 0, s, x, coef, norm_part, g, m, d.C_in,   \
                      Cg, d.B, prep, wdw)
+#define WCC_FWD_SQ_NT(DWM)                                                                            \
+  hipLaunchKernelGGL((haar_fwd_kernel<D, V, false, false, 1, DWM, float, true, true>), grid_flat,     \
+                     block, 0, s, x, coef, norm_part, g, m, d.C_in, Cg, d.B, prep, wdw)
+      const bool nt = pl.stream && !pl.split;  // (an input far larger than the memory-side cache)
       if (wdw != nullptr) {
         if constexpr (V == 4) {
           const bool edges = dw_needs_edges(m);
-          if (pl.split) { if (edges) WCC_FWD_SQ(true, 2); else WCC_FWD_SQ(true, 1); }
-          else          { if (edges) WCC_FWD_SQ(false, 2); else WCC_FWD_SQ(false, 1); }
+          if (nt)            { if (edges) WCC_FWD_SQ_NT(2); else WCC_FWD_SQ_NT(1); }
+          else if (pl.split) { if (edges) WCC_FWD_SQ(true, 2); else WCC_FWD_SQ(true, 1); }
+          else               { if (edges) WCC_FWD_SQ(false, 2); else WCC_FWD_SQ(false, 1); }
           return hipGetLastError();
         }
         return hipErrorInvalidValue;
       }
-      if (pl.split) WCC_FWD_SQ(true, 0); else WCC_FWD_SQ(false, 0);
+      if (nt) WCC_FWD_SQ_NT(0); else if (pl.split) WCC_FWD_SQ(true, 0); else WCC_FWD_SQ(false, 0);
+#undef WCC_FWD_SQ_NT
 #undef WCC_FWD_SQ
       return hipGetLastError();
     }
