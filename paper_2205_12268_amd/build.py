@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(CSRC, "libwcc.so")
-SOURCES = ["haar.hip", "select.hip", "gather.hip", "pointwise.hip", "depthwise.hip", "wcc_api.hip"]
+SOURCES = ["haar_fwd.hip", "haar_keep.hip", "haar_inv.hip", "select.hip", "gather.hip", "pointwise.hip",
+           "depthwise.hip", "wcc_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]
@@ -25,7 +26,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = False) -> str:
     """Always recompiles every source; returns the path of the shared library."""
-    with ThreadPoolExecutor(max_workers=min(5, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:

@@ -1,0 +1,335 @@
+// Zero filling and the inverse transform (the decompression step after Eq. wavelet_transform;
+// the last loop of Alg. 1), with the skip connection of the inverted residual block.
+#include "strip.h"
+
+namespace wcc {
+namespace {
+
+// ---- synthesis with zero filling ------------------------------------------------------------
+// On this chip loads and stores retire through one in-order counter: a load issued after a
+// store cannot be waited for without waiting for the store.  A wave that alternates "fetch the
+// kept values of channel c, rebuild, store" therefore pays a full store round trip per channel.
+// The kernel below issues the fetches of channel c + 1 BEFORE the stores of channel c, with
+// the same number of memory instructions on every path (no branch around a load or a store),
+// so that waiting for them only needs the stores of channel c - 1 to have retired.
+//
+// To make that cheap the kept positions of a strip -- the same for every channel, and few --
+// are packed once per wave into a list (rank j, cell), slot by slot and lane by lane, held in
+// registers, 64 entries a row.  Per channel the wave fetches yc[.., j] for the whole list with
+// a few dense loads (neighbouring entries have mostly neighbouring j), drops the values into an
+// LDS tile laid out [slot][lane] whose other cells stay zero, and every lane reads its slots
+// back from there.  Lanes outside the plane take part in the list work and send their stores
+// to a scratch line.  Strips that keep more than kInvCap positions, layers with more than 2^20
+// kept positions, and d = 4 (whose tile would not fit) take the plain path: ranks in registers,
+// one conditional load per slot.
+constexpr int kInvCap = 1024;          // packed entries per wave
+constexpr uint32_t kInvNone = ~0u;     // list padding
+constexpr int kInvRankBits = 20;       // entry = rank | cell << 20
+
+// Plain path: jj[slot] = rank j of the position inside the kept list, or -1 (dropped -> 0);
+// one conditional load per slot that some lane keeps.
+template <int D, int V>
+struct InvDirect {
+  const float *plane;  // yc[b, o, :]
+  int jj[slot_count(D, V)];
+  uint64_t any[2];     // wave-uniform: bit s set if some lane keeps slot s
+  template <int L, int J>
+  __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) {
+      const int s = base + i * CV + e;
+      float t = 0.f;
+      if ((any[s >> 6] >> (s & 63)) & 1) {
+        const int j = jj[s];
+        if (j >= 0) t = plane[j];
+      }
+      v[e] = t;
+    }
+  }
+};
+
+// Staged: the lane's cell of the [slot][lane] LDS tile (zero unless the position is kept).
+template <int D, int V>
+struct InvStaged {
+  const float *cell;   // &tile[0][lane]
+  uint64_t any[2];     // wave-uniform: bit s set if some lane keeps slot s
+  template <int L, int J>
+  __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) {
+      const int s = base + i * CV + e;
+      v[e] = ((any[s >> 6] >> (s & 63)) & 1) ? cell[s * kWave] : 0.f;
+    }
+  }
+};
+
+template <int D, int V, int L, class Source>
+__device__ __forceinline__ void inv_levels(float (&out)[rows_at(D, L - 1)][cols_at(V, L - 1)],
+                                           const LanePos<D> &p, const Source &src) {
+  constexpr int R2 = rows_at(D, L), VI = cols_at(V, L - 1), V2 = cols_at(V, L);
+  constexpr int SI = span_at(V, L - 1);
+  float ll[R2][V2];
+  if constexpr (L < D) {
+    inv_levels<D, V, L + 1>(ll, p, src);
+  } else {
+#pragma unroll
+    for (int i = 0; i < R2; ++i) src.template get_row<L, 0>(i, ll[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < R2; ++i) {
+    float y2[V2], y3[V2], y4[V2];
+    src.template get_row<L, 1>(i, y2);
+    src.template get_row<L, 2>(i, y3);
+    src.template get_row<L, 3>(i, y4);
+#pragma unroll
+    for (int e = 0; e < V2; ++e) {
+      const float s1 = ll[i][e] + y3[e], s2 = ll[i][e] - y3[e];
+      const float d1 = y2[e] + y4[e], d2 = y2[e] - y4[e];
+      const float a = 0.5f * (s1 + d1), b = 0.5f * (s1 - d1);
+      const float c = 0.5f * (s2 + d2), d = 0.5f * (s2 - d2);
+      if constexpr (VI >= 2) {
+        out[2 * i][2 * e] = a; out[2 * i][2 * e + 1] = b;
+        out[2 * i + 1][2 * e] = c; out[2 * i + 1][2 * e + 1] = d;
+      } else {
+        // every lane of the group holds the same (y1..y4); the left half keeps the left pixel
+        const bool left = (p.lc & SI) == 0;
+        out[2 * i][0] = left ? a : b;
+        out[2 * i + 1][0] = left ? c : d;
+      }
+    }
+  }
+}
+
+// The channel walk of the staged path with NI dense fetches per channel.  mine[i]: the lane's
+// list entries (kInvNone: padding).  row_step: W for lanes inside the plane, 0 for the others
+// (whose dst is the scratch line).
+// RES: res + (what dst points at, relative to the output tensor) is added to every stored row.
+template <int D, int V, int NI, bool RES, class YT>
+__device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane, int64_t k, int n_ch,
+                                                const uint32_t (&mine)[kInvCap / kWave],
+                                                uint32_t *tile, const InvStaged<D, V> &staged,
+                                                const LanePos<D> &p, YT *dst, int row_step,
+                                                int64_t dst_step, const YT *res) {
+  constexpr int R = 1 << D;
+  constexpr uint32_t kRank = (1u << kInvRankBits) - 1u;
+  float vn[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) vn[i] = plane[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+  auto channel = [&](int c) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      if (mine[i] != kInvNone) tile[mine[i] >> kInvRankBits] = __float_as_uint(vn[i]);
+    // the next channel's values travel while this one is built (past the end: the last again)
+    const float *nx = plane + (size_t)min(c + 1, n_ch - 1) * k;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) vn[i] = nx[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+    float skip[RES ? R : 1][V];
+    if constexpr (RES) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) load_row_stream<V>(res + (size_t)r * row_step, skip[r]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    wave_lds_fence();
+    float out[R][V];
+    inv_levels<D, V, 1>(out, p, staged);
+    wave_lds_fence();
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (RES) {
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < V; ++e) out[r][e] += skip[r][e];
+      res += dst_step;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) store_row_stream<V>(dst + (size_t)r * row_step, out[r]);
+    dst += dst_step;
+  };
+  // The first channel stands outside the loop: at the loop head the outstanding memory
+  // operations are then "fetches, then R stores" on both incoming paths, and the wait for a
+  // fetch need not cover the stores.
+  channel(0);
+  for (int c = 1; c < n_ch; ++c) channel(c);
+}
+
+// yc [B, C, k] + jmap [B, N] -> y [B, C, H, W].  grid = (ceil(units/4), G, B), block = 256.
+// scratch: 1 KiB that lanes outside the plane may overwrite.  RES: y = residual + (the above),
+// residual [B, C, H, W] (the skip connection of Eq. (inverted)); it may be y itself.
+// YT: float or bf16_t, the storage type of y and of the residual.
+template <int D, int V, bool RES, class YT>
+__global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restrict__ yc,
+                                                            const int32_t *__restrict__ jmap,
+                                                            YT *y, Geo g, StripMap m, int C,
+                                                            int Cg, int64_t k, float *scratch,
+                                                            const YT *residual) {
+  constexpr int R = 1 << D;
+  constexpr int NS = slot_count(D, V);
+  constexpr bool kStaged = D <= 3;  // the [slot][lane] tiles of four waves fit in LDS
+  constexpr int CAP = NS * kWave < kInvCap ? NS * kWave : kInvCap;  // entries a wave can pack
+  static_assert(NS <= 128, "slot mask is 128 bits wide");
+  static_assert(!kStaged || NS * kWave <= (1 << (32 - kInvRankBits)), "cell index fits above the rank");
+  __shared__ uint32_t tiles[kStaged ? 4 : 1][kStaged ? NS * kWave : 1];
+  const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int unit = blockIdx.x * 4 + wv;
+  const int grp = blockIdx.y, b = blockIdx.z;
+  LanePos<D> p;
+  int row0, col0;
+  const bool active = locate<D, V>(m, g, unit, p, row0, col0);
+  const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
+  if (__ballot(active) == 0 || c0 >= c1) return;  // whole waves leave
+
+  const int32_t *jm = jmap + (size_t)b * g.N;
+  const float *plane = yc + ((size_t)b * C + c0) * k;
+  const size_t first = ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+  YT *dst = y + first;
+
+  // ranks of this lane's positions (the same for every channel), slot by slot
+  InvDirect<D, V> src;
+  src.any[0] = src.any[1] = 0;
+  int count = 0;  // kept positions of this wave's strip (wave-uniform)
+  auto fetch = [&](auto Lc, auto Jc) {
+    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+    constexpr int CV = cols_at(V, L);
+#pragma unroll
+    for (int i = 0; i < rows_at(D, L); ++i)
+#pragma unroll
+      for (int e = 0; e < CV; ++e) {
+        constexpr int base = slot_base(D, V, L, J);
+        int j = -1;
+        if (active) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
+        src.jj[base + i * CV + e] = j;
+      }
+  };
+  auto each_level = [&](auto Lc) {
+    constexpr int L = decltype(Lc)::value;
+    fetch(Lc, std::integral_constant<int, 1>{});
+    fetch(Lc, std::integral_constant<int, 2>{});
+    fetch(Lc, std::integral_constant<int, 3>{});
+    if constexpr (L == D) fetch(Lc, std::integral_constant<int, 0>{});
+  };
+  each_level(std::integral_constant<int, 1>{});
+  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+  if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+  // (all map loads are in flight before the first vote waits for one)
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    const uint64_t kept = __ballot(src.jj[s] >= 0);
+    if (kept != 0) src.any[s >> 6] |= (uint64_t)1 << (s & 63);
+    count += __popcll(kept);
+  }
+
+  if constexpr (kStaged) {
+    if (count <= CAP && k <= ((int64_t)1 << kInvRankBits)) {
+      // pack (rank, cell): slot-major, then lane (a band row's kept positions have consecutive
+      // j).  The tile serves as scratch for the list before it becomes the staging area.
+      uint32_t *tile = tiles[wv];
+      int running = 0;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        if ((src.any[s >> 6] >> (s & 63)) & 1) {
+          const int j = src.jj[s];
+          const uint64_t kept = __ballot(j >= 0);
+          const int at = running + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32),
+                                       __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
+          if (j >= 0) tile[at] = (uint32_t)j | ((uint32_t)(s * kWave + lane) << kInvRankBits);
+          running += __popcll(kept);
+        }
+      }
+      wave_lds_fence();
+      uint32_t mine[kInvCap / kWave];  // this lane's share of the list: entries lane + 64 i
+#pragma unroll
+      for (int i = 0; i < kInvCap / kWave; ++i) {
+        const int e = lane + 64 * i;
+        mine[i] = (i < CAP / kWave && e < count) ? tile[e] : kInvNone;
+      }
+      wave_lds_fence();
+#pragma unroll
+      for (int s = 0; s < NS; ++s) tile[s * kWave + lane] = 0u;
+
+      InvStaged<D, V> staged;
+      staged.cell = reinterpret_cast<const float *>(tile) + lane;
+      staged.any[0] = src.any[0];
+      staged.any[1] = src.any[1];
+      YT *sink_line = reinterpret_cast<YT *>(scratch) + lane * V;
+      YT *to = active ? dst : sink_line;
+      const YT *res = (RES && active) ? residual + first : sink_line;
+      const int row_step = active ? g.W : 0;
+      const int64_t dst_step = active ? g.N : 0;
+      const int ni = (count + 63) >> 6;
+      if (ni <= 4)
+        inv_staged_walk<D, V, 4, RES, YT>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
+      else if (ni <= 8)
+        inv_staged_walk<D, V, 8, RES, YT>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
+      else
+        inv_staged_walk<D, V, 16, RES, YT>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
+      return;
+    }
+  }
+
+  // plain path
+  if (!active) return;
+  src.plane = plane;
+  const YT *res = RES ? residual + first : nullptr;
+  for (int c = c0; c < c1; ++c) {
+    float out[R][V];
+    inv_levels<D, V, 1>(out, p, src);
+    if constexpr (RES) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        float skip[V];
+        load_row_stream<V>(res + (size_t)r * g.W, skip);
+#pragma unroll
+        for (int e = 0; e < V; ++e) out[r][e] += skip[e];
+      }
+      res += g.N;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) store_row_stream<V>(dst + (size_t)r * g.W, out[r]);
+    src.plane += k;
+    dst += g.N;
+  }
+}
+
+template <int D, int V>
+hipError_t inv_launch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, void *y,
+                      int G, float *scratch, const void *residual, hipStream_t s) {
+  const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
+  const StripMap m = make_map(d, V);
+  const int Cg = (d.C_out + G - 1) / G;
+  dim3 grid((m.units + 3) / 4, G, d.B);
+#define WCC_INV(RES, YT)                                                                          \
+  hipLaunchKernelGGL((scatter_ihaar_kernel<D, V, RES, YT>), grid, dim3(256), 0, s, yc, jmap,      \
+                     static_cast<YT *>(y), g, m, d.C_out, Cg, k, scratch,                         \
+                     static_cast<const YT *>(residual))
+  if (d.act_dtype == WCC_BF16) { if (residual) WCC_INV(true, bf16_t); else WCC_INV(false, bf16_t); }
+  else                         { if (residual) WCC_INV(true, float); else WCC_INV(false, float); }
+#undef WCC_INV
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t inv_dispatch(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap, void *y,
+                        int G, float *scratch, const void *residual, hipStream_t s) {
+  const bool v4 = d.W % 4 == 0;
+  switch (d.levels) {
+    case 1: return v4 ? inv_launch<1, 4>(d, k, yc, jmap, y, G, scratch, residual, s)
+                      : inv_launch<1, 2>(d, k, yc, jmap, y, G, scratch, residual, s);
+    case 2: return inv_launch<2, 4>(d, k, yc, jmap, y, G, scratch, residual, s);
+    case 3: return inv_launch<3, 4>(d, k, yc, jmap, y, G, scratch, residual, s);
+    case 4: return inv_launch<4, 4>(d, k, yc, jmap, y, G, scratch, residual, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
+                                void *y, float *scratch, const void *residual, hipStream_t s) {
+  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 2048, 8), scratch, residual, s);
+}
+
+}  // namespace wcc

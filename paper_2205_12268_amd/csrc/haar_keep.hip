@@ -1,0 +1,315 @@
+// Second transform pass of the fused layer: the kept coefficients go straight to their
+// compressed place (Eq. T of the joint shrinkage), optionally as 8-bit codes.
+#include "strip.h"
+
+namespace wcc {
+namespace {
+
+// ---- second pass of the fused layer: transform again, keep only the selected positions ----
+// xc[b, c, jmap[b, q]] = HWT_d(x[b, c])[q] for the kept q; dropped coefficients never reach
+// memory.  Also raises the alpha slots to max |kept coefficient| (nullable).
+// Q8: the clipping parameter is known beforehand (the caller supplied it), so the kept
+// coefficients leave the chip as signed 8-bit codes (Eq. quantweights) instead of fp32.
+template <int D, int V, bool Q8>
+struct KeepSink {
+  using Out = std::conditional_t<Q8, int8_t, float>;
+  // Every slot is stored through a buffer descriptor of the channel's compressed vector, with
+  // the byte offset of the slot's rank, or an offset beyond the vector for a position that is
+  // not kept: the hardware drops such a lane's store.  No store sits behind a branch, so the
+  // number of stores per channel is fixed and the wait for the prefetched rows of the next
+  // channel does not have to drain them (loads and stores retire through one counter); and no
+  // slot needs a 64-bit address or a saved lane mask, which halves the kernel's registers.
+  static constexpr uint32_t kDropped = 0xFFFFFFFFu;
+  __amdgpu_buffer_rsrc_t xc_c;     // xc[b, c, :]
+  uint32_t at[slot_count(D, V)];   // byte offset of the slot's rank, or kDropped
+  float vmax;
+  Quant quant;
+  __device__ __forceinline__ explicit KeepSink(float alpha) : quant(alpha) {}
+  // plane: xc[b, c, :] (wave-uniform), k elements
+  __device__ __forceinline__ void aim(Out *plane, int64_t k) {
+    xc_c = __builtin_amdgcn_make_buffer_rsrc(plane, 0, (int)(uint32_t)(k * (int64_t)sizeof(Out)),
+                                             0x00020000 /* raw dwords, no swizzle */);
+  }
+  template <int L, int J>
+  __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
+                                          bool owner) {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+    (void)p;
+    (void)owner;  // (at[] is kDropped for the lanes that do not own the value)
+#pragma unroll
+    for (int e = 0; e < CV; ++e) {
+      const int s = base + i * CV + e;
+      if constexpr (Q8) {
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)quant.code(v[e]), xc_c, at[s], 0, 0);
+      } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[e]), xc_c, at[s], 0, 0);
+        vmax = fmaxf(vmax, at[s] != kDropped ? fabsf(v[e]) : 0.f);
+      }
+    }
+  }
+};
+
+// The same sink for a strip that keeps few of its positions.  One sparse store per slot costs
+// the memory pipeline an instruction each, whatever the number of lanes that keep something
+// (measured: the stores were a third of the pass).  Here every lane drops its values into an LDS
+// tile laid out [slot][lane]; after the last level the wave goes through the strip's packed list
+// of kept positions (64 entries a row, built once, the same for every channel), picks each
+// entry's value from the tile and stores NI dense rows instead of one row per slot.
+template <int D, int V, bool Q8, int NI>
+struct KeepStagedSink {
+  using Out = std::conditional_t<Q8, int8_t, float>;
+  static constexpr uint32_t kDropped = 0xFFFFFFFFu;
+  __amdgpu_buffer_rsrc_t xc_c;  // xc[b, c, :]
+  uint32_t *tile;               // [slot][lane]
+  int lane;
+  uint32_t cell[NI];            // tile index of the entry's position
+  uint32_t at[NI];              // byte offset of the entry's rank, or kDropped (list padding)
+  float vmax;
+  Quant quant;
+  __device__ __forceinline__ explicit KeepStagedSink(float alpha) : quant(alpha) {}
+  __device__ __forceinline__ void aim(Out *plane, int64_t k) {
+    xc_c = __builtin_amdgcn_make_buffer_rsrc(plane, 0, (int)(uint32_t)(k * (int64_t)sizeof(Out)),
+                                             0x00020000 /* raw dwords, no swizzle */);
+  }
+  template <int L, int J>
+  __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
+                                          bool owner) {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+    (void)p;
+    (void)owner;  // (a value a lane does not own is in no list)
+#pragma unroll
+    for (int e = 0; e < CV; ++e) tile[(base + i * CV + e) * kWave + lane] = __float_as_uint(v[e]);
+  }
+  // once per channel, after the last level
+  __device__ __forceinline__ void flush() {
+    wave_lds_fence();
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const float v = __uint_as_float(tile[cell[i]]);
+      if constexpr (Q8) {
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)quant.code(v), xc_c, at[i], 0, 0);
+      } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), xc_c, at[i], 0, 0);
+        vmax = fmaxf(vmax, at[i] != kDropped ? fabsf(v) : 0.f);
+      }
+    }
+    wave_lds_fence();
+  }
+};
+
+// grid = (ceil(units/4), G, B), block = 256.  DWM as in haar_fwd_kernel.  Q8: xc is int8 codes
+// for the clipping parameter q_alpha (> 0), and alpha_slots must be null.
+template <int D, int V, int PF, int DWM, bool Q8, class XT, bool NT = false>
+__global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x,
+                                                        const int32_t *__restrict__ jmap,
+                                                        void *__restrict__ xc, float *alpha_slots,
+                                                        Geo g, StripMap m, int C, int Cg, int64_t k,
+                                                        const float *__restrict__ wdw,
+                                                        float q_alpha) {
+  __shared__ float wmax[4];
+  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int grp = blockIdx.y, b = blockIdx.z;
+  LanePos<D> p;
+  int row0, col0;
+  const bool active = locate<D, V>(m, g, unit, p, row0, col0);
+  const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
+
+  using Sink = KeepSink<D, V, Q8>;
+  Sink sink(Q8 ? q_alpha : 0.f);
+  const int32_t *jm = jmap + (size_t)b * g.N;
+  auto fetch = [&](auto Lc, auto Jc) {
+    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+    constexpr int CV = cols_at(V, L), S2 = span_at(V, L);
+    const bool owner = (S2 == 1) || ((p.lc & (S2 - 1)) == 0);
+#pragma unroll
+    for (int i = 0; i < rows_at(D, L); ++i)
+#pragma unroll
+      for (int e = 0; e < CV; ++e) {
+        constexpr int base = slot_base(D, V, L, J);
+        const int s = base + i * CV + e;
+        int j = -1;
+        if (active && owner) j = jm[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
+        sink.at[s] = (uint32_t)j;  // (turned into a byte offset below, once all loads are out)
+      }
+  };
+  auto each_level = [&](auto Lc) {
+    constexpr int L = decltype(Lc)::value;
+    fetch(Lc, std::integral_constant<int, 1>{});
+    fetch(Lc, std::integral_constant<int, 2>{});
+    fetch(Lc, std::integral_constant<int, 3>{});
+    if constexpr (L == D) fetch(Lc, std::integral_constant<int, 0>{});
+  };
+  each_level(std::integral_constant<int, 1>{});
+  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+  if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+  using Out = typename Sink::Out;
+  const XT *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+  Out *plane = static_cast<Out *>(xc) + ((size_t)b * C + c0) * k;
+  // walks the group's channels with whichever sink; returns its max |kept coefficient|
+  auto walk = [&](auto &sk, auto &&next_channel) {
+    sk.vmax = 0.f;
+    sk.aim(plane, k);
+    if constexpr (DWM == 0) {
+      channel_loop<D, V, PF, NT>(src, g.N, g.W, c1 - c0, p, sk, next_channel);
+    } else {
+      const DwLane q = dw_lane<D, V>(g, m, p, row0, col0);
+      channel_loop_dw<D, V, DWM == 2, true, false>(src, wdw + (size_t)c0 * 9, g.N, c1 - c0, q, p, sk,
+                                                   next_channel);
+    }
+    return sk.vmax;
+  };
+
+  float mx = 0.f;
+  bool done = false;
+  // Dense stores pay where a strip keeps at most half of its slots' worth of positions.  (With
+  // K_dw folded in the kernel is bound by its arithmetic and registers; there the staging
+  // measured 5-10 % slower than one store per slot.)
+  constexpr int NS = slot_count(D, V);
+  constexpr bool kStaged = V == 4 && (D == 2 || D == 3) && DWM == 0;
+  if constexpr (kStaged) {
+    __shared__ uint32_t tiles[4][NS * kWave];
+    constexpr int kRankBits = 20;  // list entry = rank | tile index << 20
+    int count = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) count += __popcll(__ballot((int)sink.at[s] >= 0));
+    const int ni = (count + kWave - 1) / kWave;
+    const bool whole = __ballot(active) == ~(uint64_t)0;  // (a ragged wave takes the plain path)
+    if (whole && c0 < c1 && ni <= NS / 2 && ni <= 16 && k <= ((int64_t)1 << kRankBits)) {
+      const int lane = threadIdx.x & (kWave - 1);
+      uint32_t *tile = tiles[threadIdx.x >> 6];
+      // pack (rank, tile index): slot-major, then lane (a band row's kept positions have
+      // consecutive ranks).  The tile is scratch for the list before it becomes the staging area.
+      int running = 0;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const int j = (int)sink.at[s];
+        const uint64_t kept = __ballot(j >= 0);
+        const int to = running + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
+        if (j >= 0) tile[to] = (uint32_t)j | ((uint32_t)(s * kWave + lane) << kRankBits);
+        running += __popcll(kept);
+      }
+      wave_lds_fence();
+      auto run = [&](auto ni_c) {
+        constexpr int NI = decltype(ni_c)::value;
+        KeepStagedSink<D, V, Q8, NI> st(Q8 ? q_alpha : 0.f);
+        st.tile = tile;
+        st.lane = lane;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+          const int e = lane + kWave * i;
+          const uint32_t packed = e < count ? tile[e] : 0u;
+          st.cell[i] = e < count ? packed >> kRankBits : (uint32_t)lane;
+          st.at[i] = e < count ? (packed & ((1u << kRankBits) - 1u)) * (uint32_t)sizeof(Out) : Sink::kDropped;
+        }
+        wave_lds_fence();
+        mx = walk(st, [&plane, k](auto &sk) {
+          sk.flush();
+          plane += k;
+          sk.aim(plane, k);
+        });
+      };
+      if (ni <= 4) run(std::integral_constant<int, 4>{});
+      else if (ni <= 8) run(std::integral_constant<int, 8>{});
+      else run(std::integral_constant<int, 16>{});  // (ni <= 16 is part of the condition above)
+      done = true;
+    }
+  }
+  if (!done && active && c0 < c1) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      sink.at[s] = (int)sink.at[s] >= 0 ? sink.at[s] * (uint32_t)sizeof(Out) : Sink::kDropped;
+    mx = walk(sink, [&plane, k](Sink &sk) {
+      plane += k;
+      sk.aim(plane, k);
+    });
+  }
+  if (alpha_slots == nullptr) return;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    mx = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    // integer max on the bit pattern of a non-negative float: exact and order-independent;
+    // workgroups spread over the slots because atomics on one address serialise
+    unsigned int *a = reinterpret_cast<unsigned int *>(alpha_slots) +
+                      ((blockIdx.x + 3u * blockIdx.y + 11u * blockIdx.z) & (kAlphaSlots - 1));
+    const unsigned int mine = __float_as_uint(mx);
+    if (mine > __hip_atomic_load(a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(a, mine);
+  }
+}
+
+template <int D, int V, class XT>
+hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_t *jmap, void *xc,
+                         float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
+  const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
+  const StripMap m = make_map(d, V);
+  const int Cg = (d.C_in + pl.G - 1) / pl.G;
+  dim3 grid((m.units + 3) / 4, pl.G, d.B);
+  const bool q8 = q_alpha > 0.f;
+#define WCC_KEEP(PF, DWM)                                                                          \
+  do {                                                                                             \
+    if (q8)                                                                                        \
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, true, XT>), grid, dim3(256), 0, s, x,   \
+                         jmap, xc, nullptr, g, m, d.C_in, Cg, k, wdw, q_alpha);                    \
+    else                                                                                           \
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, false, XT>), grid, dim3(256), 0, s, x,  \
+                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, k, wdw, 0.f);                    \
+  } while (0)
+  if constexpr (V == 4) {
+    if (wdw != nullptr) {  // K_dw in front of the transform
+      if (dw_needs_edges(m)) WCC_KEEP(1, 2); else WCC_KEEP(1, 1);
+      return hipGetLastError();
+    }
+  }
+  if (wdw != nullptr) return hipErrorInvalidValue;
+  if (pl.stream) {
+    if (q8)
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0, true, XT, true>), grid, dim3(256), 0, s, x,
+                         jmap, xc, nullptr, g, m, d.C_in, Cg, k, wdw, q_alpha);
+    else
+      hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0, false, XT, true>), grid, dim3(256), 0, s, x,
+                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, k, wdw, 0.f);
+    return hipGetLastError();
+  }
+  WCC_KEEP(1, 0);
+#undef WCC_KEEP
+  return hipGetLastError();
+}
+
+template <int D, int V>
+hipError_t keep_launch(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap, void *xc,
+                       float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
+  if (d.act_dtype == WCC_BF16)
+    return keep_launch_t<D, V>(d, k, static_cast<const bf16_t *>(x), jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+  return keep_launch_t<D, V>(d, k, static_cast<const float *>(x), jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+}
+
+}  // namespace
+
+hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap, void *xc,
+                         float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
+  const bool v4 = d.W % 4 == 0;
+  switch (d.levels) {
+    case 1: return v4 ? keep_launch<1, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s)
+                      : keep_launch<1, 2>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+    case 2: return keep_launch<2, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+    case 3: return keep_launch<3, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+    case 4: return keep_launch<4, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap,
+                            void *xc, float *alpha_slots, const float *wdw, float q_alpha,
+                            hipStream_t s) {
+  const Plan pl{groups_for(d, d.C_in, arithmetic_bound(d, wdw != nullptr) ? 4096 : 1024, 8), false,
+                streams(d)};
+  return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+}
+
+}  // namespace wcc
