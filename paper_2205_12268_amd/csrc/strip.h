@@ -163,9 +163,12 @@ __device__ __forceinline__ void store_row_stream(float *dst, const float (&src)[
 // rounds to nearest even.
 __device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
-__device__ __forceinline__ uint32_t to_bf16(float f) {
-  const uint32_t u = __float_as_uint(f);
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// two floats -> two bf16 in one word (first one in the low half), round to nearest even: one
+// v_cvt_pk_bf16_f32 on this chip
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
 }
 template <int V>
 __device__ __forceinline__ void load_row(const bf16_t *src, float (&dst)[V]) {
@@ -179,9 +182,9 @@ __device__ __forceinline__ void load_row(const bf16_t *src, float (&dst)[V]) {
 }
 template <int V>
 __device__ __forceinline__ void store_row(bf16_t *dst, const float (&src)[V]) {
-  const uint32_t a = to_bf16(src[0]) | (to_bf16(src[1]) << 16);
+  const uint32_t a = pack_bf16(src[0], src[1]);
   if constexpr (V == 4) {
-    const uint32_t b = to_bf16(src[2]) | (to_bf16(src[3]) << 16);
+    const uint32_t b = pack_bf16(src[2], src[3]);
     *reinterpret_cast<uint2 *>(dst) = make_uint2(a, b);
   } else {
     *reinterpret_cast<uint32_t *>(dst) = a;
@@ -200,11 +203,11 @@ __device__ __forceinline__ void load_row_stream(const bf16_t *src, float (&dst)[
 }
 template <int V>
 __device__ __forceinline__ void store_row_stream(bf16_t *dst, const float (&src)[V]) {
-  const uint32_t a = to_bf16(src[0]) | (to_bf16(src[1]) << 16);
+  const uint32_t a = pack_bf16(src[0], src[1]);
   if constexpr (V == 4) {
     stream_u2 t;
     t.x = a;
-    t.y = to_bf16(src[2]) | (to_bf16(src[3]) << 16);
+    t.y = pack_bf16(src[2], src[3]);
     __builtin_nontemporal_store(t, reinterpret_cast<stream_u2 *>(dst));
   } else {
     __builtin_nontemporal_store(a, reinterpret_cast<uint32_t *>(dst));
