@@ -9,7 +9,7 @@ import pytest
 import torch
 
 from paper_2205_12268_amd import synth, wcc
-from tests.util import desc_of, dev, oracle_scale, rel_l2, tol_for, upload_weights
+from tests.util import dev, oracle_scale, rel_l2, tol_for, upload_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -21,13 +21,19 @@ def _huge_plane():
                        levels=2, keep_num=1, keep_den=2, seed=synth.SEED_BASE + 0x800)
 
 
-@pytest.mark.parametrize("n", [2, 3, 4, "huge_plane"])
-def test_full_size_forward(ref, n):
+@pytest.mark.parametrize("n,norm", [(2, "l1"), (3, "l1"), (4, "l1"), ("huge_plane", "l1"),
+                                    (2, "l2"), (3, "l2"), (4, "l2")])
+def test_full_size_forward(ref, n, norm):
+    """norm = "l2" (bench.py --norm l2): sums of squares round in fp32, so the index sets are
+    checked for validity against the oracle's fp64 norms and the oracle then follows the
+    GPU's sets; with the L1 norm they are the oracle's own, bit for bit."""
     cfg = _huge_plane() if n == "huge_plane" else synth.config(n)
     n = 9 if n == "huge_plane" else n
-    print(f"workload {cfg.name}: generating inputs", flush=True)
+    print(f"workload {cfg.name}, {norm} norm: generating inputs", flush=True)
     x, w = synth.make_inputs(cfg)
-    d = desc_of(cfg)
+    d = wcc.make_desc(cfg.B, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
+                      cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.F32,
+                      wcc.NORM_L2 if norm == "l2" else wcc.NORM_L1)
     N, k = cfg.N, cfg.k
     ctx = wcc.Context(0)
     ctx.ensure_workspace(d)
@@ -50,12 +56,37 @@ def test_full_size_forward(ref, n):
         y2.fill_(float("nan"))
         ctx.wcc_forward(d, xd, wd, wsd, float(alpha.item()), y2, idx2, None)
         assert torch.equal(idx, idx2) and torch.equal(y, y2)
+    # the selected list handed back in as a caller's list: the same kernels after the select,
+    # so the same output bit for bit; and the first-k list against the same list given explicitly
+    ctx.wcc_forward_fixed(d, xd, wd, wsd, 0.0, idx, y2, None)
+    assert torch.equal(y, y2)
+    if norm == "l1" and n != 9:
+        y3 = torch.full_like(y, float("nan"))
+        ctx.wcc_forward_fixed(d, xd, wd, wsd, 0.0, None, y2, None)
+        first_k = torch.arange(k, dtype=torch.int32, device="cuda").repeat(cfg.B, 1).contiguous()
+        ctx.wcc_forward_fixed(d, xd, wd, wsd, 0.0, first_k, y3, None)
+        assert torch.equal(y2, y3) and not torch.equal(y2, y)
+        del y3, first_k
     del y2, idx2
 
     print("  oracle: transform, norms, selection", flush=True)
     coef = ref.haar_fwd(x, cfg.levels).reshape(cfg.B, cfg.C_in, N)
-    o_idx = ref.topk(ref.channel_norm(coef), k)
-    np.testing.assert_array_equal(idx.cpu().numpy().astype(np.int64), o_idx)
+    o_norm = ref.channel_norm(coef, norm)
+    g_idx = idx.cpu().numpy().astype(np.int64)
+    if norm == "l1":
+        o_idx = ref.topk(o_norm, k)
+        np.testing.assert_array_equal(g_idx, o_idx)
+    else:
+        for b in range(cfg.B):
+            sel = g_idx[b]
+            assert np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] < N
+            kth = np.sort(o_norm[b])[::-1][k - 1]
+            dropped = np.ones(N, dtype=bool)
+            dropped[sel] = False
+            assert o_norm[b][sel].min() >= kth * (1 - 1e-5)
+            assert o_norm[b][dropped].max() <= kth * (1 + 1e-5)
+        o_idx = g_idx
+    del o_norm
     xc = ref.gather(coef, o_idx)
     del coef
     o_alpha = float(np.float32(ref.absmax(xc)))
