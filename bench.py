@@ -56,6 +56,31 @@ def read_traffic(profile_dir: str, workload: str, kernel: str):
     return None
 
 
+def stream_ceilings(ctx, wcc, torch, nbytes: int = 512 << 20, reps: int = 4) -> dict:
+    """GB/s of the library's plain streaming kernels (read, write, copy; ordinary and
+    non-temporal accesses) over buffers of `nbytes`, twice the memory-side cache, each at four
+    grid sizes with the best one reported: what this machine's memory system gives to the simplest
+    code, for placing the stage rates above."""
+    a = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").fill_(1.0)
+    b = torch.empty_like(a)
+    out = {"bytes": nbytes}
+    for name, kind, moved in (("read", wcc.PROBE_READ, 1), ("write", wcc.PROBE_WRITE, 1),
+                              ("copy", wcc.PROBE_COPY, 2)):
+        for nt in (False, True):
+            best = 0.0
+            for blocks in (2048, 8192, 32768, 131072):
+                ctx.wcc_probe_stream(kind, a, b, nbytes, nt, blocks)
+                t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                t0.record()
+                for _ in range(reps):
+                    ctx.wcc_probe_stream(kind, a, b, nbytes, nt, blocks)
+                t1.record()
+                t1.synchronize()
+                best = max(best, moved * nbytes * reps / (t0.elapsed_time(t1) * 1e-3) / 1e9)
+            out[name + ("_nt" if nt else "")] = round(best, 1)
+    return out
+
+
 def bench_stack(args, synth, run_layer, ctx) -> int:
     """The 16 point-wise layers of the backbone stack, one after the other (each on its own
     synthetic input; the depthwise convolutions between them are not on the path)."""
@@ -263,6 +288,9 @@ def main() -> int:
                     help="--config 6: skip timing the dense block built from library convolutions")
     ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
                     help="graph: the step is recorded once into a HIP graph and replayed")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="single-layer workloads: skip timing the plain read / write / copy kernels "
+                         "(reported as stream_ceilings_GBs)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="R",
                     help="also run R plain device-to-device copies of the input tensor (a copy "
                          "kernel of known size, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -426,6 +454,8 @@ def main() -> int:
                              / (stage_us["pointwise"] * 1e-6) / 1e12, 2),
     }
 
+    if not args.no_ceilings:
+        out["stream_ceilings_GBs"] = stream_ceilings(ctx, wcc, torch)
     if args.cold_input:
         out["cold_input_ms_per_step"] = round(run_layer.cold_ms, 5)
     if not args.no_cpu_baseline:

@@ -164,7 +164,7 @@ template <int D, int V, bool RES, class YT>
 __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restrict__ yc,
                                                             const int32_t *__restrict__ jmap,
                                                             YT *y, Geo g, StripMap m, int C,
-                                                            int Cg, int64_t k, float *scratch,
+                                                            int G, int64_t k, float *scratch,
                                                             const YT *residual) {
   constexpr int R = 1 << D;
   constexpr int NS = slot_count(D, V);
@@ -179,8 +179,14 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
   LanePos<D> p;
   int row0, col0;
   const bool active = locate<D, V>(m, g, unit, p, row0, col0);
-  const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
-  if (__ballot(active) == 0 || c0 >= c1) return;  // whole waves leave
+  // Group grp takes the channels grp, grp + G, grp + 2G, ...: the groups that run side by side
+  // then write neighbouring planes of y, a window of G planes that moves through the tensor,
+  // instead of G windows a group's width apart (workload 2's inverse 29.6 -> 27.3 us, the
+  // block's expand layer 503 -> 478 us).
+  const int c0 = grp;
+  const int n_ch = c0 >= C ? 0 : (C - c0 + G - 1) / G;
+  if (__ballot(active) == 0 || n_ch <= 0) return;  // whole waves leave
+  const int64_t kstep = (int64_t)G * k, nstep = (int64_t)G * g.N;
 
   const int32_t *jm = jmap + (size_t)b * g.N;
   const float *plane = yc + ((size_t)b * C + c0) * k;
@@ -259,14 +265,14 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
       YT *to = active ? dst : sink_line;
       const YT *res = (RES && active) ? residual + first : sink_line;
       const int row_step = active ? g.W : 0;
-      const int64_t dst_step = active ? g.N : 0;
+      const int64_t dst_step = active ? nstep : 0;
       const int ni = (count + 63) >> 6;
       if (ni <= 4)
-        inv_staged_walk<D, V, 4, RES, YT>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 4, RES, YT>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
       else if (ni <= 8)
-        inv_staged_walk<D, V, 8, RES, YT>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 8, RES, YT>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
       else
-        inv_staged_walk<D, V, 16, RES, YT>(plane, k, c1 - c0, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 16, RES, YT>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
       return;
     }
   }
@@ -275,7 +281,7 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
   if (!active) return;
   src.plane = plane;
   const YT *res = RES ? residual + first : nullptr;
-  for (int c = c0; c < c1; ++c) {
+  for (int c = 0; c < n_ch; ++c) {
     float out[R][V];
     inv_levels<D, V, 1>(out, p, src);
     if constexpr (RES) {
@@ -286,12 +292,12 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
 #pragma unroll
         for (int e = 0; e < V; ++e) out[r][e] += skip[e];
       }
-      res += g.N;
+      res += nstep;
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) store_row_stream<V>(dst + (size_t)r * g.W, out[r]);
-    src.plane += k;
-    dst += g.N;
+    src.plane += kstep;
+    dst += nstep;
   }
 }
 
@@ -300,11 +306,10 @@ hipError_t inv_launch(const wcc_desc &d, int64_t k, const float *yc, const int32
                       int G, float *scratch, const void *residual, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
-  const int Cg = (d.C_out + G - 1) / G;
   dim3 grid((m.units + 3) / 4, G, d.B);
 #define WCC_INV(RES, YT)                                                                          \
   hipLaunchKernelGGL((scatter_ihaar_kernel<D, V, RES, YT>), grid, dim3(256), 0, s, yc, jmap,      \
-                     static_cast<YT *>(y), g, m, d.C_out, Cg, k, scratch,                         \
+                     static_cast<YT *>(y), g, m, d.C_out, G, k, scratch,                          \
                      static_cast<const YT *>(residual))
   if (d.act_dtype == WCC_BF16) { if (residual) WCC_INV(true, bf16_t); else WCC_INV(false, bf16_t); }
   else                         { if (residual) WCC_INV(true, float); else WCC_INV(false, float); }
@@ -329,7 +334,7 @@ hipError_t inv_dispatch(const wcc_desc &d, int64_t k, const float *yc, const int
 
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
                                 void *y, float *scratch, const void *residual, hipStream_t s) {
-  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 2048, 8), scratch, residual, s);
+  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 4096, 8), scratch, residual, s);
 }
 
 }  // namespace wcc

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <algorithm>
 
 #include "wcc.h"
 
@@ -171,6 +172,12 @@ hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const f
 // residual (nullable): [B, C_out, H, W] added to the result (may be y itself)
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
                                 void *y, float *scratch, const void *residual, hipStream_t s);
+// plain streaming kernel of `bytes` bytes (a multiple of 16): kind = wcc_probe_kind; read sums
+// src and writes nothing (dst: 16 bytes it may write in principle), write fills dst, copy moves
+// src to dst; nt: with the non-temporal hint; blocks: workgroups of 256 threads walking the
+// buffer with a grid stride (<= 0: 8192)
+hipError_t launch_probe(int kind, const void *src, void *dst, size_t bytes, bool nt, int blocks,
+                        hipStream_t s);
 // out[i] = the two signed 4-bit codes of packed[i / 2] widened to int8 (n = number of codes, even)
 hipError_t launch_unpack_i4(const uint8_t *packed, int8_t *out, int64_t n, hipStream_t s);
 // depthwise 3x3, stride 1, zero padding 1: x, y [B, C, H, W], w [C, 3, 3]
