@@ -105,8 +105,8 @@ template <int D, int V, int PF, int DWM, bool Q8, class XT, bool NT = false>
 __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x,
                                                         const int32_t *__restrict__ jmap,
                                                         void *__restrict__ xc, float *alpha_slots,
-                                                        Geo g, StripMap m, int C, int Cg, int64_t k,
-                                                        const float *__restrict__ wdw,
+                                                        Geo g, StripMap m, int C, int Cg, int cstep,
+                                                        int64_t k, const float *__restrict__ wdw,
                                                         float q_alpha) {
   __shared__ float wmax[4];
   const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -114,7 +114,11 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
   LanePos<D> p;
   int row0, col0;
   const bool active = locate<D, V>(m, g, unit, p, row0, col0);
-  const int c0 = grp * Cg, c1 = min(C, c0 + Cg);
+  // the channels of a group: Cg consecutive ones (cstep = 1), or every cstep-th one from grp
+  // (cstep = the number of groups)
+  const int c0 = cstep == 1 ? grp * Cg : grp;
+  const int n_ch = c0 >= C ? 0 : (cstep == 1 ? min(C, c0 + Cg) - c0 : (C - c0 + cstep - 1) / cstep);
+  const int64_t kstep = (int64_t)cstep * k;
 
   using Sink = KeepSink<D, V, Q8>;
   Sink sink(Q8 ? q_alpha : 0.f);
@@ -153,10 +157,10 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
     sk.vmax = 0.f;
     sk.aim(plane, k);
     if constexpr (DWM == 0) {
-      channel_loop<D, V, PF, NT>(src, g.N, g.W, c1 - c0, p, sk, next_channel);
+      channel_loop<D, V, PF, NT>(src, g.N * cstep, g.W, n_ch, p, sk, next_channel);
     } else {
       const DwLane q = dw_lane<D, V>(g, m, p, row0, col0);
-      channel_loop_dw<D, V, DWM == 2, true, false>(src, wdw + (size_t)c0 * 9, g.N, c1 - c0, q, p, sk,
+      channel_loop_dw<D, V, DWM == 2, true, false>(src, wdw + (size_t)c0 * 9, g.N, n_ch, q, p, sk,
                                                    next_channel);
     }
     return sk.vmax;
@@ -179,7 +183,7 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
     for (int s = 0; s < NS; ++s) count += __popcll(__ballot((int)sink.at[s] >= 0));
     const int ni = (count + kWave - 1) / kWave;
     const bool whole = __ballot(active) == ~(uint64_t)0;  // (a ragged wave takes the plain path)
-    if (whole && c0 < c1 && ni <= NS / 2 && ni <= 16 && k <= ((int64_t)1 << kRankBits)) {
+    if (whole && n_ch > 0 && ni <= NS / 2 && ni <= 16 && k <= ((int64_t)1 << kRankBits)) {
       const int lane = threadIdx.x & (kWave - 1);
       uint32_t *tile = tiles[threadIdx.x >> 6];
       // pack (rank, tile index): slot-major, then lane (a band row's kept positions have
@@ -208,9 +212,9 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
           st.at[i] = e < count ? (packed & ((1u << kRankBits) - 1u)) * (uint32_t)sizeof(Out) : Sink::kDropped;
         }
         wave_lds_fence();
-        mx = walk(st, [&plane, k](auto &sk) {
+        mx = walk(st, [&plane, k, kstep](auto &sk) {
           sk.flush();
-          plane += k;
+          plane += kstep;
           sk.aim(plane, k);
         });
       };
@@ -220,12 +224,12 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
       done = true;
     }
   }
-  if (!done && active && c0 < c1) {
+  if (!done && active && n_ch > 0) {
 #pragma unroll
     for (int s = 0; s < NS; ++s)
       sink.at[s] = (int)sink.at[s] >= 0 ? sink.at[s] * (uint32_t)sizeof(Out) : Sink::kDropped;
-    mx = walk(sink, [&plane, k](Sink &sk) {
-      plane += k;
+    mx = walk(sink, [&plane, k, kstep](Sink &sk) {
+      plane += kstep;
       sk.aim(plane, k);
     });
   }
@@ -251,16 +255,21 @@ hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_in + pl.G - 1) / pl.G;
+  // Without K_dw in front, group g takes the channels g, g + G, ...: groups running side by
+  // side then read neighbouring planes of x and write neighbouring planes of xc (keep pass of
+  // workloads 2 and 4 and the stack 2 % faster).  The folded walk indexes its 3x3 weights by
+  // consecutive channels and keeps the blocks.
+  const int cstep = wdw == nullptr ? pl.G : 1;
   dim3 grid((m.units + 3) / 4, pl.G, d.B);
   const bool q8 = q_alpha > 0.f;
 #define WCC_KEEP(PF, DWM)                                                                          \
   do {                                                                                             \
     if (q8)                                                                                        \
       hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, true, XT>), grid, dim3(256), 0, s, x,   \
-                         jmap, xc, nullptr, g, m, d.C_in, Cg, k, wdw, q_alpha);                    \
+                         jmap, xc, nullptr, g, m, d.C_in, Cg, cstep, k, wdw, q_alpha);                    \
     else                                                                                           \
       hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, false, XT>), grid, dim3(256), 0, s, x,  \
-                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, k, wdw, 0.f);                    \
+                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, cstep, k, wdw, 0.f);                    \
   } while (0)
   if constexpr (V == 4) {
     if (wdw != nullptr) {  // K_dw in front of the transform
@@ -272,10 +281,10 @@ hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_
   if (pl.stream) {
     if (q8)
       hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0, true, XT, true>), grid, dim3(256), 0, s, x,
-                         jmap, xc, nullptr, g, m, d.C_in, Cg, k, wdw, q_alpha);
+                         jmap, xc, nullptr, g, m, d.C_in, Cg, cstep, k, wdw, q_alpha);
     else
       hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0, false, XT, true>), grid, dim3(256), 0, s, x,
-                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, k, wdw, 0.f);
+                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, cstep, k, wdw, 0.f);
     return hipGetLastError();
   }
   WCC_KEEP(1, 0);

@@ -42,7 +42,8 @@ def stats(path: str) -> str:
 
 
 def _is_copy(kernel: str) -> bool:
-    return "copy" in kernel.lower()
+    """The runtime's device-to-device copy kernel (what torch's copy_ launches)."""
+    return "copyBuffer" in kernel
 
 
 def _mean_counter(path: str, counter: str):
