@@ -175,7 +175,10 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
   __shared__ uint32_t tiles[kStaged ? 4 : 1][kStaged ? NS * kWave : 1];
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int unit = blockIdx.x * 4 + wv;
-  const int grp = blockIdx.y, b = blockIdx.z;
+  // Samples are taken last to first: the contraction wrote yc first to last, so what is still
+  // in the memory-side cache when this kernel starts is the tail, and it is read before the
+  // rest of the reads push it out.
+  const int grp = blockIdx.y, b = gridDim.z - 1 - blockIdx.z;
   LanePos<D> p;
   int row0, col0;
   const bool active = locate<D, V>(m, g, unit, p, row0, col0);
