@@ -44,7 +44,7 @@ __device__ __forceinline__ void hist_add(uint32_t *lh, uint32_t digit, bool vali
   for (int round = 0; round < 2; ++round) {
     if (todo == 0) break;
     const int leader = __ffsll((unsigned long long)todo) - 1;
-    const uint32_t d0 = __shfl(digit, leader, 64);
+    const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);  // leader is wave-uniform
     const uint64_t same = __ballot(valid && digit == d0);
     if (lane == leader) atomicAdd(&lh[d0], (uint32_t)__popcll(same));
     if (digit == d0) valid = false;
@@ -65,11 +65,41 @@ __device__ __forceinline__ void hist_add_spread(uint32_t *lh, uint32_t digit, bo
   }
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave (all of them active), on the data-parallel
+// shifts of the vector unit instead of six round trips through the LDS crossbar: shifts by
+// 1, 2, 4, 8 inside rows of 16 lanes (a lane shifted in from outside its row adds 0), then lane
+// 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
+  uint32_t v = x;
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31
+  return v;
+}
+
+// Smallest / largest value over the 64 lanes (all active), every lane gets it: the moves of the
+// scan with the operation's identity shifted in; lane 63 ends up with the whole wave's result.
+template <bool MAX>
+__device__ __forceinline__ uint32_t wave_extreme(uint32_t x) {
+  constexpr int id = MAX ? 0 : -1;
+  uint32_t v = x;
+  auto join = [](uint32_t a, uint32_t b) { return MAX ? max(a, b) : min(a, b); };
+  v = join(v, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)v, 0x111, 0xf, 0xf, false));
+  v = join(v, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)v, 0x112, 0xf, 0xf, false));
+  v = join(v, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)v, 0x114, 0xf, 0xf, false));
+  v = join(v, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)v, 0x118, 0xf, 0xf, false));
+  v = join(v, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)v, 0x142, 0xa, 0xf, false));
+  v = join(v, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)v, 0x143, 0xc, 0xf, false));
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 // block-wide sum of v (all threads get it); `tmp` has NW (waves per workgroup) entries
 template <int NW = kWaves>
 __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *tmp) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  v = (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_scan(v), 63);
   __syncthreads();  // tmp may still be read from a previous use
   if ((threadIdx.x & 63) == 0) tmp[threadIdx.x >> 6] = v;
   __syncthreads();
@@ -83,12 +113,7 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *tmp) {
 template <int NW = kWaves>
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *tmp) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  uint32_t inc = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t n = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += n;
-  }
+  const uint32_t inc = wave_inclusive_scan(v);
   __syncthreads();
   if (lane == 63) tmp[wv] = inc;
   __syncthreads();
@@ -393,11 +418,8 @@ __global__ __launch_bounds__(kSmallThreads) void select_small_kernel(
     rel[4 * s] = k4.x; rel[4 * s + 1] = k4.y; rel[4 * s + 2] = k4.z; rel[4 * s + 3] = k4.w;
   }
   // smallest and largest key of the sample
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, 64));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, 64));
-  }
+  kmin = wave_extreme<false>(kmin);
+  kmax = wave_extreme<true>(kmax);
   if (lane == 0) { tmp[wv] = kmin; tmp[kSmallWaves + wv] = kmax; }
   __syncthreads();
 #pragma unroll
@@ -427,13 +449,7 @@ __global__ __launch_bounds__(kSmallThreads) void select_small_kernel(
       for (int e = 0; e < 4; ++e) packed += ((rel[4 * s + e] > T) << 16) + (rel[4 * s + e] == T);
     }
     uint32_t inc = packed;
-    if (s < slots) {
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t n = __shfl_up(inc, off, 64);
-        if (lane >= off) inc += n;
-      }
-    }
+    if (s < slots) inc = wave_inclusive_scan(packed);  // (uniform over the workgroup)
     ex[s] = inc - packed;
     if (lane == 63) tmp[s * kSmallWaves + wv] = inc;
   }
@@ -441,13 +457,7 @@ __global__ __launch_bounds__(kSmallThreads) void select_small_kernel(
   static_assert(kSmallSlots * kSmallWaves == 64, "one wave scans the totals");
   if (t < 64) {  // wave 0: exclusive scan of the 64 totals
     const uint32_t v = tmp[t];
-    uint32_t inc = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t n = __shfl_up(inc, off, 64);
-      if (lane >= off) inc += n;
-    }
-    tmp[t] = inc - v;
+    tmp[t] = wave_inclusive_scan(v) - v;
   }
   __syncthreads();
 
