@@ -227,13 +227,14 @@ __global__ __launch_bounds__(kThreads) void select_hist_kernel(const float *__re
   uint32_t *gh = hist_b + (size_t)PASS * kRadixBins;
 
   for (int i = t; i < bins; i += kThreads) lh[i] = 0;
-  uint32_t prefix, remain;
-  current_state<PASS>(hist_b, st + b, k, prefix, remain, tmp, bcast, blockIdx.x == 0);
-  __syncthreads();
+  // the keys do not depend on the digit picked below: their load travels under it
   const int64_t q0 = (int64_t)blockIdx.x * kSelectChunk + (int64_t)t * kPer;
   const bool in = q0 < N;  // N is a multiple of 4: a thread's four keys are all in or all out
   uint4 k4 = make_uint4(0, 0, 0, 0);
   if (in) k4 = load_keys<REDUCE>(src, norm, G, (int64_t)B * N, (int64_t)b * N + q0);
+  uint32_t prefix, remain;
+  current_state<PASS>(hist_b, st + b, k, prefix, remain, tmp, bcast, blockIdx.x == 0);
+  __syncthreads();
   const uint32_t key[4] = {k4.x, k4.y, k4.z, k4.w};
   uint32_t above = 0;
 #pragma unroll
@@ -281,6 +282,11 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__re
   __shared__ uint32_t bcast[2];
   const int b = blockIdx.y, t = threadIdx.x;
   const uint32_t *keys = reinterpret_cast<const uint32_t *>(norm) + (size_t)b * N;
+  // (the keys do not depend on the threshold: their load travels under its computation)
+  const int64_t q0 = (int64_t)blockIdx.x * kSelectChunk + (int64_t)t * kPer;
+  const bool in = q0 < N;
+  uint4 k4 = make_uint4(0, 0, 0, 0);
+  if (in) k4 = *reinterpret_cast<const uint4 *>(keys + q0);
   uint32_t T, r_take;  // threshold key, and how many keys equal to it are still needed
   current_state<3>(hist + (size_t)b * 3 * kRadixBins, st + b, (uint32_t)k, T, r_take, tmp, bcast,
                    blockIdx.x == 0);
@@ -298,10 +304,6 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__re
   gt0 = block_sum(gt0, tmp);
   eq0 = block_sum(eq0, tmp);
 
-  const int64_t q0 = (int64_t)blockIdx.x * kSelectChunk + (int64_t)t * kPer;
-  const bool in = q0 < N;
-  uint4 k4 = make_uint4(0, 0, 0, 0);
-  if (in) k4 = *reinterpret_cast<const uint4 *>(keys + q0);
   const uint32_t key[4] = {k4.x, k4.y, k4.z, k4.w};
   uint32_t packed = 0;  // hi16: keys above T, lo16: keys equal to T (each <= 1024 a workgroup)
 #pragma unroll
