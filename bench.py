@@ -78,6 +78,15 @@ def stream_ceilings(ctx, wcc, torch, nbytes: int = 512 << 20, reps: int = 4) -> 
                 t1.synchronize()
                 best = max(best, moved * nbytes * reps / (t0.elapsed_time(t1) * 1e-3) / 1e9)
             out[name + ("_nt" if nt else "")] = round(best, 1)
+    for nt in (False, True):  # the same fill with eight stores a thread (what a strip kernel's waves do)
+        ctx.wcc_probe_stream(wcc.PROBE_WRITE8, None, b, nbytes, nt)
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for _ in range(reps):
+            ctx.wcc_probe_stream(wcc.PROBE_WRITE8, None, b, nbytes, nt)
+        t1.record()
+        t1.synchronize()
+        out["write8" + ("_nt" if nt else "")] = round(nbytes * reps / (t0.elapsed_time(t1) * 1e-3) / 1e9, 1)
     return out
 
 

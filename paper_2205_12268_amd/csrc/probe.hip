@@ -41,6 +41,20 @@ __global__ __launch_bounds__(256) void probe_write_kernel(vf4 *__restrict__ dst,
     probe_store<NT>(dst + i, v);
 }
 
+// The same fill with eight stores a thread: a workgroup writes 32 KiB in a row, every store
+// instruction of it 4 KiB (what a kernel does whose waves own several rows of a tile; the rate
+// drops with the stores per thread although the bytes and their order in memory are the same).
+template <bool NT>
+__global__ __launch_bounds__(256) void probe_write8_kernel(vf4 *__restrict__ dst, size_t n) {
+  const size_t first = (size_t)blockIdx.x * (256 * 8) + threadIdx.x;
+  const vf4 v = {1.f, 2.f, 3.f, 4.f};
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const size_t i = first + (size_t)r * 256;
+    if (i < n) probe_store<NT>(dst + i, v);
+  }
+}
+
 template <bool NT>
 __global__ __launch_bounds__(256) void probe_copy_kernel(const vf4 *__restrict__ src,
                                                          vf4 *__restrict__ dst, size_t n) {
@@ -70,6 +84,12 @@ hipError_t launch_probe(int kind, const void *src, void *dst, size_t bytes, bool
       if (nt) hipLaunchKernelGGL(probe_copy_kernel<true>, grid, block, 0, s, in, out, n);
       else hipLaunchKernelGGL(probe_copy_kernel<false>, grid, block, 0, s, in, out, n);
       break;
+    case WCC_PROBE_WRITE8: {
+      const dim3 g8((unsigned)((n + 2047) / 2048));
+      if (nt) hipLaunchKernelGGL(probe_write8_kernel<true>, g8, block, 0, s, out, n);
+      else hipLaunchKernelGGL(probe_write8_kernel<false>, g8, block, 0, s, out, n);
+      break;
+    }
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

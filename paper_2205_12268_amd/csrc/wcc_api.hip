@@ -269,8 +269,9 @@ int64_t wcc_k(const wcc_desc *desc) {
 
 wcc_status wcc_probe_stream(wcc_ctx *ctx, int kind, const void *src, void *dst, size_t bytes,
                             int nontemporal, int blocks, void *stream) {
-  if (!ctx || !dst || (kind != WCC_PROBE_WRITE && !src)) return WCC_ERR_NULL;
-  if (kind != WCC_PROBE_READ && kind != WCC_PROBE_WRITE && kind != WCC_PROBE_COPY) return WCC_ERR_DTYPE;
+  if (kind < WCC_PROBE_READ || kind > WCC_PROBE_WRITE8) return WCC_ERR_DTYPE;
+  const bool writes_only = kind == WCC_PROBE_WRITE || kind == WCC_PROBE_WRITE8;
+  if (!ctx || !dst || (!writes_only && !src)) return WCC_ERR_NULL;
   if (bytes == 0 || bytes % 16 != 0 || blocks < 0 || blocks > (1 << 24)) return WCC_ERR_SHAPE;
   return wcc::launch_probe(kind, src, dst, bytes, nontemporal != 0, blocks, static_cast<hipStream_t>(stream)) == hipSuccess
              ? WCC_OK : WCC_ERR_HIP;

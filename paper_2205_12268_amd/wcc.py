@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libwcc.so")
 
 F32, BF16, I8, I4 = 0, 1, 2, 3
 NORM_L1, NORM_L2 = 0, 1
-PROBE_READ, PROBE_WRITE, PROBE_COPY = 0, 1, 2
+PROBE_READ, PROBE_WRITE, PROBE_COPY, PROBE_WRITE8 = 0, 1, 2, 3
 STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "event_pair",
           "depthwise")
 

@@ -26,6 +26,9 @@ def test_probe_kernels_move_what_they_say(nt):
     want = torch.tensor([1.0, 2.0, 3.0, 4.0], device="cuda").repeat(n // 4)
     assert torch.equal(dst[:n], want) and bool((dst[n:] == -1.0).all())
     dst.fill_(-1.0)
+    ctx.wcc_probe_stream(wcc.PROBE_WRITE8, None, dst, n * 4, nt)
+    assert torch.equal(dst[:n], want) and bool((dst[n:] == -1.0).all())
+    dst.fill_(-1.0)
     ctx.wcc_probe_stream(wcc.PROBE_READ, src, dst, n * 4, nt)
     torch.cuda.synchronize()
     assert torch.equal(src, keep) and bool((dst == -1.0).all())
@@ -37,7 +40,7 @@ def test_probe_errors():
     a = torch.zeros(64, device="cuda")
     b = torch.zeros(64, device="cuda")
     for args, status in (((wcc.PROBE_COPY, None, b, 256), 1), ((wcc.PROBE_COPY, a, None, 256), 1),
-                         ((wcc.PROBE_READ, None, b, 256), 1), ((7, a, b, 256), 3),
+                         ((wcc.PROBE_READ, None, b, 256), 1), ((7, a, b, 256), 3), ((-1, a, b, 256), 3),
                          ((wcc.PROBE_COPY, a, b, 0), 2), ((wcc.PROBE_COPY, a, b, 100), 2),
                          ((wcc.PROBE_COPY, a, b, 256, False, -1), 2)):
         with pytest.raises(wcc.WccError) as e:
