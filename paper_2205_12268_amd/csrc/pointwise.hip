@@ -284,7 +284,10 @@ hipError_t mfma_dispatch(const wcc_desc &d, int64_t k, const void *w, const floa
   };
   if (d.C_out > 128 && wgs(256, 128) >= want) WCC_MFMA(256, 128, 1);
   if (d.C_out <= 128 && wgs(128, 128) >= want) WCC_MFMA(128, 128, 1);
-  if (d.C_out > 64 && wgs(128, 64) >= want) WCC_MFMA(128, 64, 1);
+  // (a quarter of the chip is enough for the 128-row tile: on the short signals of deep layers
+  // the smaller tile quantises and stages every activation once more per extra row tile, which
+  // costs more than the idle units: 960 -> 320 channels at k = 512, 19.5 -> 17.2 us)
+  if (d.C_out > 64 && wgs(128, 64) >= want / 4) WCC_MFMA(128, 64, 1);
   WCC_MFMA(64, 64, 1);
 #undef WCC_MFMA
 }
