@@ -15,7 +15,7 @@ import pytest
 import torch
 
 from paper_2205_12268_amd import synth, wcc
-from tests.util import dev, oracle_scale, rel_l2, upload_weights
+from tests.util import assert_valid_index_set, layer_with_index_set, dev, oracle_scale, rel_l2, upload_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -59,22 +59,6 @@ CASES = [
 ]
 
 
-def layer_with_index_set(ref, lcfg, w, x64, idx):
-    """Alg. 1 on x64 with the index set given (steps after the selection)."""
-    N = lcfg.N
-    coef = ref.haar_fwd(x64, lcfg.levels).reshape(lcfg.B, lcfg.C_in, N)
-    norm = ref.channel_norm(coef)
-    xc = ref.gather(coef, idx)
-    if lcfg.act_bits:
-        alpha = float(np.float32(ref.absmax(xc)))
-        xhat = ref.quant_codes(xc, alpha, lcfg.act_bits)
-    else:
-        alpha, xhat = 0.0, xc
-    yc = ref.pointwise(w.values, oracle_scale(ref, lcfg, w, alpha), xhat)
-    y = ref.haar_inv(ref.scatter(yc, idx, N), lcfg.H, lcfg.W, lcfg.levels)
-    return y, norm
-
-
 @pytest.mark.parametrize("cfg", CASES, ids=lambda c: c.name)
 def test_block_stage_by_stage_and_end_to_end(ref, ctx, cfg):
     x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
@@ -116,23 +100,22 @@ def test_block_stage_by_stage_and_end_to_end(ref, ctx, cfg):
     g_idx3 = idx3.cpu().numpy().astype(np.int64)
     want_branch, norm = layer_with_index_set(ref, l1, w3, g_t2.astype(np.float64), g_idx3)
     for b in range(cfg.B):
-        sel = g_idx3[b]
-        assert np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] < cfg.N
-        kth = np.sort(norm[b])[::-1][cfg.k - 1]
-        dropped = np.ones(cfg.N, dtype=bool)
-        dropped[sel] = False
-        assert norm[b][sel].min() >= kth * (1 - 1e-5)
-        if dropped.any():
-            assert norm[b][dropped].max() <= kth * (1 + 1e-5)
+        assert_valid_index_set(norm[b], g_idx3[b], cfg.k)
     g_branch = y.cpu().numpy().astype(np.float64) - x.astype(np.float64)
     assert rel_l2(g_branch, want_branch) <= tol
 
-    # end to end against the independent oracle chain (its own index sets throughout)
-    o_y = ref.block_forward(x, w1.values, w1.scale, w_dw, w3.values, w3.scale, cfg.levels,
-                            cfg.keep_num, cfg.keep_den, cfg.act_bits)[0]
-    err = rel_l2(g_branch, o_y - x)
-    print(f"{cfg.name}: end-to-end rel-L2 of the branch = {err:.3e}", flush=True)
-    assert err <= (1e-4 if tol == 1e-5 else 3e-2)
+    # End to end against the independent oracle chain (its own index sets throughout).  Where
+    # the two second-layer sets agree the chain is held to the same bar; where fp32 and fp64
+    # norms order two nearly equal positions differently both sets are correct, the outputs
+    # belong to different sets, and the figure is printed only.
+    o = ref.block_forward(x, w1.values, w1.scale, w_dw, w3.values, w3.scale, cfg.levels,
+                          cfg.keep_num, cfg.keep_den, cfg.act_bits)
+    err = rel_l2(g_branch, o[0] - x)
+    same = np.array_equal(g_idx3, o[4])
+    print(f"{cfg.name}: end-to-end rel-L2 of the branch = {err:.3e} (second index set "
+          f"{'equal' if same else 'differs'})", flush=True)
+    if same:
+        assert err <= tol
 
 
 def test_block_error_paths(ctx):
@@ -158,3 +141,27 @@ def test_block_error_paths(ctx):
     with pytest.raises(wcc.WccError) as e:
         ctx.wcc_block_forward(i8, x, w, None, wd, w, None, y)
     assert e.value.status == 1  # int8 weights need their scales
+
+
+@pytest.mark.parametrize("width,want_t2", [(16, True), (18, False)])
+def test_block_refusal_enqueues_nothing(ctx, width, want_t2):
+    """bf16 feature maps need K_dw folded into the transform (W % 4 == 0, no K_dw output asked
+    for).  The refusal comes with the other argument checks: no kernel has run, so the output,
+    the caller's middle tensor and the workspace are as they were."""
+    d = wcc.make_block_desc(1, 8, 2, 16, width, 1, 1, 4, wcc.BF16, 8, wcc.BF16)
+    need = ctx.ensure_workspace(d)
+    x = torch.ones((1, 8, 16, width), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((16, 8), dtype=torch.int16, device="cuda")
+    wd = torch.zeros((16, 3, 3), device="cuda")
+    y = torch.full_like(x, 5.0)
+    t1 = torch.full((1, 16, 16, width), 7.0, dtype=torch.bfloat16, device="cuda")
+    t2 = torch.full((1, 16, 16, width), 9.0, dtype=torch.float32, device="cuda") if want_t2 else None
+    ctx._ws.fill_(0x5A)
+    torch.cuda.synchronize()
+    with pytest.raises(wcc.WccError) as e:
+        ctx.wcc_block_forward(d, x, w, None, wd, w, None, y, t1, t2)
+    assert e.value.status == 6  # WCC_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((y == 5.0).all()) and bool((t1 == 7.0).all())
+    assert t2 is None or bool((t2 == 9.0).all())
+    assert bool((ctx._ws[:need] == 0x5A).all())

@@ -1,8 +1,8 @@
 """The single-layer workloads at their full sizes, in the launch configuration bench.py times.
 
 The oracle runs the cheap stages in full (transform, norms, selection, gather, quantiser,
-contraction) so index sets and alpha are compared exactly; the last stage (zero filling +
-inverse transform) is evaluated by the oracle on sampled (sample, channel) planes.
+contraction) so index sets and alpha are compared exactly, and the last stage (zero filling +
+inverse transform) plane by plane in chunks, so the whole output is compared element by element.
 """
 import numpy as np
 import pytest
@@ -96,20 +96,33 @@ def test_full_size_forward(ref, n, norm):
     del xc
     yc = ref.pointwise(w.values, oracle_scale(ref, cfg, w, o_alpha), xhat)
     del xhat
-    print("  oracle: inverse on sampled planes", flush=True)
-    rng = np.random.default_rng(n)
-    planes = {(0, 0), (cfg.B - 1, cfg.C_out - 1)}
-    while len(planes) < 6:
-        planes.add((int(rng.integers(cfg.B)), int(rng.integers(cfg.C_out))))
+    print("  oracle: zero filling + inverse transform of every plane", flush=True)
+    # all B * C_out planes, a few hundred at a time (the oracle's fp64 planes of one chunk take
+    # about 1 GB): the relative L2 error of the whole output, and of the worst single plane
     tol = tol_for(cfg)
+    chunk = max(1, min(cfg.C_out, (64 << 20) // N))
+    num = den = 0.0
     worst = 0.0
-    for (b, o) in sorted(planes):
-        z = ref.scatter(yc[b:b + 1, o:o + 1], o_idx[b:b + 1], N)
-        want = ref.haar_inv(z, cfg.H, cfg.W, cfg.levels)[0, 0]
-        err = rel_l2(y[b, o].cpu().numpy(), want)
-        worst = max(worst, err)
-        assert err <= tol, (b, o, err)
-    print(f"  worst plane rel-L2 = {worst:.3e} (tol {tol:g})", flush=True)
+    for b in range(cfg.B):
+        for o0 in range(0, cfg.C_out, chunk):
+            o1 = min(cfg.C_out, o0 + chunk)
+            z = ref.scatter(yc[b:b + 1, o0:o1], o_idx[b:b + 1], N)
+            want = ref.haar_inv(z, cfg.H, cfg.W, cfg.levels)[0]
+            del z
+            diff = y[b, o0:o1].cpu().numpy().astype(np.float64) - want
+            e2 = np.einsum("chw,chw->c", diff, diff)
+            w2 = np.einsum("chw,chw->c", want, want)
+            del diff, want
+            num += float(e2.sum())
+            den += float(w2.sum())
+            ok = w2 > 0
+            if ok.any():
+                worst = max(worst, float(np.sqrt(e2[ok] / w2[ok]).max()))
+            assert np.all(e2[~ok] == 0.0)
+        print(f"    sample {b}: done", flush=True)
+    err = float(np.sqrt(num / den))
+    print(f"  whole-output rel-L2 = {err:.3e}, worst plane {worst:.3e} (tol {tol:g})", flush=True)
+    assert err <= tol and worst <= tol
     # a property that holds at any size: Parseval, ||y[b,o]||_2 == ||yc[b,o,:]||_2
     en_gpu = torch.linalg.vector_norm(y.double(), dim=(2, 3)).cpu().numpy()
     en_ref = np.linalg.norm(yc, axis=2)
@@ -248,10 +261,11 @@ def test_full_size_block(ref, act):
     print(f"  sample 0 branch rel-L2 = {err:.3e}", flush=True)
     if bf16:
         # y = x + branch is rounded to 8 significant bits as a whole: the tolerance applies to
-        # y; the branch alone, smaller than x, carries that rounding several times enlarged
+        # y, the block's output; the branch alone, smaller than x, carries that rounding several
+        # times enlarged and is printed above for information
         err_y = rel_l2(y[0].float().cpu().numpy(), x[0].astype(np.float64) + want)
         print(f"  sample 0 output rel-L2 = {err_y:.3e}", flush=True)
-        assert err_y <= 1e-2 and err <= 5e-2
+        assert err_y <= 1e-2
     else:
         assert err <= 1e-2
     ctx.close()

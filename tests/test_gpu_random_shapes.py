@@ -10,7 +10,7 @@ import pytest
 import torch
 
 from paper_2205_12268_amd import synth, wcc
-from tests.util import desc_of, dev, rel_l2, tol_for, upload_weights
+from tests.util import assert_valid_index_set, layer_with_index_set, desc_of, dev, rel_l2, tol_for, upload_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -119,9 +119,13 @@ def draw_block(seed: int) -> synth.BlockCfg:
 
 @pytest.mark.parametrize("seed", range(12))
 def test_random_block(ref, ctx, seed):
-    """x + WCC(K3, K_dw(WCC(K1, x))) end to end against the independent oracle chain.  The
-    second layer's index set may legitimately differ where two fp64 norms are within rounding of
-    each other (its input is not dyadic), so the bar is the output tolerance."""
+    """x + WCC(K3, K_dw(WCC(K1, x))) on a random block.  The first layer sees dyadic inputs: its
+    index set is the oracle's, bit for bit, and its output is within the tolerance.  The second
+    layer's input is not dyadic, so fp32 and fp64 norms may order two nearly equal positions
+    differently and several index sets are correct: the GPU's set is checked for validity
+    against the oracle's fp64 norms of the GPU's own K_dw output, and the block's output is
+    held to the tolerance against the oracle run on that set.  The independent oracle chain
+    (its own sets throughout) is printed as a diagnostic and asserted where the sets agree."""
     cfg = draw_block(seed)
     print(f"{cfg}", flush=True)
     x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
@@ -130,13 +134,35 @@ def test_random_block(ref, ctx, seed):
     ctx.ensure_workspace(d)
     w1d, w1s = upload_weights(w1)
     w3d, w3s = upload_weights(w3)
+    mid = (cfg.B, cfg.C_mid, cfg.H, cfg.W)
     y = torch.full(x.shape, float("nan"), dtype=torch.float32, device="cuda")
+    t1 = torch.full(mid, float("nan"), dtype=torch.float32, device="cuda")
+    t2 = torch.full(mid, float("nan"), dtype=torch.float32, device="cuda")
     idx1 = torch.empty((cfg.B, cfg.k), dtype=torch.int32, device="cuda")
-    ctx.wcc_block_forward(d, dev(x), w1d, w1s, dev(w_dw), w3d, w3s, y, None, None, idx1, None)
+    idx3 = torch.empty((cfg.B, cfg.k), dtype=torch.int32, device="cuda")
+    ctx.wcc_block_forward(d, dev(x), w1d, w1s, dev(w_dw), w3d, w3s, y, t1, t2, idx1, idx3)
+    # the same block without the test outputs (K_dw folded into the transform where W % 4 == 0)
+    y_plain = torch.full_like(y, float("nan"))
+    ctx.wcc_block_forward(d, dev(x), w1d, w1s, dev(w_dw), w3d, w3s, y_plain)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_plain)
+    tol = 1e-5 if (cfg.w_dtype == synth.W_F32 and cfg.act_bits == 0) else 1e-2
     o = ref.block_forward(x, w1.values, w1.scale, w_dw, w3.values, w3.scale, cfg.levels,
                           cfg.keep_num, cfg.keep_den, cfg.act_bits)
     np.testing.assert_array_equal(idx1.cpu().numpy().astype(np.int64), o[3])
+    g_t1, g_t2 = t1.cpu().numpy(), t2.cpu().numpy()
+    assert rel_l2(g_t1, o[1]) <= tol
+    assert rel_l2(g_t2, ref.depthwise3x3(g_t1, w_dw)) <= 1e-6
+    g_idx3 = idx3.cpu().numpy().astype(np.int64)
+    want_branch, norm = layer_with_index_set(ref, cfg.layer(1), w3, g_t2.astype(np.float64), g_idx3)
+    for b in range(cfg.B):
+        assert_valid_index_set(norm[b], g_idx3[b], cfg.k)
     got = y.cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all()
-    tol = 1e-4 if cfg.w_dtype == synth.W_F32 else 3e-2
-    assert rel_l2(got - x, o[0] - x) <= tol
+    assert rel_l2(got - x, want_branch) <= tol
+    err = rel_l2(got - x, o[0] - x)
+    same = np.array_equal(g_idx3, o[4])
+    print(f"  end-to-end rel-L2 of the branch = {err:.3e} (second index set "
+          f"{'equal' if same else 'differs'})", flush=True)
+    if same:
+        assert err <= tol

@@ -39,3 +39,34 @@ def oracle_scale(ref, cfg, w, alpha):
     sx = alpha / 127.0 if cfg.act_bits else 1.0
     sw = np.ones(cfg.C_out) if w.scale is None else w.scale.astype(np.float64)
     return sx * sw
+
+
+def layer_with_index_set(ref, lcfg, w, x64, idx):
+    """Alg. 1 on x64 with the index set given (the oracle's steps after the selection).
+    Returns (y, channel norms of the wavelet vectors)."""
+    N = lcfg.N
+    coef = ref.haar_fwd(x64, lcfg.levels).reshape(lcfg.B, lcfg.C_in, N)
+    norm = ref.channel_norm(coef)
+    xc = ref.gather(coef, idx)
+    if lcfg.act_bits:
+        alpha = float(np.float32(ref.absmax(xc)))
+        xhat = ref.quant_codes(xc, alpha, lcfg.act_bits)
+    else:
+        alpha, xhat = 0.0, xc
+    yc = ref.pointwise(w.values, oracle_scale(ref, lcfg, w, alpha), xhat)
+    y = ref.haar_inv(ref.scatter(yc, idx, N), lcfg.H, lcfg.W, lcfg.levels)
+    return y, norm
+
+
+def assert_valid_index_set(norm_b, sel, k, rel=1e-5):
+    """sel is a correct answer to "the k positions with the largest norm" for norms known to a
+    relative accuracy of `rel`: strictly ascending, inside the plane, every kept norm at least
+    the k-th largest and every dropped norm at most it."""
+    N = norm_b.shape[0]
+    assert sel.shape == (k,) and np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] < N
+    kth = np.sort(norm_b)[::-1][k - 1]
+    dropped = np.ones(N, dtype=bool)
+    dropped[sel] = False
+    assert norm_b[sel].min() >= kth * (1 - rel)
+    if dropped.any():
+        assert norm_b[dropped].max() <= kth * (1 + rel)
