@@ -56,34 +56,34 @@ def read_traffic(profile_dir: str, workload: str, kernel: str):
     return None
 
 
-def stream_ceilings(ctx, wcc, torch, nbytes: int = 512 << 20, reps: int = 4) -> dict:
-    """GB/s of the library's plain streaming kernels (read, write, copy; ordinary and
+def stream_ceilings(probe, torch, nbytes: int = 512 << 20, reps: int = 4) -> dict:
+    """GB/s of the plain streaming kernels of libwcc_probe.so (read, write, copy; ordinary and
     non-temporal accesses) over buffers of `nbytes`, twice the memory-side cache, each at four
     grid sizes with the best one reported: what this machine's memory system gives to the simplest
     code, for placing the stage rates above."""
     a = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").fill_(1.0)
     b = torch.empty_like(a)
     out = {"bytes": nbytes}
-    for name, kind, moved in (("read", wcc.PROBE_READ, 1), ("write", wcc.PROBE_WRITE, 1),
-                              ("copy", wcc.PROBE_COPY, 2)):
+    for name, kind, moved in (("read", probe.READ, 1), ("write", probe.WRITE, 1),
+                              ("copy", probe.COPY, 2)):
         for nt in (False, True):
             best = 0.0
             for blocks in (2048, 8192, 32768, 131072):
-                ctx.wcc_probe_stream(kind, a, b, nbytes, nt, blocks)
+                probe.wcc_probe_stream(kind, a, b, nbytes, nt, blocks)
                 t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 t0.record()
                 for _ in range(reps):
-                    ctx.wcc_probe_stream(kind, a, b, nbytes, nt, blocks)
+                    probe.wcc_probe_stream(kind, a, b, nbytes, nt, blocks)
                 t1.record()
                 t1.synchronize()
                 best = max(best, moved * nbytes * reps / (t0.elapsed_time(t1) * 1e-3) / 1e9)
             out[name + ("_nt" if nt else "")] = round(best, 1)
     for nt in (False, True):  # the same fill with eight stores a thread (what a strip kernel's waves do)
-        ctx.wcc_probe_stream(wcc.PROBE_WRITE8, None, b, nbytes, nt)
+        probe.wcc_probe_stream(probe.WRITE8, None, b, nbytes, nt)
         t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0.record()
         for _ in range(reps):
-            ctx.wcc_probe_stream(wcc.PROBE_WRITE8, None, b, nbytes, nt)
+            probe.wcc_probe_stream(probe.WRITE8, None, b, nbytes, nt)
         t1.record()
         t1.synchronize()
         out["write8" + ("_nt" if nt else "")] = round(nbytes * reps / (t0.elapsed_time(t1) * 1e-3) / 1e9, 1)
@@ -464,7 +464,8 @@ def main() -> int:
     }
 
     if not args.no_ceilings:
-        out["stream_ceilings_GBs"] = stream_ceilings(ctx, wcc, torch)
+        from paper_2205_12268_amd import probe
+        out["stream_ceilings_GBs"] = stream_ceilings(probe, torch)
     if args.cold_input:
         out["cold_input_ms_per_step"] = round(run_layer.cold_ms, 5)
     if not args.no_cpu_baseline:

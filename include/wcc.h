@@ -249,22 +249,6 @@ wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const voi
  * profiling is on (default 1). */
 wcc_status wcc_set_block_profile_layer(wcc_ctx *ctx, int layer);
 
-/* ---- measurement aid (not a step of the method) ------------------------------------------
- * One plain streaming kernel over `bytes` bytes (a multiple of 16, > 0) on `stream`: what the
- * memory system of this device gives to the simplest possible code, to be timed by the caller
- * beside the kernels above.  READ sums src [device] and writes nothing (dst [device] must still
- * point at >= 16 writable bytes); WRITE fills dst with the floats 1, 2, 3, 4 repeated; COPY
- * moves src to dst (the two must not overlap); WRITE8 is WRITE with eight stores a thread, a
- * workgroup covering 32 KiB in a row (`blocks` is ignored; bytes / 32768 + 1 workgroups at most
- * 2^31 - 1).  nontemporal != 0: the accesses carry the
- * non-temporal hint, as the transform kernels' streaming accesses do.  blocks: workgroups of
- * 256 threads that walk the buffer with a grid stride (0: 8192; at most 2^24).  Pointers
- * 16-byte aligned.  Errors: WCC_ERR_NULL, WCC_ERR_SHAPE (bytes, blocks), WCC_ERR_DTYPE (kind),
- * WCC_ERR_HIP. */
-typedef enum { WCC_PROBE_READ = 0, WCC_PROBE_WRITE = 1, WCC_PROBE_COPY = 2, WCC_PROBE_WRITE8 = 3 } wcc_probe_kind;
-wcc_status wcc_probe_stream(wcc_ctx *ctx, int kind, const void *src, void *dst, size_t bytes,
-                            int nontemporal, int blocks, void *stream);
-
 #ifdef __cplusplus
 }
 #endif

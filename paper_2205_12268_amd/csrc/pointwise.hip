@@ -10,8 +10,8 @@
 // kernel is built around the activation stream: a workgroup owns BM = 128 or 256 output rows
 // (all of C_out when it fits, so every activation is read and quantised once) and BN = 128
 // positions; each thread loads its share of a 64-channel chunk of the [C_in x BN] activation
-// tile (NPF chunks could go out together; more than one was measured at every shape and never
-// paid: it costs registers, and with them the second workgroup on the compute unit),
+// tile (several chunks going out together was measured at every shape and never paid: it costs
+// registers, and with them the second workgroup on the compute unit),
 // quantises it in registers, transposes 4(n) x CPT(c) patches into LDS, and the waves (wave w
 // owns rows 32w..32w+31 and all BN columns) run the MFMAs 64 channels at a time.  As soon as
 // a chunk's registers are in LDS the next chunk's loads (activations and weights) are issued,
@@ -84,8 +84,7 @@ struct Patch {
 
 // grid = (ceil(k/BN), ceil(M/BM), B), block = 2*BM threads.  Needs k % 4 == 0 and
 // K % 8 == 0 (bf16 weights) or K % 16 == 0 (int8 weights).
-// NPF: 64-channel chunks whose activation loads are issued together (1, 2 or 4).
-template <int BM, int BN, int NPF, bool F32, bool I8W>
+template <int BM, int BN, bool F32, bool I8W>
 __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
     const void *__restrict__ w, const float *__restrict__ w_scale, const void *__restrict__ xq,
     const float *__restrict__ alpha, bool slots, float *alpha_out, float *__restrict__ yc, int M,
@@ -115,12 +114,13 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   // per column tile (gridDim.y = 1) the stores of a row tile drain while the next one is being
   // computed, instead of holding the compute unit until they are out.
   for (int m0 = blockIdx.y * BM; m0 < M; m0 += gridDim.y * BM) {
-  floatx16 accf[NB];
-  intx16 acci[NB];
+  // accumulators of the NB column blocks: int32 for int8 weights, fp32 for bf16 weights
+  using Acc = std::conditional_t<I8W, intx16, floatx16>;
+  Acc acc[NB];
 #pragma unroll
   for (int i = 0; i < NB; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { accf[i][r] = 0.f; acci[i][r] = 0; }
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0;
 
   // weights of chunk kc: wreg <- w[m0 + a_row][kc*64 + this thread's share], zero outside.
   // They are fetched one chunk ahead (while the MFMAs of the previous chunk run).
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
     }
   };
 
-  Patch<F32, CPT> raw[NPF];
+  Patch<F32, CPT> raw;  // the one chunk of activations in flight
   // activations: quantise, transpose the CPT x 4 patch, store with the n rows permuted
   auto stage_patch = [&](const Patch<F32, CPT> &pt, const Quant &quant, auto fast_c) {
     constexpr bool FAST = decltype(fast_c)::value;
@@ -175,13 +175,12 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   // this thread's four positions in channel kq * CPT of chunk 0
   const bool n_in = n0 + 4 * g < k;
   const char *xp = static_cast<const char *>(xb) + ((size_t)(kq * CPT) * k + n0 + 4 * g) * (F32 ? 4 : 1);
-  static_assert(NPF == 1, "one chunk of activations in flight");
   load_w(0);
-  raw[0].load(xp, K, k, kq * CPT, n_in);
+  raw.load(xp, K, k, kq * CPT, n_in);
   for (int kc = 0; kc < nchunks; ++kc) {
     {
-      if (quant.fast) stage_patch(raw[0], quant, std::true_type{});
-      else stage_patch(raw[0], quant, std::false_type{});
+      if (quant.fast) stage_patch(raw, quant, std::true_type{});
+      else stage_patch(raw, quant, std::false_type{});
 #pragma unroll
       for (int q = 0; q < APT; ++q)
         *reinterpret_cast<uint4 *>(&As[a_row * LDR + a_half * (BK / 2) * ESZ + q * 16]) = wreg[q];
@@ -189,7 +188,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
       // both register tiles are in LDS now: the next chunk travels while this one is multiplied
       if (kc + 1 < nchunks) {
         load_w(kc + 1);
-        raw[0].load(xp + (size_t)(kc + 1) * BK * k * (F32 ? 4 : 1), K, k, (kc + 1) * BK + kq * CPT, n_in);
+        raw.load(xp + (size_t)(kc + 1) * BK * k * (F32 ? 4 : 1), K, k, (kc + 1) * BK + kq * CPT, n_in);
       }
       const int fr = lane & 31, half = lane >> 5;
       if constexpr (I8W) {
@@ -201,7 +200,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
           for (int i = 0; i < NB; ++i) {
             const intx4 bb = __builtin_bit_cast(
                 intx4, *reinterpret_cast<const uint4 *>(&Bs[(i * 32 + fr) * LDR + ks * 32 + half * 16]));
-            acci[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bb, acci[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bb, acc[i], 0, 0, 0);
           }
         }
       } else {
@@ -213,7 +212,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
           for (int i = 0; i < NB; ++i) {
             const bf16x8 bb = __builtin_bit_cast(
                 bf16x8, *reinterpret_cast<const uint4 *>(&Bs[(i * 32 + fr) * LDR + (ks * 16 + half * 8) * 2]));
-            accf[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, accf[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[i], 0, 0, 0);
           }
         }
       }
@@ -231,7 +230,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
       float v[NB];
       const float sc = I8W ? sx * w_scale[m] : sx;
 #pragma unroll
-      for (int i = 0; i < NB; ++i) v[i] = I8W ? (float)acci[i][r] * sc : accf[i][r] * sc;
+      for (int i = 0; i < NB; ++i) v[i] = (float)acc[i][r] * sc;
       float *dst = yc + ((size_t)b * M + m) * k + n;
       if (stream_out) {  // (wave-uniform) an output that no cache will hold for its reader
         if constexpr (NB == 4) {
@@ -251,7 +250,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   }  // row tiles
 }
 
-template <int BM, int BN, int NPF, bool I8W>
+template <int BM, int BN, bool I8W>
 hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
                        const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
                        float *yc, hipStream_t s) {
@@ -262,10 +261,10 @@ hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float 
   // better left there (measured); beyond that the output is streamed past it.
   const bool stream_out = (int64_t)d.B * d.C_out * k * 4 > ((int64_t)512 << 20);
   if (f32)
-    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, NPF, true, I8W>), grid, block, 0, s, w, w_scale,
+    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, true, I8W>), grid, block, 0, s, w, w_scale,
                        xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k, stream_out);
   else
-    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, NPF, false, I8W>), grid, block, 0, s, w, w_scale,
+    hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, false, I8W>), grid, block, 0, s, w, w_scale,
                        xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k, stream_out);
   return hipGetLastError();
 }
@@ -276,19 +275,19 @@ template <bool I8W>
 hipError_t mfma_dispatch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
                          const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
                          float *yc, hipStream_t s) {
-#define WCC_MFMA(BM_, BN_, NPF_) \
-  return mfma_launch<BM_, BN_, NPF_, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s)
+#define WCC_MFMA(BM_, BN_) \
+  return mfma_launch<BM_, BN_, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s)
   const int64_t want = 256;  // compute units
   auto wgs = [&](int bm, int bn) {
     return ((k + bn - 1) / bn) * ((d.C_out + bm - 1) / bm) * (int64_t)d.B;
   };
-  if (d.C_out > 128 && wgs(256, 128) >= want) WCC_MFMA(256, 128, 1);
-  if (d.C_out <= 128 && wgs(128, 128) >= want) WCC_MFMA(128, 128, 1);
+  if (d.C_out > 128 && wgs(256, 128) >= want) WCC_MFMA(256, 128);
+  if (d.C_out <= 128 && wgs(128, 128) >= want) WCC_MFMA(128, 128);
   // (a quarter of the chip is enough for the 128-row tile: on the short signals of deep layers
   // the smaller tile quantises and stages every activation once more per extra row tile, which
   // costs more than the idle units: 960 -> 320 channels at k = 512, 19.5 -> 17.2 us)
-  if (d.C_out > 64 && wgs(128, 64) >= want / 4) WCC_MFMA(128, 64, 1);
-  WCC_MFMA(64, 64, 1);
+  if (d.C_out > 64 && wgs(128, 64) >= want / 4) WCC_MFMA(128, 64);
+  WCC_MFMA(64, 64);
 #undef WCC_MFMA
 }
 

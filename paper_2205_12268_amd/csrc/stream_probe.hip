@@ -1,9 +1,13 @@
 // Plain streaming kernels of known size: what this memory system gives to the simplest code,
 // measured beside the path's kernels so that their rates can be placed against it (and not
-// only against the published 8 TB/s).  Not part of the method.
-#include "wcc_internal.h"
+// only against the published 8 TB/s).  Not part of the method and not part of libwcc: this file
+// is the whole of libwcc_probe.so, a measurement aid that bench.py loads.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <algorithm>
 
-namespace wcc {
+#include "wcc_probe.h"
+
 namespace {
 
 typedef float vf4 __attribute__((ext_vector_type(4)));
@@ -65,8 +69,15 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const vf4 *__restrict__
 
 }  // namespace
 
-hipError_t launch_probe(int kind, const void *src, void *dst, size_t bytes, bool nt, int blocks,
-                        hipStream_t s) {
+extern "C" int wcc_probe_stream(int kind, const void *src, void *dst, size_t bytes, int nontemporal,
+                                int blocks, void *stream) {
+  if (kind < WCC_PROBE_READ || kind > WCC_PROBE_WRITE8) return WCC_PROBE_ERR_KIND;
+  const bool writes_only = kind == WCC_PROBE_WRITE || kind == WCC_PROBE_WRITE8;
+  if (!dst || (!writes_only && !src)) return WCC_PROBE_ERR_NULL;
+  if (bytes == 0 || bytes % 16 != 0 || blocks < 0 || blocks > (1 << 24)) return WCC_PROBE_ERR_SIZE;
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) return WCC_PROBE_ERR_SIZE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool nt = nontemporal != 0;
   const size_t n = bytes / 16;
   const vf4 *in = static_cast<const vf4 *>(src);
   vf4 *out = static_cast<vf4 *>(dst);
@@ -84,15 +95,13 @@ hipError_t launch_probe(int kind, const void *src, void *dst, size_t bytes, bool
       if (nt) hipLaunchKernelGGL(probe_copy_kernel<true>, grid, block, 0, s, in, out, n);
       else hipLaunchKernelGGL(probe_copy_kernel<false>, grid, block, 0, s, in, out, n);
       break;
-    case WCC_PROBE_WRITE8: {
+    default: {
+      if ((n + 2047) / 2048 > 0x7FFFFFFFull) return WCC_PROBE_ERR_SIZE;
       const dim3 g8((unsigned)((n + 2047) / 2048));
       if (nt) hipLaunchKernelGGL(probe_write8_kernel<true>, g8, block, 0, s, out, n);
       else hipLaunchKernelGGL(probe_write8_kernel<false>, g8, block, 0, s, out, n);
       break;
     }
-    default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
+  return hipGetLastError() == hipSuccess ? WCC_PROBE_OK : WCC_PROBE_ERR_HIP;
 }
-
-}  // namespace wcc

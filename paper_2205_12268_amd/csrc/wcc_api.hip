@@ -267,16 +267,6 @@ int64_t wcc_k(const wcc_desc *desc) {
   return k_of(*desc);
 }
 
-wcc_status wcc_probe_stream(wcc_ctx *ctx, int kind, const void *src, void *dst, size_t bytes,
-                            int nontemporal, int blocks, void *stream) {
-  if (kind < WCC_PROBE_READ || kind > WCC_PROBE_WRITE8) return WCC_ERR_DTYPE;
-  const bool writes_only = kind == WCC_PROBE_WRITE || kind == WCC_PROBE_WRITE8;
-  if (!ctx || !dst || (!writes_only && !src)) return WCC_ERR_NULL;
-  if (bytes == 0 || bytes % 16 != 0 || blocks < 0 || blocks > (1 << 24)) return WCC_ERR_SHAPE;
-  return wcc::launch_probe(kind, src, dst, bytes, nontemporal != 0, blocks, static_cast<hipStream_t>(stream)) == hipSuccess
-             ? WCC_OK : WCC_ERR_HIP;
-}
-
 wcc_status wcc_set_profiling(wcc_ctx *ctx, int enabled) {
   if (!ctx) return WCC_ERR_NULL;
   if (enabled && !ctx->ev_ok) {
@@ -503,6 +493,11 @@ wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const voi
   if (misaligned(x) || misaligned(w1) || misaligned(w3) || misaligned(y) || misaligned(t1_out) ||
       misaligned(t2_out) || misaligned(idx1_out) || misaligned(idx3_out))
     return WCC_ERR_ALIGN;
+  // K_dw is folded into the two transform passes of the project layer (its output is never
+  // written) when the width allows; the stand-alone kernel runs otherwise, and when the caller
+  // asks for K_dw's output.  It reads and writes fp32 only.
+  const bool fold = desc->W % 4 == 0;
+  if (desc->act_dtype != WCC_F32 && (!fold || t2_out)) return WCC_ERR_UNSUPPORTED;
   const BlockLayout BL = block_layout(*desc, d1, d3);
   if (!ctx->ws || ctx->ws_bytes < BL.total) return WCC_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -515,11 +510,6 @@ wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const voi
   st = forward_on(ctx, ws + BL.layer, ws_layout(d1), d1, x, w1, w1_scale, 0.f, t1, idx1_out, nullptr,
                   nullptr, nullptr, prof && ctx->block_profile_layer == 0, s);
   if (st != WCC_OK) return st;
-  // K_dw is folded into the two transform passes of the project layer (its output is never
-  // written) when the width allows; the stand-alone kernel runs otherwise, and when the caller
-  // asks for K_dw's output
-  const bool fold = desc->W % 4 == 0;
-  if (desc->act_dtype != WCC_F32 && (!fold || t2_out)) return WCC_ERR_UNSUPPORTED;
   if (!fold || t2_out) {
     if (prof) WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][0], s));
     WCC_TRY(launch_depthwise3x3(d3.B, d3.C_in, d3.H, d3.W, static_cast<const float *>(t1), w_dw, t2, s));

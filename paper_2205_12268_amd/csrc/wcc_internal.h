@@ -15,8 +15,8 @@ constexpr int kMaxLevels = 4;      // register-resident strip transform up to 16
 constexpr int kRadixBins = 2048;   // 11 + 11 + 10 bit radix select
 constexpr int kSelectChunk = 1024; // keys per workgroup in the select kernels
 constexpr int kSfxStride = 1024;   // per-workgroup suffix sums of the low-digit histogram
-constexpr int kAlphaSlots = 64;
-constexpr int kInvScratchBytes = 1024;  // one 16-byte line per lane for stores that must go nowhere    // max|kept c| is reduced into this many slots, then combined
+constexpr int kAlphaSlots = 64;    // max|kept c| is reduced into this many slots, then combined
+constexpr int kInvScratchBytes = 1024;  // one 16-byte line per lane for stores that must go nowhere
 
 // Geometry of the wavelet vector of one plane (Eq. wavelet_transform for d levels).
 struct Geo {
@@ -107,7 +107,10 @@ struct Quant {
   __device__ __forceinline__ float level_as(float v) const {
     float u;
     if constexpr (FAST) {
-      const float q0 = __fmul_rn(v, y);
+      // (a first quotient beyond +-2 clips to +-1 whatever the correction adds; held at +-2 it
+      // cannot overflow, and with it the correction cannot turn infinity into NaN for a large
+      // |v| over a small caller-supplied alpha)
+      const float q0 = __builtin_amdgcn_fmed3f(__fmul_rn(v, y), -2.f, 2.f);
       const float r = __fmaf_rn(-q0, alpha, v);
       u = __fmaf_rn(r, y, q0);
     } else {
@@ -172,12 +175,6 @@ hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const f
 // residual (nullable): [B, C_out, H, W] added to the result (may be y itself)
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
                                 void *y, float *scratch, const void *residual, hipStream_t s);
-// plain streaming kernel of `bytes` bytes (a multiple of 16): kind = wcc_probe_kind; read sums
-// src and writes nothing (dst: 16 bytes it may write in principle), write fills dst, copy moves
-// src to dst; nt: with the non-temporal hint; blocks: workgroups of 256 threads walking the
-// buffer with a grid stride (<= 0: 8192)
-hipError_t launch_probe(int kind, const void *src, void *dst, size_t bytes, bool nt, int blocks,
-                        hipStream_t s);
 // out[i] = the two signed 4-bit codes of packed[i / 2] widened to int8 (n = number of codes, even)
 hipError_t launch_unpack_i4(const uint8_t *packed, int8_t *out, int64_t n, hipStream_t s);
 // depthwise 3x3, stride 1, zero padding 1: x, y [B, C, H, W], w [C, 3, 3]

@@ -16,7 +16,6 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libwcc.so")
 
 F32, BF16, I8, I4 = 0, 1, 2, 3
 NORM_L1, NORM_L2 = 0, 1
-PROBE_READ, PROBE_WRITE, PROBE_COPY, PROBE_WRITE8 = 0, 1, 2, 3
 STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "event_pair",
           "depthwise")
 
@@ -24,7 +23,7 @@ EXPORTS = ("wcc_create", "wcc_destroy", "wcc_workspace_bytes", "wcc_set_workspac
            "wcc_status_string", "wcc_set_profiling", "wcc_stage_times", "wcc_haar_fwd",
            "wcc_joint_topk", "wcc_gather_quant", "wcc_pointwise", "wcc_scatter_ihaar",
            "wcc_forward", "wcc_forward_fixed", "wcc_block_workspace_bytes", "wcc_depthwise3x3", "wcc_block_forward",
-           "wcc_set_block_profile_layer", "wcc_probe_stream")
+           "wcc_set_block_profile_layer")
 
 
 class Desc(C.Structure):
@@ -83,7 +82,6 @@ def lib():
         L.wcc_depthwise3x3.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp, vp]
         L.wcc_block_forward.argtypes = [vp, bp] + [vp] * 12
         L.wcc_set_block_profile_layer.argtypes = [vp, C.c_int]
-        L.wcc_probe_stream.argtypes = [vp, C.c_int, vp, vp, C.c_size_t, C.c_int, C.c_int, vp]
         for name in EXPORTS:
             if name not in ("wcc_k", "wcc_status_string"):
                 getattr(L, name).restype = C.c_int
@@ -228,9 +226,3 @@ class Context:
 
     def set_block_profile_layer(self, layer: int) -> None:
         _check(lib().wcc_set_block_profile_layer(self._h, int(layer)), "wcc_set_block_profile_layer")
-
-    def wcc_probe_stream(self, kind: int, src, dst, nbytes: int, nontemporal: bool = False,
-                         blocks: int = 0) -> None:
-        _check(lib().wcc_probe_stream(self._h, int(kind), _ptr(src), _ptr(dst), C.c_size_t(nbytes),
-                                      int(bool(nontemporal)), int(blocks), _stream()),
-               "wcc_probe_stream")

@@ -11,8 +11,8 @@ from paper_2205_12268_amd import synth, wcc
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "wcc.h")).read()
+def declared_functions(header="wcc.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(wcc_[a-z_0-9]+)\s*\(", text))
     return sorted(names)
@@ -30,6 +30,19 @@ def test_library_exports_every_declared_symbol():
     L = C.CDLL(wcc.LIB_PATH)
     for n in declared_functions():
         assert getattr(L, n) is not None, n
+
+
+def test_probe_library_is_separate_and_exports_its_header():
+    """The streaming probe is a measurement aid in a library of its own: libwcc exports none of
+    it, and libwcc_probe.so exports what include/wcc_probe.h declares."""
+    from paper_2205_12268_amd import probe
+    names = declared_functions("wcc_probe.h")
+    assert set(names) == set(probe.EXPORTS) == {"wcc_probe_stream"}
+    P = C.CDLL(probe.LIB_PATH)
+    for n in names:
+        assert getattr(P, n) is not None, n
+    assert not hasattr(C.CDLL(wcc.LIB_PATH), "wcc_probe_stream")
+    assert "probe" not in open(os.path.join(ROOT, "include", "wcc.h")).read()
 
 
 def test_k_and_workspace_are_pure_host_functions():

@@ -309,6 +309,34 @@ def test_quantiser_codes_on_arbitrary_floats(ref, ctx, alpha_bits):
     np.testing.assert_array_equal(xc.cpu().numpy().astype(np.float64), ref.quant_codes(coef, alpha, 8))
 
 
+@pytest.mark.parametrize("alpha", [1e-10, 3e-3, 7.5e18])
+def test_quantiser_clips_values_whose_quotient_overflows(ref, ctx, alpha):
+    """Finite coefficients so far above a caller-supplied clipping parameter that v / alpha is
+    beyond fp32: Eq. (quantweights) clips them to +-1, so the codes are +-127 with the sign of v
+    (the reciprocal route of the kernel must not turn the overflow into another code)."""
+    cfg = case("overflow", 1, 16, 16, 64, 64, 1, 1, 1, F32, 8)
+    d = desc_of(cfg)
+    ctx.ensure_workspace(d)
+    rng = np.random.default_rng(11)
+    n = 16 * cfg.N
+    with np.errstate(over="ignore"):
+        mag = np.float32(alpha) * np.exp2(rng.uniform(-4.0, 126.0, n)).astype(np.float32)
+    mag = np.minimum(mag, np.float32(3.0e38))
+    v = (mag * rng.choice([-1.0, 1.0], n).astype(np.float32)).astype(np.float32)
+    v[:8] = np.array([3.4e38, -3.4e38, 3.0e28, -3.0e28, 1.0e30, -1.0e30, 2.0, -2.0], dtype=np.float32)
+    coef = v.reshape(1, 16, cfg.N)
+    idx = torch.arange(cfg.N, dtype=torch.int32, device="cuda")[None].contiguous()
+    xc = torch.zeros((1, 16, cfg.N), dtype=torch.int8, device="cuda")
+    a = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ctx.wcc_gather_quant(d, dev(coef), idx, float(np.float32(alpha)), xc, a)
+    got = xc.cpu().numpy().astype(np.float64)
+    want = ref.quant_codes(coef, float(np.float32(alpha)), 8)
+    np.testing.assert_array_equal(got, want)
+    big = np.abs(coef.astype(np.float64)) >= 2.0 * float(np.float32(alpha))
+    assert big.sum() > n // 2
+    np.testing.assert_array_equal(got[big], 127.0 * np.sign(coef[big]))
+
+
 @pytest.mark.parametrize("cfg", [SMALL[0], SMALL[1], SMALL[6], SMALL[12]], ids=lambda c: c.name)
 @pytest.mark.parametrize("kind", ["prefix", "given"])
 def test_forward_with_a_fixed_index_list(ref, ctx, cfg, kind):
