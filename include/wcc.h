@@ -197,6 +197,26 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const void *x, const 
                        int32_t *idx_out /*nullable*/, float *alpha_out_dev /*nullable*/,
                        void *stream);
 
+/* ---- wcc_forward for callers that cannot allocate -------------------------------------------
+ * For code that may not call hipMalloc and has no workspace to hand over: work recorded under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
+ * same kernels and same results as wcc_forward, but the intermediates live in a fixed array of
+ * WCC_STATIC_SCRATCH_BYTES inside the library's device image (every GPU the library is loaded
+ * on holds that much until the process ends) instead of the context's workspace, which is not
+ * touched and need not be attached.  The call allocates and frees nothing, on the host or on
+ * the device.  A layer whose wcc_workspace_bytes() exceeds WCC_STATIC_SCRATCH_BYTES returns
+ * WCC_ERR_WORKSPACE and enqueues nothing.  The device that is current must be the one the
+ * context was created for (else WCC_ERR_UNSUPPORTED).  All calls on one GPU share the one
+ * array, whatever their context or stream: calls that overlap in time on one GPU race; every
+ * buffer that must start from a known value is cleared by the call's own first kernel, so calls
+ * in sequence need no clean-up in between.  Stage profiling (wcc_set_profiling) does not
+ * apply. */
+#define WCC_STATIC_SCRATCH_BYTES (64u << 20)
+wcc_status wcc_forward_static(wcc_ctx *ctx, const wcc_desc *desc, const void *x, const void *w,
+                              const float *w_scale /*nullable unless I8*/, float alpha_in, void *y,
+                              int32_t *idx_out /*nullable*/, float *alpha_out_dev /*nullable*/,
+                              void *stream);
+
 /* ---- variant: the layer with an index list that does not depend on the input ------------
  * The footnote of the section "Joint hard shrinkage" mentions keeping the upper-left part of
  * the wavelet transform for any image.  idx [B,k] (strictly ascending per sample, values in

@@ -1,11 +1,39 @@
 // C ABI of libwcc: argument checks, workspace carving, and the order in which the kernels of
 // Alg. 1 are enqueued.  No arithmetic of the method happens on the host.
+#include <mutex>
 #include <new>
 
 #include "wcc_internal.h"
 
+// Scratch memory of wcc_forward_static, inside the library's device image: every GPU the library
+// runs on holds its own copy at its own address until the process ends.  Host code never uses
+// the array's name as an address; static_scratch_of() asks the runtime where the current
+// device's copy lives, once per device.
+static __device__ __align__(256) unsigned char scratch[WCC_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on device i (nullptr: not asked yet)
+
+// Address of `scratch` on `device`, which must be the current device.
+hipError_t static_scratch_of(int device, void **out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device] == nullptr) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
+}  // namespace
+
 struct wcc_ctx {
-  int device = 0;
+  int device = 0;               // the device wcc_create was given: owner of static_ws
+  void *static_ws = nullptr;    // that device's copy of `scratch`
   void *ws = nullptr;
   size_t ws_bytes = 0;
   bool profiling = false;
@@ -231,9 +259,16 @@ wcc_status wcc_create(wcc_ctx **out, int device) {
   *out = nullptr;
   int n = 0;
   if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return WCC_ERR_HIP;
+  // where this device keeps the static scratch array (asked with that device current)
+  int prev = 0;
+  void *sp = nullptr;
+  if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) return WCC_ERR_HIP;
+  const hipError_t e = static_scratch_of(device, &sp);
+  if (hipSetDevice(prev) != hipSuccess || e != hipSuccess) return WCC_ERR_HIP;
   wcc_ctx *c = new (std::nothrow) wcc_ctx;
   if (!c) return WCC_ERR_HIP;
   c->device = device;
+  c->static_ws = sp;
   *out = c;
   return WCC_OK;
 }
@@ -429,6 +464,27 @@ wcc_status wcc_forward(wcc_ctx *ctx, const wcc_desc *desc, const void *x, const 
     ctx->have_times = true;
   }
   return WCC_OK;
+}
+
+wcc_status wcc_forward_static(wcc_ctx *ctx, const wcc_desc *desc, const void *x, const void *w,
+                              const float *w_scale, float alpha_in, void *y, int32_t *idx_out,
+                              float *alpha_out_dev, void *stream) {
+  if (!ctx || !x || !w || !y) return WCC_ERR_NULL;
+  wcc_status st = check_desc(desc);
+  if (st != WCC_OK) return st;
+  if (coded(desc->w_dtype) && !w_scale) return WCC_ERR_NULL;
+  if (misaligned(x) || misaligned(w) || misaligned(y) || misaligned(idx_out)) return WCC_ERR_ALIGN;
+  const WsLayout L = ws_layout(*desc);
+  if (L.total > (size_t)WCC_STATIC_SCRATCH_BYTES) return WCC_ERR_WORKSPACE;
+  // the scratch array belongs to the context's device: the kernels must run there
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess) return WCC_ERR_HIP;
+  if (cur != ctx->device || ctx->static_ws == nullptr) return WCC_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // every buffer that has to start at a known value (histograms, alpha slots) is cleared by the
+  // first kernel of the layer itself, as with a caller's workspace of unknown content
+  return forward_on(ctx, static_cast<char *>(ctx->static_ws), L, *desc, x, w, w_scale, alpha_in, y,
+                    idx_out, alpha_out_dev, nullptr, nullptr, false, s);
 }
 
 wcc_status wcc_forward_fixed(wcc_ctx *ctx, const wcc_desc *desc, const void *x, const void *w,

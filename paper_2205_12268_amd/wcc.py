@@ -15,6 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libwcc.so")
 
 F32, BF16, I8, I4 = 0, 1, 2, 3
+STATIC_SCRATCH_BYTES = 64 << 20  # WCC_STATIC_SCRATCH_BYTES of wcc.h
 NORM_L1, NORM_L2 = 0, 1
 STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "event_pair",
           "depthwise")
@@ -22,7 +23,7 @@ STAGES = ("haar_fwd", "norm_select", "gather", "pointwise", "scatter_ihaar", "ev
 EXPORTS = ("wcc_create", "wcc_destroy", "wcc_workspace_bytes", "wcc_set_workspace", "wcc_k",
            "wcc_status_string", "wcc_set_profiling", "wcc_stage_times", "wcc_haar_fwd",
            "wcc_joint_topk", "wcc_gather_quant", "wcc_pointwise", "wcc_scatter_ihaar",
-           "wcc_forward", "wcc_forward_fixed", "wcc_block_workspace_bytes", "wcc_depthwise3x3", "wcc_block_forward",
+           "wcc_forward", "wcc_forward_static", "wcc_forward_fixed", "wcc_block_workspace_bytes", "wcc_depthwise3x3", "wcc_block_forward",
            "wcc_set_block_profile_layer")
 
 
@@ -76,6 +77,7 @@ def lib():
         L.wcc_pointwise.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp]
         L.wcc_scatter_ihaar.argtypes = [vp, dp, vp, vp, vp, vp]
         L.wcc_forward.argtypes = [vp, dp, vp, vp, vp, C.c_float, vp, vp, vp, vp]
+        L.wcc_forward_static.argtypes = [vp, dp, vp, vp, vp, C.c_float, vp, vp, vp, vp]
         L.wcc_forward_fixed.argtypes = [vp, dp, vp, vp, vp, C.c_float, vp, vp, vp, vp]
         bp = C.POINTER(BlockDesc)
         L.wcc_block_workspace_bytes.argtypes = [bp, C.POINTER(C.c_size_t)]
@@ -205,6 +207,11 @@ class Context:
         _check(lib().wcc_forward(self._h, C.byref(desc), _ptr(x), _ptr(w), _ptr(w_scale),
                                  C.c_float(alpha_in), _ptr(y), _ptr(idx_out), _ptr(alpha_out),
                                  _stream()), "wcc_forward")
+
+    def wcc_forward_static(self, desc, x, w, w_scale, alpha_in, y, idx_out=None, alpha_out=None):
+        _check(lib().wcc_forward_static(self._h, C.byref(desc), _ptr(x), _ptr(w), _ptr(w_scale),
+                                        C.c_float(alpha_in), _ptr(y), _ptr(idx_out), _ptr(alpha_out),
+                                        _stream()), "wcc_forward_static")
 
     def wcc_forward_fixed(self, desc, x, w, w_scale, alpha_in, idx, y, alpha_out=None):
         _check(lib().wcc_forward_fixed(self._h, C.byref(desc), _ptr(x), _ptr(w), _ptr(w_scale),
