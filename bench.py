@@ -3,9 +3,12 @@
 
 A step is one ``wcc_forward`` (Haar transform -> joint top-k -> gather/quantise -> 1x1
 contraction -> scatter + inverse Haar) over one batch of seeded synthetic feature maps that
-are already resident in HBM.  Prints ONE JSON line: whole-layer Gpixel*ch/s, the roofline
-fraction of the dominant kernel (measured with HIP events inside the library around that
-kernel), and the CPU oracle timed on this host as a reported baseline.
+are already resident in HBM.  The default workload is the largest single-layer configuration
+(the expansion layer: B 4, 64 -> 256 channels, 512 x 1024, 3 levels, keep 1/8).  Prints ONE
+JSON line: whole-layer Gpixel*ch/s, the roofline fraction of the dominant kernel (measured
+with HIP events inside the library around that kernel), every stage against the HBM peak, the
+contraction against the matrix-core peak, and the CPU oracle timed on this host as a reported
+baseline.
 """
 from __future__ import annotations
 
@@ -20,6 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+# dense matrix-core peaks (published) by the contraction's operand type, TFLOP/s (TOP/s for int8);
+# fp32 weights or unquantised activations run on the vector ALUs (fp32 vector peak)
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "int8": 5000.0, "f32": 157.3}
+CACHE_BYTES = 256 << 20  # memory-side cache
 
 
 # stage of wcc_forward -> the one kernel it launches (norm_select is four small kernels)
@@ -27,20 +34,39 @@ STAGE_KERNEL = {"haar_fwd": "haar_fwd_kernel", "gather": "haar_keep_kernel",
                 "pointwise": "pointwise", "scatter_ihaar": "scatter_ihaar_kernel"}
 
 
-def algorithmic_bytes(cfg, act_bytes: int = 4) -> dict:
+def algorithmic_bytes(cfg, act_bytes: int = 4, xc_bytes: int | None = None) -> dict:
     """Bytes each stage of the fused layer must move per call: what the method itself reads
-    and writes (feature maps of act_bytes per element, fp32 kept coefficients, int32 positions),
-    not what an implementation adds."""
+    and writes (feature maps of act_bytes per element, kept coefficients of xc_bytes -- one for
+    8-bit codes, four for fp32 --, int32 positions), not what an implementation adds."""
     B, Ci, Co, N, k = cfg.B, cfg.C_in, cfg.C_out, cfg.N, cfg.k
     bw = {0: 4, 1: 2, 2: 1, 3: 0.5}[cfg.w_dtype]
     a = act_bytes
+    if xc_bytes is None:
+        xc_bytes = 1 if (cfg.act_bits == 8 and k % 4 == 0) else 4
     return {
         "haar_fwd": a * B * Ci * N + 4 * B * N,                    # read x, write norms
         "norm_select": 4 * B * N + 4 * B * k,                      # read norms, write I
-        "gather": a * B * Ci * N + 4 * B * k + 4 * B * Ci * k,     # read x and I, write X_wt[I]
-        "pointwise": 4 * B * Ci * k + bw * Ci * Co + 4 * B * Co * k,
+        "gather": a * B * Ci * N + 4 * B * k + xc_bytes * B * Ci * k,  # read x and I, write X_wt[I]
+        "pointwise": xc_bytes * B * Ci * k + bw * Ci * Co + 4 * B * Co * k,
         "scatter_ihaar": 4 * B * Co * k + 4 * B * k + a * B * Co * N,
     }
+
+
+def read_profile_column(profile_dir: str, prefix: str, workload: str, kernel: str, column: int):
+    """One number of the committed rocprofv3 summary `<prefix>_<workload>.txt` for the first
+    kernel whose name starts with `kernel` (column counted over whitespace-separated fields),
+    or None if there is no such file or line."""
+    path = os.path.join(profile_dir, f"{prefix}_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        t = line.split()
+        if len(t) > column and t[0].startswith(kernel) and not line.startswith("#"):
+            try:
+                return float(t[column])
+            except ValueError:
+                return None
+    return None
 
 
 def read_traffic(profile_dir: str, workload: str, kernel: str):
@@ -273,8 +299,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2,
-                    help="single-layer workload 1..4, 5 = the 16-layer backbone stack, "
+    ap.add_argument("--config", type=int, default=3,
+                    help="single-layer workload 1..4 (default 3, the largest), 5 = the 16-layer backbone stack, "
                          "6 = the inverted residual block of the paper's timing table")
     ap.add_argument("--keep", default="1/4", help="kept fraction for --config 5 and 6 (num/den)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -422,15 +448,24 @@ def main() -> int:
 
     pix_ch = cfg.B * cfg.H * cfg.W * cfg.C_in
     value = pix_ch / dt / 1e9
-    alg = algorithmic_bytes(cfg, 2 if args.act == "bf16" else 4)
-    if args.alpha == "static" and cfg.act_bits:  # kept coefficients travel as int8 codes
-        alg["gather"] -= 3 * cfg.B * cfg.C_in * cfg.k
-        alg["pointwise"] -= 3 * cfg.B * cfg.C_in * cfg.k
+    act_bytes = 2 if args.act == "bf16" else 4
+    # kept coefficients travel as 8-bit codes whenever the clipping parameter is known before the
+    # second transform pass: from the caller, or from the selection (not with a fixed list)
+    codes = cfg.act_bits == 8 and cfg.k % 4 == 0 and (args.alpha == "static" or args.index_list == "select")
+    alg = algorithmic_bytes(cfg, act_bytes, 1 if codes else 4)
     if args.index_list == "prefix":  # no norm pass, no selection: only the rank map is written
         alg["haar_fwd"], alg["norm_select"] = 0, 4 * cfg.B * cfg.N
+    # stage_us is the HIP-event bracket around each stage as recorded (it holds the kernel and its
+    # launch gap); the roofline figures use it as it is, so they err on the low side, and the
+    # bracket less the cost of the two event records is reported beside it
     dom = max(STAGE_KERNEL, key=lambda n: stage_us[n])  # the single kernel that takes longest
     achieved = alg[dom] / (stage_us[dom] * 1e-6) / 1e9
-    traffic = read_traffic(os.path.join(ROOT, "profiles"), cfg.name, STAGE_KERNEL[dom])
+    prof = os.path.join(ROOT, "profiles")
+    traffic = read_traffic(prof, cfg.name, STAGE_KERNEL[dom])
+    x_bytes = act_bytes * pix_ch
+    wname = {0: "f32", 1: "bf16", 2: "int8", 3: "int8"}[cfg.w_dtype] if cfg.act_bits == 8 else "f32"
+    flops = 2.0 * cfg.B * cfg.C_in * cfg.C_out * cfg.k
+    gemm_tflops = flops / (stage_us["pointwise"] * 1e-6) / 1e12
     out = {
         "metric": "WCC layer forward throughput",
         "value": round(value, 3),
@@ -442,7 +477,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": {0: "f32", 1: "bf16", 2: "int8"}[cfg.w_dtype],
+        "dtype": {0: "f32", 1: "bf16", 2: "int8", 3: "int8"}[cfg.w_dtype],
         "data": "synthetic",
         "launch": args.launch,
         "config": {"workload": cfg.name, "B": cfg.B, "C_in": cfg.C_in, "C_out": cfg.C_out,
@@ -453,14 +488,33 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": STAGE_KERNEL[dom], "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "algorithmic_bytes": alg[dom],
-                     "kernel_us": round(stage_us[dom], 2)},
+                     "kernel_us": round(stage_us[dom], 2),
+                     "kernel_us_less_event_pair": round(max(stage_us[dom] - pair_us, 0.0), 2),
+                     "profile_avg_us": read_profile_column(prof, "kernel_stats", cfg.name,
+                                                           STAGE_KERNEL[dom], 2)},
         "stages_us": {n: round(v, 2) for n, v in stage_us.items()},
         "event_pair_us": round(pair_us, 2),
         "stages_alg_GBs": {n: round(alg[n] / (stage_us[n] * 1e-6) / 1e9, 1)
                            for n in stage_us if stage_us[n] > 0},
+        "stages_frac_of_hbm_peak": {n: round(alg[n] / (stage_us[n] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+                                    for n in stage_us if stage_us[n] > 0},
+        # an input that fits the memory-side cache is still there from the step before: the
+        # transform passes' rates are then cache-served, not HBM rates (see --cold-input)
+        "input_cache_resident": bool(x_bytes <= CACHE_BYTES),
         "layer_alg_GBs": round(sum(alg.values()) / dt / 1e9, 1),
-        "gemm_tflops": round(2.0 * cfg.B * cfg.C_in * cfg.C_out * cfg.k
-                             / (stage_us["pointwise"] * 1e-6) / 1e12, 2),
+        "layer_frac_of_hbm_peak": round(sum(alg.values()) / dt / 1e9 / HBM_PEAK_GBS, 4),
+        "gemm_tflops": round(gemm_tflops, 2),
+        # the contraction against the matrix-core peak of its operand type, and the counter's
+        # own reading of how busy the matrix cores were (profiles/sq_counters_*.txt); the stage
+        # is bound by HBM at these shapes, so its HBM fraction stands beside it
+        "mfma": {"kernel": "pointwise_mfma_kernel", "flops": flops,
+                 "achieved_tflops": round(gemm_tflops, 2), "peak_tflops": MFMA_PEAK_TFLOPS[wname],
+                 "frac": round(gemm_tflops / MFMA_PEAK_TFLOPS[wname], 4),
+                 "busy_frac_counter": read_profile_column(prof, "sq_counters", cfg.name,
+                                                          "pointwise_mfma_kernel", -1),
+                 "arithmetic_intensity_flop_per_byte": round(flops / alg["pointwise"], 1),
+                 "frac_of_hbm_peak": round(alg["pointwise"] / (stage_us["pointwise"] * 1e-6) / 1e9
+                                           / HBM_PEAK_GBS, 4)},
     }
 
     if not args.no_ceilings:
@@ -472,18 +526,21 @@ def main() -> int:
         from oracle import wcc_ref
         cores = min(len(os.sched_getaffinity(0)), 16)
         wcc_ref.set_threads(cores)
+        # a bounded sample of the same workload: its first image (every step of the path is per
+        # image), repeated for about 10 s
+        xs = x[:1]
         reps, spent = 0, 0.0
-        while reps < 1 or (spent < 10.0 and reps < 50):  # about 10 s of CPU work
+        while reps < 1 or (spent < 10.0 and reps < 50):
             t1 = time.perf_counter()
-            wcc_ref.forward(x, w.values, None if w.scale is None else w.scale, cfg.levels,
+            wcc_ref.forward(xs, w.values, None if w.scale is None else w.scale, cfg.levels,
                             cfg.keep_num, cfg.keep_den, act_bits=cfg.act_bits)
             spent += time.perf_counter() - t1
             reps += 1
         cpu_dt = spent / reps
-        out["cpu_baseline"] = {"value": round(pix_ch / cpu_dt / 1e9, 5), "unit": "Gpixel*ch/s",
+        out["cpu_baseline"] = {"value": round(pix_ch / cfg.B / cpu_dt / 1e9, 5), "unit": "Gpixel*ch/s",
                                "cores": cores, "kind": "oracle",
-                               "sample": f"full {cfg.name} forward, {reps} repetitions, "
-                                         f"{cpu_dt:.3f} s each"}
+                               "sample": f"forward of 1 of the {cfg.B} images of {cfg.name}, "
+                                         f"{reps} repetitions, {cpu_dt:.3f} s each"}
     print(json.dumps(out))
     ctx.close()
     return 0

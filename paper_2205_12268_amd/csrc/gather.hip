@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
                                                        const float *__restrict__ alpha_slots,
                                                        float *__restrict__ alpha_out,
                                                        int8_t *__restrict__ codes) {
-  const float alpha = alpha_from_slots(alpha_slots);
+  const float alpha = alpha_max(alpha_slots, kAlphaSlots);
   if (blockIdx.x == 0 && threadIdx.x == 0) alpha_out[0] = alpha;
   const Quant a(alpha);
   const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 16;

@@ -6,12 +6,17 @@ namespace wcc {
 namespace {
 
 // ---- analysis ---------------------------------------------------------------------------
-// STORE = false: only the |coefficient| sums are kept (the norm-only pass of the fused layer).
+// STORE = false: only the |coefficient| sums are kept (the norm-only pass of the fused layer),
+// and beside them the largest |coefficient| over the channels at every position: the largest
+// of those over the positions the selection keeps is the layer's clipping parameter alpha, known
+// that way before the second pass, which can then decide the 8-bit codes itself.
 // SQ: the sums are of squared coefficients (one fused multiply-add each) instead.
 template <int D, int V, bool STORE, bool SQ = false>
 struct FwdSink {
+  static constexpr bool MX = !STORE;
   float *plane;  // wavelet vector of the current (b, c)
   float acc[slot_count(D, V)];
+  float top[MX ? slot_count(D, V) : 1];  // max over the channels of |coefficient|
   template <int L, int J>
   __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
                                           bool owner) {
@@ -21,6 +26,7 @@ struct FwdSink {
     for (int e = 0; e < CV; ++e) {
       float &a = acc[base + i * CV + e];
       a = SQ ? fmaf(v[e], v[e], a) : a + fabsf(v[e]);
+      if constexpr (MX) top[base + i * CV + e] = fmaxf(top[base + i * CV + e], fabsf(v[e]));
     }
     if (!STORE || !owner) return;
     float *dst = plane + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
@@ -34,7 +40,8 @@ struct FwdSink {
 };
 
 // x [B, C, H, W] -> coef [B, C, N]; partial norms over this block's channel group to
-// norm_part [G, B, N] (nullable).  block = 256.
+// norm_part [G, B, N] (nullable); without STORE also the group's max |coefficient| per position
+// to max_part [G, B, N] (nullable).  block = 256.
 // SPLIT = false: grid = (ceil(units/4), G, B); each wave of a workgroup takes its own strip unit
 //                and walks all channels of the group.
 // SPLIT = true:  grid = (units, G, B); the four waves share one strip unit and take a quarter
@@ -48,7 +55,8 @@ template <int D, int V, bool SPLIT, bool STORE, int PF, int DWM, class XT, bool 
           bool NT = false>
 __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
                                                        float *__restrict__ coef,
-                                                       float *__restrict__ norm_part, Geo g,
+                                                       float *__restrict__ norm_part,
+                                                       float *__restrict__ max_part, Geo g,
                                                        StripMap m, int C, int Cg, int B,
                                                        SelectPrep prep,
                                                        const float *__restrict__ wdw) {
@@ -72,6 +80,11 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
   FwdSink<D, V, STORE, SQ> sink;
 #pragma unroll
   for (int s = 0; s < NS; ++s) sink.acc[s] = 0.f;
+  constexpr bool MX = FwdSink<D, V, STORE, SQ>::MX;
+  if constexpr (MX) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) sink.top[s] = 0.f;
+  }
 
   if (p.active && c0 < c1) {
     const XT *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
@@ -96,42 +109,64 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
       for (int s = 0; s < NS; ++s) comb[wv - 1][s][lane] = sink.acc[s];
     }
     __syncthreads();
-    if (wv > 0) return;
+    if (wv == 0) {
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
-      sink.acc[s] = ((sink.acc[s] + comb[0][s][lane]) + comb[1][s][lane]) + comb[2][s][lane];
-  }
-  if (!p.active) return;
-  float *np = norm_part + ((size_t)grp * B + b) * g.N;
-  // write the accumulated |coefficient| sums with the same addressing as the coefficients
-  auto flush = [&](auto Lc, auto Jc) {
-    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
-    constexpr int CV = cols_at(V, L), S2 = span_at(V, L);
-    const bool owner = (S2 == 1) || ((p.lc & (S2 - 1)) == 0);
-    if (!owner) return;
+      for (int s = 0; s < NS; ++s)
+        sink.acc[s] = ((sink.acc[s] + comb[0][s][lane]) + comb[1][s][lane]) + comb[2][s][lane];
+    }
+    if constexpr (MX) {
+      if (max_part != nullptr) {  // (uniform over the grid) the maxima meet in the same buffer
+        __syncthreads();
+        if (wv > 0) {
 #pragma unroll
-    for (int i = 0; i < rows_at(D, L); ++i) {
-      float *dst = np + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
-      if constexpr (CV == 2) {
-        *reinterpret_cast<float2 *>(dst) = make_float2(sink.acc[slot_base(D, V, L, J) + i * CV],
-                                                       sink.acc[slot_base(D, V, L, J) + i * CV + 1]);
-      } else {
+          for (int s = 0; s < NS; ++s) comb[wv - 1][s][lane] = sink.top[s];
+        }
+        __syncthreads();
+        if (wv == 0) {
 #pragma unroll
-        for (int e = 0; e < CV; ++e) dst[e] = sink.acc[slot_base(D, V, L, J) + i * CV + e];
+          for (int s = 0; s < NS; ++s)
+            sink.top[s] = fmaxf(fmaxf(sink.top[s], comb[0][s][lane]), fmaxf(comb[1][s][lane], comb[2][s][lane]));
+        }
       }
     }
+    if (wv > 0) return;
+  }
+  if (!p.active) return;
+  // write the per-position values with the same addressing as the coefficients
+  auto write_plane = [&](float *np, const float *vals) {
+    auto flush = [&](auto Lc, auto Jc) {
+      constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+      constexpr int CV = cols_at(V, L), S2 = span_at(V, L);
+      const bool owner = (S2 == 1) || ((p.lc & (S2 - 1)) == 0);
+      if (!owner) return;
+#pragma unroll
+      for (int i = 0; i < rows_at(D, L); ++i) {
+        float *dst = np + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
+        if constexpr (CV == 2) {
+          *reinterpret_cast<float2 *>(dst) = make_float2(vals[slot_base(D, V, L, J) + i * CV],
+                                                         vals[slot_base(D, V, L, J) + i * CV + 1]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < CV; ++e) dst[e] = vals[slot_base(D, V, L, J) + i * CV + e];
+        }
+      }
+    };
+    auto each_level = [&](auto Lc) {
+      constexpr int L = decltype(Lc)::value;
+      flush(Lc, std::integral_constant<int, 1>{});
+      flush(Lc, std::integral_constant<int, 2>{});
+      flush(Lc, std::integral_constant<int, 3>{});
+      if constexpr (L == D) flush(Lc, std::integral_constant<int, 0>{});
+    };
+    each_level(std::integral_constant<int, 1>{});
+    if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+    if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+    if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
   };
-  auto each_level = [&](auto Lc) {
-    constexpr int L = decltype(Lc)::value;
-    flush(Lc, std::integral_constant<int, 1>{});
-    flush(Lc, std::integral_constant<int, 2>{});
-    flush(Lc, std::integral_constant<int, 3>{});
-    if constexpr (L == D) flush(Lc, std::integral_constant<int, 0>{});
-  };
-  each_level(std::integral_constant<int, 1>{});
-  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
-  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
-  if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+  write_plane(norm_part + ((size_t)grp * B + b) * g.N, sink.acc);
+  if constexpr (MX) {
+    if (max_part != nullptr) write_plane(max_part + ((size_t)grp * B + b) * g.N, sink.top);
+  }
 }
 
 // ---- small helpers ----------------------------------------------------------------------------
@@ -173,30 +208,31 @@ __global__ __launch_bounds__(256) void channel_norm_kernel(const float *__restri
 
 // x is fp32, or bf16 when the layer's activations are stored that way (fused calls only)
 template <int D, int V, bool STORE>
-hipError_t fwd_launch(const wcc_desc &d, const void *x, float *coef, float *norm_part, Plan pl,
-                      const SelectPrep &prep, const float *wdw, hipStream_t s);
+hipError_t fwd_launch(const wcc_desc &d, const void *x, float *coef, float *norm_part,
+                      float *max_part, Plan pl, const SelectPrep &prep, const float *wdw, hipStream_t s);
 
 template <int D, int V, bool STORE, class XT>
-hipError_t fwd_launch_t(const wcc_desc &d, const XT *x, float *coef, float *norm_part, Plan pl,
-                        const SelectPrep &prep, const float *wdw, hipStream_t s) {
+hipError_t fwd_launch_t(const wcc_desc &d, const XT *x, float *coef, float *norm_part,
+                        float *max_part, Plan pl, const SelectPrep &prep, const float *wdw,
+                        hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_in + pl.G - 1) / pl.G;
   const dim3 grid_split(m.units, pl.G, d.B), grid_flat((m.units + 3) / 4, pl.G, d.B), block(256);
 #define WCC_FWD(SPLIT, PF, DWM)                                                                       \
   hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, STORE, PF, DWM, XT>),                              \
-                     SPLIT ? grid_split : grid_flat, block, 0, s, x, coef, norm_part, g, m, d.C_in,   \
+                     SPLIT ? grid_split : grid_flat, block, 0, s, x, coef, norm_part, max_part, g, m, d.C_in,   \
                      Cg, d.B, prep, wdw)
   if (d.norm == WCC_NORM_L2) {
     // sums of squares: the norm-only pass over fp32 maps, prefetch depth 1
     if constexpr (!STORE && std::is_same<XT, float>::value) {
 #define WCC_FWD_SQ(SPLIT, DWM)                                                                        \
   hipLaunchKernelGGL((haar_fwd_kernel<D, V, SPLIT, false, 1, DWM, float, true>),                      \
-                     SPLIT ? grid_split : grid_flat, block, 0, s, x, coef, norm_part, g, m, d.C_in,   \
+                     SPLIT ? grid_split : grid_flat, block, 0, s, x, coef, norm_part, max_part, g, m, d.C_in,   \
                      Cg, d.B, prep, wdw)
 #define WCC_FWD_SQ_NT(DWM)                                                                            \
   hipLaunchKernelGGL((haar_fwd_kernel<D, V, false, false, 1, DWM, float, true, true>), grid_flat,     \
-                     block, 0, s, x, coef, norm_part, g, m, d.C_in, Cg, d.B, prep, wdw)
+                     block, 0, s, x, coef, norm_part, max_part, g, m, d.C_in, Cg, d.B, prep, wdw)
       const bool nt = pl.stream && !pl.split;  // (an input far larger than the memory-side cache)
       if (wdw != nullptr) {
         if constexpr (V == 4) {
@@ -219,7 +255,7 @@ hipError_t fwd_launch_t(const wcc_desc &d, const XT *x, float *coef, float *norm
     if (pl.stream && !pl.split) {  // an input far larger than the memory-side cache, read once
 #define WCC_FWD_NT(DWM)                                                                               \
   hipLaunchKernelGGL((haar_fwd_kernel<D, V, false, false, 1, DWM, XT, false, true>), grid_flat,       \
-                     block, 0, s, x, coef, norm_part, g, m, d.C_in, Cg, d.B, prep, wdw)
+                     block, 0, s, x, coef, norm_part, max_part, g, m, d.C_in, Cg, d.B, prep, wdw)
       if (wdw != nullptr) {
         if constexpr (V == 4) {
           if (dw_needs_edges(m)) WCC_FWD_NT(2); else WCC_FWD_NT(1);
@@ -248,13 +284,13 @@ hipError_t fwd_launch_t(const wcc_desc &d, const XT *x, float *coef, float *norm
 }
 
 template <int D, int V, bool STORE>
-hipError_t fwd_launch(const wcc_desc &d, const void *x, float *coef, float *norm_part, Plan pl,
-                      const SelectPrep &prep, const float *wdw, hipStream_t s) {
+hipError_t fwd_launch(const wcc_desc &d, const void *x, float *coef, float *norm_part,
+                      float *max_part, Plan pl, const SelectPrep &prep, const float *wdw, hipStream_t s) {
   if constexpr (!STORE) {
     if (d.act_dtype == WCC_BF16)
-      return fwd_launch_t<D, V, STORE>(d, static_cast<const bf16_t *>(x), coef, norm_part, pl, prep, wdw, s);
+      return fwd_launch_t<D, V, STORE>(d, static_cast<const bf16_t *>(x), coef, norm_part, max_part, pl, prep, wdw, s);
   }
-  return fwd_launch_t<D, V, STORE>(d, static_cast<const float *>(x), coef, norm_part, pl, prep, wdw, s);
+  return fwd_launch_t<D, V, STORE>(d, static_cast<const float *>(x), coef, norm_part, max_part, pl, prep, wdw, s);
 }
 
 }  // namespace
@@ -268,15 +304,16 @@ int forward_groups(const wcc_desc &d, bool folded_dw) {
 }
 
 template <bool STORE>
-hipError_t fwd_dispatch(const wcc_desc &d, const void *x, float *coef, float *norm_part, Plan pl,
-                        const SelectPrep &prep, const float *wdw, hipStream_t s) {
+hipError_t fwd_dispatch(const wcc_desc &d, const void *x, float *coef, float *norm_part,
+                        float *max_part, Plan pl, const SelectPrep &prep, const float *wdw,
+                        hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
-    case 1: return v4 ? fwd_launch<1, 4, STORE>(d, x, coef, norm_part, pl, prep, wdw, s)
-                      : fwd_launch<1, 2, STORE>(d, x, coef, norm_part, pl, prep, wdw, s);
-    case 2: return fwd_launch<2, 4, STORE>(d, x, coef, norm_part, pl, prep, wdw, s);
-    case 3: return fwd_launch<3, 4, STORE>(d, x, coef, norm_part, pl, prep, wdw, s);
-    case 4: return fwd_launch<4, 4, STORE>(d, x, coef, norm_part, pl, prep, wdw, s);
+    case 1: return v4 ? fwd_launch<1, 4, STORE>(d, x, coef, norm_part, max_part, pl, prep, wdw, s)
+                      : fwd_launch<1, 2, STORE>(d, x, coef, norm_part, max_part, pl, prep, wdw, s);
+    case 2: return fwd_launch<2, 4, STORE>(d, x, coef, norm_part, max_part, pl, prep, wdw, s);
+    case 3: return fwd_launch<3, 4, STORE>(d, x, coef, norm_part, max_part, pl, prep, wdw, s);
+    case 4: return fwd_launch<4, 4, STORE>(d, x, coef, norm_part, max_part, pl, prep, wdw, s);
   }
   return hipErrorInvalidValue;
 }
@@ -293,13 +330,13 @@ Plan fwd_plan(const wcc_desc &d, int G) {
 
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part, int G,
                            const SelectPrep &prep, hipStream_t s) {
-  return fwd_dispatch<true>(d, x, coef, norm_part, fwd_plan(d, G), prep, nullptr, s);
+  return fwd_dispatch<true>(d, x, coef, norm_part, nullptr, fwd_plan(d, G), prep, nullptr, s);
 }
 
-hipError_t launch_haar_norm(const wcc_desc &d, const void *x, float *norm_part, int G,
-                            const SelectPrep &prep, const float *wdw, hipStream_t s) {
+hipError_t launch_haar_norm(const wcc_desc &d, const void *x, float *norm_part, float *max_part,
+                            int G, const SelectPrep &prep, const float *wdw, hipStream_t s) {
   const Plan pl = fwd_plan(d, G);
-  return fwd_dispatch<false>(d, x, nullptr, norm_part, pl, prep, wdw, s);
+  return fwd_dispatch<false>(d, x, nullptr, norm_part, max_part, pl, prep, wdw, s);
 }
 
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s) {

@@ -100,14 +100,18 @@ struct KeepStagedSink {
 };
 
 // grid = (ceil(units/4), G, B), block = 256.  DWM as in haar_fwd_kernel.  Q8: xc is int8 codes
-// for the clipping parameter q_alpha (> 0), and alpha_slots must be null.
+// for the clipping parameter q_alpha (> 0) or, if alpha_src is given, for the largest of its
+// n_alpha entries (what the selection found as max |kept coefficient|); alpha_slots must be
+// null then.
 template <int D, int V, int PF, int DWM, bool Q8, class XT, bool NT = false>
 __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x,
                                                         const int32_t *__restrict__ jmap,
                                                         void *__restrict__ xc, float *alpha_slots,
                                                         Geo g, StripMap m, int C, int Cg, int cstep,
                                                         int64_t k, const float *__restrict__ wdw,
-                                                        float q_alpha) {
+                                                        float q_alpha,
+                                                        const float *__restrict__ alpha_src,
+                                                        int n_alpha, float *alpha_pub) {
   __shared__ float wmax[4];
   const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int grp = blockIdx.y, b = blockIdx.z;
@@ -121,7 +125,7 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
   const int64_t kstep = (int64_t)cstep * k;
 
   using Sink = KeepSink<D, V, Q8>;
-  Sink sink(Q8 ? q_alpha : 0.f);
+  Sink sink(0.f);
   const int32_t *jm = jmap + (size_t)b * g.N;
   auto fetch = [&](auto Lc, auto Jc) {
     constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
@@ -149,6 +153,17 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
   if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
   if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
   if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
+  if constexpr (Q8) {
+    // The clipping parameter the selection found: the largest of its workgroups' maxima.  Taken
+    // here, behind the rank loads, so that the two round trips to memory overlap.  The first
+    // workgroup leaves it as one float for the contraction that follows.
+    if (alpha_src != nullptr) {  // (uniform over the grid)
+      q_alpha = alpha_max(alpha_src, n_alpha);
+      if (alpha_pub != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)
+        alpha_pub[0] = q_alpha;
+    }
+    sink.quant = Quant(q_alpha);
+  }
   using Out = typename Sink::Out;
   const XT *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
   Out *plane = static_cast<Out *>(xc) + ((size_t)b * C + c0) * k;
@@ -251,7 +266,8 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
 
 template <int D, int V, class XT>
 hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_t *jmap, void *xc,
-                         float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
+                         float *alpha_slots, Plan pl, const float *wdw, float q_alpha,
+                         const float *alpha_src, int n_alpha, float *alpha_pub, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V);
   const int Cg = (d.C_in + pl.G - 1) / pl.G;
@@ -261,15 +277,15 @@ hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_
   // consecutive channels and keeps the blocks.
   const int cstep = wdw == nullptr ? pl.G : 1;
   dim3 grid((m.units + 3) / 4, pl.G, d.B);
-  const bool q8 = q_alpha > 0.f;
+  const bool q8 = q_alpha > 0.f || alpha_src != nullptr;
 #define WCC_KEEP(PF, DWM)                                                                          \
   do {                                                                                             \
     if (q8)                                                                                        \
       hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, true, XT>), grid, dim3(256), 0, s, x,   \
-                         jmap, xc, nullptr, g, m, d.C_in, Cg, cstep, k, wdw, q_alpha);                    \
+                         jmap, xc, nullptr, g, m, d.C_in, Cg, cstep, k, wdw, q_alpha, alpha_src, n_alpha, alpha_pub);                    \
     else                                                                                           \
       hipLaunchKernelGGL((haar_keep_kernel<D, V, PF, DWM, false, XT>), grid, dim3(256), 0, s, x,  \
-                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, cstep, k, wdw, 0.f);                    \
+                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, cstep, k, wdw, 0.f, nullptr, 0, nullptr);                    \
   } while (0)
   if constexpr (V == 4) {
     if (wdw != nullptr) {  // K_dw in front of the transform
@@ -281,10 +297,10 @@ hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_
   if (pl.stream) {
     if (q8)
       hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0, true, XT, true>), grid, dim3(256), 0, s, x,
-                         jmap, xc, nullptr, g, m, d.C_in, Cg, cstep, k, wdw, q_alpha);
+                         jmap, xc, nullptr, g, m, d.C_in, Cg, cstep, k, wdw, q_alpha, alpha_src, n_alpha, alpha_pub);
     else
       hipLaunchKernelGGL((haar_keep_kernel<D, V, 1, 0, false, XT, true>), grid, dim3(256), 0, s, x,
-                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, cstep, k, wdw, 0.f);
+                         jmap, xc, alpha_slots, g, m, d.C_in, Cg, cstep, k, wdw, 0.f, nullptr, 0, nullptr);
     return hipGetLastError();
   }
   WCC_KEEP(1, 0);
@@ -294,33 +310,35 @@ hipError_t keep_launch_t(const wcc_desc &d, int64_t k, const XT *x, const int32_
 
 template <int D, int V>
 hipError_t keep_launch(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap, void *xc,
-                       float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
+                       float *alpha_slots, Plan pl, const float *wdw, float q_alpha,
+                       const float *alpha_src, int n_alpha, float *alpha_pub, hipStream_t s) {
   if (d.act_dtype == WCC_BF16)
-    return keep_launch_t<D, V>(d, k, static_cast<const bf16_t *>(x), jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
-  return keep_launch_t<D, V>(d, k, static_cast<const float *>(x), jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+    return keep_launch_t<D, V>(d, k, static_cast<const bf16_t *>(x), jmap, xc, alpha_slots, pl, wdw, q_alpha, alpha_src, n_alpha, alpha_pub, s);
+  return keep_launch_t<D, V>(d, k, static_cast<const float *>(x), jmap, xc, alpha_slots, pl, wdw, q_alpha, alpha_src, n_alpha, alpha_pub, s);
 }
 
 }  // namespace
 
 hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap, void *xc,
-                         float *alpha_slots, Plan pl, const float *wdw, float q_alpha, hipStream_t s) {
+                         float *alpha_slots, Plan pl, const float *wdw, float q_alpha,
+                         const float *alpha_src, int n_alpha, float *alpha_pub, hipStream_t s) {
   const bool v4 = d.W % 4 == 0;
   switch (d.levels) {
-    case 1: return v4 ? keep_launch<1, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s)
-                      : keep_launch<1, 2>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
-    case 2: return keep_launch<2, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
-    case 3: return keep_launch<3, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
-    case 4: return keep_launch<4, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+    case 1: return v4 ? keep_launch<1, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, alpha_src, n_alpha, alpha_pub, s)
+                      : keep_launch<1, 2>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, alpha_src, n_alpha, alpha_pub, s);
+    case 2: return keep_launch<2, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, alpha_src, n_alpha, alpha_pub, s);
+    case 3: return keep_launch<3, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, alpha_src, n_alpha, alpha_pub, s);
+    case 4: return keep_launch<4, 4>(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, alpha_src, n_alpha, alpha_pub, s);
   }
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap,
                             void *xc, float *alpha_slots, const float *wdw, float q_alpha,
-                            hipStream_t s) {
+                            const float *alpha_src, int n_alpha, float *alpha_pub, hipStream_t s) {
   const Plan pl{groups_for(d, d.C_in, arithmetic_bound(d, wdw != nullptr) ? 4096 : 1024, 8), false,
                 streams(d)};
-  return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, s);
+  return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, alpha_src, n_alpha, alpha_pub, s);
 }
 
 }  // namespace wcc

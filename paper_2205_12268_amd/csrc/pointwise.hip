@@ -39,11 +39,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(int)))) int intx16;
 
 constexpr int BK = 64;
 
-// The layer's alpha: one float, or the max of the gather's slots.  The first workgroup also
-// publishes it to alpha_out (nullable).  Called by every thread of the workgroup.
-__device__ __forceinline__ float load_alpha(const float *__restrict__ alpha, bool slots,
-                                            float *alpha_out) {
-  const float a = slots ? alpha_from_slots(alpha) : alpha[0];
+// The layer's alpha: the largest of n partial maxima (n = 1: alpha itself).  The first workgroup
+// also publishes it to alpha_out (nullable).  Called by every thread of the workgroup.
+__device__ __forceinline__ float load_alpha(const float *__restrict__ alpha, int n, float *alpha_out) {
+  const float a = alpha_max(alpha, n);
   if (alpha_out && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)
     alpha_out[0] = a;
   return a;
@@ -87,7 +86,7 @@ struct Patch {
 template <int BM, int BN, bool F32, bool I8W>
 __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
     const void *__restrict__ w, const float *__restrict__ w_scale, const void *__restrict__ xq,
-    const float *__restrict__ alpha, bool slots, float *alpha_out, float *__restrict__ yc, int M,
+    const float *__restrict__ alpha, int n_alpha, float *alpha_out, float *__restrict__ yc, int M,
     int K, int64_t k, bool stream_out) {
   constexpr int T = 2 * BM;
   constexpr int NB = BN / 32;                // 32-column blocks of the tile: 4 or 2
@@ -108,7 +107,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   const int g = t % NG, kq = t / NG;         // activation loader: n group (4 n), channel group
   const int nchunks = (K + BK - 1) / BK;
 
-  const float al = load_alpha(alpha, slots, alpha_out);
+  const float al = load_alpha(alpha, n_alpha, alpha_out);
   const Quant quant(al);
   // A workgroup takes the row tiles blockIdx.y, blockIdx.y + gridDim.y, ...: with one workgroup
   // per column tile (gridDim.y = 1) the stores of a row tile drain while the next one is being
@@ -252,7 +251,7 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
 
 template <int BM, int BN, bool I8W>
 hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
-                       const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
+                       const void *xc, bool f32, const float *alpha, int n_alpha, float *alpha_out,
                        float *yc, hipStream_t s) {
   dim3 grid((unsigned)((k + BN - 1) / BN), (d.C_out + BM - 1) / BM, d.B), block(2 * BM);
   // several row tiles: one workgroup walks them all where the column tiles alone fill the chip
@@ -262,10 +261,10 @@ hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float 
   const bool stream_out = (int64_t)d.B * d.C_out * k * 4 > ((int64_t)512 << 20);
   if (f32)
     hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, true, I8W>), grid, block, 0, s, w, w_scale,
-                       xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k, stream_out);
+                       xc, alpha, n_alpha, alpha_out, yc, d.C_out, d.C_in, k, stream_out);
   else
     hipLaunchKernelGGL((pointwise_mfma_kernel<BM, BN, false, I8W>), grid, block, 0, s, w, w_scale,
-                       xc, alpha, slots, alpha_out, yc, d.C_out, d.C_in, k, stream_out);
+                       xc, alpha, n_alpha, alpha_out, yc, d.C_out, d.C_in, k, stream_out);
   return hipGetLastError();
 }
 
@@ -273,10 +272,10 @@ hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float 
 // once), as long as they give every compute unit a workgroup; otherwise smaller ones.
 template <bool I8W>
 hipError_t mfma_dispatch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
-                         const void *xc, bool f32, const float *alpha, bool slots, float *alpha_out,
+                         const void *xc, bool f32, const float *alpha, int n_alpha, float *alpha_out,
                          float *yc, hipStream_t s) {
 #define WCC_MFMA(BM_, BN_) \
-  return mfma_launch<BM_, BN_, I8W>(d, k, w, w_scale, xc, f32, alpha, slots, alpha_out, yc, s)
+  return mfma_launch<BM_, BN_, I8W>(d, k, w, w_scale, xc, f32, alpha, n_alpha, alpha_out, yc, s)
   const int64_t want = 256;  // compute units
   auto wgs = [&](int bm, int bn) {
     return ((k + bn - 1) / bn) * ((d.C_out + bm - 1) / bm) * (int64_t)d.B;
@@ -315,7 +314,7 @@ __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restri
                                                             const float *__restrict__ w_scale,
                                                             const void *__restrict__ xc,
                                                             const float *__restrict__ alpha,
-                                                            bool slots, float *alpha_out,
+                                                            int n_alpha, float *alpha_out,
                                                             float *__restrict__ yc, int M, int K,
                                                             int64_t k) {
   __shared__ float Ws[FK][FT + 1];
@@ -324,7 +323,7 @@ __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restri
   const int b = blockIdx.z, m0 = blockIdx.y * FT;
   const int64_t n0 = (int64_t)blockIdx.x * FT;
   float acc[4][4] = {};
-  const float al = XM != 0 ? load_alpha(alpha, slots, alpha_out) : 0.f;
+  const float al = XM != 0 ? load_alpha(alpha, n_alpha, alpha_out) : 0.f;
   const Quant quant(al);
   for (int k0 = 0; k0 < K; k0 += FK) {
     // Ws[kk][mm] = w[m0 + mm][k0 + kk]
@@ -376,41 +375,41 @@ __global__ __launch_bounds__(256) void pointwise_fma_kernel(const void *__restri
 
 template <int WDT, int XM>
 hipError_t fma_launch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
-                      const void *xc, const float *alpha, bool slots, float *alpha_out, float *yc,
+                      const void *xc, const float *alpha, int n_alpha, float *alpha_out, float *yc,
                       hipStream_t s) {
   dim3 grid((unsigned)((k + FT - 1) / FT), (d.C_out + FT - 1) / FT, d.B);
   hipLaunchKernelGGL((pointwise_fma_kernel<WDT, XM>), grid, dim3(256), 0, s, w, w_scale, xc, alpha,
-                     slots, alpha_out, yc, d.C_out, d.C_in, k);
+                     n_alpha, alpha_out, yc, d.C_out, d.C_in, k);
   return hipGetLastError();
 }
 
 template <int WDT>
 hipError_t fma_dispatch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
-                        const void *xc, int xm, const float *alpha, bool slots, float *alpha_out,
+                        const void *xc, int xm, const float *alpha, int n_alpha, float *alpha_out,
                         float *yc, hipStream_t s) {
   switch (xm) {
-    case 0: return fma_launch<WDT, 0>(d, k, w, w_scale, xc, alpha, slots, alpha_out, yc, s);
-    case 1: return fma_launch<WDT, 1>(d, k, w, w_scale, xc, alpha, slots, alpha_out, yc, s);
-    default: return fma_launch<WDT, 2>(d, k, w, w_scale, xc, alpha, slots, alpha_out, yc, s);
+    case 0: return fma_launch<WDT, 0>(d, k, w, w_scale, xc, alpha, n_alpha, alpha_out, yc, s);
+    case 1: return fma_launch<WDT, 1>(d, k, w, w_scale, xc, alpha, n_alpha, alpha_out, yc, s);
+    default: return fma_launch<WDT, 2>(d, k, w, w_scale, xc, alpha, n_alpha, alpha_out, yc, s);
   }
 }
 
 }  // namespace
 
 hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
-                            const void *xc, bool xc_is_f32, const float *alpha, bool slots,
+                            const void *xc, bool xc_is_f32, const float *alpha, int n_alpha,
                             float *alpha_out, float *yc, hipStream_t s) {
   const bool quant = d.act_quant_bits == 8;
   const int K = d.C_in;
   if (quant && d.w_dtype == WCC_BF16 && K % 8 == 0 && k % 4 == 0)
-    return mfma_dispatch<false>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s);
+    return mfma_dispatch<false>(d, k, w, w_scale, xc, xc_is_f32, alpha, n_alpha, alpha_out, yc, s);
   if (quant && d.w_dtype == WCC_I8 && K % 16 == 0 && k % 4 == 0)
-    return mfma_dispatch<true>(d, k, w, w_scale, xc, xc_is_f32, alpha, slots, alpha_out, yc, s);
+    return mfma_dispatch<true>(d, k, w, w_scale, xc, xc_is_f32, alpha, n_alpha, alpha_out, yc, s);
   const int xm = !quant ? 0 : (xc_is_f32 ? 2 : 1);
   switch (d.w_dtype) {
-    case WCC_F32: return fma_dispatch<WCC_F32>(d, k, w, w_scale, xc, xm, alpha, slots, alpha_out, yc, s);
-    case WCC_BF16: return fma_dispatch<WCC_BF16>(d, k, w, w_scale, xc, xm, alpha, slots, alpha_out, yc, s);
-    case WCC_I8: return fma_dispatch<WCC_I8>(d, k, w, w_scale, xc, xm, alpha, slots, alpha_out, yc, s);
+    case WCC_F32: return fma_dispatch<WCC_F32>(d, k, w, w_scale, xc, xm, alpha, n_alpha, alpha_out, yc, s);
+    case WCC_BF16: return fma_dispatch<WCC_BF16>(d, k, w, w_scale, xc, xm, alpha, n_alpha, alpha_out, yc, s);
+    case WCC_I8: return fma_dispatch<WCC_I8>(d, k, w, w_scale, xc, xm, alpha, n_alpha, alpha_out, yc, s);
   }
   return hipErrorInvalidValue;
 }

@@ -153,6 +153,35 @@ __device__ __forceinline__ uint4 load_keys(const float *__restrict__ src, float 
                     __float_as_uint(v.w));
 }
 
+// max over the G channel groups of their largest |coefficient| at this thread's four positions
+// (top_part [G, B, N], written by the norm-only transform pass)
+__device__ __forceinline__ float4 load_top(const float *__restrict__ top_part, int G, int64_t BN,
+                                           int64_t at) {
+  float4 m = *reinterpret_cast<const float4 *>(top_part + at);
+  for (int g = 1; g < G; ++g) {
+    const float4 t = *reinterpret_cast<const float4 *>(top_part + (int64_t)g * BN + at);
+    m.x = fmaxf(m.x, t.x); m.y = fmaxf(m.y, t.y); m.z = fmaxf(m.z, t.z); m.w = fmaxf(m.w, t.w);
+  }
+  return m;
+}
+
+// block_top[slot] = the workgroup's largest kept |coefficient| (v >= 0 in every thread, all
+// threads of the workgroup call; `tmp` has NW entries).  A plain store per workgroup: the
+// consumers take the maximum over all of them.
+template <int NW>
+__device__ __forceinline__ void publish_top(float v, float *block_top, size_t slot, uint32_t *tmp) {
+  const uint32_t w = wave_extreme<true>(__float_as_uint(v));  // (>= 0: floats order like their bits)
+  __syncthreads();  // tmp may still be read from a previous use
+  if ((threadIdx.x & 63) == 0) tmp[threadIdx.x >> 6] = w;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) mine = max(mine, tmp[i]);
+    block_top[slot] = __uint_as_float(mine);
+  }
+}
+
 // Turns the finished histogram of pass P into the digit that holds the remaining rank:
 // the digit D with count(> D) < remain <= count(>= D), scanning from the top digit down.
 // Every thread returns the same (prefix, remain) for the next pass.
@@ -269,7 +298,10 @@ __global__ __launch_bounds__(kThreads) void select_hist_kernel(const float *__re
 }
 
 // Ordered compaction.  grid = (nblk, B), block = 256.  jmap (nullable) gets the rank of
-// every kept position and -1 for every dropped one.
+// every kept position and -1 for every dropped one.  top_part (nullable, [G, B, N]): the largest
+// |coefficient| over the channels at every position; its maximum over the positions this
+// workgroup keeps goes to block_top[b, blockIdx.x] (the largest of those is the layer's clipping
+// parameter alpha).
 __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__restrict__ norm,
                                                                int64_t N, int64_t k,
                                                                const uint32_t *__restrict__ hist,
@@ -277,7 +309,9 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__re
                                                                const uint16_t *__restrict__ block_sfx,
                                                                const uint32_t *__restrict__ block_gthi,
                                                                int nblk, int32_t *__restrict__ idx,
-                                                               int32_t *__restrict__ jmap) {
+                                                               int32_t *__restrict__ jmap,
+                                                               const float *__restrict__ top_part,
+                                                               int G, int B, float *block_top) {
   __shared__ uint32_t tmp[kWaves];
   __shared__ uint32_t bcast[2];
   const int b = blockIdx.y, t = threadIdx.x;
@@ -287,6 +321,8 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__re
   const bool in = q0 < N;
   uint4 k4 = make_uint4(0, 0, 0, 0);
   if (in) k4 = *reinterpret_cast<const uint4 *>(keys + q0);
+  float4 top4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (in && top_part) top4 = load_top(top_part, G, (int64_t)B * N, (int64_t)b * N + q0);
   uint32_t T, r_take;  // threshold key, and how many keys equal to it are still needed
   current_state<3>(hist + (size_t)b * 3 * kRadixBins, st + b, (uint32_t)k, T, r_take, tmp, bcast,
                    blockIdx.x == 0);
@@ -311,20 +347,26 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__re
     if (in) packed += ((key[e] > T) << 16) + (key[e] == T);
   const uint32_t ex = block_exclusive_scan(packed, tmp);
   uint32_t gt = gt0 + (ex >> 16), eq = eq0 + (ex & 0xFFFFu);
-  if (!in) return;
 
-  int32_t *out = idx + (size_t)b * k;
-  int32_t jm[4];
+  float kept_top = 0.f;
+  if (in) {
+    int32_t *out = idx + (size_t)b * k;
+    const float top[4] = {top4.x, top4.y, top4.z, top4.w};
+    int32_t jm[4];
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const bool is_gt = key[e] > T, is_eq = key[e] == T;
-    const bool keep = is_gt || (is_eq && eq < r_take);
-    const uint32_t j = gt + min(eq, r_take);
-    if (keep) out[j] = (int32_t)(q0 + e);
-    jm[e] = keep ? (int32_t)j : -1;
-    gt += is_gt; eq += is_eq;
+    for (int e = 0; e < 4; ++e) {
+      const bool is_gt = key[e] > T, is_eq = key[e] == T;
+      const bool keep = is_gt || (is_eq && eq < r_take);
+      const uint32_t j = gt + min(eq, r_take);
+      if (keep) out[j] = (int32_t)(q0 + e);
+      jm[e] = keep ? (int32_t)j : -1;
+      kept_top = fmaxf(kept_top, keep ? top[e] : 0.f);
+      gt += is_gt; eq += is_eq;
+    }
+    if (jmap) *reinterpret_cast<int4 *>(jmap + (size_t)b * N + q0) = make_int4(jm[0], jm[1], jm[2], jm[3]);
   }
-  if (jmap) *reinterpret_cast<int4 *>(jmap + (size_t)b * N + q0) = make_int4(jm[0], jm[1], jm[2], jm[3]);
+  if (top_part)  // (uniform over the grid)
+    publish_top<kWaves>(kept_top, block_top, (size_t)b * nblk + blockIdx.x, tmp);
 }
 
 // ---- small planes: the whole select of one sample in ONE workgroup -------------------------
@@ -399,25 +441,30 @@ __device__ __forceinline__ void small_pass(const uint32_t (&rel)[4 * kSmallSlots
 template <bool REDUCE>
 __global__ __launch_bounds__(kSmallThreads) void select_small_kernel(
     const float *__restrict__ src, float *__restrict__ norm, int G, int64_t N, int B, uint32_t k,
-    int slots, int32_t *__restrict__ idx, int32_t *__restrict__ jmap) {
+    int slots, int32_t *__restrict__ idx, int32_t *__restrict__ jmap,
+    const float *__restrict__ top_part, float *block_top) {
   __shared__ uint32_t lh[kRadixBins];
   __shared__ uint32_t tmp[kSmallSlots * kSmallWaves];
   __shared__ uint32_t bcast[2];
   const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
   uint32_t rel[4 * kSmallSlots];
+  float topv[4 * kSmallSlots];  // largest |coefficient| over the channels at the key's position
   uint32_t vmask = 0;  // bit s: slot s of this thread lies inside the plane (N is a multiple of 4)
   uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
 #pragma unroll
   for (int s = 0; s < kSmallSlots; ++s) {
     const int64_t pos = ((int64_t)s * kSmallThreads + t) * 4;
     uint4 k4 = make_uint4(0, 0, 0, 0);
+    float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
     if (s < slots && pos < N) {
       k4 = load_keys<REDUCE>(src, norm, G, (int64_t)B * N, (int64_t)b * N + pos);
+      if (top_part) t4 = load_top(top_part, G, (int64_t)B * N, (int64_t)b * N + pos);
       vmask |= 1u << s;
       kmin = min(kmin, min(min(k4.x, k4.y), min(k4.z, k4.w)));
       kmax = max(kmax, max(max(k4.x, k4.y), max(k4.z, k4.w)));
     }
     rel[4 * s] = k4.x; rel[4 * s + 1] = k4.y; rel[4 * s + 2] = k4.z; rel[4 * s + 3] = k4.w;
+    topv[4 * s] = t4.x; topv[4 * s + 1] = t4.y; topv[4 * s + 2] = t4.z; topv[4 * s + 3] = t4.w;
   }
   // smallest and largest key of the sample
   kmin = wave_extreme<false>(kmin);
@@ -464,6 +511,7 @@ __global__ __launch_bounds__(kSmallThreads) void select_small_kernel(
   __syncthreads();
 
   int32_t *out = idx + (size_t)b * k;
+  float kept_top = 0.f;  // largest |coefficient| over the channels at a kept position
 #pragma unroll
   for (int s = 0; s < kSmallSlots; ++s) {
     if ((vmask >> s) & 1u) {
@@ -480,11 +528,14 @@ __global__ __launch_bounds__(kSmallThreads) void select_small_kernel(
         const uint32_t j = gt + min(eq, r_take);
         if (keep) out[j] = (int32_t)(pos + e);
         jm[e] = keep ? (int32_t)j : -1;
+        kept_top = fmaxf(kept_top, keep ? topv[4 * s + e] : 0.f);
         gt += is_gt; eq += is_eq;
       }
       if (jmap) *reinterpret_cast<int4 *>(jmap + (size_t)b * N + pos) = make_int4(jm[0], jm[1], jm[2], jm[3]);
     }
   }
+  if (top_part)  // (uniform over the grid)
+    publish_top<kSmallWaves>(kept_top, block_top, (size_t)b, tmp);
 }
 
 // jmap from an arbitrary ascending index list: fill with -1, then jmap[b][idx[b][j]] = j
@@ -532,6 +583,11 @@ SelectPrep make_prep(void *ws_base, const WsLayout &L, float *alpha_slots, float
   return p;
 }
 
+// how many partial maxima launch_select leaves in block_top: one per workgroup of its last kernel
+int select_top_count(const wcc_desc &d, const WsLayout &L) {
+  return (int64_t)d.H * d.W <= kSmallMaxN ? d.B : d.B * L.nblk;
+}
+
 hipError_t launch_select_init(const SelectPrep &p, int B, hipStream_t s) {
   hipLaunchKernelGGL(select_init_kernel, dim3(B), dim3(256), 0, s, p, B);
   return hipGetLastError();
@@ -539,7 +595,7 @@ hipError_t launch_select_init(const SelectPrep &p, int B, hipStream_t s) {
 
 hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, float *norm_out,
                          int64_t k, void *ws_base, const WsLayout &L, int32_t *idx, int32_t *jmap,
-                         hipStream_t s) {
+                         const float *top_part, float *block_top, hipStream_t s) {
   const int64_t N = (int64_t)d.H * d.W;
   char *ws = static_cast<char *>(ws_base);
   uint32_t *hist = reinterpret_cast<uint32_t *>(ws + L.hist);
@@ -552,10 +608,10 @@ hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, fl
     const int slots = (int)((N + 4 * kSmallThreads - 1) / (4 * kSmallThreads));
     if (G > 1)
       hipLaunchKernelGGL((select_small_kernel<true>), dim3(d.B), dim3(kSmallThreads), 0, s,
-                         norm_or_part, norm_out, G, N, d.B, k32, slots, idx, jmap);
+                         norm_or_part, norm_out, G, N, d.B, k32, slots, idx, jmap, top_part, block_top);
     else
       hipLaunchKernelGGL((select_small_kernel<false>), dim3(d.B), dim3(kSmallThreads), 0, s,
-                         norm_or_part, nullptr, 1, N, d.B, k32, slots, idx, jmap);
+                         norm_or_part, nullptr, 1, N, d.B, k32, slots, idx, jmap, top_part, block_top);
     return hipGetLastError();
   }
   dim3 grid(nblk, d.B), block(kThreads);
@@ -573,7 +629,7 @@ hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, fl
   hipLaunchKernelGGL((select_hist_kernel<2, false>), grid, block, 0, s, norm, nullptr, 1, N, d.B, k32,
                      hist, st, nblk, sfx, gthi);
   hipLaunchKernelGGL(select_emit_kernel, grid, block, 0, s, norm, N, k, hist, st, sfx, gthi, nblk, idx,
-                     jmap);
+                     jmap, top_part, G, d.B, block_top);
   return hipGetLastError();
 }
 

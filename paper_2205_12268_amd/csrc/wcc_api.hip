@@ -104,6 +104,7 @@ WsLayout ws_layout(const wcc_desc &d, bool folded_dw) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
   L.norm_part = take((size_t)L.G * B * N * 4);
+  L.max_part = take(d.act_quant_bits == 8 ? (size_t)L.G * B * N * 4 : 0);
   L.norm = take(B * N * 4);
   L.hist = take(B * 3 * kRadixBins * 4);
   L.state = take(B * sizeof(SelectState));
@@ -112,6 +113,7 @@ WsLayout ws_layout(const wcc_desc &d, bool folded_dw) {
   L.jmap = take(B * N * 4);
   L.idx = take(B * k * 4);
   L.alpha = take(256);
+  L.block_top = take(d.act_quant_bits == 8 ? B * (size_t)L.nblk * 4 : 0);
   L.scratch = take(kInvScratchBytes);
   L.xc32 = take(B * (size_t)d.C_in * k * 4);
   L.yc = take(B * (size_t)d.C_out * k * 4);
@@ -124,15 +126,15 @@ WsLayout ws_layout(const wcc_desc &d, bool folded_dw) {
 // The contraction, with 4-bit weight codes widened to int8 in the workspace first.
 hipError_t pointwise_any(char *ws, const WsLayout &L, const wcc_desc &d, int64_t k, const void *w,
                          const float *w_scale, const void *xc, bool xc_is_f32, const float *alpha,
-                         bool alpha_is_slots, float *alpha_out, float *yc, hipStream_t s) {
+                         int n_alpha, float *alpha_out, float *yc, hipStream_t s) {
   if (d.w_dtype != WCC_I4)
-    return launch_pointwise(d, k, w, w_scale, xc, xc_is_f32, alpha, alpha_is_slots, alpha_out, yc, s);
+    return launch_pointwise(d, k, w, w_scale, xc, xc_is_f32, alpha, n_alpha, alpha_out, yc, s);
   int8_t *w8 = reinterpret_cast<int8_t *>(ws + L.w8);
   const hipError_t e = launch_unpack_i4(static_cast<const uint8_t *>(w), w8, (int64_t)d.C_out * d.C_in, s);
   if (e != hipSuccess) return e;
   wcc_desc d8 = d;
   d8.w_dtype = WCC_I8;
-  return launch_pointwise(d8, k, w8, w_scale, xc, xc_is_f32, alpha, alpha_is_slots, alpha_out, yc, s);
+  return launch_pointwise(d8, k, w8, w_scale, xc, xc_is_f32, alpha, n_alpha, alpha_out, yc, s);
 }
 
 // Where the index set I of a layer comes from.
@@ -166,16 +168,35 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
     return hipEventRecord(ctx->ev[stage][which], s);
   };
 
+  // Where the clipping parameter comes from decides in which form the kept coefficients travel.
+  //   caller's alpha:  the second pass decides the codes itself, int8 leaves the chip;
+  //   selected list:   the first pass also keeps max_c |coefficient| per position and the
+  //                    selection's last kernel reduces it over the positions each of its
+  //                    workgroups keeps (block_top), so alpha is known before the second pass,
+  //                    which again decides the codes itself;
+  //   fixed list (no first pass), k % 4 != 0 (the contraction reads four codes a word), or more
+  //   workgroup maxima than a consumer should have to combine:
+  //                    the second pass writes fp32 and raises the slots, the contraction's
+  //                    loader quantises.
+  const bool given = quant && alpha_in > 0.f;
+  const int n_top = select_top_count(d, L);
+  const bool early = quant && !given && list == kListSelect && k % 4 == 0 && n_top <= 8192;
+  const bool codes_now = early || (given && k % 4 == 0);
+  float *tops = reinterpret_cast<float *>(ws + L.block_top);
+  // the contraction finds alpha in the slots: as the largest of them, or (early) as the one
+  // float the second pass left there after combining the selection's maxima
+  const int n_alpha = early ? 1 : kAlphaSlots;
+  float *top = early ? reinterpret_cast<float *>(ws + L.max_part) : nullptr;
   if (list == kListSelect) {
     // A: the transform, first pass: only the channel norms of X_wt leave the chip (the same
     // kernel clears the selection state)
     WCC_TRY(mark(WCC_T_HAAR_FWD, 0));
-    WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, L.G,
+    WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, top, L.G,
                              make_prep(ws, L, slots, quant ? alpha_in : 0.f), wdw, s));
     WCC_TRY(mark(WCC_T_HAAR_FWD, 1));
     // B: norms, index set I (ascending), rank map for the inverse
     WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
-    WCC_TRY(launch_select(d, L.G == 1 ? norm : part, L.G, norm, k, ws, L, idx, jmap, s));
+    WCC_TRY(launch_select(d, L.G == 1 ? norm : part, L.G, norm, k, ws, L, idx, jmap, top, tops, s));
     WCC_TRY(mark(WCC_T_NORM_SELECT, 1));
   } else {
     // a list that does not depend on the input: no norm pass, no selection
@@ -188,16 +209,16 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
     WCC_TRY(mark(WCC_T_NORM_SELECT, 1));
   }
   // A again + B': the transform, second pass: X_wt[I] is written straight into its compressed
-  // place (the dropped coefficients never reach memory); alpha = max |kept coefficient|
+  // place (the dropped coefficients never reach memory)
   WCC_TRY(mark(WCC_T_GATHER, 0));
-  // (with the caller's alpha the codes can be decided right there: int8 leaves the chip)
-  const bool codes_now = quant && alpha_in > 0.f && k % 4 == 0;
-  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !(alpha_in > 0.f)) ? slots : nullptr, wdw,
-                           codes_now ? alpha_in : 0.f, s));
+  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !given && !codes_now) ? slots : nullptr, wdw,
+                           (given && codes_now) ? alpha_in : 0.f, early ? tops : nullptr, n_top,
+                           early ? slots : nullptr, s));
   WCC_TRY(mark(WCC_T_GATHER, 1));
-  // C: Y_wt = Conv(K_1x1, X_wt[I]); the kept coefficients are quantised as they are loaded
+  // C: Y_wt = Conv(K_1x1, X_wt[I]) (kept coefficients still in fp32 are quantised as they are
+  // loaded)
   WCC_TRY(mark(WCC_T_POINTWISE, 0));
-  WCC_TRY(pointwise_any(ws, L, d, k, w, w_scale, xc32, !codes_now, slots, true,
+  WCC_TRY(pointwise_any(ws, L, d, k, w, w_scale, xc32, !codes_now, slots, n_alpha,
                         quant ? alpha_out_dev : nullptr, yc, s));
   WCC_TRY(mark(WCC_T_POINTWISE, 1));
   // D + E: Y^0[I] = Y_wt, inverse levels
@@ -376,7 +397,7 @@ wcc_status wcc_joint_topk(wcc_ctx *ctx, const wcc_desc *desc, const float *coef,
   }
   const int64_t k = k_of(*desc);
   WCC_TRY(launch_select_init(make_prep(ws, L, nullptr, 0.f), desc->B, s));
-  WCC_TRY(launch_select(*desc, norm, 1, nullptr, k, ws, L, idx, nullptr, s));
+  WCC_TRY(launch_select(*desc, norm, 1, nullptr, k, ws, L, idx, nullptr, nullptr, nullptr, s));
   return WCC_OK;
 }
 
@@ -418,7 +439,7 @@ wcc_status wcc_pointwise(wcc_ctx *ctx, const wcc_desc *desc, const void *w, cons
   const WsLayout L = ws_layout(*desc);
   if (desc->w_dtype == WCC_I4 && (st = need_ws(ctx, L)) != WCC_OK) return st;
   WCC_TRY(pointwise_any(static_cast<char *>(ctx->ws), L, *desc, k_of(*desc), w, w_scale, xc,
-                        desc->act_quant_bits == 0, alpha_dev, false, nullptr, yc,
+                        desc->act_quant_bits == 0, alpha_dev, 1, nullptr, yc,
                         static_cast<hipStream_t>(stream)));
   return WCC_OK;
 }

@@ -30,6 +30,7 @@ struct Geo {
 // How the workspace is carved up for one layer (offsets in bytes, all multiples of 256).
 struct WsLayout {
   size_t norm_part;   // [G, B, N] fp32 partial channel norms
+  size_t max_part;    // [G, B, N] fp32 largest |coefficient| of each channel group (8-bit layers)
   size_t norm;        // [B, N] fp32
   size_t hist;        // [B, 3, kRadixBins] u32
   size_t state;       // [B] SelectState
@@ -38,8 +39,9 @@ struct WsLayout {
   size_t jmap;        // [B, N] int32: rank of a kept position, -1 otherwise
   size_t idx;         // [B, k] int32
   size_t alpha;       // kAlphaSlots floats: partial maxima of |kept coefficient|
+  size_t block_top;   // [B, nblk] fp32: the same, one per workgroup of the selection's last kernel
   size_t scratch;     // kInvScratchBytes: sink for the stores of lanes outside the plane
-  size_t xc32;        // [B, C_in, k] fp32
+  size_t xc32;        // [B, C_in, k] fp32, or int8 codes in its first quarter
   size_t yc;          // [B, C_out, k] fp32  (wcc_forward only)
   size_t w8;          // [C_out, C_in] int8: WCC_I4 weights widened (else empty)
   size_t total;
@@ -69,13 +71,21 @@ __device__ inline void prep_sample(const SelectPrep &p, int b, int tid, int nthr
   if (b == 0 && p.alpha && tid < kAlphaSlots) p.alpha[tid] = p.alpha_in > 0.f ? p.alpha_in : 0.f;
 }
 
-// alpha = max over the slots the gather's workgroups raised (all slots hold alpha_in when the
-// caller supplied it).  Called by whole waves; every lane gets the result.
-__device__ __forceinline__ float alpha_from_slots(const float *__restrict__ slots) {
-  float v = slots[threadIdx.x & (kAlphaSlots - 1)];
+// alpha = the largest of n partial maxima (n = 1: alpha itself; kAlphaSlots: the slots the
+// second transform pass raised, or that hold the caller's alpha; otherwise one value per
+// workgroup of the selection's last kernel).  Called by every thread of a workgroup of whole
+// waves (at most 16); every thread gets the result.  Partial maxima are >= 0.
+__device__ __forceinline__ float alpha_max(const float *__restrict__ p, int n) {
+  __shared__ float wave_top[16];
+  float v = 0.f;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) v = fmaxf(v, p[i]);
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  return v;
+  if ((threadIdx.x & (kWave - 1)) == 0) wave_top[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float a = 0.f;
+  for (int i = 0; i < (int)(blockDim.x >> 6); ++i) a = fmaxf(a, wave_top[i]);
+  return a;
 }
 
 // The scale-clip-round of Eq. (quantweights), signed, b = 8, operation by operation in fp32:
@@ -137,12 +147,17 @@ hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float
 // wdw (nullable, [C_in, 3, 3]): the transform's input is the depthwise 3x3 convolution of x
 // with these kernels, computed on the fly; needs W % 4 == 0
 // (x: fp32, or bf16 if d.act_dtype says so; the same for y and residual further down)
-hipError_t launch_haar_norm(const wcc_desc &d, const void *x, float *norm_part, int G,
-                            const SelectPrep &prep, const float *wdw, hipStream_t s);
-// q_alpha > 0: xc is int8 codes for that clipping parameter (alpha_slots unused); else fp32
+// max_part (nullable, [G, B, N]): also receives every group's largest |coefficient| per position
+hipError_t launch_haar_norm(const wcc_desc &d, const void *x, float *norm_part, float *max_part,
+                            int G, const SelectPrep &prep, const float *wdw, hipStream_t s);
+// q_alpha > 0, or alpha_src given (n_alpha floats whose largest is the clipping parameter,
+// read on the device): xc is int8 codes for that clipping parameter (alpha_slots unused); else
+// xc is fp32 and alpha_slots (nullable) is raised to max |kept coefficient|
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap,
                             void *xc, float *alpha_slots /*nullable*/, const float *wdw /*nullable*/,
-                            float q_alpha, hipStream_t s);
+                            float q_alpha, const float *alpha_src /*nullable*/, int n_alpha,
+                            float *alpha_pub /*nullable: receives that largest value*/,
+                            hipStream_t s);
 hipError_t launch_norm_reduce(const float *norm_part, int G, int64_t BN, float *norm, hipStream_t s);
 hipError_t launch_channel_norm(const float *coef, int B, int C, int64_t N, bool squares, float *norm,
                                hipStream_t s);
@@ -150,9 +165,15 @@ SelectPrep make_prep(void *ws_base, const WsLayout &L, float *alpha_slots, float
 hipError_t launch_select_init(const SelectPrep &p, int B, hipStream_t s);
 // G > 1: norm_or_part is [G, B, N] partial norms, reduced into norm_out on the fly;
 // G == 1: norm_or_part is the norm array and norm_out is unused.  Needs prepared state.
+// top_part (nullable, [G, B, N], the max_part of launch_haar_norm): every workgroup of the last
+// kernel writes the largest of its values over the positions it keeps to block_top
+// (select_top_count() floats); the largest of those is max |kept coefficient|.  Plain stores:
+// thousands of atomics arriving together on a few addresses serialise (25 us on 2048 of them).
 hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, float *norm_out,
                          int64_t k, void *ws_base, const WsLayout &L, int32_t *idx,
-                         int32_t *jmap /*nullable*/, hipStream_t s);
+                         int32_t *jmap /*nullable*/, const float *top_part, float *block_top,
+                         hipStream_t s);
+int select_top_count(const wcc_desc &d, const WsLayout &L);
 hipError_t launch_jmap_from_idx(const int32_t *idx, int B, int64_t N, int64_t k, int32_t *jmap,
                                 hipStream_t s);
 // rank map (and index list, nullable) of "the first k positions of every sample"
@@ -166,10 +187,10 @@ hipError_t launch_quantize(const float *xc32, int64_t n, const float *alpha_slot
                            int8_t *codes, hipStream_t s);
 // xc_is_f32 with act_quant_bits = 8: xc holds the unquantised kept coefficients and the
 // kernel quantises them while loading (the fused path); otherwise xc is what the ABI says.
-// alpha_is_slots: alpha points at kAlphaSlots partial maxima (combined in the kernel, and
-// written to alpha_out[0] if that is not null) instead of at one float.
+// alpha points at n_alpha partial maxima whose largest is the clipping parameter (combined in
+// the kernel, and written to alpha_out[0] if that is not null); n_alpha = 1: alpha itself.
 hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const float *w_scale,
-                            const void *xc, bool xc_is_f32, const float *alpha, bool alpha_is_slots,
+                            const void *xc, bool xc_is_f32, const float *alpha, int n_alpha,
                             float *alpha_out, float *yc, hipStream_t s);
 // scratch: kInvScratchBytes of device memory that the kernel may overwrite with anything
 // residual (nullable): [B, C_out, H, W] added to the result (may be y itself)

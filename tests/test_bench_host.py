@@ -11,22 +11,22 @@ from paper_2205_12268_amd import synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
-# Bytes per call worked out by hand from the workload shapes (fp32 maps, 4-byte positions):
-# transform = B*C_in*N*4 read + B*N*4 of norms; inverse = B*C_out*k*4 + B*k*4 + B*C_out*N*4;
-# contraction = B*C_in*k*4 + weights + B*C_out*k*4.
+# Bytes per call worked out by hand from the workload shapes (fp32 maps, 4-byte positions, kept
+# coefficients as 8-bit codes): transform = B*C_in*N*4 read + B*N*4 of norms;
+# inverse = B*C_out*k*4 + B*k*4 + B*C_out*N*4; contraction = B*C_in*k + weights + B*C_out*k*4.
 HAND = {
     2: dict(N=131072, k=32768,
             haar_fwd=134_217_728 + 524_288,
             scatter_ihaar=33_554_432 + 131_072 + 134_217_728,
-            pointwise=33_554_432 + 2 * 65_536 + 33_554_432),
+            pointwise=8_388_608 + 2 * 65_536 + 33_554_432),
     3: dict(N=524_288, k=65_536,
             haar_fwd=536_870_912 + 8_388_608,
             scatter_ihaar=268_435_456 + 1_048_576 + 2_147_483_648,
-            pointwise=67_108_864 + 2 * 16_384 + 268_435_456),
+            pointwise=16_777_216 + 2 * 16_384 + 268_435_456),
     4: dict(N=122_880, k=7_680,
             haar_fwd=503_316_480 + 3_932_160,
             scatter_ihaar=31_457_280 + 245_760 + 503_316_480,
-            pointwise=31_457_280 + 16_384 + 31_457_280),
+            pointwise=7_864_320 + 16_384 + 31_457_280),
 }
 
 
@@ -38,8 +38,11 @@ def test_algorithmic_bytes_match_hand_counts(n):
     got = bench.algorithmic_bytes(cfg)
     for stage in ("haar_fwd", "scatter_ihaar", "pointwise"):
         assert got[stage] == want[stage], stage
-    # the keep pass reads the input again and writes the kept coefficients once
-    assert got["gather"] == 4 * cfg.B * cfg.C_in * (cfg.N + cfg.k) + 4 * cfg.B * cfg.k
+    # the keep pass reads the input again and writes the kept coefficients once, as codes
+    assert got["gather"] == cfg.B * cfg.C_in * (4 * cfg.N + cfg.k) + 4 * cfg.B * cfg.k
+    # kept coefficients that travel as fp32 (a fixed index list with the layer's own alpha)
+    f32 = bench.algorithmic_bytes(cfg, 4, 4)
+    assert f32["gather"] - got["gather"] == 3 * cfg.B * cfg.C_in * cfg.k == f32["pointwise"] - got["pointwise"]
     assert got["norm_select"] == 4 * cfg.B * (cfg.N + cfg.k)
 
 
