@@ -13,7 +13,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(CSRC, "libwcc.so")
 PROBE_LIB = os.path.join(CSRC, "libwcc_probe.so")
 SOURCES = ["haar_fwd.hip", "haar_keep.hip", "haar_inv.hip", "select.hip", "gather.hip", "pointwise.hip",
-           "depthwise.hip", "wcc_api.hip"]
+           "depthwise.hip", "haar_chain.hip", "wcc_api.hip"]
 PROBE_SOURCES = ["stream_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,0 +1,528 @@
+// Compressed-domain chaining of the inverted residual block (appendix "Inference times",
+// paragraph on memory bandwidth and traffic: Haar transform, depthwise convolution and
+// gather / scatter applied separately per channel and in parts, with small intermediates, the
+// full result kept only in compressed form).
+//
+// The project layer's input is K_dw t1 with t1 = iHWT(T^T Y_wt) the expand layer's output.  The
+// two transform passes of the project layer (channel norms; kept coefficients) take t1 from
+// where it already is in compressed form -- the expand layer's Y_wt [B, C, k] and its rank map
+// -- instead of from a feature map in memory: per channel a wave rebuilds the 2^d rows of its
+// strip and the one row above and below it (inverse transform of the kept values, everything
+// else zero), convolves them with the channel's 3x3 kernel and transforms the result again, all
+// in registers and LDS.  The expanded feature map, the largest tensor of the block, is neither
+// written nor read; the passes read k/N of it, twice.  This is also the mirror fusion "inverse
+// transform followed by the depthwise convolution".
+//
+// The arithmetic is that of the kernels it replaces, operation by operation (synthesis
+// butterflies of haar_inv.hip, multiply-adds in the order of depthwise.hip, analysis of strip.h),
+// so the values that enter the norms and the quantiser are the same bits.
+//
+// Limits (the caller falls back to the materialised route otherwise): W % 4 == 0, d <= 3, and
+// a row of the plane fits into one wave row (W <= 256), so that the convolution's outside
+// columns come from neighbouring lanes or are the plane's zero border.
+#include "strip_io.h"
+
+namespace wcc {
+namespace {
+
+constexpr int V4 = 4;
+
+// ---- slots of ONE row of a strip (the halo rows) -------------------------------------------------
+// To rebuild a single image row only the band row that contains it is needed at every level.
+__host__ __device__ constexpr int hslot_base(int D, int V, int l, int j) {
+  int s = 0;
+  for (int m = 1; m < l; ++m) s += 3 * cols_at(V, m);
+  return s + (l == D ? j : j - 1) * cols_at(V, l);
+}
+__host__ __device__ constexpr int hslot_count(int D, int V) {
+  return hslot_base(D, V, D, 3) + cols_at(V, D);
+}
+
+// source of a halo row: the lane's cell of the [slot][lane] tile, slots counted from `first`
+template <int D, int V>
+struct RowStaged {
+  const float *cell;  // &tile[first slot][lane]
+  uint32_t any;       // wave-uniform: bit s set if some lane keeps halo slot s
+  template <int L, int J>
+  __device__ __forceinline__ void get(float (&v)[cols_at(V, L)]) const {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = hslot_base(D, V, L, J);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) v[e] = ((any >> (base + e)) & 1u) ? cell[(base + e) * kWave] : 0.f;
+  }
+};
+
+// One image row of a strip: its last one (BOTTOM) or its first one.  The same expressions as
+// inv_levels evaluates for that row.
+template <int D, int V, int L, bool BOTTOM, class Source>
+__device__ __forceinline__ void inv_row(float (&out)[cols_at(V, L - 1)], const LanePos<D> &p,
+                                        const Source &src) {
+  constexpr int VI = cols_at(V, L - 1), V2 = cols_at(V, L);
+  constexpr int SI = span_at(V, L - 1);
+  float ll[V2];
+  if constexpr (L < D) inv_row<D, V, L + 1, BOTTOM>(ll, p, src);
+  else src.template get<L, 0>(ll);
+  float y2[V2], y3[V2], y4[V2];
+  src.template get<L, 1>(y2);
+  src.template get<L, 2>(y3);
+  src.template get<L, 3>(y4);
+#pragma unroll
+  for (int e = 0; e < V2; ++e) {
+    const float s1 = ll[e] + y3[e], s2 = ll[e] - y3[e];
+    const float d1 = y2[e] + y4[e], d2 = y2[e] - y4[e];
+    const float l = BOTTOM ? 0.5f * (s2 + d2) : 0.5f * (s1 + d1);
+    const float r = BOTTOM ? 0.5f * (s2 - d2) : 0.5f * (s1 - d1);
+    if constexpr (VI >= 2) {
+      out[2 * e] = l;
+      out[2 * e + 1] = r;
+    } else {
+      out[0] = ((p.lc & SI) == 0) ? l : r;
+    }
+  }
+}
+
+// ---- the channel walk ----------------------------------------------------------------------------
+constexpr int kChainCap = 2048;  // packed entries per wave (32 a lane)
+
+// What a wave knows about the producer layer's kept positions around its strip.
+template <int D>
+struct ChainGeo {
+  static constexpr int NS = slot_count(D, V4), HS = hslot_count(D, V4), NT = NS + 2 * HS;
+  uint64_t any;        // wave-uniform: bit s set if some lane keeps slot s (NT <= 64)
+  int count;           // kept entries of the wave (wave-uniform)
+  bool packed;         // the tile holds the wave's packed list (rank | cell << kInvRankBits)
+};
+
+// Calls f(slot, position in the producer's rank map, exists) for the lane's NT slots: the strip's
+// own NS slots, then the HS slots of the band rows that hold the image row above the strip,
+// then those of the row below.
+template <int D, class F>
+__device__ __forceinline__ void chain_slots(const LanePos<D> &p, bool active, bool up_in, bool dn_in,
+                                            F &&f) {
+  constexpr int NS = ChainGeo<D>::NS, HS = ChainGeo<D>::HS;
+  auto band_rows = [&](auto Lc, auto Jc) {
+    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+    constexpr int CV = cols_at(V4, L);
+    const int band = J * p.nl[L] + p.off[L];
+#pragma unroll
+    for (int i = 0; i < rows_at(D, L); ++i)
+#pragma unroll
+      for (int e = 0; e < CV; ++e) f(slot_base(D, V4, L, J) + i * CV + e, band + i * p.rowlen[L] + e, active);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) {
+      f(NS + hslot_base(D, V4, L, J) + e, band - p.rowlen[L] + e, active && up_in);
+      f(NS + HS + hslot_base(D, V4, L, J) + e, band + rows_at(D, L) * p.rowlen[L] + e, active && dn_in);
+    }
+  };
+  auto each_level = [&](auto Lc) {
+    constexpr int L = decltype(Lc)::value;
+    band_rows(Lc, std::integral_constant<int, 1>{});
+    band_rows(Lc, std::integral_constant<int, 2>{});
+    band_rows(Lc, std::integral_constant<int, 3>{});
+    if constexpr (L == D) band_rows(Lc, std::integral_constant<int, 0>{});
+  };
+  each_level(std::integral_constant<int, 1>{});
+  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+}
+
+// Looks up the lane's slots in the producer's rank map jm1 (one sample) and, if the wave keeps
+// at most kChainCap of them (and the ranks fit their bit field), packs (rank, cell) into `tile`:
+// slot-major, then lane.
+template <int D>
+__device__ __forceinline__ ChainGeo<D> chain_setup(const int32_t *__restrict__ jm1, int64_t k1,
+                                                   const LanePos<D> &p, bool active, bool up_in,
+                                                   bool dn_in, uint32_t *tile) {
+  constexpr int NT = ChainGeo<D>::NT;
+  static_assert(NT <= 64, "one 64-bit slot mask");
+  static_assert(NT * kWave <= (1 << (32 - kInvRankBits)), "cell index fits above the rank");
+  const int lane = threadIdx.x & (kWave - 1);
+  int jj[NT];  // rank in the producer's list, or -1
+  chain_slots<D>(p, active, up_in, dn_in, [&](int s, int pos, bool exists) {
+    int j = -1;
+    if (exists) j = jm1[pos];
+    jj[s] = j;
+  });
+  ChainGeo<D> cg;
+  cg.any = 0;
+  cg.count = 0;
+#pragma unroll
+  for (int s = 0; s < NT; ++s) {
+    const uint64_t kept = __ballot(jj[s] >= 0);
+    if (kept != 0) cg.any |= (uint64_t)1 << s;
+    cg.count += __popcll(kept);
+  }
+  cg.packed = cg.count <= kChainCap && cg.count <= NT * kWave && k1 <= ((int64_t)1 << kInvRankBits);
+  if (cg.packed) {
+    int running = 0;
+#pragma unroll
+    for (int s = 0; s < NT; ++s) {
+      if ((cg.any >> s) & 1) {
+        const int j = jj[s];
+        const uint64_t kept = __ballot(j >= 0);
+        const int at = running + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
+        if (j >= 0) tile[at] = (uint32_t)j | ((uint32_t)(s * kWave + lane) << kInvRankBits);
+        running += __popcll(kept);
+      }
+    }
+    wave_lds_fence();
+  }
+  return cg;
+}
+
+// Walks n_ch channels of the producer's compressed output yc1 (first channel at `plane`, channel
+// stride k1): per channel the kept values around the strip go into the wave's [slot][lane] LDS
+// tile (whose other cells stay zero), the strip's 2^d rows and the rows above and below are
+// rebuilt from it, convolved with the channel's 3x3 kernel (wdw: first channel's, 9 floats a
+// channel) and transformed into `sink`; after(sink) runs once per channel.
+// Waves whose list is packed fetch it with dense loads, one channel ahead; the others (strips
+// that keep more than kChainCap positions) look every slot up in the rank map again, channel
+// after channel: slow, and rare.
+template <int D, class Sink, class After>
+__device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int64_t k1, int n_ch,
+                                           const float *__restrict__ wdw, const ChainGeo<D> &cg,
+                                           const int32_t *__restrict__ jm1, bool active, bool up_in,
+                                           bool dn_in, uint32_t *tile, const LanePos<D> &p,
+                                           bool first_lane, bool last_lane, Sink &sink, After &&after) {
+  constexpr int R = 1 << D, RR = R + 2, V = V4;
+  constexpr int NS = ChainGeo<D>::NS, HS = ChainGeo<D>::HS, NT = ChainGeo<D>::NT;
+  const int lane = threadIdx.x & (kWave - 1);
+
+  InvStaged<D, V> own;
+  own.cell = reinterpret_cast<const float *>(tile) + lane;
+  own.any[0] = cg.any;
+  own.any[1] = 0;
+  RowStaged<D, V> up, dn;
+  up.cell = own.cell + NS * kWave;
+  dn.cell = own.cell + (NS + HS) * kWave;
+  up.any = (uint32_t)(cg.any >> NS) & ((1u << HS) - 1u);
+  dn.any = (uint32_t)(cg.any >> (NS + HS)) & ((1u << HS) - 1u);
+
+  // the tile holds a channel's kept values: rebuild, convolve with kw[0..8], transform
+  auto compute = [&](const float *kw) {
+    float k[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) k[t] = kw[t];
+    wave_lds_fence();
+    float six[RR][V + 2];
+    {
+      float mid[R][V];
+      inv_levels<D, V, 1>(mid, p, own);
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < V; ++e) six[r + 1][e + 1] = mid[r][e];
+      float edge[V];
+      inv_row<D, V, 1, true>(edge, p, up);
+#pragma unroll
+      for (int e = 0; e < V; ++e) six[0][e + 1] = edge[e];
+      inv_row<D, V, 1, false>(edge, p, dn);
+#pragma unroll
+      for (int e = 0; e < V; ++e) six[RR - 1][e + 1] = edge[e];
+    }
+    wave_lds_fence();
+#pragma unroll
+    for (int i = 0; i < RR; ++i) {
+      float l = __shfl_up(six[i][V], 1, kWave), r = __shfl_down(six[i][1], 1, kWave);
+      if (first_lane) l = 0.f;  // the plane's zero border
+      if (last_lane) r = 0.f;
+      six[i][0] = l;
+      six[i][V + 1] = r;
+    }
+    float t1[R][V];
+#pragma unroll
+    for (int o = 0; o < R; ++o) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) t1[o][e] = 0.f;
+#pragma unroll
+      for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+#pragma unroll
+          for (int e = 0; e < V; ++e) t1[o][e] = fmaf(k[i * 3 + j], six[o + i][e + j], t1[o][e]);
+    }
+    fwd_levels<D, V, 1>(t1, p, sink);
+    after(sink);
+  };
+
+  if (cg.packed) {
+    auto run = [&](auto ni_c) {
+      constexpr int NI = decltype(ni_c)::value;
+      // lists of more than 16 rows do without the channel of values in flight (registers)
+      constexpr bool AHEAD = NI <= 16;
+      constexpr uint32_t kRank = (1u << kInvRankBits) - 1u;
+      uint32_t mine[NI];  // this lane's share of the list: entries lane + 64 i
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int e = lane + kWave * i;
+        mine[i] = e < cg.count ? tile[e] : kInvNone;
+      }
+      wave_lds_fence();
+#pragma unroll
+      for (int s = 0; s < NT; ++s) tile[s * kWave + lane] = 0u;
+      float vn[AHEAD ? NI : 1];
+      if constexpr (AHEAD) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) vn[i] = plane[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+      }
+      auto channel = [&](int c) {
+        if constexpr (AHEAD) {
+#pragma unroll
+          for (int i = 0; i < NI; ++i)
+            if (mine[i] != kInvNone) tile[mine[i] >> kInvRankBits] = __float_as_uint(vn[i]);
+          // the next channel's values travel while this one is worked on (past the end: the last again)
+          const float *nx = plane + (size_t)min(c + 1, n_ch - 1) * k1;
+#pragma unroll
+          for (int i = 0; i < NI; ++i) vn[i] = nx[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+          __builtin_amdgcn_sched_barrier(0);
+        } else {
+          const float *pc = plane + (size_t)c * k1;
+#pragma unroll
+          for (int i = 0; i < NI; ++i) {
+            const float v = pc[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+            if (mine[i] != kInvNone) tile[mine[i] >> kInvRankBits] = __float_as_uint(v);
+          }
+        }
+        compute(wdw + (size_t)c * 9);
+      };
+      channel(0);
+      for (int c = 1; c < n_ch; ++c) channel(c);
+    };
+    const int ni = (cg.count + kWave - 1) >> 6;
+    if (ni <= 4) run(std::integral_constant<int, 4>{});
+    else if (ni <= 8) run(std::integral_constant<int, 8>{});
+    else if (ni <= 16) run(std::integral_constant<int, 16>{});
+    else run(std::integral_constant<int, 32>{});
+    return;
+  }
+
+  // plain path: every slot is looked up again for every channel
+#pragma unroll
+  for (int s = 0; s < NT; ++s) tile[s * kWave + lane] = 0u;
+  for (int c = 0; c < n_ch; ++c) {
+    const float *pc = plane + (size_t)c * k1;
+    chain_slots<D>(p, active, up_in, dn_in, [&](int s, int pos, bool exists) {
+      if ((cg.any >> s) & 1) {
+        int j = -1;
+        if (exists) j = jm1[pos];
+        if (j >= 0) tile[s * kWave + lane] = __float_as_uint(pc[j]);
+      }
+    });
+    compute(wdw + (size_t)c * 9);
+  }
+}
+
+// LDS of a workgroup: four waves' [slot][lane] tiles
+template <int D>
+struct ChainTiles {
+  static constexpr int kWords = ChainGeo<D>::NT * kWave;
+};
+
+// ---- first pass: channel norms of HWT(K_dw t1) ------------------------------------------------------
+// grid = (ceil(units/4), G, B), block = 256.  yc1 [B, C, k1], jmap1 [B, N]: the producer layer's
+// compressed output and rank map; wdw [C, 3, 3].  Writes the partial norms (and the partial
+// maxima of |coefficient|, nullable) of channel group grp to norm_part / max_part [G, B, N].
+template <int D, bool SQ>
+__global__ __launch_bounds__(256, 2) void chain_norm_kernel(const float *__restrict__ yc1,
+                                                         const int32_t *__restrict__ jmap1,
+                                                         int64_t k1, const float *__restrict__ wdw,
+                                                         float *__restrict__ norm_part,
+                                                         float *__restrict__ max_part, Geo g,
+                                                         StripMap m, int C, int Cg, int B,
+                                                         SelectPrep prep) {
+  constexpr int NS = slot_count(D, V4);
+  __shared__ uint32_t tiles[4][ChainTiles<D>::kWords];
+  const int wv = threadIdx.x >> 6;
+  const int unit = blockIdx.x * 4 + wv;
+  const int grp = blockIdx.y, b = blockIdx.z;
+  // one workgroup per sample clears the state of the selection that follows this kernel
+  if (blockIdx.x == 0 && grp == 0) prep_sample(prep, b, threadIdx.x, 256);
+  LanePos<D> p;
+  int row0, col0;
+  const bool active = locate<D, V4>(m, g, unit, p, row0, col0);
+  const int c0 = grp * Cg, n_ch = min(C, c0 + Cg) - c0;
+  if (__ballot(active) == 0 || n_ch <= 0) return;  // whole waves leave
+
+  const int32_t *jm1 = jmap1 + (size_t)b * g.N;
+  const bool up_in = row0 > 0, dn_in = row0 + (1 << D) < g.H;
+  const ChainGeo<D> cg = chain_setup<D>(jm1, k1, p, active, up_in, dn_in, tiles[wv]);
+
+  FwdSink<D, V4, false, SQ> sink;
+#pragma unroll
+  for (int s = 0; s < NS; ++s) { sink.acc[s] = 0.f; sink.top[s] = 0.f; }
+  sink.plane = nullptr;
+  chain_walk<D>(yc1 + ((size_t)b * C + c0) * k1, k1, n_ch, wdw + (size_t)c0 * 9, cg, jm1, active,
+                up_in, dn_in, tiles[wv], p, p.lc == 0, p.lc == m.lpr - 1 || col0 + V4 >= g.W, sink,
+                [](FwdSink<D, V4, false, SQ> &) {});
+  if (!active) return;
+  write_slots<D, V4>(norm_part + ((size_t)grp * B + b) * g.N, sink.acc, p);
+  if (max_part != nullptr) write_slots<D, V4>(max_part + ((size_t)grp * B + b) * g.N, sink.top, p);
+}
+
+// ---- second pass: the kept coefficients of HWT(K_dw t1) ---------------------------------------------
+// grid = (ceil(units/4), G, B), block = 256.  jmap3: the consumer layer's rank map; xc
+// [B, C, k3] fp32, or int8 codes with Q8 (clipping parameter: q_alpha > 0, or the largest of the
+// n_alpha floats at alpha_src; the first workgroup leaves it at alpha_pub[0]).  Without Q8 the
+// alpha slots (nullable) are raised to max |kept coefficient|.
+template <int D, bool Q8>
+__global__ __launch_bounds__(256, 2) void chain_keep_kernel(const float *__restrict__ yc1,
+                                                         const int32_t *__restrict__ jmap1,
+                                                         int64_t k1, const float *__restrict__ wdw,
+                                                         const int32_t *__restrict__ jmap3,
+                                                         void *__restrict__ xc, int64_t k3,
+                                                         float *alpha_slots, Geo g, StripMap m,
+                                                         int C, int Cg, float q_alpha,
+                                                         const float *__restrict__ alpha_src,
+                                                         int n_alpha, float *alpha_pub) {
+  constexpr int NS = slot_count(D, V4);
+  __shared__ uint32_t tiles[4][ChainTiles<D>::kWords];
+  __shared__ float wmax[4];
+  const int wv = threadIdx.x >> 6;
+  const int unit = blockIdx.x * 4 + wv;
+  const int grp = blockIdx.y, b = blockIdx.z;
+  LanePos<D> p;
+  int row0, col0;
+  const bool active = locate<D, V4>(m, g, unit, p, row0, col0);
+  const int c0 = grp * Cg, n_ch = max(min(C, c0 + Cg) - c0, 0);
+
+  using Sink = KeepSink<D, V4, Q8>;
+  using Out = typename Sink::Out;
+  Sink sink(0.f);
+  // byte offsets of the consumer's ranks (or "dropped")
+  const int32_t *jm3 = jmap3 + (size_t)b * g.N;
+  auto fetch = [&](auto Lc, auto Jc) {
+    constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
+    constexpr int CV = cols_at(V4, L), S2 = span_at(V4, L);
+    const bool owner = (S2 == 1) || ((p.lc & (S2 - 1)) == 0);
+#pragma unroll
+    for (int i = 0; i < rows_at(D, L); ++i)
+#pragma unroll
+      for (int e = 0; e < CV; ++e) {
+        int j = -1;
+        if (active && owner) j = jm3[J * p.nl[L] + p.off[L] + i * p.rowlen[L] + e];
+        sink.at[slot_base(D, V4, L, J) + i * CV + e] = (uint32_t)j;
+      }
+  };
+  auto each_level = [&](auto Lc) {
+    constexpr int L = decltype(Lc)::value;
+    fetch(Lc, std::integral_constant<int, 1>{});
+    fetch(Lc, std::integral_constant<int, 2>{});
+    fetch(Lc, std::integral_constant<int, 3>{});
+    if constexpr (L == D) fetch(Lc, std::integral_constant<int, 0>{});
+  };
+  each_level(std::integral_constant<int, 1>{});
+  if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
+  if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
+
+  const int32_t *jm1 = jmap1 + (size_t)b * g.N;
+  const bool up_in = row0 > 0, dn_in = row0 + (1 << D) < g.H;
+  const ChainGeo<D> cg = chain_setup<D>(jm1, k1, p, active, up_in, dn_in, tiles[wv]);
+
+  if constexpr (Q8) {
+    if (alpha_src != nullptr) {  // (uniform over the grid; every thread of the workgroup is here)
+      q_alpha = alpha_max(alpha_src, n_alpha);
+      if (alpha_pub != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)
+        alpha_pub[0] = q_alpha;
+    }
+    sink.quant = Quant(q_alpha);
+  }
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+    sink.at[s] = (int)sink.at[s] >= 0 ? sink.at[s] * (uint32_t)sizeof(Out) : Sink::kDropped;
+  sink.vmax = 0.f;
+
+  if (__ballot(active) != 0 && n_ch > 0) {
+    Out *plane3 = static_cast<Out *>(xc) + ((size_t)b * C + c0) * k3;
+    sink.aim(plane3, k3);
+    chain_walk<D>(yc1 + ((size_t)b * C + c0) * k1, k1, n_ch, wdw + (size_t)c0 * 9, cg, jm1, active,
+                  up_in, dn_in, tiles[wv], p, p.lc == 0, p.lc == m.lpr - 1 || col0 + V4 >= g.W, sink,
+                  [&plane3, k3](Sink &sk) {
+                    plane3 += k3;
+                    sk.aim(plane3, k3);
+                  });
+  }
+  if constexpr (Q8) return;
+  if (alpha_slots == nullptr) return;
+  float mx = sink.vmax;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  if ((threadIdx.x & 63) == 0) wmax[wv] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    mx = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    unsigned int *a = reinterpret_cast<unsigned int *>(alpha_slots) +
+                      ((blockIdx.x + 3u * blockIdx.y + 11u * blockIdx.z) & (kAlphaSlots - 1));
+    const unsigned int mine = __float_as_uint(mx);
+    if (mine > __hip_atomic_load(a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(a, mine);
+  }
+}
+
+}  // namespace
+
+// Can the project layer d take its input from a producer's compressed output (see the limits at
+// the top of this file)?
+bool chain_supported(const wcc_desc &d) {
+  if (d.W % 4 != 0 || d.levels > 3) return false;
+  const StripMap m = make_map(d, V4);
+  return !dw_needs_edges(m);
+}
+
+hipError_t launch_chain_norm(const wcc_desc &d, const ChainSrc &src, const float *wdw,
+                             float *norm_part, float *max_part, int G, const SelectPrep &prep,
+                             hipStream_t s) {
+  const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
+  const StripMap m = make_map(d, V4);
+  const int Cg = (d.C_in + G - 1) / G;
+  const dim3 grid((m.units + 3) / 4, G, d.B), block(256);
+  const bool sq = d.norm == WCC_NORM_L2;
+#define WCC_CHAIN_NORM(D_)                                                                          \
+  do {                                                                                              \
+    if (sq)                                                                                         \
+      hipLaunchKernelGGL((chain_norm_kernel<D_, true>), grid, block, 0, s, src.yc, src.jmap, src.k, \
+                         wdw, norm_part, max_part, g, m, d.C_in, Cg, d.B, prep);                    \
+    else                                                                                            \
+      hipLaunchKernelGGL((chain_norm_kernel<D_, false>), grid, block, 0, s, src.yc, src.jmap,       \
+                         src.k, wdw, norm_part, max_part, g, m, d.C_in, Cg, d.B, prep);             \
+  } while (0)
+  switch (d.levels) {
+    case 1: WCC_CHAIN_NORM(1); break;
+    case 2: WCC_CHAIN_NORM(2); break;
+    case 3: WCC_CHAIN_NORM(3); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef WCC_CHAIN_NORM
+  return hipGetLastError();
+}
+
+hipError_t launch_chain_keep(const wcc_desc &d, int64_t k, const ChainSrc &src, const float *wdw,
+                             const int32_t *jmap, void *xc, float *alpha_slots, float q_alpha,
+                             const float *alpha_src, int n_alpha, float *alpha_pub, hipStream_t s) {
+  const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
+  const StripMap m = make_map(d, V4);
+  const int G = groups_for(d, d.C_in, 4096, 8);
+  const int Cg = (d.C_in + G - 1) / G;
+  const dim3 grid((m.units + 3) / 4, G, d.B), block(256);
+  const bool q8 = q_alpha > 0.f || alpha_src != nullptr;
+#define WCC_CHAIN_KEEP(D_)                                                                          \
+  do {                                                                                              \
+    if (q8)                                                                                         \
+      hipLaunchKernelGGL((chain_keep_kernel<D_, true>), grid, block, 0, s, src.yc, src.jmap, src.k, \
+                         wdw, jmap, xc, k, nullptr, g, m, d.C_in, Cg, q_alpha, alpha_src, n_alpha,  \
+                         alpha_pub);                                                                \
+    else                                                                                            \
+      hipLaunchKernelGGL((chain_keep_kernel<D_, false>), grid, block, 0, s, src.yc, src.jmap,       \
+                         src.k, wdw, jmap, xc, k, alpha_slots, g, m, d.C_in, Cg, 0.f, nullptr, 0,   \
+                         nullptr);                                                                  \
+  } while (0)
+  switch (d.levels) {
+    case 1: WCC_CHAIN_KEEP(1); break;
+    case 2: WCC_CHAIN_KEEP(2); break;
+    case 3: WCC_CHAIN_KEEP(3); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef WCC_CHAIN_KEEP
+  return hipGetLastError();
+}
+
+}  // namespace wcc

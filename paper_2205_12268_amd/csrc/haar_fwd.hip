@@ -1,43 +1,9 @@
 // First transform pass of the fused layer and the stand-alone analysis (Eq. HaarKernel,
 // Eq. wavelet_transform), with the channel norm of Alg. 1 fused in.
-#include "strip.h"
+#include "strip_io.h"
 
 namespace wcc {
 namespace {
-
-// ---- analysis ---------------------------------------------------------------------------
-// STORE = false: only the |coefficient| sums are kept (the norm-only pass of the fused layer),
-// and beside them the largest |coefficient| over the channels at every position: the largest
-// of those over the positions the selection keeps is the layer's clipping parameter alpha, known
-// that way before the second pass, which can then decide the 8-bit codes itself.
-// SQ: the sums are of squared coefficients (one fused multiply-add each) instead.
-template <int D, int V, bool STORE, bool SQ = false>
-struct FwdSink {
-  static constexpr bool MX = !STORE;
-  float *plane;  // wavelet vector of the current (b, c)
-  float acc[slot_count(D, V)];
-  float top[MX ? slot_count(D, V) : 1];  // max over the channels of |coefficient|
-  template <int L, int J>
-  __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
-                                          bool owner) {
-    constexpr int CV = cols_at(V, L);
-    constexpr int base = slot_base(D, V, L, J);
-#pragma unroll
-    for (int e = 0; e < CV; ++e) {
-      float &a = acc[base + i * CV + e];
-      a = SQ ? fmaf(v[e], v[e], a) : a + fabsf(v[e]);
-      if constexpr (MX) top[base + i * CV + e] = fmaxf(top[base + i * CV + e], fabsf(v[e]));
-    }
-    if (!STORE || !owner) return;
-    float *dst = plane + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
-    if constexpr (CV == 2) {
-      *reinterpret_cast<float2 *>(dst) = make_float2(v[0], v[1]);
-    } else {
-#pragma unroll
-      for (int e = 0; e < CV; ++e) dst[e] = v[e];
-    }
-  }
-};
 
 // x [B, C, H, W] -> coef [B, C, N]; partial norms over this block's channel group to
 // norm_part [G, B, N] (nullable); without STORE also the group's max |coefficient| per position
@@ -132,40 +98,9 @@ __global__ __launch_bounds__(256) void haar_fwd_kernel(const XT *__restrict__ x,
     if (wv > 0) return;
   }
   if (!p.active) return;
-  // write the per-position values with the same addressing as the coefficients
-  auto write_plane = [&](float *np, const float *vals) {
-    auto flush = [&](auto Lc, auto Jc) {
-      constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
-      constexpr int CV = cols_at(V, L), S2 = span_at(V, L);
-      const bool owner = (S2 == 1) || ((p.lc & (S2 - 1)) == 0);
-      if (!owner) return;
-#pragma unroll
-      for (int i = 0; i < rows_at(D, L); ++i) {
-        float *dst = np + (J * p.nl[L] + p.off[L] + i * p.rowlen[L]);
-        if constexpr (CV == 2) {
-          *reinterpret_cast<float2 *>(dst) = make_float2(vals[slot_base(D, V, L, J) + i * CV],
-                                                         vals[slot_base(D, V, L, J) + i * CV + 1]);
-        } else {
-#pragma unroll
-          for (int e = 0; e < CV; ++e) dst[e] = vals[slot_base(D, V, L, J) + i * CV + e];
-        }
-      }
-    };
-    auto each_level = [&](auto Lc) {
-      constexpr int L = decltype(Lc)::value;
-      flush(Lc, std::integral_constant<int, 1>{});
-      flush(Lc, std::integral_constant<int, 2>{});
-      flush(Lc, std::integral_constant<int, 3>{});
-      if constexpr (L == D) flush(Lc, std::integral_constant<int, 0>{});
-    };
-    each_level(std::integral_constant<int, 1>{});
-    if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
-    if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
-    if constexpr (D >= 4) each_level(std::integral_constant<int, 4>{});
-  };
-  write_plane(norm_part + ((size_t)grp * B + b) * g.N, sink.acc);
+  write_slots<D, V>(norm_part + ((size_t)grp * B + b) * g.N, sink.acc, p);
   if constexpr (MX) {
-    if (max_part != nullptr) write_plane(max_part + ((size_t)grp * B + b) * g.N, sink.top);
+    if (max_part != nullptr) write_slots<D, V>(max_part + ((size_t)grp * B + b) * g.N, sink.top, p);
   }
 }
 
@@ -299,8 +234,9 @@ hipError_t fwd_launch(const wcc_desc &d, const void *x, float *coef, float *norm
 // channels a group that is at most 1/16 of the transform's own traffic.  Measured on gfx950:
 // about a thousand waves, each walking as many channels as possible, stream best; more
 // groups only pay when a layer has fewer strips than that.
-int forward_groups(const wcc_desc &d, bool folded_dw) {
-  return groups_for(d, d.C_in, arithmetic_bound(d, folded_dw) ? 4096 : 1024, 16);
+int forward_groups(const wcc_desc &d, int front) {
+  const bool busy = front == kFrontChain || arithmetic_bound(d, front == kFrontDw);
+  return groups_for(d, d.C_in, busy ? 4096 : 1024, 16);
 }
 
 template <bool STORE>

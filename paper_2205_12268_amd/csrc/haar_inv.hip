@@ -1,6 +1,6 @@
 // Zero filling and the inverse transform (the decompression step after Eq. wavelet_transform;
 // the last loop of Alg. 1), with the skip connection of the inverted residual block.
-#include "strip.h"
+#include "strip_io.h"
 
 namespace wcc {
 namespace {
@@ -22,88 +22,6 @@ namespace {
 // to a scratch line.  Strips that keep more than kInvCap positions, layers with more than 2^20
 // kept positions, and d = 4 (whose tile would not fit) take the plain path: ranks in registers,
 // one conditional load per slot.
-constexpr int kInvCap = 1024;          // packed entries per wave
-constexpr uint32_t kInvNone = ~0u;     // list padding
-constexpr int kInvRankBits = 20;       // entry = rank | cell << 20
-
-// Plain path: jj[slot] = rank j of the position inside the kept list, or -1 (dropped -> 0);
-// one conditional load per slot that some lane keeps.
-template <int D, int V>
-struct InvDirect {
-  const float *plane;  // yc[b, o, :]
-  int jj[slot_count(D, V)];
-  uint64_t any[2];     // wave-uniform: bit s set if some lane keeps slot s
-  template <int L, int J>
-  __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
-    constexpr int CV = cols_at(V, L);
-    constexpr int base = slot_base(D, V, L, J);
-#pragma unroll
-    for (int e = 0; e < CV; ++e) {
-      const int s = base + i * CV + e;
-      float t = 0.f;
-      if ((any[s >> 6] >> (s & 63)) & 1) {
-        const int j = jj[s];
-        if (j >= 0) t = plane[j];
-      }
-      v[e] = t;
-    }
-  }
-};
-
-// Staged: the lane's cell of the [slot][lane] LDS tile (zero unless the position is kept).
-template <int D, int V>
-struct InvStaged {
-  const float *cell;   // &tile[0][lane]
-  uint64_t any[2];     // wave-uniform: bit s set if some lane keeps slot s
-  template <int L, int J>
-  __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
-    constexpr int CV = cols_at(V, L);
-    constexpr int base = slot_base(D, V, L, J);
-#pragma unroll
-    for (int e = 0; e < CV; ++e) {
-      const int s = base + i * CV + e;
-      v[e] = ((any[s >> 6] >> (s & 63)) & 1) ? cell[s * kWave] : 0.f;
-    }
-  }
-};
-
-template <int D, int V, int L, class Source>
-__device__ __forceinline__ void inv_levels(float (&out)[rows_at(D, L - 1)][cols_at(V, L - 1)],
-                                           const LanePos<D> &p, const Source &src) {
-  constexpr int R2 = rows_at(D, L), VI = cols_at(V, L - 1), V2 = cols_at(V, L);
-  constexpr int SI = span_at(V, L - 1);
-  float ll[R2][V2];
-  if constexpr (L < D) {
-    inv_levels<D, V, L + 1>(ll, p, src);
-  } else {
-#pragma unroll
-    for (int i = 0; i < R2; ++i) src.template get_row<L, 0>(i, ll[i]);
-  }
-#pragma unroll
-  for (int i = 0; i < R2; ++i) {
-    float y2[V2], y3[V2], y4[V2];
-    src.template get_row<L, 1>(i, y2);
-    src.template get_row<L, 2>(i, y3);
-    src.template get_row<L, 3>(i, y4);
-#pragma unroll
-    for (int e = 0; e < V2; ++e) {
-      const float s1 = ll[i][e] + y3[e], s2 = ll[i][e] - y3[e];
-      const float d1 = y2[e] + y4[e], d2 = y2[e] - y4[e];
-      const float a = 0.5f * (s1 + d1), b = 0.5f * (s1 - d1);
-      const float c = 0.5f * (s2 + d2), d = 0.5f * (s2 - d2);
-      if constexpr (VI >= 2) {
-        out[2 * i][2 * e] = a; out[2 * i][2 * e + 1] = b;
-        out[2 * i + 1][2 * e] = c; out[2 * i + 1][2 * e + 1] = d;
-      } else {
-        // every lane of the group holds the same (y1..y4); the left half keeps the left pixel
-        const bool left = (p.lc & SI) == 0;
-        out[2 * i][0] = left ? a : b;
-        out[2 * i + 1][0] = left ? c : d;
-      }
-    }
-  }
-}
-
 // The channel walk of the staged path with NI dense fetches per channel.  mine[i]: the lane's
 // list entries (kInvNone: padding).  row_step: W for lanes inside the plane, 0 for the others
 // (whose dst is the scratch line).

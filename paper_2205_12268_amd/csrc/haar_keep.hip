@@ -1,103 +1,9 @@
 // Second transform pass of the fused layer: the kept coefficients go straight to their
 // compressed place (Eq. T of the joint shrinkage), optionally as 8-bit codes.
-#include "strip.h"
+#include "strip_io.h"
 
 namespace wcc {
 namespace {
-
-// ---- second pass of the fused layer: transform again, keep only the selected positions ----
-// xc[b, c, jmap[b, q]] = HWT_d(x[b, c])[q] for the kept q; dropped coefficients never reach
-// memory.  Also raises the alpha slots to max |kept coefficient| (nullable).
-// Q8: the clipping parameter is known beforehand (the caller supplied it), so the kept
-// coefficients leave the chip as signed 8-bit codes (Eq. quantweights) instead of fp32.
-template <int D, int V, bool Q8>
-struct KeepSink {
-  using Out = std::conditional_t<Q8, int8_t, float>;
-  // Every slot is stored through a buffer descriptor of the channel's compressed vector, with
-  // the byte offset of the slot's rank, or an offset beyond the vector for a position that is
-  // not kept: the hardware drops such a lane's store.  No store sits behind a branch, so the
-  // number of stores per channel is fixed and the wait for the prefetched rows of the next
-  // channel does not have to drain them (loads and stores retire through one counter); and no
-  // slot needs a 64-bit address or a saved lane mask, which halves the kernel's registers.
-  static constexpr uint32_t kDropped = 0xFFFFFFFFu;
-  __amdgpu_buffer_rsrc_t xc_c;     // xc[b, c, :]
-  uint32_t at[slot_count(D, V)];   // byte offset of the slot's rank, or kDropped
-  float vmax;
-  Quant quant;
-  __device__ __forceinline__ explicit KeepSink(float alpha) : quant(alpha) {}
-  // plane: xc[b, c, :] (wave-uniform), k elements
-  __device__ __forceinline__ void aim(Out *plane, int64_t k) {
-    xc_c = __builtin_amdgcn_make_buffer_rsrc(plane, 0, (int)(uint32_t)(k * (int64_t)sizeof(Out)),
-                                             0x00020000 /* raw dwords, no swizzle */);
-  }
-  template <int L, int J>
-  __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
-                                          bool owner) {
-    constexpr int CV = cols_at(V, L);
-    constexpr int base = slot_base(D, V, L, J);
-    (void)p;
-    (void)owner;  // (at[] is kDropped for the lanes that do not own the value)
-#pragma unroll
-    for (int e = 0; e < CV; ++e) {
-      const int s = base + i * CV + e;
-      if constexpr (Q8) {
-        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)quant.code(v[e]), xc_c, at[s], 0, 0);
-      } else {
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[e]), xc_c, at[s], 0, 0);
-        vmax = fmaxf(vmax, at[s] != kDropped ? fabsf(v[e]) : 0.f);
-      }
-    }
-  }
-};
-
-// The same sink for a strip that keeps few of its positions.  One sparse store per slot costs
-// the memory pipeline an instruction each, whatever the number of lanes that keep something
-// (measured: the stores were a third of the pass).  Here every lane drops its values into an LDS
-// tile laid out [slot][lane]; after the last level the wave goes through the strip's packed list
-// of kept positions (64 entries a row, built once, the same for every channel), picks each
-// entry's value from the tile and stores NI dense rows instead of one row per slot.
-template <int D, int V, bool Q8, int NI>
-struct KeepStagedSink {
-  using Out = std::conditional_t<Q8, int8_t, float>;
-  static constexpr uint32_t kDropped = 0xFFFFFFFFu;
-  __amdgpu_buffer_rsrc_t xc_c;  // xc[b, c, :]
-  uint32_t *tile;               // [slot][lane]
-  int lane;
-  uint32_t cell[NI];            // tile index of the entry's position
-  uint32_t at[NI];              // byte offset of the entry's rank, or kDropped (list padding)
-  float vmax;
-  Quant quant;
-  __device__ __forceinline__ explicit KeepStagedSink(float alpha) : quant(alpha) {}
-  __device__ __forceinline__ void aim(Out *plane, int64_t k) {
-    xc_c = __builtin_amdgcn_make_buffer_rsrc(plane, 0, (int)(uint32_t)(k * (int64_t)sizeof(Out)),
-                                             0x00020000 /* raw dwords, no swizzle */);
-  }
-  template <int L, int J>
-  __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V, L)],
-                                          bool owner) {
-    constexpr int CV = cols_at(V, L);
-    constexpr int base = slot_base(D, V, L, J);
-    (void)p;
-    (void)owner;  // (a value a lane does not own is in no list)
-#pragma unroll
-    for (int e = 0; e < CV; ++e) tile[(base + i * CV + e) * kWave + lane] = __float_as_uint(v[e]);
-  }
-  // once per channel, after the last level
-  __device__ __forceinline__ void flush() {
-    wave_lds_fence();
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const float v = __uint_as_float(tile[cell[i]]);
-      if constexpr (Q8) {
-        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)quant.code(v), xc_c, at[i], 0, 0);
-      } else {
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), xc_c, at[i], 0, 0);
-        vmax = fmaxf(vmax, at[i] != kDropped ? fabsf(v) : 0.f);
-      }
-    }
-    wave_lds_fence();
-  }
-};
 
 // grid = (ceil(units/4), G, B), block = 256.  DWM as in haar_fwd_kernel.  Q8: xc is int8 codes
 // for the clipping parameter q_alpha (> 0) or, if alpha_src is given, for the largest of its

@@ -96,10 +96,10 @@ wcc_status need_ws(const wcc_ctx *ctx, const WsLayout &L) {
 
 }  // namespace
 
-WsLayout ws_layout(const wcc_desc &d, bool folded_dw) {
+WsLayout ws_layout(const wcc_desc &d, int front) {
   WsLayout L{};
   const size_t N = (size_t)d.H * d.W, B = d.B, k = (size_t)k_of(d);
-  L.G = forward_groups(d, folded_dw);
+  L.G = forward_groups(d, front);
   L.nblk = (int)((N + kSelectChunk - 1) / kSelectChunk);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
@@ -144,13 +144,16 @@ enum { kListSelect = 0,  // joint shrinkage: top-k channel norms (Alg. 1)
 
 // One WCC layer (Alg. 1 with the quantiser) on a workspace that starts at `ws`.  residual
 // (nullable, [B, C_out, H, W]) is added to the output by the last kernel.  wdw (nullable,
-// [C_in, 3, 3]): the layer's input is K_dw x, convolved on the fly by both transform passes.  prof: bracket the
-// stages with the context's events.
+// [C_in, 3, 3]): the layer's input is K_dw x, convolved on the fly by both transform passes; with
+// src given (x unused) it is K_dw t1, t1 rebuilt from a producer layer's compressed output.
+// stop_before_inverse: the layer ends with Y_wt in its workspace (y unused), for a consumer that
+// takes it from there.  prof: bracket the stages with the context's events.
 wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc &d, const void *x,
                       const void *w, const float *w_scale, float alpha_in, void *y,
                       int32_t *idx_out, float *alpha_out_dev, const void *residual,
                       const float *wdw, bool prof, hipStream_t s, int list = kListSelect,
-                      const int32_t *idx_given = nullptr) {
+                      const int32_t *idx_given = nullptr, const ChainSrc *src = nullptr,
+                      bool stop_before_inverse = false) {
   const int64_t k = k_of(d);
   const bool quant = d.act_quant_bits == 8;
 
@@ -191,8 +194,12 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
     // A: the transform, first pass: only the channel norms of X_wt leave the chip (the same
     // kernel clears the selection state)
     WCC_TRY(mark(WCC_T_HAAR_FWD, 0));
-    WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, top, L.G,
-                             make_prep(ws, L, slots, quant ? alpha_in : 0.f), wdw, s));
+    if (src)
+      WCC_TRY(launch_chain_norm(d, *src, wdw, L.G == 1 ? norm : part, top, L.G,
+                                make_prep(ws, L, slots, quant ? alpha_in : 0.f), s));
+    else
+      WCC_TRY(launch_haar_norm(d, x, L.G == 1 ? norm : part, top, L.G,
+                               make_prep(ws, L, slots, quant ? alpha_in : 0.f), wdw, s));
     WCC_TRY(mark(WCC_T_HAAR_FWD, 1));
     // B: norms, index set I (ascending), rank map for the inverse
     WCC_TRY(mark(WCC_T_NORM_SELECT, 0));
@@ -211,9 +218,14 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
   // A again + B': the transform, second pass: X_wt[I] is written straight into its compressed
   // place (the dropped coefficients never reach memory)
   WCC_TRY(mark(WCC_T_GATHER, 0));
-  WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !given && !codes_now) ? slots : nullptr, wdw,
-                           (given && codes_now) ? alpha_in : 0.f, early ? tops : nullptr, n_top,
-                           early ? slots : nullptr, s));
+  if (src)
+    WCC_TRY(launch_chain_keep(d, k, *src, wdw, jmap, xc32, (quant && !given && !codes_now) ? slots : nullptr,
+                              (given && codes_now) ? alpha_in : 0.f, early ? tops : nullptr, n_top,
+                              early ? slots : nullptr, s));
+  else
+    WCC_TRY(launch_haar_keep(d, k, x, jmap, xc32, (quant && !given && !codes_now) ? slots : nullptr, wdw,
+                             (given && codes_now) ? alpha_in : 0.f, early ? tops : nullptr, n_top,
+                             early ? slots : nullptr, s));
   WCC_TRY(mark(WCC_T_GATHER, 1));
   // C: Y_wt = Conv(K_1x1, X_wt[I]) (kept coefficients still in fp32 are quantised as they are
   // loaded)
@@ -221,6 +233,7 @@ wcc_status forward_on(wcc_ctx *ctx, char *ws, const WsLayout &L, const wcc_desc 
   WCC_TRY(pointwise_any(ws, L, d, k, w, w_scale, xc32, !codes_now, slots, n_alpha,
                         quant ? alpha_out_dev : nullptr, yc, s));
   WCC_TRY(mark(WCC_T_POINTWISE, 1));
+  if (stop_before_inverse) return WCC_OK;
   // D + E: Y^0[I] = Y_wt, inverse levels
   WCC_TRY(mark(WCC_T_SCATTER_IHAAR, 0));
   WCC_TRY(launch_scatter_ihaar(d, k, yc, jmap, y, reinterpret_cast<float *>(ws + L.scratch), residual, s));
@@ -241,16 +254,29 @@ wcc_status block_layers(const wcc_block_desc *bd, wcc_desc &d1, wcc_desc &d3) {
   return st != WCC_OK ? st : check_desc(&d3);
 }
 
-struct BlockLayout { size_t t1, t2, layer, total; };
+// What stands in front of the project layer's transform: K_dw's output in memory, K_dw folded
+// into the passes that read the expand layer's output, or both rebuilt from the expand layer's
+// compressed output (chained: possible when nobody asks for the middle tensors).
+int block_front(const wcc_block_desc &bd, const wcc_desc &d3, bool wants_middle) {
+  if (bd.W % 4 != 0) return kFrontNone;
+  return (!wants_middle && chain_supported(d3)) ? kFrontChain : kFrontDw;
+}
 
+struct BlockLayout { size_t t1, t2, layer1, layer3, total; };
+
+// The two layers have workspaces of their own: chained, the project layer reads the expand
+// layer's compressed output while it fills its own.
 BlockLayout block_layout(const wcc_block_desc &bd, const wcc_desc &d1, const wcc_desc &d3) {
   BlockLayout L{};
   const size_t mid = align256((size_t)bd.B * d1.C_out * bd.H * bd.W * 4);
   L.t1 = 0;
   L.t2 = mid;
-  L.layer = 2 * mid;
-  const size_t a = ws_layout(d1).total, b = ws_layout(d3, bd.W % 4 == 0).total;
-  L.total = L.layer + (a > b ? a : b);
+  L.layer1 = 2 * mid;
+  L.layer3 = L.layer1 + ws_layout(d1).total;
+  // (the chained front asks for the most channel groups, so its layout is the largest)
+  const size_t b = std::max(ws_layout(d3, block_front(bd, d3, true)).total,
+                            ws_layout(d3, block_front(bd, d3, false)).total);
+  L.total = L.layer3 + b;
   return L;
 }
 
@@ -579,26 +605,43 @@ wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const voi
   if (!ctx->ws || ctx->ws_bytes < BL.total) return WCC_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   char *ws = static_cast<char *>(ctx->ws);
-  void *t1 = t1_out ? t1_out : static_cast<void *>(ws + BL.t1);
-  float *t2 = t2_out ? t2_out : reinterpret_cast<float *>(ws + BL.t2);
   const bool prof = ctx->profiling && ctx->ev_ok;
+  const int front = block_front(*desc, d3, t1_out != nullptr || t2_out != nullptr);
+  const WsLayout L1 = ws_layout(d1), L3 = ws_layout(d3, front);
 
-  // K1 (expand), K_dw, K3 (project) with the skip connection added by the last kernel
-  st = forward_on(ctx, ws + BL.layer, ws_layout(d1), d1, x, w1, w1_scale, 0.f, t1, idx1_out, nullptr,
-                  nullptr, nullptr, prof && ctx->block_profile_layer == 0, s);
-  if (st != WCC_OK) return st;
-  if (!fold || t2_out) {
-    if (prof) WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][0], s));
-    WCC_TRY(launch_depthwise3x3(d3.B, d3.C_in, d3.H, d3.W, static_cast<const float *>(t1), w_dw, t2, s));
-    if (prof) {
-      WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][1], s));
-      ctx->marked[WCC_T_DEPTHWISE] = true;
+  if (front == kFrontChain) {
+    // Chained: the expand layer stops at its compressed output; the project layer's transform
+    // passes rebuild the rows they need from it, convolve and transform them.  Neither middle
+    // tensor exists.
+    st = forward_on(ctx, ws + BL.layer1, L1, d1, x, w1, w1_scale, 0.f, nullptr, idx1_out, nullptr,
+                    nullptr, nullptr, prof && ctx->block_profile_layer == 0, s, kListSelect, nullptr,
+                    nullptr, true);
+    if (st != WCC_OK) return st;
+    const ChainSrc src{reinterpret_cast<const float *>(ws + BL.layer1 + L1.yc),
+                       reinterpret_cast<const int32_t *>(ws + BL.layer1 + L1.jmap), k_of(d1)};
+    st = forward_on(ctx, ws + BL.layer3, L3, d3, nullptr, w3, w3_scale, 0.f, y, idx3_out, nullptr, x,
+                    w_dw, prof && ctx->block_profile_layer == 1, s, kListSelect, nullptr, &src);
+    if (st != WCC_OK) return st;
+  } else {
+    void *t1 = t1_out ? t1_out : static_cast<void *>(ws + BL.t1);
+    float *t2 = t2_out ? t2_out : reinterpret_cast<float *>(ws + BL.t2);
+    // K1 (expand), K_dw, K3 (project) with the skip connection added by the last kernel
+    st = forward_on(ctx, ws + BL.layer1, L1, d1, x, w1, w1_scale, 0.f, t1, idx1_out, nullptr,
+                    nullptr, nullptr, prof && ctx->block_profile_layer == 0, s);
+    if (st != WCC_OK) return st;
+    if (!fold || t2_out) {
+      if (prof) WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][0], s));
+      WCC_TRY(launch_depthwise3x3(d3.B, d3.C_in, d3.H, d3.W, static_cast<const float *>(t1), w_dw, t2, s));
+      if (prof) {
+        WCC_TRY(hipEventRecord(ctx->ev[WCC_T_DEPTHWISE][1], s));
+        ctx->marked[WCC_T_DEPTHWISE] = true;
+      }
     }
+    st = forward_on(ctx, ws + BL.layer3, L3, d3, fold ? t1 : static_cast<void *>(t2), w3, w3_scale, 0.f, y,
+                    idx3_out, nullptr, x, fold ? w_dw : nullptr,
+                    prof && ctx->block_profile_layer == 1, s);
+    if (st != WCC_OK) return st;
   }
-  st = forward_on(ctx, ws + BL.layer, ws_layout(d3, fold), d3, fold ? t1 : static_cast<void *>(t2), w3, w3_scale, 0.f, y,
-                  idx3_out, nullptr, x, fold ? w_dw : nullptr,
-                  prof && ctx->block_profile_layer == 1, s);
-  if (st != WCC_OK) return st;
   if (prof) {
     WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][0], s));
     WCC_TRY(hipEventRecord(ctx->ev[WCC_T_EVENT_PAIR][1], s));

@@ -136,9 +136,30 @@ struct Quant {
   __device__ __forceinline__ int code(float v) const { return (int)level(v); }
 };
 
-// folded_dw: the layer's input is K_dw x, convolved on the fly by the transform passes
-WsLayout ws_layout(const wcc_desc &d, bool folded_dw = false);
-int forward_groups(const wcc_desc &d, bool folded_dw);
+// What stands in front of a layer's transform passes.
+enum Front {
+  kFrontNone = 0,   // the layer's input is x as it is
+  kFrontDw = 1,     // K_dw x, convolved on the fly by both passes
+  kFrontChain = 2   // K_dw iHWT(T^T Y_wt) of a producer layer, rebuilt from its compressed output
+};
+WsLayout ws_layout(const wcc_desc &d, int front = kFrontNone);
+int forward_groups(const wcc_desc &d, int front);
+
+// A producer layer's compressed output: t1 = iHWT(T^T yc), yc [B, C, k], jmap [B, N] its rank map
+struct ChainSrc {
+  const float *yc;
+  const int32_t *jmap;
+  int64_t k;
+};
+bool chain_supported(const wcc_desc &d);
+// the two transform passes of a layer whose input is K_dw t1 (wdw [C_in, 3, 3]); otherwise as
+// launch_haar_norm / launch_haar_keep
+hipError_t launch_chain_norm(const wcc_desc &d, const ChainSrc &src, const float *wdw,
+                             float *norm_part, float *max_part, int G, const SelectPrep &prep,
+                             hipStream_t s);
+hipError_t launch_chain_keep(const wcc_desc &d, int64_t k, const ChainSrc &src, const float *wdw,
+                             const int32_t *jmap, void *xc, float *alpha_slots, float q_alpha,
+                             const float *alpha_src, int n_alpha, float *alpha_pub, hipStream_t s);
 
 // launchers (each returns hipGetLastError() after its launches)
 hipError_t launch_haar_fwd(const wcc_desc &d, const float *x, float *coef, float *norm_part,

@@ -15,7 +15,7 @@ import pytest
 import torch
 
 from paper_2205_12268_amd import synth, wcc
-from tests.util import assert_valid_index_set, layer_with_index_set, dev, oracle_scale, rel_l2, upload_weights
+from tests.util import assert_valid_index_set, check_block_without_middle_outputs, layer_with_index_set, dev, oracle_scale, rel_l2, upload_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -79,11 +79,6 @@ def test_block_stage_by_stage_and_end_to_end(ref, ctx, cfg):
     torch.cuda.synchronize()
     tol = 1e-5 if (cfg.w_dtype == F32 and cfg.act_bits == 0) else 1e-2
 
-    # without the test outputs (middle tensors in the workspace): the same result
-    y_b = torch.empty_like(y)
-    ctx.wcc_block_forward(d, xd, w1d, w1s, dev(w_dw), w3d, w3s, y_b)
-    torch.cuda.synchronize()
-    assert torch.equal(y, y_b)
 
     # layer 1 (dyadic input): exact index set, output within tolerance
     o_t1, o_idx1, _ = ref.forward(x, w1.values, w1.scale, cfg.levels, cfg.keep_num, cfg.keep_den,
@@ -103,6 +98,12 @@ def test_block_stage_by_stage_and_end_to_end(ref, ctx, cfg):
         assert_valid_index_set(norm[b], g_idx3[b], cfg.k)
     g_branch = y.cpu().numpy().astype(np.float64) - x.astype(np.float64)
     assert rel_l2(g_branch, want_branch) <= tol
+
+    # without the test outputs: chained in the compressed domain where the shape allows
+    same = check_block_without_middle_outputs(ref, ctx, cfg, d, xd, x.astype(np.float64), w1d, w1s,
+                                              dev(w_dw), w3d, w3s, w3, g_t2, y, idx3, tol)
+    print(f"{cfg.name}: call without middle outputs chose {'the same' if same else 'another valid'} "
+          f"second index set", flush=True)
 
     # End to end against the independent oracle chain (its own index sets throughout).  Where
     # the two second-layer sets agree the chain is held to the same bar; where fp32 and fp64

@@ -1,0 +1,131 @@
+"""Compressed-domain chaining of the inverted residual block (appendix "Inference times",
+paragraph on memory bandwidth and traffic) against the oracle and against the route that forms
+the middle tensors (needs an MI355X).
+
+wcc_block_forward chains the two layers when no middle output is asked for and the shape allows
+(W % 4 == 0, W <= 256, d <= 3): the project layer's transform passes rebuild the rows they need
+from the expand layer's compressed output.  The shapes below walk through what that code
+depends on: one, two and four strips a wave, planes of one strip (no row above or below), many
+strips, rows that leave lanes idle, every level count, kept lists of 4, 8, 16 and 32 rows a wave
+and strips that keep everything (the slot-by-slot route), no quantiser, int8 weights, several
+samples and channel groups.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2205_12268_amd import synth, wcc
+from tests.util import (assert_valid_index_set, check_block_without_middle_outputs, dev,
+                        layer_with_index_set, rel_l2, upload_weights)
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16, I8 = synth.W_F32, synth.W_BF16, synth.W_I8
+
+
+def blk(name, B, C, e, H, W, d, num, den, wd, bits, sigma=2.0):
+    return synth.BlockCfg(name, B, C, e, H, W, d, num, den, wd, bits, sigma=sigma,
+                          seed=synth.SEED_BASE + 0xC00 + sum(map(ord, name)))
+
+
+CASES = [
+    blk("full_wave_d3", 1, 8, 4, 64, 256, 3, 1, 8, BF16, 8, 3.0),      # W = 256: one strip a wave
+    blk("two_strips_d3", 2, 8, 2, 48, 128, 3, 1, 4, BF16, 8),          # two strips a wave
+    blk("idle_lanes_d3", 1, 4, 3, 40, 96, 3, 1, 4, BF16, 8),           # 24 of 32 lanes a row
+    blk("four_strips_d2", 1, 8, 2, 36, 64, 2, 1, 4, I8, 8),            # four strips a wave, ragged last wave
+    blk("one_strip_plane", 2, 4, 2, 8, 64, 3, 1, 2, BF16, 8),          # no row above or below
+    blk("d1_tall", 1, 4, 2, 30, 32, 1, 1, 2, BF16, 8),                 # d = 1: every slot is a halo slot
+    blk("d2_half", 1, 8, 4, 64, 256, 2, 1, 2, BF16, 8),                # long lists (16 rows a wave)
+    blk("d3_half", 1, 4, 2, 32, 256, 3, 1, 2, BF16, 8),                # lists of more than 16 rows
+    blk("keep_all_d3", 1, 4, 2, 24, 256, 3, 1, 1, BF16, 8),            # every strip beyond the list: slot by slot
+    blk("keep_few_d3", 1, 8, 2, 64, 256, 3, 1, 64, BF16, 8, 3.0),      # short lists, empty strips
+    blk("f32_noquant_d2", 2, 4, 3, 16, 48, 2, 1, 3, F32, 0, 1.0),      # fp32 path, k % 4 != 0
+    blk("ragged_k_d3", 1, 8, 2, 24, 40, 3, 3, 7, BF16, 8),             # k % 4 != 0 with the quantiser
+    blk("many_channels", 2, 16, 8, 32, 64, 3, 1, 4, BF16, 8),          # 128 middle channels in groups
+]
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = wcc.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("cfg", CASES, ids=lambda c: c.name)
+def test_chained_block_matches_oracle_and_materialised_route(ref, ctx, cfg):
+    print(f"{cfg}", flush=True)
+    x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
+    d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
+                            cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+    ctx.ensure_workspace(d)
+    xd = dev(x)
+    w1d, w1s = upload_weights(w1)
+    w3d, w3s = upload_weights(w3)
+    wdd = dev(w_dw)
+    mid = (cfg.B, cfg.C_mid, cfg.H, cfg.W)
+    y = torch.full(x.shape, float("nan"), dtype=torch.float32, device="cuda")
+    t1 = torch.full(mid, float("nan"), dtype=torch.float32, device="cuda")
+    t2 = torch.full(mid, float("nan"), dtype=torch.float32, device="cuda")
+    idx1 = torch.empty((cfg.B, cfg.k), dtype=torch.int32, device="cuda")
+    idx3 = torch.empty((cfg.B, cfg.k), dtype=torch.int32, device="cuda")
+    # the route that forms the middle tensors, held to the oracle first
+    ctx.wcc_block_forward(d, xd, w1d, w1s, wdd, w3d, w3s, y, t1, t2, idx1, idx3)
+    torch.cuda.synchronize()
+    tol = 1e-5 if (cfg.w_dtype == F32 and cfg.act_bits == 0) else 1e-2
+    o_t1, o_idx1, _ = ref.forward(x, w1.values, w1.scale, cfg.levels, cfg.keep_num, cfg.keep_den,
+                                  act_bits=cfg.act_bits)
+    np.testing.assert_array_equal(idx1.cpu().numpy().astype(np.int64), o_idx1)
+    g_t1, g_t2 = t1.cpu().numpy(), t2.cpu().numpy()
+    assert rel_l2(g_t1, o_t1) <= tol
+    assert rel_l2(g_t2, ref.depthwise3x3(g_t1, w_dw)) <= 1e-6
+    g_idx3 = idx3.cpu().numpy().astype(np.int64)
+    want_branch, norm = layer_with_index_set(ref, cfg.layer(1), w3, g_t2.astype(np.float64), g_idx3)
+    for b in range(cfg.B):
+        assert_valid_index_set(norm[b], g_idx3[b], cfg.k)
+    assert rel_l2(y.cpu().numpy().astype(np.float64) - x, want_branch) <= tol
+    # the chained call: first index set exact, second one valid, output against the oracle
+    idx1_c = torch.full_like(idx1, -7)
+    y_c = torch.full_like(y, float("nan"))
+    ctx.wcc_block_forward(d, xd, w1d, w1s, wdd, w3d, w3s, y_c, None, None, idx1_c, None)
+    torch.cuda.synchronize()
+    assert torch.equal(idx1_c, idx1)
+    same = check_block_without_middle_outputs(ref, ctx, cfg, d, xd, x.astype(np.float64), w1d, w1s, wdd,
+                                              w3d, w3s, w3, g_t2, y, idx3, tol)
+    print(f"  second index set {'equal: outputs equal bit for bit' if same else 'differs: both valid'}",
+          flush=True)
+    # run to run: the chained call gives the same bits again
+    y_c2 = torch.full_like(y, float("nan"))
+    ctx.wcc_block_forward(d, xd, w1d, w1s, wdd, w3d, w3s, y_c2)
+    torch.cuda.synchronize()
+    assert torch.equal(y_c, y_c2)
+
+
+@pytest.mark.parametrize("cfg", [CASES[0], CASES[1], CASES[3], CASES[6]], ids=lambda c: c.name)
+def test_chained_block_with_bf16_maps(ctx, cfg):
+    """x and y stored as bf16.  Chained, the middle tensors are never stored, so storage is all
+    that differs from the chained call with fp32 maps on the same bf16-valued input: the same index
+    sets, and that call's output rounded once to nearest even.  (The fp32 call is the one held
+    to the oracle above.)"""
+    x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
+    x = synth.round_to_bf16(x)
+    w1d, w1s = upload_weights(w1)
+    w3d, w3s = upload_weights(w3)
+    wdd = dev(w_dw)
+    out = {}
+    for act, tdt in ((wcc.F32, torch.float32), (wcc.BF16, torch.bfloat16)):
+        d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
+                                cfg.keep_den, cfg.w_dtype, cfg.act_bits, act)
+        ctx.ensure_workspace(d)
+        xd = dev(x).to(tdt)
+        y = torch.full(x.shape, float("nan"), dtype=tdt, device="cuda")
+        idx1 = torch.full((cfg.B, cfg.k), -7, dtype=torch.int32, device="cuda")
+        idx3 = torch.full((cfg.B, cfg.k), -7, dtype=torch.int32, device="cuda")
+        ctx.wcc_block_forward(d, xd, w1d, w1s, wdd, w3d, w3s, y, None, None, idx1, idx3)
+        torch.cuda.synchronize()
+        out[act] = (y, idx1, idx3)
+    y32, i1, i3 = out[wcc.F32]
+    y16, j1, j3 = out[wcc.BF16]
+    assert torch.equal(i1, j1) and torch.equal(i3, j3)
+    want_bits = synth._round_to_bf16_bits(y32.cpu().numpy())
+    np.testing.assert_array_equal(y16.view(torch.int16).cpu().numpy().view(np.uint16), want_bits)

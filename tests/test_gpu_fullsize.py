@@ -200,11 +200,41 @@ def test_full_size_block(ref, act):
     print("  gpu block forward", flush=True)
     ctx.wcc_block_forward(d, xd, w1d, None, dev(w_dw), w3d, None, y, t1, t2, idx1, idx3)
     torch.cuda.synchronize()
+    # The call bench.py times: no middle outputs, so the two layers are chained in the compressed
+    # domain (the expanded tensors are never formed).  With fp32 maps the chained passes rebuild
+    # the same numbers: where both calls choose the same second index set the outputs are equal
+    # bit for bit, else this call's set is checked for validity further down.  With bf16 maps the
+    # materialised middle tensor is rounded to bf16 and the chained one is not, so the two
+    # outputs agree to the tolerance only.
     y2 = torch.empty_like(y)
-    ctx.wcc_block_forward(d, xd, w1d, None, dev(w_dw), w3d, None, y2)  # middle tensors in the workspace
+    idx3_2 = torch.empty_like(idx3)
+    ctx.wcc_block_forward(d, xd, w1d, None, dev(w_dw), w3d, None, y2, None, None, None, idx3_2)
     torch.cuda.synchronize()
-    assert torch.equal(y.view(torch.int16) if bf16 else y, y2.view(torch.int16) if bf16 else y2)
-    del y2
+    same3 = bool(torch.equal(idx3, idx3_2))
+    print(f"  call without middle outputs: second index set {'equal' if same3 else 'differs'}", flush=True)
+    if bf16:
+        # storage is all that differs from the chained call with fp32 maps on the same (bf16-valued)
+        # input: the same index sets, and that call's output rounded once to nearest even
+        d32 = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
+                                  cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.F32)
+        ctx.ensure_workspace(d32)
+        y32 = torch.empty(x.shape, dtype=torch.float32, device="cuda")
+        idx3_32 = torch.empty_like(idx3)
+        ctx.wcc_block_forward(d32, xd.float(), w1d, None, dev(w_dw), w3d, None, y32, None, None, None, idx3_32)
+        torch.cuda.synchronize()
+        assert torch.equal(idx3_2, idx3_32)
+        want_bits = synth._round_to_bf16_bits(y32.cpu().numpy())
+        np.testing.assert_array_equal(y2.view(torch.int16).cpu().numpy().view(np.uint16), want_bits)
+        del y32, idx3_32, want_bits
+        ctx.ensure_workspace(d)
+        print(f"  rel-L2 between the chained and the materialised output: "
+              f"{rel_l2(y2.float().cpu().numpy(), y.float().cpu().numpy()):.3e}", flush=True)
+    else:
+        if same3:
+            assert torch.equal(y, y2)
+        assert rel_l2(y2.cpu().numpy(), y.cpu().numpy()) <= 1e-2
+    g_idx3_2 = idx3_2.cpu().numpy().astype(np.int64)
+    del y2, idx3_2
 
     print("  oracle: first layer's selection", flush=True)
     coef = ref.haar_fwd(x, cfg.levels).reshape(cfg.B, cfg.C, N)
@@ -254,6 +284,12 @@ def test_full_size_block(ref, act):
     dropped = np.ones(N, dtype=bool)
     dropped[sel] = False
     assert norm0[sel].min() >= kth * (1 - 1e-5) and norm0[dropped].max() <= kth * (1 + 1e-5)
+    if not bf16:  # the chained call's own set, against the same fp64 norms
+        sel2 = g_idx3_2[0]
+        assert np.all(np.diff(sel2) > 0) and sel2[0] >= 0 and sel2[-1] < N
+        dropped2 = np.ones(N, dtype=bool)
+        dropped2[sel2] = False
+        assert norm0[sel2].min() >= kth * (1 - 1e-5) and norm0[dropped2].max() <= kth * (1 + 1e-5)
     yc = ref.pointwise(w3.values, np.full(cfg.C, a3 / 127.0), ref.quant_codes(keep0, a3, 8))
     want = ref.haar_inv(ref.scatter(yc, g_idx3[0:1], N), cfg.H, cfg.W, cfg.levels)[0]
     got = y[0].float().cpu().numpy().astype(np.float64) - x[0].astype(np.float64)

@@ -70,3 +70,28 @@ def assert_valid_index_set(norm_b, sel, k, rel=1e-5):
     assert norm_b[sel].min() >= kth * (1 - rel)
     if dropped.any():
         assert norm_b[dropped].max() <= kth * (1 + rel)
+
+
+def check_block_without_middle_outputs(ref, ctx, cfg, d, xd, x_np, w1d, w1s, wdd, w3d, w3s, w3,
+                                       g_t2, y_mat, idx3_mat, tol):
+    """The block called without the test outputs: where the shape allows, the library then
+    chains the two layers in the compressed domain (the middle tensors are never formed).  Its
+    second index set must be valid for the fp64 norms of K_dw's output as the materialised call
+    gave it (g_t2; the chained passes rebuild the same fp32 numbers), its output must match the
+    oracle run on that set, and where the two calls chose the same set (same kept values, same
+    alpha, same codes) the outputs must be equal bit for bit.  Returns whether the sets agreed."""
+    y_p = torch.full_like(y_mat, float("nan"))
+    idx3_p = torch.full_like(idx3_mat, -7)
+    ctx.wcc_block_forward(d, xd, w1d, w1s, wdd, w3d, w3s, y_p, None, None, None, idx3_p)
+    torch.cuda.synchronize()
+    g_idx3 = idx3_p.cpu().numpy().astype(np.int64)
+    want_branch, norm = layer_with_index_set(ref, cfg.layer(1), w3, g_t2.astype(np.float64), g_idx3)
+    for b in range(cfg.B):
+        assert_valid_index_set(norm[b], g_idx3[b], cfg.k)
+    got = y_p.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert rel_l2(got - x_np, want_branch) <= tol
+    same = bool(torch.equal(idx3_p, idx3_mat))
+    if same:
+        assert torch.equal(y_p, y_mat)
+    return same
