@@ -21,6 +21,9 @@
 // a row of the plane fits into one wave row (W <= 256), so that the convolution's outside
 // columns come from neighbouring lanes or are the plane's zero border.
 #include "strip_io.h"
+#ifdef WCC_CHAIN_DEBUG
+#include <cstdio>
+#endif
 
 namespace wcc {
 namespace {
@@ -38,17 +41,34 @@ __host__ __device__ constexpr int hslot_count(int D, int V) {
   return hslot_base(D, V, D, 3) + cols_at(V, D);
 }
 
-// source of a halo row: the lane's cell of the [slot][lane] tile, slots counted from `first`
-template <int D, int V>
-struct RowStaged {
-  const float *cell;  // &tile[first slot][lane]
-  uint32_t any;       // wave-uniform: bit s set if some lane keeps halo slot s
+// The wave's LDS tile is laid out [lane][slot]: a lane's NT slots are contiguous, so one channel's
+// kept values come back with NT / 4 16-byte reads and no branch (cells of positions that are
+// not kept hold zero).  The lane stride is an odd multiple of four words: the 16 lanes of one
+// read cycle then touch every bank once.
+__host__ __device__ constexpr int chain_stride(int nt) { return (nt / 4) % 2 == 1 ? nt : nt + 4; }
+
+// sources of the synthesis: the lane's slots as read back from the tile into registers
+template <int D, int V, int N>
+struct RegStrip {
+  const float (&c)[N];
+  template <int L, int J>
+  __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) v[e] = c[base + i * CV + e];
+  }
+};
+template <int D, int V, int N>
+struct RegRow {
+  const float (&c)[N];
+  int first;  // the halo row's first slot
   template <int L, int J>
   __device__ __forceinline__ void get(float (&v)[cols_at(V, L)]) const {
     constexpr int CV = cols_at(V, L);
     constexpr int base = hslot_base(D, V, L, J);
 #pragma unroll
-    for (int e = 0; e < CV; ++e) v[e] = ((any >> (base + e)) & 1u) ? cell[(base + e) * kWave] : 0.f;
+    for (int e = 0; e < CV; ++e) v[e] = c[first + base + e];
   }
 };
 
@@ -88,6 +108,7 @@ constexpr int kChainCap = 2048;  // packed entries per wave (32 a lane)
 template <int D>
 struct ChainGeo {
   static constexpr int NS = slot_count(D, V4), HS = hslot_count(D, V4), NT = NS + 2 * HS;
+  static constexpr int STRIDE = chain_stride(NT);  // words between two lanes' slots in the tile
   uint64_t any;        // wave-uniform: bit s set if some lane keeps slot s (NT <= 64)
   int count;           // kept entries of the wave (wave-uniform)
   bool packed;         // the tile holds the wave's packed list (rank | cell << kInvRankBits)
@@ -135,7 +156,9 @@ __device__ __forceinline__ ChainGeo<D> chain_setup(const int32_t *__restrict__ j
                                                    bool dn_in, uint32_t *tile) {
   constexpr int NT = ChainGeo<D>::NT;
   static_assert(NT <= 64, "one 64-bit slot mask");
-  static_assert(NT * kWave <= (1 << (32 - kInvRankBits)), "cell index fits above the rank");
+  constexpr int STRIDE = ChainGeo<D>::STRIDE;
+  static_assert(STRIDE * kWave <= (1 << (32 - kInvRankBits)), "cell index fits above the rank");
+  static_assert(NT % 4 == 0 && STRIDE % 4 == 0, "16-byte reads of a lane's slots");
   const int lane = threadIdx.x & (kWave - 1);
   int jj[NT];  // rank in the producer's list, or -1
   chain_slots<D>(p, active, up_in, dn_in, [&](int s, int pos, bool exists) {
@@ -152,7 +175,7 @@ __device__ __forceinline__ ChainGeo<D> chain_setup(const int32_t *__restrict__ j
     if (kept != 0) cg.any |= (uint64_t)1 << s;
     cg.count += __popcll(kept);
   }
-  cg.packed = cg.count <= kChainCap && cg.count <= NT * kWave && k1 <= ((int64_t)1 << kInvRankBits);
+  cg.packed = cg.count <= kChainCap && k1 <= ((int64_t)1 << kInvRankBits);
   if (cg.packed) {
     int running = 0;
 #pragma unroll
@@ -162,7 +185,7 @@ __device__ __forceinline__ ChainGeo<D> chain_setup(const int32_t *__restrict__ j
         const uint64_t kept = __ballot(j >= 0);
         const int at = running + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32),
                                      __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
-        if (j >= 0) tile[at] = (uint32_t)j | ((uint32_t)(s * kWave + lane) << kInvRankBits);
+        if (j >= 0) tile[at] = (uint32_t)j | ((uint32_t)(lane * STRIDE + s) << kInvRankBits);
         running += __popcll(kept);
       }
     }
@@ -172,8 +195,8 @@ __device__ __forceinline__ ChainGeo<D> chain_setup(const int32_t *__restrict__ j
 }
 
 // Walks n_ch channels of the producer's compressed output yc1 (first channel at `plane`, channel
-// stride k1): per channel the kept values around the strip go into the wave's [slot][lane] LDS
-// tile (whose other cells stay zero), the strip's 2^d rows and the rows above and below are
+// stride k1): per channel the kept values around the strip go into the wave's LDS
+// tile (laid out [lane][slot]; its other cells stay zero), the strip's 2^d rows and the rows above and below are
 // rebuilt from it, convolved with the channel's 3x3 kernel (wdw: first channel's, 9 floats a
 // channel) and transformed into `sink`; after(sink) runs once per channel.
 // Waves whose list is packed fetch it with dense loads, one channel ahead; the others (strips
@@ -187,17 +210,9 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
                                            bool first_lane, bool last_lane, Sink &sink, After &&after) {
   constexpr int R = 1 << D, RR = R + 2, V = V4;
   constexpr int NS = ChainGeo<D>::NS, HS = ChainGeo<D>::HS, NT = ChainGeo<D>::NT;
+  constexpr int STRIDE = ChainGeo<D>::STRIDE;
   const int lane = threadIdx.x & (kWave - 1);
-
-  InvStaged<D, V> own;
-  own.cell = reinterpret_cast<const float *>(tile) + lane;
-  own.any[0] = cg.any;
-  own.any[1] = 0;
-  RowStaged<D, V> up, dn;
-  up.cell = own.cell + NS * kWave;
-  dn.cell = own.cell + (NS + HS) * kWave;
-  up.any = (uint32_t)(cg.any >> NS) & ((1u << HS) - 1u);
-  dn.any = (uint32_t)(cg.any >> (NS + HS)) & ((1u << HS) - 1u);
+  uint32_t *mine_row = tile + lane * STRIDE;  // this lane's slots
 
   // the tile holds a channel's kept values: rebuild, convolve with kw[0..8], transform
   auto compute = [&](const float *kw) {
@@ -207,6 +222,14 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
     wave_lds_fence();
     float six[RR][V + 2];
     {
+      float cells[NT];
+#pragma unroll
+      for (int q = 0; q < NT / 4; ++q) {
+        const float4 t = reinterpret_cast<const float4 *>(mine_row)[q];
+        cells[4 * q] = t.x; cells[4 * q + 1] = t.y; cells[4 * q + 2] = t.z; cells[4 * q + 3] = t.w;
+      }
+      const RegStrip<D, V, NT> own{cells};
+      const RegRow<D, V, NT> up{cells, NS}, dn{cells, NS + HS};
       float mid[R][V];
       inv_levels<D, V, 1>(mid, p, own);
 #pragma unroll
@@ -249,46 +272,68 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
   if (cg.packed) {
     auto run = [&](auto ni_c) {
       constexpr int NI = decltype(ni_c)::value;
-      // lists of more than 16 rows do without the channel of values in flight (registers)
-      constexpr bool AHEAD = NI <= 16;
+      // Channels of values in flight ahead of the one being worked on: two for short lists,
+      // one for lists of up to 16 rows, none beyond (registers).
+      constexpr int DEPTH = NI <= 8 ? 2 : (NI <= 16 ? 1 : 0);
       constexpr uint32_t kRank = (1u << kInvRankBits) - 1u;
-      uint32_t mine[NI];  // this lane's share of the list: entries lane + 64 i
+      // this lane's share of the list: entries lane + 64 i.  Past the end of the list an entry
+      // repeats the list's first one: it fetches the same value and drops it into the same cell,
+      // so no load and no LDS write needs a lane mask or a branch.
+      uint32_t mine[NI];
+      const uint32_t first = tile[0];
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
         const int e = lane + kWave * i;
-        mine[i] = e < cg.count ? tile[e] : kInvNone;
+        mine[i] = e < cg.count ? tile[e] : first;
       }
       wave_lds_fence();
 #pragma unroll
-      for (int s = 0; s < NT; ++s) tile[s * kWave + lane] = 0u;
-      float vn[AHEAD ? NI : 1];
-      if constexpr (AHEAD) {
+      for (int s = 0; s < NT; ++s) mine_row[s] = 0u;
+      auto fetch = [&](float (&dst)[NI], int ch) {  // (past the last channel: the last again)
+        const float *nx = plane + (size_t)min(ch, n_ch - 1) * k1;
 #pragma unroll
-        for (int i = 0; i < NI; ++i) vn[i] = plane[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
-      }
-      auto channel = [&](int c) {
-        if constexpr (AHEAD) {
+        for (int i = 0; i < NI; ++i) dst[i] = nx[mine[i] & kRank];
+      };
+      auto drop = [&](const float (&src)[NI]) {
 #pragma unroll
-          for (int i = 0; i < NI; ++i)
-            if (mine[i] != kInvNone) tile[mine[i] >> kInvRankBits] = __float_as_uint(vn[i]);
-          // the next channel's values travel while this one is worked on (past the end: the last again)
-          const float *nx = plane + (size_t)min(c + 1, n_ch - 1) * k1;
+        for (int i = 0; i < NI; ++i) tile[mine[i] >> kInvRankBits] = __float_as_uint(src[i]);
+      };
+      if constexpr (DEPTH == 0) {
+        for (int c = 0; c < n_ch; ++c) {
+          float v[NI];
+          fetch(v, c);
+          drop(v);
+          compute(wdw + (size_t)c * 9);
+        }
+      } else {
+        float vn[DEPTH][NI];
 #pragma unroll
-          for (int i = 0; i < NI; ++i) vn[i] = nx[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
-          __builtin_amdgcn_sched_barrier(0);
-        } else {
-          const float *pc = plane + (size_t)c * k1;
+        for (int u = 0; u < DEPTH; ++u) fetch(vn[u], u);
+        int c = 0;
+        for (; c + DEPTH <= n_ch; c += DEPTH) {
 #pragma unroll
-          for (int i = 0; i < NI; ++i) {
-            const float v = pc[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
-            if (mine[i] != kInvNone) tile[mine[i] >> kInvRankBits] = __float_as_uint(v);
+          for (int u = 0; u < DEPTH; ++u) {
+            drop(vn[u]);
+            fetch(vn[u], c + u + DEPTH);  // travels while the channels in between are worked on
+            __builtin_amdgcn_sched_barrier(0);
+            compute(wdw + (size_t)(c + u) * 9);
           }
         }
-        compute(wdw + (size_t)c * 9);
-      };
-      channel(0);
-      for (int c = 1; c < n_ch; ++c) channel(c);
+#pragma unroll
+        for (int u = 0; u < DEPTH - 1; ++u) {
+          if (c + u < n_ch) {
+            drop(vn[u]);
+            compute(wdw + (size_t)(c + u) * 9);
+          }
+        }
+      }
     };
+    if (cg.count == 0) {  // nothing kept around this strip: every channel is zero
+#pragma unroll
+      for (int s = 0; s < NT; ++s) mine_row[s] = 0u;
+      for (int c = 0; c < n_ch; ++c) compute(wdw + (size_t)c * 9);
+      return;
+    }
     const int ni = (cg.count + kWave - 1) >> 6;
     if (ni <= 4) run(std::integral_constant<int, 4>{});
     else if (ni <= 8) run(std::integral_constant<int, 8>{});
@@ -299,32 +344,36 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
 
   // plain path: every slot is looked up again for every channel
 #pragma unroll
-  for (int s = 0; s < NT; ++s) tile[s * kWave + lane] = 0u;
+  for (int s = 0; s < NT; ++s) mine_row[s] = 0u;
   for (int c = 0; c < n_ch; ++c) {
     const float *pc = plane + (size_t)c * k1;
     chain_slots<D>(p, active, up_in, dn_in, [&](int s, int pos, bool exists) {
       if ((cg.any >> s) & 1) {
         int j = -1;
         if (exists) j = jm1[pos];
-        if (j >= 0) tile[s * kWave + lane] = __float_as_uint(pc[j]);
+        if (j >= 0) mine_row[s] = __float_as_uint(pc[j]);
       }
     });
     compute(wdw + (size_t)c * 9);
   }
 }
 
-// LDS of a workgroup: four waves' [slot][lane] tiles
+// Waves per workgroup: two, so that a workgroup's tiles stay small enough for several workgroups
+// to share a compute unit's LDS.
+constexpr int kChainWaves = 2;
+
+// LDS of a workgroup: its waves' [lane][slot] tiles
 template <int D>
 struct ChainTiles {
-  static constexpr int kWords = ChainGeo<D>::NT * kWave;
+  static constexpr int kWords = ChainGeo<D>::STRIDE * kWave;
 };
 
 // ---- first pass: channel norms of HWT(K_dw t1) ------------------------------------------------------
-// grid = (ceil(units/4), G, B), block = 256.  yc1 [B, C, k1], jmap1 [B, N]: the producer layer's
+// grid = (ceil(units/kChainWaves), G, B), block = kChainWaves waves.  yc1 [B, C, k1], jmap1 [B, N]: the producer layer's
 // compressed output and rank map; wdw [C, 3, 3].  Writes the partial norms (and the partial
 // maxima of |coefficient|, nullable) of channel group grp to norm_part / max_part [G, B, N].
 template <int D, bool SQ>
-__global__ __launch_bounds__(256, 2) void chain_norm_kernel(const float *__restrict__ yc1,
+__global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_norm_kernel(const float *__restrict__ yc1,
                                                          const int32_t *__restrict__ jmap1,
                                                          int64_t k1, const float *__restrict__ wdw,
                                                          float *__restrict__ norm_part,
@@ -332,12 +381,12 @@ __global__ __launch_bounds__(256, 2) void chain_norm_kernel(const float *__restr
                                                          StripMap m, int C, int Cg, int B,
                                                          SelectPrep prep) {
   constexpr int NS = slot_count(D, V4);
-  __shared__ uint32_t tiles[4][ChainTiles<D>::kWords];
+  __shared__ uint32_t tiles[kChainWaves][ChainTiles<D>::kWords];
   const int wv = threadIdx.x >> 6;
-  const int unit = blockIdx.x * 4 + wv;
+  const int unit = blockIdx.x * kChainWaves + wv;
   const int grp = blockIdx.y, b = blockIdx.z;
   // one workgroup per sample clears the state of the selection that follows this kernel
-  if (blockIdx.x == 0 && grp == 0) prep_sample(prep, b, threadIdx.x, 256);
+  if (blockIdx.x == 0 && grp == 0) prep_sample(prep, b, threadIdx.x, kChainWaves * kWave);
   LanePos<D> p;
   int row0, col0;
   const bool active = locate<D, V4>(m, g, unit, p, row0, col0);
@@ -350,23 +399,29 @@ __global__ __launch_bounds__(256, 2) void chain_norm_kernel(const float *__restr
 
   FwdSink<D, V4, false, SQ> sink;
 #pragma unroll
-  for (int s = 0; s < NS; ++s) { sink.acc[s] = 0.f; sink.top[s] = 0.f; }
+  for (int s = 0; s < NS; ++s) sink.acc[s] = 0.f;
+  if constexpr (FwdSink<D, V4, false, SQ>::MX) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) sink.top[s] = 0.f;
+  }
   sink.plane = nullptr;
   chain_walk<D>(yc1 + ((size_t)b * C + c0) * k1, k1, n_ch, wdw + (size_t)c0 * 9, cg, jm1, active,
                 up_in, dn_in, tiles[wv], p, p.lc == 0, p.lc == m.lpr - 1 || col0 + V4 >= g.W, sink,
                 [](FwdSink<D, V4, false, SQ> &) {});
   if (!active) return;
   write_slots<D, V4>(norm_part + ((size_t)grp * B + b) * g.N, sink.acc, p);
-  if (max_part != nullptr) write_slots<D, V4>(max_part + ((size_t)grp * B + b) * g.N, sink.top, p);
+  if constexpr (FwdSink<D, V4, false, SQ>::MX) {
+    if (max_part != nullptr) write_slots<D, V4>(max_part + ((size_t)grp * B + b) * g.N, sink.top, p);
+  }
 }
 
 // ---- second pass: the kept coefficients of HWT(K_dw t1) ---------------------------------------------
-// grid = (ceil(units/4), G, B), block = 256.  jmap3: the consumer layer's rank map; xc
+// grid = (ceil(units/kChainWaves), G, B), block = kChainWaves waves.  jmap3: the consumer layer's rank map; xc
 // [B, C, k3] fp32, or int8 codes with Q8 (clipping parameter: q_alpha > 0, or the largest of the
 // n_alpha floats at alpha_src; the first workgroup leaves it at alpha_pub[0]).  Without Q8 the
 // alpha slots (nullable) are raised to max |kept coefficient|.
 template <int D, bool Q8>
-__global__ __launch_bounds__(256, 2) void chain_keep_kernel(const float *__restrict__ yc1,
+__global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(const float *__restrict__ yc1,
                                                          const int32_t *__restrict__ jmap1,
                                                          int64_t k1, const float *__restrict__ wdw,
                                                          const int32_t *__restrict__ jmap3,
@@ -376,10 +431,10 @@ __global__ __launch_bounds__(256, 2) void chain_keep_kernel(const float *__restr
                                                          const float *__restrict__ alpha_src,
                                                          int n_alpha, float *alpha_pub) {
   constexpr int NS = slot_count(D, V4);
-  __shared__ uint32_t tiles[4][ChainTiles<D>::kWords];
-  __shared__ float wmax[4];
+  __shared__ uint32_t tiles[kChainWaves][ChainTiles<D>::kWords];
+  __shared__ float wmax[kChainWaves];
   const int wv = threadIdx.x >> 6;
-  const int unit = blockIdx.x * 4 + wv;
+  const int unit = blockIdx.x * kChainWaves + wv;
   const int grp = blockIdx.y, b = blockIdx.z;
   LanePos<D> p;
   int row0, col0;
@@ -450,7 +505,9 @@ __global__ __launch_bounds__(256, 2) void chain_keep_kernel(const float *__restr
   if ((threadIdx.x & 63) == 0) wmax[wv] = mx;
   __syncthreads();
   if (threadIdx.x == 0) {
-    mx = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    mx = wmax[0];
+#pragma unroll
+    for (int i = 1; i < kChainWaves; ++i) mx = fmaxf(mx, wmax[i]);
     unsigned int *a = reinterpret_cast<unsigned int *>(alpha_slots) +
                       ((blockIdx.x + 3u * blockIdx.y + 11u * blockIdx.z) & (kAlphaSlots - 1));
     const unsigned int mine = __float_as_uint(mx);
@@ -474,7 +531,7 @@ hipError_t launch_chain_norm(const wcc_desc &d, const ChainSrc &src, const float
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
   const StripMap m = make_map(d, V4);
   const int Cg = (d.C_in + G - 1) / G;
-  const dim3 grid((m.units + 3) / 4, G, d.B), block(256);
+  const dim3 grid((m.units + kChainWaves - 1) / kChainWaves, G, d.B), block(kChainWaves * kWave);
   const bool sq = d.norm == WCC_NORM_L2;
 #define WCC_CHAIN_NORM(D_)                                                                          \
   do {                                                                                              \
@@ -502,7 +559,7 @@ hipError_t launch_chain_keep(const wcc_desc &d, int64_t k, const ChainSrc &src, 
   const StripMap m = make_map(d, V4);
   const int G = groups_for(d, d.C_in, 4096, 8);
   const int Cg = (d.C_in + G - 1) / G;
-  const dim3 grid((m.units + 3) / 4, G, d.B), block(256);
+  const dim3 grid((m.units + kChainWaves - 1) / kChainWaves, G, d.B), block(kChainWaves * kWave);
   const bool q8 = q_alpha > 0.f || alpha_src != nullptr;
 #define WCC_CHAIN_KEEP(D_)                                                                          \
   do {                                                                                              \
@@ -524,5 +581,18 @@ hipError_t launch_chain_keep(const wcc_desc &d, int64_t k, const ChainSrc &src, 
 #undef WCC_CHAIN_KEEP
   return hipGetLastError();
 }
+
+#ifdef WCC_CHAIN_DEBUG
+extern "C" void wcc_debug_chain_occ() {
+  int n = -1;
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, chain_norm_kernel<3, false>, kChainWaves * kWave, 0);
+  printf("chain_norm<3>: blocks/CU %d (err %d), threads %d\n", n, (int)e, kChainWaves * kWave);
+  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, chain_keep_kernel<3, true>, kChainWaves * kWave, 0);
+  printf("chain_keep<3,q8>: blocks/CU %d (err %d)\n", n, (int)e);
+  hipFuncAttributes a;
+  e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(chain_norm_kernel<3, false>));
+  printf("norm: regs %d shared %zu local %zu maxthreads %d\n", a.numRegs, a.sharedSizeBytes, a.localSizeBytes, a.maxThreadsPerBlock);
+}
+#endif
 
 }  // namespace wcc

@@ -15,7 +15,11 @@ namespace {
 // SQ: the sums are of squared coefficients (one fused multiply-add each) instead.
 template <int D, int V, bool STORE, bool SQ = false>
 struct FwdSink {
+#ifdef WCC_NO_TOP
+  static constexpr bool MX = false;
+#else
   static constexpr bool MX = !STORE;
+#endif
   float *plane;  // wavelet vector of the current (b, c)
   float acc[slot_count(D, V)];
   float top[MX ? slot_count(D, V) : 1];  // max over the channels of |coefficient|
