@@ -249,6 +249,15 @@ typedef struct {
  * own workspaces.  Pure host function. */
 wcc_status wcc_block_workspace_bytes(const wcc_block_desc *desc, size_t *bytes);
 
+/* 1 if wcc_block_forward, called without middle outputs (t1_out = t2_out = NULL), chains the
+ * two layers of this block in the compressed domain -- the appendix "Inference times", paragraph
+ * on memory bandwidth and traffic: transform, depthwise convolution and gather / scatter applied
+ * per channel and in parts, the full result kept only in compressed form -- so that the expanded
+ * feature maps are never formed; 0 if it forms them; -1 for an invalid descriptor.  Chained:
+ * W % 4 == 0, W <= 256, levels <= 3 and at most a third of the coefficients kept.  Pure host
+ * function. */
+int32_t wcc_block_is_chained(const wcc_block_desc *desc);
+
 /* K_dw: y[b,c,r,q] = sum_{i,j=0..2} w[c,i,j] * x[b,c,r+i-1,q+j-1], zero outside the plane
  * (cross-correlation, stride 1, zero padding 1, no bias; the paper names the operator only).
  * x, y [B,C,H,W] fp32 device, w [C,3,3] fp32 device; x and y must not overlap. */
@@ -258,7 +267,12 @@ wcc_status wcc_depthwise3x3(wcc_ctx *ctx, int32_t B, int32_t C, int32_t H, int32
 /* The block.  w1_scale / w3_scale as in wcc_forward (int8 weights only); alpha of each layer is
  * the largest kept |coefficient| of that layer.  t1_out / t2_out (nullable, [B, C*expansion,
  * H, W]) receive K1's output and K_dw's output, idx1_out / idx3_out (nullable, [B,k]) the two
- * index sets: they exist for tests.  Needs a workspace of wcc_block_workspace_bytes. */
+ * index sets: they exist for tests.  Asking for a middle output makes the call form both middle
+ * tensors; without, it chains the layers where wcc_block_is_chained() says so (the second
+ * layer then sees the same fp32 numbers, summed into its channel norms in another grouping, so
+ * its index set may differ from the other route's where two norms are within rounding of each
+ * other; with bf16 maps the chained middle tensor is not rounded to bf16).  Needs a workspace of
+ * wcc_block_workspace_bytes. */
 wcc_status wcc_block_forward(wcc_ctx *ctx, const wcc_block_desc *desc, const void *x,
                              const void *w1, const float *w1_scale, const float *w_dw,
                              const void *w3, const float *w3_scale, void *y,

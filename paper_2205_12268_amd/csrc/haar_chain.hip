@@ -112,6 +112,7 @@ struct ChainGeo {
   uint64_t any;        // wave-uniform: bit s set if some lane keeps slot s (NT <= 64)
   int count;           // kept entries of the wave (wave-uniform)
   bool packed;         // the tile holds the wave's packed list (rank | cell << kInvRankBits)
+  int jj[NT];          // rank in the producer's list of the lane's slot, or -1 (used if !packed)
 };
 
 // Calls f(slot, position in the producer's rank map, exists) for the lane's NT slots: the strip's
@@ -160,13 +161,13 @@ __device__ __forceinline__ ChainGeo<D> chain_setup(const int32_t *__restrict__ j
   static_assert(STRIDE * kWave <= (1 << (32 - kInvRankBits)), "cell index fits above the rank");
   static_assert(NT % 4 == 0 && STRIDE % 4 == 0, "16-byte reads of a lane's slots");
   const int lane = threadIdx.x & (kWave - 1);
-  int jj[NT];  // rank in the producer's list, or -1
+  ChainGeo<D> cg;
+  int (&jj)[NT] = cg.jj;
   chain_slots<D>(p, active, up_in, dn_in, [&](int s, int pos, bool exists) {
     int j = -1;
     if (exists) j = jm1[pos];
     jj[s] = j;
   });
-  ChainGeo<D> cg;
   cg.any = 0;
   cg.count = 0;
 #pragma unroll
@@ -199,15 +200,16 @@ __device__ __forceinline__ ChainGeo<D> chain_setup(const int32_t *__restrict__ j
 // tile (laid out [lane][slot]; its other cells stay zero), the strip's 2^d rows and the rows above and below are
 // rebuilt from it, convolved with the channel's 3x3 kernel (wdw: first channel's, 9 floats a
 // channel) and transformed into `sink`; after(sink) runs once per channel.
-// Waves whose list is packed fetch it with dense loads, one channel ahead; the others (strips
-// that keep more than kChainCap positions) look every slot up in the rank map again, channel
-// after channel: slow, and rare.
-template <int D, class Sink, class After>
+// Waves whose list is packed fetch it with dense loads, one or two channels ahead; the others
+// (strips that keep more than kChainCap positions) load slot by slot from the ranks they hold in
+// registers, a channel's loads in flight together.
+// NI_FIXED > 0: the packed list is walked with that many rows a wave (the caller has checked that
+// it fits); 0: the shortest of 4, 8, 16, 32 rows that holds it.
+template <int D, int NI_FIXED = 0, class Sink, class After>
 __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int64_t k1, int n_ch,
                                            const float *__restrict__ wdw, const ChainGeo<D> &cg,
-                                           const int32_t *__restrict__ jm1, bool active, bool up_in,
-                                           bool dn_in, uint32_t *tile, const LanePos<D> &p,
-                                           bool first_lane, bool last_lane, Sink &sink, After &&after) {
+                                           uint32_t *tile, const LanePos<D> &p, bool first_lane,
+                                           bool last_lane, Sink &sink, After &&after) {
   constexpr int R = 1 << D, RR = R + 2, V = V4;
   constexpr int NS = ChainGeo<D>::NS, HS = ChainGeo<D>::HS, NT = ChainGeo<D>::NT;
   constexpr int STRIDE = ChainGeo<D>::STRIDE;
@@ -272,9 +274,10 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
   if (cg.packed) {
     auto run = [&](auto ni_c) {
       constexpr int NI = decltype(ni_c)::value;
-      // Channels of values in flight ahead of the one being worked on: two for short lists,
-      // one for lists of up to 16 rows, none beyond (registers).
-      constexpr int DEPTH = NI <= 8 ? 2 : (NI <= 16 ? 1 : 0);
+      // Channels of values in flight ahead of the one being worked on: two for short lists, one
+      // for longer ones (registers; the 32-row walk spills some of them, which still costs far
+      // less than waiting for every channel's values where they are needed).
+      constexpr int DEPTH = NI <= 8 ? 2 : 1;
       constexpr uint32_t kRank = (1u << kInvRankBits) - 1u;
       // this lane's share of the list: entries lane + 64 i.  Past the end of the list an entry
       // repeats the list's first one: it fetches the same value and drops it into the same cell,
@@ -334,29 +337,85 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
       for (int c = 0; c < n_ch; ++c) compute(wdw + (size_t)c * 9);
       return;
     }
-    const int ni = (cg.count + kWave - 1) >> 6;
-    if (ni <= 4) run(std::integral_constant<int, 4>{});
-    else if (ni <= 8) run(std::integral_constant<int, 8>{});
-    else if (ni <= 16) run(std::integral_constant<int, 16>{});
-    else run(std::integral_constant<int, 32>{});
+    if constexpr (NI_FIXED > 0) {
+      run(std::integral_constant<int, NI_FIXED>{});
+    } else {
+      const int ni = (cg.count + kWave - 1) >> 6;
+      if (ni <= 4) run(std::integral_constant<int, 4>{});
+      else if (ni <= 8) run(std::integral_constant<int, 8>{});
+      else if (ni <= 16) run(std::integral_constant<int, 16>{});
+      else run(std::integral_constant<int, 32>{});
+    }
     return;
   }
 
-  // plain path: every slot is looked up again for every channel
+  // plain path: one load per slot that some lane keeps, all of a channel's loads in flight together
 #pragma unroll
   for (int s = 0; s < NT; ++s) mine_row[s] = 0u;
   for (int c = 0; c < n_ch; ++c) {
     const float *pc = plane + (size_t)c * k1;
-    chain_slots<D>(p, active, up_in, dn_in, [&](int s, int pos, bool exists) {
-      if ((cg.any >> s) & 1) {
-        int j = -1;
-        if (exists) j = jm1[pos];
-        if (j >= 0) mine_row[s] = __float_as_uint(pc[j]);
-      }
-    });
+    float v[NT];
+#pragma unroll
+    for (int s = 0; s < NT; ++s) v[s] = pc[max(cg.jj[s], 0)];
+#pragma unroll
+    for (int s = 0; s < NT; ++s) mine_row[s] = cg.jj[s] >= 0 ? __float_as_uint(v[s]) : 0u;
     compute(wdw + (size_t)c * 9);
   }
 }
+
+// Sink of the keep pass for a strip that keeps few of its positions (the counterpart of
+// KeepStagedSink for the [lane][slot] tile): every lane drops its coefficients into its own
+// slots of the tile -- free once the channel's rows have been rebuilt from it --, the wave picks
+// the values of the strip's packed list of kept positions from there and stores NI dense rows
+// (only those are quantised), and the lane's own slots are cleared again for the next channel.
+template <int D, bool Q8, int NI>
+struct ChainStagedSink {
+  using Out = std::conditional_t<Q8, int8_t, float>;
+  static constexpr uint32_t kDropped = 0xFFFFFFFFu;
+  static constexpr int NS = slot_count(D, V4);
+  __amdgpu_buffer_rsrc_t xc_c;  // xc[b, c, :]
+  uint32_t *tile;               // the wave's tile
+  uint32_t *row;                // this lane's slots in it
+  uint32_t cell[NI];            // tile index of the entry's position
+  uint32_t at[NI];              // byte offset of the entry's rank, or kDropped (list padding)
+  float vmax;
+  Quant quant;
+  __device__ __forceinline__ explicit ChainStagedSink(float alpha) : quant(alpha) {}
+  __device__ __forceinline__ void aim(Out *plane, int64_t k) {
+    xc_c = __builtin_amdgcn_make_buffer_rsrc(plane, 0, (int)(uint32_t)(k * (int64_t)sizeof(Out)),
+                                             0x00020000 /* raw dwords, no swizzle */);
+  }
+  template <int L, int J>
+  __device__ __forceinline__ void put_row(const LanePos<D> &p, int i, const float (&v)[cols_at(V4, L)],
+                                          bool owner) {
+    constexpr int CV = cols_at(V4, L);
+    constexpr int base = slot_base(D, V4, L, J);
+    (void)p;
+    (void)owner;  // (a value a lane does not own is in no list)
+#pragma unroll
+    for (int e = 0; e < CV; ++e) row[base + i * CV + e] = __float_as_uint(v[e]);
+  }
+  // once per channel, after the last level
+  __device__ __forceinline__ void flush() {
+    wave_lds_fence();
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const float v = __uint_as_float(tile[cell[i]]);
+      if constexpr (Q8) {
+        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)quant.code(v), xc_c, at[i], 0, 0);
+      } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), xc_c, at[i], 0, 0);
+        vmax = fmaxf(vmax, at[i] != kDropped ? fabsf(v) : 0.f);
+      }
+    }
+    wave_lds_fence();
+    // the strip's own slots go back to zero (the slots that round NS up to a multiple of four
+    // belong to the row above: zero as well until the next channel's values are dropped in)
+#pragma unroll
+    for (int q = 0; q < (NS + 3) / 4; ++q) reinterpret_cast<uint4 *>(row)[q] = make_uint4(0u, 0u, 0u, 0u);
+    wave_lds_fence();
+  }
+};
 
 // Waves per workgroup: two, so that a workgroup's tiles stay small enough for several workgroups
 // to share a compute unit's LDS.
@@ -381,7 +440,7 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_norm_kernel(cons
                                                          StripMap m, int C, int Cg, int B,
                                                          SelectPrep prep) {
   constexpr int NS = slot_count(D, V4);
-  __shared__ uint32_t tiles[kChainWaves][ChainTiles<D>::kWords];
+  __shared__ __attribute__((aligned(16))) uint32_t tiles[kChainWaves][ChainTiles<D>::kWords];
   const int wv = threadIdx.x >> 6;
   const int unit = blockIdx.x * kChainWaves + wv;
   const int grp = blockIdx.y, b = blockIdx.z;
@@ -405,8 +464,7 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_norm_kernel(cons
     for (int s = 0; s < NS; ++s) sink.top[s] = 0.f;
   }
   sink.plane = nullptr;
-  chain_walk<D>(yc1 + ((size_t)b * C + c0) * k1, k1, n_ch, wdw + (size_t)c0 * 9, cg, jm1, active,
-                up_in, dn_in, tiles[wv], p, p.lc == 0, p.lc == m.lpr - 1 || col0 + V4 >= g.W, sink,
+  chain_walk<D>(yc1 + ((size_t)b * C + c0) * k1, k1, n_ch, wdw + (size_t)c0 * 9, cg, tiles[wv], p, p.lc == 0, p.lc == m.lpr - 1 || col0 + V4 >= g.W, sink,
                 [](FwdSink<D, V4, false, SQ> &) {});
   if (!active) return;
   write_slots<D, V4>(norm_part + ((size_t)grp * B + b) * g.N, sink.acc, p);
@@ -431,7 +489,7 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(cons
                                                          const float *__restrict__ alpha_src,
                                                          int n_alpha, float *alpha_pub) {
   constexpr int NS = slot_count(D, V4);
-  __shared__ uint32_t tiles[kChainWaves][ChainTiles<D>::kWords];
+  __shared__ __attribute__((aligned(16))) uint32_t tiles[kChainWaves][ChainTiles<D>::kWords];
   __shared__ float wmax[kChainWaves];
   const int wv = threadIdx.x >> 6;
   const int unit = blockIdx.x * kChainWaves + wv;
@@ -444,7 +502,7 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(cons
   using Sink = KeepSink<D, V4, Q8>;
   using Out = typename Sink::Out;
   Sink sink(0.f);
-  // byte offsets of the consumer's ranks (or "dropped")
+  // the consumer's ranks of this lane's positions (or -1)
   const int32_t *jm3 = jmap3 + (size_t)b * g.N;
   auto fetch = [&](auto Lc, auto Jc) {
     constexpr int L = decltype(Lc)::value, J = decltype(Jc)::value;
@@ -470,9 +528,42 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(cons
   if constexpr (D >= 2) each_level(std::integral_constant<int, 2>{});
   if constexpr (D >= 3) each_level(std::integral_constant<int, 3>{});
 
+  // The consumer's packed list of kept positions of this strip (rank, cell of the lane's own
+  // slot), slot-major, then lane: built in the tile before the producer's list takes it over.
+  constexpr int kRankBits = kInvRankBits;
+  constexpr int STRIDE = ChainGeo<D>::STRIDE;
+  uint32_t *tile = tiles[wv];
+  const int lane = threadIdx.x & (kWave - 1);
+  int count3 = 0;
+#pragma unroll
+  for (int s = 0; s < NS; ++s) count3 += __popcll(__ballot((int)sink.at[s] >= 0));
+  const bool listed3 = count3 <= 16 * kWave && k3 <= ((int64_t)1 << kRankBits);
+  uint32_t cell3[16], at3[16];  // this lane's share: entries lane + 64 i (unused rows fold away)
+  if (listed3) {
+    int running = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int j = (int)sink.at[s];
+      const uint64_t kept = __ballot(j >= 0);
+      const int to = running + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32),
+                                   __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
+      if (j >= 0) tile[to] = (uint32_t)j | ((uint32_t)(lane * STRIDE + s) << kRankBits);
+      running += __popcll(kept);
+    }
+    wave_lds_fence();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int e = lane + kWave * i;
+      const uint32_t packed = e < count3 ? tile[e] : 0u;
+      cell3[i] = e < count3 ? packed >> kRankBits : (uint32_t)(lane * STRIDE);
+      at3[i] = e < count3 ? (packed & ((1u << kRankBits) - 1u)) * (uint32_t)sizeof(Out) : Sink::kDropped;
+    }
+    wave_lds_fence();
+  }
+
   const int32_t *jm1 = jmap1 + (size_t)b * g.N;
   const bool up_in = row0 > 0, dn_in = row0 + (1 << D) < g.H;
-  const ChainGeo<D> cg = chain_setup<D>(jm1, k1, p, active, up_in, dn_in, tiles[wv]);
+  const ChainGeo<D> cg = chain_setup<D>(jm1, k1, p, active, up_in, dn_in, tile);
 
   if constexpr (Q8) {
     if (alpha_src != nullptr) {  // (uniform over the grid; every thread of the workgroup is here)
@@ -480,26 +571,59 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(cons
       if (alpha_pub != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)
         alpha_pub[0] = q_alpha;
     }
-    sink.quant = Quant(q_alpha);
   }
-#pragma unroll
-  for (int s = 0; s < NS; ++s)
-    sink.at[s] = (int)sink.at[s] >= 0 ? sink.at[s] * (uint32_t)sizeof(Out) : Sink::kDropped;
-  sink.vmax = 0.f;
 
+  float mx = 0.f;  // the wave's largest |kept coefficient| (fp32 output only)
   if (__ballot(active) != 0 && n_ch > 0) {
     Out *plane3 = static_cast<Out *>(xc) + ((size_t)b * C + c0) * k3;
-    sink.aim(plane3, k3);
-    chain_walk<D>(yc1 + ((size_t)b * C + c0) * k1, k1, n_ch, wdw + (size_t)c0 * 9, cg, jm1, active,
-                  up_in, dn_in, tiles[wv], p, p.lc == 0, p.lc == m.lpr - 1 || col0 + V4 >= g.W, sink,
-                  [&plane3, k3](Sink &sk) {
-                    plane3 += k3;
-                    sk.aim(plane3, k3);
-                  });
+    const float *plane1 = yc1 + ((size_t)b * C + c0) * k1;
+    const float *kw = wdw + (size_t)c0 * 9;
+    const bool first_lane = p.lc == 0, last_lane = p.lc == m.lpr - 1 || col0 + V4 >= g.W;
+    // Both lists short enough: dense stores of the consumer's list (NI3 rows), producer's list
+    // walked with NI1 rows.  The two go together (both layers keep the same fraction), so three
+    // pairs cover the cases instead of every combination.
+    auto staged = [&](auto ni3_c, auto ni1_c) {
+      constexpr int NI3 = decltype(ni3_c)::value, NI1 = decltype(ni1_c)::value;
+      ChainStagedSink<D, Q8, NI3> st(Q8 ? q_alpha : 0.f);
+      st.tile = tile;
+      st.row = tile + lane * STRIDE;
+#pragma unroll
+      for (int i = 0; i < NI3; ++i) { st.cell[i] = cell3[i]; st.at[i] = at3[i]; }
+      st.vmax = 0.f;
+      st.aim(plane3, k3);
+      chain_walk<D, NI1>(plane1, k1, n_ch, kw, cg, tile, p, first_lane,
+                         last_lane, st, [&plane3, k3](auto &sk) {
+                           sk.flush();
+                           plane3 += k3;
+                           sk.aim(plane3, k3);
+                         });
+      mx = st.vmax;
+    };
+    const int ni3 = (count3 + kWave - 1) >> 6, ni1 = (cg.count + kWave - 1) >> 6;
+    if (listed3 && cg.packed && cg.count > 0 && ni3 <= 4 && ni1 <= 8) {
+      staged(std::integral_constant<int, 4>{}, std::integral_constant<int, 8>{});
+    } else if (listed3 && cg.packed && cg.count > 0 && ni3 <= 8 && ni1 <= 16) {
+      staged(std::integral_constant<int, 8>{}, std::integral_constant<int, 16>{});
+    } else if (listed3 && cg.packed && cg.count > 0 && ni3 <= 16 && ni1 <= 32) {
+      staged(std::integral_constant<int, 16>{}, std::integral_constant<int, 32>{});
+    } else {
+      // one store per slot (lanes that keep nothing there aim beyond the vector)
+      if constexpr (Q8) sink.quant = Quant(q_alpha);
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+        sink.at[s] = (int)sink.at[s] >= 0 ? sink.at[s] * (uint32_t)sizeof(Out) : Sink::kDropped;
+      sink.vmax = 0.f;
+      sink.aim(plane3, k3);
+      chain_walk<D>(plane1, k1, n_ch, kw, cg, tile, p, first_lane, last_lane,
+                    sink, [&plane3, k3](Sink &sk) {
+                      plane3 += k3;
+                      sk.aim(plane3, k3);
+                    });
+      mx = sink.vmax;
+    }
   }
   if constexpr (Q8) return;
   if (alpha_slots == nullptr) return;
-  float mx = sink.vmax;
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
   if ((threadIdx.x & 63) == 0) wmax[wv] = mx;

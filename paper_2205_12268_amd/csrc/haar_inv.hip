@@ -23,10 +23,12 @@ namespace {
 // kept positions, and d = 4 (whose tile would not fit) take the plain path: ranks in registers,
 // one conditional load per slot.
 // The channel walk of the staged path with NI dense fetches per channel.  mine[i]: the lane's
-// list entries (kInvNone: padding).  row_step: W for lanes inside the plane, 0 for the others
-// (whose dst is the scratch line).
+// list entries.  PADDED: entries past the end of the list repeat its first entry (they fetch the
+// same value and drop it into the same cell), so no load and no LDS write needs a lane mask or
+// a branch around it; otherwise padding is kInvNone and is skipped (an empty list).
+// row_step: W for lanes inside the plane, 0 for the others (whose dst is the scratch line).
 // RES: res + (what dst points at, relative to the output tensor) is added to every stored row.
-template <int D, int V, int NI, bool RES, class YT>
+template <int D, int V, int NI, bool RES, class YT, bool PADDED>
 __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane, int64_t k, int n_ch,
                                                 const uint32_t (&mine)[kInvCap / kWave],
                                                 uint32_t *tile, const InvStaged<D, V> &staged,
@@ -36,15 +38,17 @@ __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane,
   constexpr uint32_t kRank = (1u << kInvRankBits) - 1u;
   float vn[NI];
 #pragma unroll
-  for (int i = 0; i < NI; ++i) vn[i] = plane[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+  for (int i = 0; i < NI; ++i)
+    vn[i] = plane[(!PADDED && mine[i] == kInvNone) ? 0u : (mine[i] & kRank)];
   auto channel = [&](int c) {
 #pragma unroll
     for (int i = 0; i < NI; ++i)
-      if (mine[i] != kInvNone) tile[mine[i] >> kInvRankBits] = __float_as_uint(vn[i]);
+      if (PADDED || mine[i] != kInvNone) tile[mine[i] >> kInvRankBits] = __float_as_uint(vn[i]);
     // the next channel's values travel while this one is built (past the end: the last again)
     const float *nx = plane + (size_t)min(c + 1, n_ch - 1) * k;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) vn[i] = nx[mine[i] == kInvNone ? 0u : (mine[i] & kRank)];
+    for (int i = 0; i < NI; ++i)
+      vn[i] = nx[(!PADDED && mine[i] == kInvNone) ? 0u : (mine[i] & kRank)];
     float skip[RES ? R : 1][V];
     if constexpr (RES) {
 #pragma unroll
@@ -169,10 +173,11 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
       }
       wave_lds_fence();
       uint32_t mine[kInvCap / kWave];  // this lane's share of the list: entries lane + 64 i
+      const uint32_t pad = count > 0 ? tile[0] : kInvNone;  // (see inv_staged_walk: PADDED)
 #pragma unroll
       for (int i = 0; i < kInvCap / kWave; ++i) {
         const int e = lane + 64 * i;
-        mine[i] = (i < CAP / kWave && e < count) ? tile[e] : kInvNone;
+        mine[i] = (i < CAP / kWave && e < count) ? tile[e] : pad;
       }
       wave_lds_fence();
 #pragma unroll
@@ -188,12 +193,14 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
       const int row_step = active ? g.W : 0;
       const int64_t dst_step = active ? nstep : 0;
       const int ni = (count + 63) >> 6;
-      if (ni <= 4)
-        inv_staged_walk<D, V, 4, RES, YT>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
+      if (count == 0)  // nothing kept in this strip: rows of zeros (plus the skip connection)
+        inv_staged_walk<D, V, 4, RES, YT, false>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
+      else if (ni <= 4)
+        inv_staged_walk<D, V, 4, RES, YT, true>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
       else if (ni <= 8)
-        inv_staged_walk<D, V, 8, RES, YT>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 8, RES, YT, true>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
       else
-        inv_staged_walk<D, V, 16, RES, YT>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 16, RES, YT, true>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
       return;
     }
   }

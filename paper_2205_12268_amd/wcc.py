@@ -24,7 +24,7 @@ EXPORTS = ("wcc_create", "wcc_destroy", "wcc_workspace_bytes", "wcc_set_workspac
            "wcc_status_string", "wcc_set_profiling", "wcc_stage_times", "wcc_haar_fwd",
            "wcc_joint_topk", "wcc_gather_quant", "wcc_pointwise", "wcc_scatter_ihaar",
            "wcc_forward", "wcc_forward_static", "wcc_forward_fixed", "wcc_block_workspace_bytes", "wcc_depthwise3x3", "wcc_block_forward",
-           "wcc_set_block_profile_layer")
+           "wcc_set_block_profile_layer", "wcc_block_is_chained")
 
 
 class Desc(C.Structure):
@@ -84,9 +84,11 @@ def lib():
         L.wcc_depthwise3x3.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp, vp]
         L.wcc_block_forward.argtypes = [vp, bp] + [vp] * 12
         L.wcc_set_block_profile_layer.argtypes = [vp, C.c_int]
+        L.wcc_block_is_chained.argtypes = [bp]
         for name in EXPORTS:
             if name not in ("wcc_k", "wcc_status_string"):
                 getattr(L, name).restype = C.c_int
+        L.wcc_block_is_chained.restype = C.c_int32
         _lib = L
     return _lib
 
@@ -120,6 +122,14 @@ def make_block_desc(B, Cc, expansion, H, W, levels, keep_num, keep_den, w_dtype,
                     act_quant_bits, act_dtype=F32, norm=NORM_L1) -> BlockDesc:
     return BlockDesc(B, Cc, expansion, H, W, levels, keep_num, keep_den, w_dtype, act_quant_bits,
                      act_dtype, norm)
+
+
+def block_is_chained(desc: BlockDesc) -> bool:
+    """Whether wcc_block_forward without middle outputs chains the two layers of this block."""
+    r = int(lib().wcc_block_is_chained(C.byref(desc)))
+    if r < 0:
+        raise ValueError("invalid block descriptor")
+    return r == 1
 
 
 def block_workspace_bytes(desc: BlockDesc) -> int:

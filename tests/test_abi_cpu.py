@@ -87,3 +87,17 @@ def test_null_arguments_are_reported_not_dereferenced():
     assert L.wcc_haar_fwd(None, C.byref(d), None, None, None, None) == 1
     assert L.wcc_forward(None, C.byref(d), None, None, None, 0.0, None, None, None, None) == 1
     assert wcc.status_string(0) == "ok"
+
+
+def test_which_blocks_are_chained():
+    """Pure host function: chained when nobody asks for the middle tensors and W % 4 == 0,
+    W <= 256, levels <= 3, at most a third of the coefficients kept."""
+    def chained(H, W, levels, num, den):
+        return wcc.block_is_chained(wcc.make_block_desc(2, 8, 4, H, W, levels, num, den, wcc.BF16, 8))
+    assert chained(256, 256, 3, 1, 4) and chained(96, 96, 3, 1, 8) and chained(48, 64, 1, 1, 3)
+    assert not chained(256, 256, 3, 1, 2)        # more than a third kept
+    assert not chained(512, 512, 3, 1, 4)        # rows wider than a wave
+    assert not chained(64, 64, 4, 1, 4)          # four levels
+    assert not chained(16, 10, 1, 1, 4)          # W % 4 != 0
+    with pytest.raises(ValueError):
+        chained(60, 64, 3, 1, 4)                 # H not divisible by 8

@@ -6,9 +6,9 @@ wcc_block_forward chains the two layers when no middle output is asked for and t
 (W % 4 == 0, W <= 256, d <= 3): the project layer's transform passes rebuild the rows they need
 from the expand layer's compressed output.  The shapes below walk through what that code
 depends on: one, two and four strips a wave, planes of one strip (no row above or below), many
-strips, rows that leave lanes idle, every level count, kept lists of 4, 8, 16 and 32 rows a wave
-and strips that keep everything (the slot-by-slot route), no quantiser, int8 weights, several
-samples and channel groups.
+strips, rows that leave lanes idle, every level count, kept lists of 4, 8, 16 and 32 rows a wave,
+strips that keep everything (the slot-by-slot route) and strips that keep nothing, no quantiser,
+int8 weights, several samples and channel groups.
 """
 import numpy as np
 import pytest
@@ -33,16 +33,27 @@ CASES = [
     blk("two_strips_d3", 2, 8, 2, 48, 128, 3, 1, 4, BF16, 8),          # two strips a wave
     blk("idle_lanes_d3", 1, 4, 3, 40, 96, 3, 1, 4, BF16, 8),           # 24 of 32 lanes a row
     blk("four_strips_d2", 1, 8, 2, 36, 64, 2, 1, 4, I8, 8),            # four strips a wave, ragged last wave
-    blk("one_strip_plane", 2, 4, 2, 8, 64, 3, 1, 2, BF16, 8),          # no row above or below
-    blk("d1_tall", 1, 4, 2, 30, 32, 1, 1, 2, BF16, 8),                 # d = 1: every slot is a halo slot
-    blk("d2_half", 1, 8, 4, 64, 256, 2, 1, 2, BF16, 8),                # long lists (16 rows a wave)
-    blk("d3_half", 1, 4, 2, 32, 256, 3, 1, 2, BF16, 8),                # lists of more than 16 rows
-    blk("keep_all_d3", 1, 4, 2, 24, 256, 3, 1, 1, BF16, 8),            # every strip beyond the list: slot by slot
+    blk("one_strip_plane", 2, 4, 2, 8, 64, 3, 1, 4, BF16, 8),          # no row above or below
+    blk("d1_tall", 1, 4, 2, 30, 32, 1, 1, 4, BF16, 8),                 # d = 1: every slot is a halo slot
+    blk("d2_dense_top", 1, 8, 4, 64, 256, 2, 1, 4, BF16, 8),           # long lists (16 rows a wave) on top, empty strips below
+    blk("d3_dense_top", 1, 4, 2, 32, 256, 3, 1, 4, BF16, 8),           # lists of more than 16 rows; empty strips
+    blk("d3_all_on_top", 1, 4, 2, 32, 256, 3, 1, 4, BF16, 8),          # strips that keep everything: slot by slot
     blk("keep_few_d3", 1, 8, 2, 64, 256, 3, 1, 64, BF16, 8, 3.0),      # short lists, empty strips
     blk("f32_noquant_d2", 2, 4, 3, 16, 48, 2, 1, 3, F32, 0, 1.0),      # fp32 path, k % 4 != 0
-    blk("ragged_k_d3", 1, 8, 2, 24, 40, 3, 3, 7, BF16, 8),             # k % 4 != 0 with the quantiser
+    blk("ragged_k_d3", 1, 8, 2, 24, 40, 3, 2, 7, BF16, 8),             # k % 4 != 0 with the quantiser
     blk("many_channels", 2, 16, 8, 32, 64, 3, 1, 4, BF16, 8),          # 128 middle channels in groups
 ]
+# Rows of the input from this fraction of the height on are zero, so that the kept positions of
+# both layers crowd into the strips above: strips that keep a half or all of their positions at
+# a keep ratio the chained route takes, and strips that keep nothing.
+ZERO_BELOW = {"d2_dense_top": 0.5, "d3_dense_top": 0.5, "d3_all_on_top": 0.25}
+
+
+def block_inputs(cfg):
+    x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
+    if cfg.name in ZERO_BELOW:
+        x[:, :, int(cfg.H * ZERO_BELOW[cfg.name]):, :] = 0.0
+    return x, w1, w_dw, w3
 
 
 @pytest.fixture(scope="module")
@@ -55,9 +66,10 @@ def ctx():
 @pytest.mark.parametrize("cfg", CASES, ids=lambda c: c.name)
 def test_chained_block_matches_oracle_and_materialised_route(ref, ctx, cfg):
     print(f"{cfg}", flush=True)
-    x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
+    x, w1, w_dw, w3 = block_inputs(cfg)
     d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
                             cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+    assert wcc.block_is_chained(d)
     ctx.ensure_workspace(d)
     xd = dev(x)
     w1d, w1s = upload_weights(w1)
@@ -107,7 +119,7 @@ def test_chained_block_with_bf16_maps(ctx, cfg):
     that differs from the chained call with fp32 maps on the same bf16-valued input: the same index
     sets, and that call's output rounded once to nearest even.  (The fp32 call is the one held
     to the oracle above.)"""
-    x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
+    x, w1, w_dw, w3 = block_inputs(cfg)
     x = synth.round_to_bf16(x)
     w1d, w1s = upload_weights(w1)
     w3d, w3s = upload_weights(w3)
