@@ -153,11 +153,49 @@ def bench_stack(args, synth, run_layer, ctx) -> int:
     return 0
 
 
-def bench_block(args, synth, wcc, torch, np) -> int:
-    """The inverted residual block the paper timed (appendix "Inference times"): 256x256 image,
-    c_in 256, expansion 4, batch 8, one row of its table per keep ratio."""
-    num, den = (int(t) for t in args.keep.split("/"))
-    cfg = synth.block_config(num, den)
+ALU_PEAK_TFLOPS = 157.3  # fp32 vector, published (counts packed operations; this build issues none)
+# fp32 operations per pixel and middle channel of one chained transform pass (3 levels): the 3x3
+# convolution 18, the strip's synthesis 7.9, the two halo rows 2.0, the analysis 7.9, norms 2.1
+CHAIN_FLOP_PER_PIXEL_CHANNEL = 37.9
+
+# Table "Inference timing results" of the appendix "Inference times": image side, c_in, expansion,
+# batch, kept fraction, and the speed-up the paper measured on a GTX 1080 Ti (context only)
+PAPER_TABLE = [
+    (96, 512, 2, 48, (1, 4), 1.52), (96, 512, 2, 48, (1, 2), 1.20), (96, 512, 4, 24, (1, 4), 1.71),
+    (96, 512, 4, 24, (1, 2), 1.29), (96, 1024, 2, 12, (1, 4), 1.94), (96, 1024, 2, 12, (1, 2), 1.38),
+    (96, 1024, 4, 6, (1, 4), 2.13), (96, 1024, 4, 6, (1, 2), 1.47), (128, 128, 4, 80, (1, 4), 1.20),
+    (128, 128, 6, 64, (1, 4), 1.28), (128, 256, 4, 32, (1, 8), 1.81), (128, 256, 4, 32, (1, 4), 1.53),
+    (128, 256, 4, 32, (1, 2), 1.27), (256, 256, 4, 8, (1, 8), 1.85), (256, 256, 4, 8, (1, 4), 1.57),
+    (256, 256, 4, 8, (1, 2), 1.29), (256, 256, 8, 4, (1, 8), 1.99), (256, 256, 8, 4, (1, 4), 1.68),
+    (256, 256, 8, 4, (1, 2), 1.39), (512, 128, 6, 4, (1, 4), 1.41), (512, 128, 6, 2, (1, 2), 1.12),
+    (512, 256, 4, 2, (1, 8), 1.77), (512, 256, 4, 2, (1, 4), 1.52), (512, 256, 4, 2, (1, 2), 1.20),
+]
+
+
+def block_algorithmic_bytes(cfg, act_bytes: int, chained: bool) -> dict:
+    """Bytes every kernel of the block must move per call (see algorithmic_bytes).  Chained, the
+    expand layer has no inverse and the project layer's two passes read the expand layer's
+    compressed output (and its rank map) instead of the expanded feature map."""
+    alg = {}
+    for layer in (0, 1):
+        for name, v in algorithmic_bytes(cfg.layer(layer), act_bytes).items():
+            alg[f"l{layer}_{name}"] = v
+    alg["l1_scatter_ihaar"] += act_bytes * cfg.B * cfg.C * cfg.N      # the skip connection is read
+    # K_dw is folded into the project layer's passes when W % 4 == 0 (its output is never written)
+    alg["depthwise"] = 0 if cfg.W % 4 == 0 else 8 * cfg.B * cfg.C_mid * cfg.N
+    if chained:
+        l1 = cfg.layer(1)
+        xcb = 1 if (cfg.act_bits == 8 and cfg.k % 4 == 0) else 4
+        src = 4 * cfg.B * cfg.C_mid * cfg.k + 4 * cfg.B * cfg.N       # Y_wt of the expand layer + its rank map
+        alg["l0_scatter_ihaar"] = 0
+        alg["l1_haar_fwd"] = src + 4 * cfg.B * cfg.N
+        alg["l1_gather"] = src + 4 * cfg.B * cfg.k + xcb * l1.B * l1.C_in * cfg.k
+    return alg
+
+
+def time_block(cfg, args, synth, wcc, torch, np, dense: bool) -> dict:
+    """Times args.steps forwards of one inverted residual block (and, if asked, the dense block
+    on the same GPU); returns the measurements."""
     x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
     bf16 = args.act == "bf16"
     if bf16:
@@ -165,6 +203,7 @@ def bench_block(args, synth, wcc, torch, np) -> int:
     d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
                             cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.BF16 if bf16 else wcc.F32,
                             wcc.NORM_L2 if args.norm == "l2" else wcc.NORM_L1)
+    chained = wcc.block_is_chained(d)
     ctx = wcc.Context(0)
     ctx.ensure_workspace(d)
 
@@ -200,24 +239,10 @@ def bench_block(args, synth, wcc, torch, np) -> int:
             for name, ms in ctx.stage_times().items():
                 acc[name] = acc.get(name, 0.0) + ms
         ctx.set_profiling(False)
-        pair = acc.pop("event_pair")
+        acc.pop("event_pair")
         for name, v in acc.items():
             key = name if name == "depthwise" else f"l{layer}_{name}"
-            stage_us[key] = max(1e3 * (v - pair) / args.steps, 0.0)
-    alg = {}
-    ab = 2 if bf16 else 4
-    for layer in (0, 1):
-        for name, v in algorithmic_bytes(cfg.layer(layer), ab).items():
-            alg[f"l{layer}_{name}"] = v
-    alg["l1_scatter_ihaar"] += ab * cfg.B * cfg.C * cfg.N         # the skip connection is read
-    # K_dw is folded into the project layer's passes when W % 4 == 0 (its output is never written)
-    alg["depthwise"] = 0 if cfg.W % 4 == 0 else 8 * cfg.B * cfg.C_mid * cfg.N
-    kernel_of = {"depthwise": "depthwise3x3_kernel"}
-    for layer in (0, 1):
-        for name, kname in STAGE_KERNEL.items():
-            kernel_of[f"l{layer}_{name}"] = kname
-    dom = max(kernel_of, key=lambda n: stage_us[n])
-    achieved = alg[dom] / (stage_us[dom] * 1e-6) / 1e9
+            stage_us[key] = 1e3 * v / args.steps
 
     # The dense block on the same GPU (the "standard" column of the paper's table), twice:
     # (a) the framework's library convolutions in bf16 as they come -- on this stack the
@@ -225,37 +250,79 @@ def bench_block(args, synth, wcc, torch, np) -> int:
     # (b) the framework's two bf16 1x1 convolutions and the skip addition, plus this library's
     #     own depthwise kernel (fp32) on a tensor of the same shape: the fair comparison.
     dense_ms = dense_fair_ms = None
-    try:
-        if args.no_dense_baseline:
-            raise RuntimeError("switched off on the command line")
-        F = torch.nn.functional
-        xb = xd.to(torch.bfloat16)
-        k1 = torch.from_numpy(w1.values.astype(np.float32)).cuda().to(torch.bfloat16)[:, :, None, None]
-        k3 = torch.from_numpy(w3.values.astype(np.float32)).cuda().to(torch.bfloat16)[:, :, None, None]
-        kd = wdd.to(torch.bfloat16)[:, None]
+    if dense:
+        try:
+            F = torch.nn.functional
+            xb = xd.to(torch.bfloat16)
+            k1 = torch.from_numpy(w1.values.astype(np.float32)).cuda().to(torch.bfloat16)[:, :, None, None]
+            k3 = torch.from_numpy(w3.values.astype(np.float32)).cuda().to(torch.bfloat16)[:, :, None, None]
+            kd = wdd.to(torch.bfloat16)[:, None]
 
-        def timed(fn, reps):
-            for _ in range(3):
-                fn()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(reps):
-                fn()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t0) / reps * 1e3
+            def timed(fn, reps):
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    fn()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) / reps * 1e3
 
-        dense_ms = timed(lambda: xb + F.conv2d(F.conv2d(F.conv2d(xb, k1), kd, padding=1,
-                                                        groups=cfg.C_mid), k3), args.steps)
-        mid_b = F.conv2d(xb, k1)
-        mid_f = mid_b.float()
-        mid_g = torch.empty_like(mid_f)
-        dense_fair_ms = (timed(lambda: F.conv2d(xb, k1), args.steps)
-                         + timed(lambda: ctx.wcc_depthwise3x3(mid_f, wdd, mid_g), args.steps)
-                         + timed(lambda: xb + F.conv2d(mid_b, k3), args.steps))
-        del mid_b, mid_f, mid_g
-    except Exception as exc:  # the library convolutions are context only
-        print(f"bench.py: dense block baseline skipped ({exc})", file=sys.stderr)
+            if not args.table:
+                dense_ms = timed(lambda: xb + F.conv2d(F.conv2d(F.conv2d(xb, k1), kd, padding=1,
+                                                                groups=cfg.C_mid), k3), args.steps)
+            mid_b = F.conv2d(xb, k1)
+            mid_f = mid_b.float()
+            mid_g = torch.empty_like(mid_f)
+            dense_fair_ms = (timed(lambda: F.conv2d(xb, k1), args.steps)
+                             + timed(lambda: ctx.wcc_depthwise3x3(mid_f, wdd, mid_g), args.steps)
+                             + timed(lambda: xb + F.conv2d(mid_b, k3), args.steps))
+            del mid_b, mid_f, mid_g
+        except Exception as exc:  # the library convolutions are context only
+            print(f"bench.py: dense block baseline skipped ({exc})", file=sys.stderr)
+    ctx.close()
+    return {"cfg": cfg, "x": x, "w1": w1, "w_dw": w_dw, "w3": w3, "dt": dt, "stage_us": stage_us,
+            "chained": chained, "dense_ms": dense_ms, "dense_fair_ms": dense_fair_ms, "bf16": bf16}
 
+
+def block_from_shape(synth, shape: str, num: int, den: int):
+    """--shape SIDE,c,e,B or HxW,c,e,B -> a BlockCfg with 3 levels, bf16 weights, 8-bit codes."""
+    side, c, e, B = shape.split(",")
+    H, W = (int(t) for t in side.split("x")) if "x" in side else (int(side), int(side))
+    return synth.BlockCfg(f"block_{H}x{W}_c{c}_e{e}_b{B}_keep{num}of{den}", int(B), int(c), int(e), H, W,
+                          3, num, den, synth.W_BF16, 8)
+
+
+def bench_block(args, synth, wcc, torch, np) -> int:
+    """The inverted residual block the paper timed (appendix "Inference times"): by default
+    256x256 image, c_in 256, expansion 4, batch 8, one row of its table per keep ratio."""
+    num, den = (int(t) for t in args.keep.split("/"))
+    cfg = block_from_shape(synth, args.shape, num, den) if args.shape else synth.block_config(num, den)
+    r = time_block(cfg, args, synth, wcc, torch, np, dense=not args.no_dense_baseline)
+    dt, stage_us, chained, bf16 = r["dt"], r["stage_us"], r["chained"], r["bf16"]
+    dense_ms, dense_fair_ms = r["dense_ms"], r["dense_fair_ms"]
+    alg = block_algorithmic_bytes(cfg, 2 if bf16 else 4, chained)
+    kernel_of = {"depthwise": "depthwise3x3_kernel"}
+    for layer in (0, 1):
+        for name, kname in STAGE_KERNEL.items():
+            kernel_of[f"l{layer}_{name}"] = kname
+    if chained:
+        kernel_of["l1_haar_fwd"], kernel_of["l1_gather"] = "chain_norm_kernel", "chain_keep_kernel"
+    dom = max(kernel_of, key=lambda n: stage_us[n])
+    if chained and dom in ("l1_haar_fwd", "l1_gather"):
+        # the chained passes are bound by fp32 vector arithmetic, not by bytes
+        flops = CHAIN_FLOP_PER_PIXEL_CHANNEL * cfg.B * cfg.C_mid * cfg.N
+        ach = flops / (stage_us[dom] * 1e-6) / 1e12
+        roof = {"bound": "alu", "kernel": kernel_of[dom], "stage": dom, "achieved": round(ach, 2),
+                "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / ALU_PEAK_TFLOPS, 4),
+                "frac_of_unpacked_peak": round(ach / (ALU_PEAK_TFLOPS / 2), 4), "traffic": None,
+                "algorithmic_flops": flops, "algorithmic_bytes": alg[dom],
+                "kernel_us": round(stage_us[dom], 2)}
+    else:
+        achieved = alg[dom] / (stage_us[dom] * 1e-6) / 1e9
+        roof = {"bound": "hbm", "kernel": kernel_of[dom], "stage": dom, "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "algorithmic_bytes": alg[dom], "kernel_us": round(stage_us[dom], 2)}
     pix_ch = cfg.B * cfg.N * cfg.C
     out = {
         "metric": "WCC layer forward throughput", "value": round(pix_ch / dt / 1e9, 3),
@@ -264,11 +331,9 @@ def bench_block(args, synth, wcc, torch, np) -> int:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": "eager",
         "config": {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "expansion": cfg.expansion,
                    "H": cfg.H, "W": cfg.W, "levels": cfg.levels, "keep": f"{num}/{den}",
-                   "act_bits": cfg.act_bits, "act": args.act, "norm": args.norm},
-        "roofline": {"bound": "hbm", "kernel": kernel_of[dom], "stage": dom,
-                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "algorithmic_bytes": alg[dom], "kernel_us": round(stage_us[dom], 2)},
+                   "act_bits": cfg.act_bits, "act": args.act, "norm": args.norm,
+                   "route": "chained" if chained else "middle tensors formed"},
+        "roofline": roof,
         "stages_us": {n: round(v, 2) for n, v in stage_us.items()},
         "block_alg_GBs": round(sum(alg.values()) / dt / 1e9, 1),
         "dense_block_ms": {"framework_bf16": None if dense_ms is None else round(dense_ms, 4),
@@ -283,14 +348,39 @@ def bench_block(args, synth, wcc, torch, np) -> int:
         cores = min(len(os.sched_getaffinity(0)), 16)
         wcc_ref.set_threads(cores)
         t1 = time.perf_counter()
-        wcc_ref.block_forward(x[:1], w1.values, None, w_dw, w3.values, None, cfg.levels,
+        wcc_ref.block_forward(r["x"][:1], r["w1"].values, None, r["w_dw"], r["w3"].values, None, cfg.levels,
                               cfg.keep_num, cfg.keep_den, cfg.act_bits)
         cpu_dt = time.perf_counter() - t1
         out["cpu_baseline"] = {"value": round(cfg.N * cfg.C / cpu_dt / 1e9, 5), "unit": "Gpixel*ch/s",
                                "cores": cores, "kind": "oracle",
                                "sample": f"block forward of 1 of the {cfg.B} samples, {cpu_dt:.2f} s"}
     print(json.dumps(out))
-    ctx.close()
+    return 0
+
+
+def bench_table(args, synth, wcc, torch, np) -> int:
+    """Every row of the paper's timing table (batch as printed): this library's block, the fair
+    dense block on the same GPU, their ratio, and the paper's ratio as context.  One JSON line."""
+    rows = []
+    for side, c, e, B, (num, den), paper in PAPER_TABLE:
+        cfg = block_from_shape(synth, f"{side},{c},{e},{B}", num, den)
+        print(f"bench.py: {cfg.name}", file=sys.stderr, flush=True)
+        r = time_block(cfg, args, synth, wcc, torch, np, dense=True)
+        wcc_ms = r["dt"] * 1e3
+        fair = r["dense_fair_ms"]
+        rows.append({"image": side, "c_in": c, "expansion": e, "batch": B, "keep": f"{num}/{den}",
+                     "route": "chained" if r["chained"] else "middle tensors formed",
+                     "wcc_ms": round(wcc_ms, 4), "dense_ms": None if fair is None else round(fair, 4),
+                     "speedup": None if fair is None else round(fair / wcc_ms, 3),
+                     "paper_speedup_gtx1080ti": paper})
+        torch.cuda.empty_cache()
+    won = [r for r in rows if r["speedup"] and r["speedup"] > 1.0]
+    out = {"metric": "inverted residual block, WCC vs dense on the same GPU", "unit": "ms",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+           "dtype": "bf16", "act": args.act,
+           "dense": "framework bf16 1x1 convolutions + this library's fp32 depthwise kernel",
+           "rows_faster_than_dense": len(won), "rows": rows}
+    print(json.dumps(out))
     return 0
 
 
@@ -319,6 +409,11 @@ def main() -> int:
     ap.add_argument("--index-list", choices=["select", "prefix"], default="select",
                     help="prefix: wcc_forward_fixed with the first k positions instead of the joint "
                          "shrinkage's top-k (single-layer workloads)")
+    ap.add_argument("--shape", default="", metavar="SIDE,c,e,B",
+                    help="--config 6: another block shape (image side or HxW, c_in, expansion, batch)")
+    ap.add_argument("--table", action="store_true",
+                    help="the 24 rows of the paper's timing table, WCC and fair dense block each "
+                         "(use a small --steps)")
     ap.add_argument("--no-dense-baseline", action="store_true",
                     help="--config 6: skip timing the dense block built from library convolutions")
     ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
@@ -438,6 +533,8 @@ def main() -> int:
         stage_us = {n: max(1e3 * v / args.steps - pair_us, 0.0) for n, v in acc.items()}
         return dt, stage_us, pair_us, x, w
 
+    if args.table:
+        return bench_table(args, synth, wcc, torch, np)
     if args.config == 6:
         return bench_block(args, synth, wcc, torch, np)
     ctx = wcc.Context(0)

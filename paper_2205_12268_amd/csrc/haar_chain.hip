@@ -21,9 +21,6 @@
 // a row of the plane fits into one wave row (W <= 256), so that the convolution's outside
 // columns come from neighbouring lanes or are the plane's zero border.
 #include "strip_io.h"
-#ifdef WCC_CHAIN_DEBUG
-#include <cstdio>
-#endif
 
 namespace wcc {
 namespace {
@@ -41,24 +38,8 @@ __host__ __device__ constexpr int hslot_count(int D, int V) {
   return hslot_base(D, V, D, 3) + cols_at(V, D);
 }
 
-// The wave's LDS tile is laid out [lane][slot]: a lane's NT slots are contiguous, so one channel's
-// kept values come back with NT / 4 16-byte reads and no branch (cells of positions that are
-// not kept hold zero).  The lane stride is an odd multiple of four words: the 16 lanes of one
-// read cycle then touch every bank once.
-__host__ __device__ constexpr int chain_stride(int nt) { return (nt / 4) % 2 == 1 ? nt : nt + 4; }
-
-// sources of the synthesis: the lane's slots as read back from the tile into registers
-template <int D, int V, int N>
-struct RegStrip {
-  const float (&c)[N];
-  template <int L, int J>
-  __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
-    constexpr int CV = cols_at(V, L);
-    constexpr int base = slot_base(D, V, L, J);
-#pragma unroll
-    for (int e = 0; e < CV; ++e) v[e] = c[base + i * CV + e];
-  }
-};
+// (the [lane][slot] tile layout and RegStrip, the source that reads a lane's slots back from
+// registers, are in strip_io.h: the inverse transform uses them too)
 template <int D, int V, int N>
 struct RegRow {
   const float (&c)[N];
@@ -108,7 +89,7 @@ constexpr int kChainCap = 2048;  // packed entries per wave (32 a lane)
 template <int D>
 struct ChainGeo {
   static constexpr int NS = slot_count(D, V4), HS = hslot_count(D, V4), NT = NS + 2 * HS;
-  static constexpr int STRIDE = chain_stride(NT);  // words between two lanes' slots in the tile
+  static constexpr int STRIDE = tile_stride(NT);  // words between two lanes' slots in the tile
   uint64_t any;        // wave-uniform: bit s set if some lane keeps slot s (NT <= 64)
   int count;           // kept entries of the wave (wave-uniform)
   bool packed;         // the tile holds the wave's packed list (rank | cell << kInvRankBits)
@@ -705,18 +686,5 @@ hipError_t launch_chain_keep(const wcc_desc &d, int64_t k, const ChainSrc &src, 
 #undef WCC_CHAIN_KEEP
   return hipGetLastError();
 }
-
-#ifdef WCC_CHAIN_DEBUG
-extern "C" void wcc_debug_chain_occ() {
-  int n = -1;
-  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, chain_norm_kernel<3, false>, kChainWaves * kWave, 0);
-  printf("chain_norm<3>: blocks/CU %d (err %d), threads %d\n", n, (int)e, kChainWaves * kWave);
-  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, chain_keep_kernel<3, true>, kChainWaves * kWave, 0);
-  printf("chain_keep<3,q8>: blocks/CU %d (err %d)\n", n, (int)e);
-  hipFuncAttributes a;
-  e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(chain_norm_kernel<3, false>));
-  printf("norm: regs %d shared %zu local %zu maxthreads %d\n", a.numRegs, a.sharedSizeBytes, a.localSizeBytes, a.maxThreadsPerBlock);
-}
-#endif
 
 }  // namespace wcc

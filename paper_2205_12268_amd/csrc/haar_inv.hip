@@ -17,8 +17,8 @@ namespace {
 // are packed once per wave into a list (rank j, cell), slot by slot and lane by lane, held in
 // registers, 64 entries a row.  Per channel the wave fetches yc[.., j] for the whole list with
 // a few dense loads (neighbouring entries have mostly neighbouring j), drops the values into an
-// LDS tile laid out [slot][lane] whose other cells stay zero, and every lane reads its slots
-// back from there.  Lanes outside the plane take part in the list work and send their stores
+// LDS tile laid out [lane][slot] whose other cells stay zero, and every lane reads its slots
+// back from there with 16-byte reads.  Lanes outside the plane take part in the list work and send their stores
 // to a scratch line.  Strips that keep more than kInvCap positions, layers with more than 2^20
 // kept positions, and d = 4 (whose tile would not fit) take the plain path: ranks in registers,
 // one conditional load per slot.
@@ -31,9 +31,10 @@ namespace {
 template <int D, int V, int NI, bool RES, class YT, bool PADDED>
 __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane, int64_t k, int n_ch,
                                                 const uint32_t (&mine)[kInvCap / kWave],
-                                                uint32_t *tile, const InvStaged<D, V> &staged,
+                                                uint32_t *tile, const uint32_t *row,
                                                 const LanePos<D> &p, YT *dst, int row_step,
                                                 int64_t dst_step, const YT *res) {
+  constexpr int NSP = (slot_count(D, V) + 3) / 4 * 4;  // the lane's slots, whole 16-byte words
   constexpr int R = 1 << D;
   constexpr uint32_t kRank = (1u << kInvRankBits) - 1u;
   float vn[NI];
@@ -57,7 +58,18 @@ __device__ __forceinline__ void inv_staged_walk(const float *__restrict__ plane,
     __builtin_amdgcn_sched_barrier(0);
     wave_lds_fence();
     float out[R][V];
-    inv_levels<D, V, 1>(out, p, staged);
+    {
+      // the lane's slots come back with NSP / 4 16-byte reads: cells of positions that are not
+      // kept hold zero, so there is nothing to test and no branch
+      float cells[NSP];
+#pragma unroll
+      for (int q = 0; q < NSP / 4; ++q) {
+        const float4 t = reinterpret_cast<const float4 *>(row)[q];
+        cells[4 * q] = t.x; cells[4 * q + 1] = t.y; cells[4 * q + 2] = t.z; cells[4 * q + 3] = t.w;
+      }
+      const RegStrip<D, V, NSP> src{cells};
+      inv_levels<D, V, 1>(out, p, src);
+    }
     wave_lds_fence();
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (RES) {
@@ -90,11 +102,12 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
                                                             const YT *residual) {
   constexpr int R = 1 << D;
   constexpr int NS = slot_count(D, V);
-  constexpr bool kStaged = D <= 3;  // the [slot][lane] tiles of four waves fit in LDS
+  constexpr bool kStaged = D <= 3;  // the [lane][slot] tiles of four waves fit in LDS
   constexpr int CAP = NS * kWave < kInvCap ? NS * kWave : kInvCap;  // entries a wave can pack
+  constexpr int STRIDE = tile_stride((NS + 3) / 4 * 4);  // words between two lanes' slots
   static_assert(NS <= 128, "slot mask is 128 bits wide");
-  static_assert(!kStaged || NS * kWave <= (1 << (32 - kInvRankBits)), "cell index fits above the rank");
-  __shared__ uint32_t tiles[kStaged ? 4 : 1][kStaged ? NS * kWave : 1];
+  static_assert(!kStaged || STRIDE * kWave <= (1 << (32 - kInvRankBits)), "cell index fits above the rank");
+  __shared__ __attribute__((aligned(16))) uint32_t tiles[kStaged ? 4 : 1][kStaged ? STRIDE * kWave : 1];
   const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int unit = blockIdx.x * 4 + wv;
   // Samples are taken last to first: the contraction wrote yc first to last, so what is still
@@ -167,7 +180,7 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
           const uint64_t kept = __ballot(j >= 0);
           const int at = running + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(kept >> 32),
                                        __builtin_amdgcn_mbcnt_lo((uint32_t)kept, 0u));
-          if (j >= 0) tile[at] = (uint32_t)j | ((uint32_t)(s * kWave + lane) << kInvRankBits);
+          if (j >= 0) tile[at] = (uint32_t)j | ((uint32_t)(lane * STRIDE + s) << kInvRankBits);
           running += __popcll(kept);
         }
       }
@@ -180,13 +193,9 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
         mine[i] = (i < CAP / kWave && e < count) ? tile[e] : pad;
       }
       wave_lds_fence();
+      uint32_t *row = tile + lane * STRIDE;  // this lane's slots
 #pragma unroll
-      for (int s = 0; s < NS; ++s) tile[s * kWave + lane] = 0u;
-
-      InvStaged<D, V> staged;
-      staged.cell = reinterpret_cast<const float *>(tile) + lane;
-      staged.any[0] = src.any[0];
-      staged.any[1] = src.any[1];
+      for (int s = 0; s < (NS + 3) / 4 * 4; ++s) row[s] = 0u;
       YT *sink_line = reinterpret_cast<YT *>(scratch) + lane * V;
       YT *to = active ? dst : sink_line;
       const YT *res = (RES && active) ? residual + first : sink_line;
@@ -194,13 +203,13 @@ __global__ __launch_bounds__(256) void scatter_ihaar_kernel(const float *__restr
       const int64_t dst_step = active ? nstep : 0;
       const int ni = (count + 63) >> 6;
       if (count == 0)  // nothing kept in this strip: rows of zeros (plus the skip connection)
-        inv_staged_walk<D, V, 4, RES, YT, false>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 4, RES, YT, false>(plane, kstep, n_ch, mine, tile, row, p, to, row_step, dst_step, res);
       else if (ni <= 4)
-        inv_staged_walk<D, V, 4, RES, YT, true>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 4, RES, YT, true>(plane, kstep, n_ch, mine, tile, row, p, to, row_step, dst_step, res);
       else if (ni <= 8)
-        inv_staged_walk<D, V, 8, RES, YT, true>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 8, RES, YT, true>(plane, kstep, n_ch, mine, tile, row, p, to, row_step, dst_step, res);
       else
-        inv_staged_walk<D, V, 16, RES, YT, true>(plane, kstep, n_ch, mine, tile, staged, p, to, row_step, dst_step, res);
+        inv_staged_walk<D, V, 16, RES, YT, true>(plane, kstep, n_ch, mine, tile, row, p, to, row_step, dst_step, res);
       return;
     }
   }

@@ -158,7 +158,17 @@ __device__ __forceinline__ uint4 load_keys(const float *__restrict__ src, float 
 __device__ __forceinline__ float4 load_top(const float *__restrict__ top_part, int G, int64_t BN,
                                            int64_t at) {
   float4 m = *reinterpret_cast<const float4 *>(top_part + at);
-  for (int g = 1; g < G; ++g) {
+  int g = 1;
+  for (; g + 4 <= G; g += 4) {  // four loads in flight
+    float4 t[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = *reinterpret_cast<const float4 *>(top_part + (int64_t)(g + i) * BN + at);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      m.x = fmaxf(m.x, t[i].x); m.y = fmaxf(m.y, t[i].y); m.z = fmaxf(m.z, t[i].z); m.w = fmaxf(m.w, t[i].w);
+    }
+  }
+  for (; g < G; ++g) {
     const float4 t = *reinterpret_cast<const float4 *>(top_part + (int64_t)g * BN + at);
     m.x = fmaxf(m.x, t.x); m.y = fmaxf(m.y, t.y); m.z = fmaxf(m.z, t.z); m.w = fmaxf(m.w, t.w);
   }

@@ -15,11 +15,7 @@ namespace {
 // SQ: the sums are of squared coefficients (one fused multiply-add each) instead.
 template <int D, int V, bool STORE, bool SQ = false>
 struct FwdSink {
-#ifdef WCC_NO_TOP
-  static constexpr bool MX = false;
-#else
   static constexpr bool MX = !STORE;
-#endif
   float *plane;  // wavelet vector of the current (b, c)
   float acc[slot_count(D, V)];
   float top[MX ? slot_count(D, V) : 1];  // max over the channels of |coefficient|
@@ -257,5 +253,23 @@ __device__ __forceinline__ void inv_levels(float (&out)[rows_at(D, L - 1)][cols_
   }
 }
 
+// The wave's LDS tile is laid out [lane][slot]: a lane's NT slots are contiguous, so one channel's
+// kept values come back with NT / 4 16-byte reads and no branch (cells of positions that are
+// not kept hold zero).  The lane stride is an odd multiple of four words: the 16 lanes of one
+// read cycle then touch every bank once.
+__host__ __device__ constexpr int tile_stride(int nt) { return (nt / 4) % 2 == 1 ? nt : nt + 4; }
+
+// sources of the synthesis: the lane's slots as read back from the tile into registers
+template <int D, int V, int N>
+struct RegStrip {
+  const float (&c)[N];
+  template <int L, int J>
+  __device__ __forceinline__ void get_row(int i, float (&v)[cols_at(V, L)]) const {
+    constexpr int CV = cols_at(V, L);
+    constexpr int base = slot_base(D, V, L, J);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) v[e] = c[base + i * CV + e];
+  }
+};
 }  // namespace
 }  // namespace wcc
