@@ -286,11 +286,10 @@ def time_block(cfg, args, synth, wcc, torch, np, dense: bool) -> dict:
 
 
 def block_from_shape(synth, shape: str, num: int, den: int):
-    """--shape SIDE,c,e,B or HxW,c,e,B -> a BlockCfg with 3 levels, bf16 weights, 8-bit codes."""
+    """--shape SIDE,c,e,B or HxW,c,e,B -> a block of the paper's kind (3 levels, 8-bit codes)."""
     side, c, e, B = shape.split(",")
     H, W = (int(t) for t in side.split("x")) if "x" in side else (int(side), int(side))
-    return synth.BlockCfg(f"block_{H}x{W}_c{c}_e{e}_b{B}_keep{num}of{den}", int(B), int(c), int(e), H, W,
-                          3, num, den, synth.W_BF16, 8)
+    return synth.block_shape(H, W, int(c), int(e), int(B), num, den)
 
 
 def bench_block(args, synth, wcc, torch, np) -> int:

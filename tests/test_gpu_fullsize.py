@@ -167,16 +167,19 @@ def test_full_size_bf16_maps(n):
     ctx.close()
 
 
-@pytest.mark.parametrize("act", ["f32", "bf16"])
-def test_full_size_block(ref, act):
+@pytest.mark.parametrize("act,shape", [("f32", None), ("bf16", None), ("f32", (96, 1024, 4, 6)),
+                                       ("f32", (512, 128, 6, 4))])
+def test_full_size_block(ref, act, shape):
     """The block workload bench.py --config 6 times (256x256, c 256, expansion 4, batch 8,
-    keep 1/4), with fp32 and with bf16 feature maps (--act bf16), checked where the oracle can
+    keep 1/4), with fp32 and with bf16 feature maps (--act bf16), and two more rows of the
+    paper's timing table at the batch it prints (the smallest image with the most channels,
+    chained; the largest image, whose middle tensors are formed), checked where the oracle can
     follow: the first layer's index sets in full, its output and K_dw on sampled planes, and
     the second layer on one sample (valid index set for the fp64 norms of K_dw applied to the
     GPU's own middle tensor, output for that index set).  With bf16 maps K_dw exists only
     folded into the second layer's transform, so its output is the oracle's."""
     bf16 = act == "bf16"
-    cfg = synth.block_config(1, 4)
+    cfg = synth.block_config(1, 4) if shape is None else synth.block_shape(shape[0], shape[0], *shape[1:], 1, 4)
     print(f"workload {cfg.name} ({act} maps): generating inputs", flush=True)
     x, w1, w_dw, w3 = synth.make_block_inputs(cfg)
     if bf16:
@@ -184,6 +187,8 @@ def test_full_size_block(ref, act):
     N, k = cfg.N, cfg.k
     d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
                             cfg.keep_den, cfg.w_dtype, cfg.act_bits, wcc.BF16 if bf16 else wcc.F32)
+    print(f"  route without middle outputs: {'chained' if wcc.block_is_chained(d) else 'middle tensors formed'}",
+          flush=True)
     ctx = wcc.Context(0)
     ctx.ensure_workspace(d)
     tdt = torch.bfloat16 if bf16 else torch.float32
