@@ -17,9 +17,13 @@
 // butterflies of haar_inv.hip, multiply-adds in the order of depthwise.hip, analysis of strip.h),
 // so the values that enter the norms and the quantiser are the same bits.
 //
+// A row of the plane wider than one wave row (256 columns) is shared by the 2 or 4 waves of a
+// workgroup, one 256-column segment each: per channel every wave leaves the first and last
+// column of its rebuilt rows in LDS, the workgroup meets at a barrier, and the end lanes take the
+// convolution's outside column from the neighbouring segment there.
+//
 // Limits (the caller falls back to the materialised route otherwise): W % 4 == 0, d <= 3, and
-// a row of the plane fits into one wave row (W <= 256), so that the convolution's outside
-// columns come from neighbouring lanes or are the plane's zero border.
+// W <= 256 or a row made of exactly 2 or 4 wave rows (256 < W <= 512, 768 < W <= 1024).
 #include "strip_io.h"
 
 namespace wcc {
@@ -186,12 +190,17 @@ __device__ __forceinline__ ChainGeo<D> chain_setup(const int32_t *__restrict__ j
 // registers, a channel's loads in flight together.
 // NI_FIXED > 0: the packed list is walked with that many rows a wave (the caller has checked that
 // it fits); 0: the shortest of 4, 8, 16, 32 rows that holds it.
-template <int D, int NI_FIXED = 0, class Sink, class After>
+// SEGS > 1: the plane's row is shared by the SEGS waves of the workgroup (this one holds segment
+// `seg`); xchg is the workgroup's exchange buffer (ChainXchg<D, SEGS>::kWords floats).  Every wave
+// of the workgroup then runs compute() once per channel, whatever path it takes: one barrier each.
+template <int D, int SEGS, int NI_FIXED = 0, class Sink, class After>
 __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int64_t k1, int n_ch,
                                            const float *__restrict__ wdw, const ChainGeo<D> &cg,
                                            uint32_t *tile, const LanePos<D> &p, bool first_lane,
-                                           bool last_lane, Sink &sink, After &&after) {
+                                           bool last_lane, float *xchg, int seg, Sink &sink,
+                                           After &&after) {
   constexpr int R = 1 << D, RR = R + 2, V = V4;
+  int parity = 0;  // which half of the exchange buffer this channel uses
   constexpr int NS = ChainGeo<D>::NS, HS = ChainGeo<D>::HS, NT = ChainGeo<D>::NT;
   constexpr int STRIDE = ChainGeo<D>::STRIDE;
   const int lane = threadIdx.x & (kWave - 1);
@@ -228,11 +237,32 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
       for (int e = 0; e < V; ++e) six[RR - 1][e + 1] = edge[e];
     }
     wave_lds_fence();
+    // the column beyond a wave row's end: the plane's zero border, or (SEGS > 1) the neighbouring
+    // segment's boundary column.  Two buffers alternate: a wave can be one barrier ahead of
+    // another, never two, so the buffer it writes is not the one a slower wave still reads.
+    float beyond[RR];
+#pragma unroll
+    for (int i = 0; i < RR; ++i) beyond[i] = 0.f;
+    if constexpr (SEGS > 1) {
+      float *ex = xchg + parity * (SEGS * 2 * RR);
+      parity ^= 1;
+      if (lane == 0 || lane == kWave - 1) {
+        float *out = ex + (seg * 2 + (lane == 0 ? 0 : 1)) * RR;
+#pragma unroll
+        for (int i = 0; i < RR; ++i) out[i] = lane == 0 ? six[i][1] : six[i][V];
+      }
+      __syncthreads();
+      if ((lane == 0 && seg > 0) || (lane == kWave - 1 && seg < SEGS - 1)) {
+        const float *in = ex + (lane == 0 ? (seg - 1) * 2 + 1 : (seg + 1) * 2) * RR;
+#pragma unroll
+        for (int i = 0; i < RR; ++i) beyond[i] = in[i];
+      }
+    }
 #pragma unroll
     for (int i = 0; i < RR; ++i) {
       float l = __shfl_up(six[i][V], 1, kWave), r = __shfl_down(six[i][1], 1, kWave);
-      if (first_lane) l = 0.f;  // the plane's zero border
-      if (last_lane) r = 0.f;
+      if (first_lane) l = beyond[i];
+      if (last_lane) r = beyond[i];
       six[i][0] = l;
       six[i][V + 1] = r;
     }
@@ -398,9 +428,17 @@ struct ChainStagedSink {
   }
 };
 
-// Waves per workgroup: two, so that a workgroup's tiles stay small enough for several workgroups
-// to share a compute unit's LDS.
+// Waves per workgroup: two (independent of each other when a wave row holds a whole row of the
+// plane), so that a workgroup's tiles stay small enough for several workgroups to share a
+// compute unit's LDS; with SEGS segments a row, the SEGS waves that share it.
 constexpr int kChainWaves = 2;
+__host__ __device__ constexpr int chain_waves(int segs) { return segs > 1 ? segs : kChainWaves; }
+
+// the boundary columns of the segments' rebuilt rows: [2 buffers][segment][first | last column][row]
+template <int D, int SEGS>
+struct ChainXchg {
+  static constexpr int kWords = SEGS > 1 ? 2 * SEGS * 2 * ((1 << D) + 2) : 1;
+};
 
 // LDS of a workgroup: its waves' [lane][slot] tiles
 template <int D>
@@ -409,29 +447,32 @@ struct ChainTiles {
 };
 
 // ---- first pass: channel norms of HWT(K_dw t1) ------------------------------------------------------
-// grid = (ceil(units/kChainWaves), G, B), block = kChainWaves waves.  yc1 [B, C, k1], jmap1 [B, N]: the producer layer's
+// grid = (ceil(units/waves), G, B), block = waves = chain_waves(SEGS) waves.  yc1 [B, C, k1], jmap1 [B, N]: the producer layer's
 // compressed output and rank map; wdw [C, 3, 3].  Writes the partial norms (and the partial
 // maxima of |coefficient|, nullable) of channel group grp to norm_part / max_part [G, B, N].
-template <int D, bool SQ>
-__global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_norm_kernel(const float *__restrict__ yc1,
+template <int D, bool SQ, int SEGS>
+__global__ __launch_bounds__(chain_waves(SEGS) * kWave, 4 / chain_waves(SEGS)) void chain_norm_kernel(const float *__restrict__ yc1,
                                                          const int32_t *__restrict__ jmap1,
                                                          int64_t k1, const float *__restrict__ wdw,
                                                          float *__restrict__ norm_part,
                                                          float *__restrict__ max_part, Geo g,
                                                          StripMap m, int C, int Cg, int B,
                                                          SelectPrep prep) {
-  constexpr int NS = slot_count(D, V4);
-  __shared__ __attribute__((aligned(16))) uint32_t tiles[kChainWaves][ChainTiles<D>::kWords];
+  constexpr int NS = slot_count(D, V4), WAVES = chain_waves(SEGS);
+  __shared__ __attribute__((aligned(16))) uint32_t tiles[WAVES][ChainTiles<D>::kWords];
+  __shared__ float xchg[ChainXchg<D, SEGS>::kWords];
   const int wv = threadIdx.x >> 6;
-  const int unit = blockIdx.x * kChainWaves + wv;
+  const int unit = blockIdx.x * WAVES + wv;  // (SEGS > 1: the workgroup's waves share a strip)
   const int grp = blockIdx.y, b = blockIdx.z;
   // one workgroup per sample clears the state of the selection that follows this kernel
-  if (blockIdx.x == 0 && grp == 0) prep_sample(prep, b, threadIdx.x, kChainWaves * kWave);
+  if (blockIdx.x == 0 && grp == 0) prep_sample(prep, b, threadIdx.x, WAVES * kWave);
   LanePos<D> p;
   int row0, col0;
   const bool active = locate<D, V4>(m, g, unit, p, row0, col0);
   const int c0 = grp * Cg, n_ch = min(C, c0 + Cg) - c0;
-  if (__ballot(active) == 0 || n_ch <= 0) return;  // whole waves leave
+  // whole waves leave (SEGS > 1: the waves of a workgroup share their strip, and every segment
+  // has lanes inside the plane, so they leave or stay together)
+  if (__ballot(active) == 0 || n_ch <= 0) return;
 
   const int32_t *jm1 = jmap1 + (size_t)b * g.N;
   const bool up_in = row0 > 0, dn_in = row0 + (1 << D) < g.H;
@@ -445,8 +486,9 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_norm_kernel(cons
     for (int s = 0; s < NS; ++s) sink.top[s] = 0.f;
   }
   sink.plane = nullptr;
-  chain_walk<D>(yc1 + ((size_t)b * C + c0) * k1, k1, n_ch, wdw + (size_t)c0 * 9, cg, tiles[wv], p, p.lc == 0, p.lc == m.lpr - 1 || col0 + V4 >= g.W, sink,
-                [](FwdSink<D, V4, false, SQ> &) {});
+  chain_walk<D, SEGS>(yc1 + ((size_t)b * C + c0) * k1, k1, n_ch, wdw + (size_t)c0 * 9, cg, tiles[wv], p,
+                      p.lc == 0, p.lc == m.lpr - 1 || col0 + V4 >= g.W, xchg, wv, sink,
+                      [](FwdSink<D, V4, false, SQ> &) {});
   if (!active) return;
   write_slots<D, V4>(norm_part + ((size_t)grp * B + b) * g.N, sink.acc, p);
   if constexpr (FwdSink<D, V4, false, SQ>::MX) {
@@ -455,12 +497,12 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_norm_kernel(cons
 }
 
 // ---- second pass: the kept coefficients of HWT(K_dw t1) ---------------------------------------------
-// grid = (ceil(units/kChainWaves), G, B), block = kChainWaves waves.  jmap3: the consumer layer's rank map; xc
+// grid = (ceil(units/waves), G, B), block = waves = chain_waves(SEGS) waves.  jmap3: the consumer layer's rank map; xc
 // [B, C, k3] fp32, or int8 codes with Q8 (clipping parameter: q_alpha > 0, or the largest of the
 // n_alpha floats at alpha_src; the first workgroup leaves it at alpha_pub[0]).  Without Q8 the
 // alpha slots (nullable) are raised to max |kept coefficient|.
-template <int D, bool Q8>
-__global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(const float *__restrict__ yc1,
+template <int D, bool Q8, int SEGS>
+__global__ __launch_bounds__(chain_waves(SEGS) * kWave, 4 / chain_waves(SEGS)) void chain_keep_kernel(const float *__restrict__ yc1,
                                                          const int32_t *__restrict__ jmap1,
                                                          int64_t k1, const float *__restrict__ wdw,
                                                          const int32_t *__restrict__ jmap3,
@@ -469,11 +511,12 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(cons
                                                          int C, int Cg, float q_alpha,
                                                          const float *__restrict__ alpha_src,
                                                          int n_alpha, float *alpha_pub) {
-  constexpr int NS = slot_count(D, V4);
-  __shared__ __attribute__((aligned(16))) uint32_t tiles[kChainWaves][ChainTiles<D>::kWords];
-  __shared__ float wmax[kChainWaves];
+  constexpr int NS = slot_count(D, V4), WAVES = chain_waves(SEGS);
+  __shared__ __attribute__((aligned(16))) uint32_t tiles[WAVES][ChainTiles<D>::kWords];
+  __shared__ float xchg[ChainXchg<D, SEGS>::kWords];
+  __shared__ float wmax[WAVES];
   const int wv = threadIdx.x >> 6;
-  const int unit = blockIdx.x * kChainWaves + wv;
+  const int unit = blockIdx.x * WAVES + wv;
   const int grp = blockIdx.y, b = blockIdx.z;
   LanePos<D> p;
   int row0, col0;
@@ -572,8 +615,8 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(cons
       for (int i = 0; i < NI3; ++i) { st.cell[i] = cell3[i]; st.at[i] = at3[i]; }
       st.vmax = 0.f;
       st.aim(plane3, k3);
-      chain_walk<D, NI1>(plane1, k1, n_ch, kw, cg, tile, p, first_lane,
-                         last_lane, st, [&plane3, k3](auto &sk) {
+      chain_walk<D, SEGS, NI1>(plane1, k1, n_ch, kw, cg, tile, p, first_lane,
+                         last_lane, xchg, wv, st, [&plane3, k3](auto &sk) {
                            sk.flush();
                            plane3 += k3;
                            sk.aim(plane3, k3);
@@ -595,7 +638,7 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(cons
         sink.at[s] = (int)sink.at[s] >= 0 ? sink.at[s] * (uint32_t)sizeof(Out) : Sink::kDropped;
       sink.vmax = 0.f;
       sink.aim(plane3, k3);
-      chain_walk<D>(plane1, k1, n_ch, kw, cg, tile, p, first_lane, last_lane,
+      chain_walk<D, SEGS>(plane1, k1, n_ch, kw, cg, tile, p, first_lane, last_lane, xchg, wv,
                     sink, [&plane3, k3](Sink &sk) {
                       plane3 += k3;
                       sk.aim(plane3, k3);
@@ -612,7 +655,7 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(cons
   if (threadIdx.x == 0) {
     mx = wmax[0];
 #pragma unroll
-    for (int i = 1; i < kChainWaves; ++i) mx = fmaxf(mx, wmax[i]);
+    for (int i = 1; i < WAVES; ++i) mx = fmaxf(mx, wmax[i]);
     unsigned int *a = reinterpret_cast<unsigned int *>(alpha_slots) +
                       ((blockIdx.x + 3u * blockIdx.y + 11u * blockIdx.z) & (kAlphaSlots - 1));
     const unsigned int mine = __float_as_uint(mx);
@@ -622,30 +665,54 @@ __global__ __launch_bounds__(kChainWaves * kWave, 2) void chain_keep_kernel(cons
 
 }  // namespace
 
+// How the chained passes tile a plane: as the other strip kernels do where a wave row holds a
+// whole row of the plane; else full wave rows side by side (one strip a wave, ceil(W/256) segments).
+static StripMap chain_map(const wcc_desc &d) {
+  StripMap m = make_map(d, V4);
+  if (dw_needs_edges(m)) {
+    m.lpr = kWave;
+    m.log_lpr = 6;
+    m.col_segs = (m.lanes_w + kWave - 1) / kWave;
+    m.units = m.strips * m.col_segs;
+  }
+  return m;
+}
+
+// Segments of a row (waves that share it): 1 if a wave row holds the whole row, else 2 or 4;
+// 0: a shape the chained passes do not take.
+static int chain_segments(const wcc_desc &d) {
+  if (d.W % 4 != 0 || d.levels > 3) return 0;
+  const StripMap m = chain_map(d);
+  if (!dw_needs_edges(m)) return 1;
+  return (m.col_segs == 2 || m.col_segs == 4) ? m.col_segs : 0;
+}
+
 // Can the project layer d take its input from a producer's compressed output (see the limits at
 // the top of this file)?
-bool chain_supported(const wcc_desc &d) {
-  if (d.W % 4 != 0 || d.levels > 3) return false;
-  const StripMap m = make_map(d, V4);
-  return !dw_needs_edges(m);
-}
+bool chain_supported(const wcc_desc &d) { return chain_segments(d) != 0; }
 
 hipError_t launch_chain_norm(const wcc_desc &d, const ChainSrc &src, const float *wdw,
                              float *norm_part, float *max_part, int G, const SelectPrep &prep,
                              hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
-  const StripMap m = make_map(d, V4);
+  const StripMap m = chain_map(d);
   const int Cg = (d.C_in + G - 1) / G;
-  const dim3 grid((m.units + kChainWaves - 1) / kChainWaves, G, d.B), block(kChainWaves * kWave);
+  const int segs = chain_segments(d), waves = chain_waves(segs);
+  if (segs == 0) return hipErrorInvalidValue;
+  const dim3 grid((m.units + waves - 1) / waves, G, d.B), block(waves * kWave);
   const bool sq = d.norm == WCC_NORM_L2;
-#define WCC_CHAIN_NORM(D_)                                                                          \
-  do {                                                                                              \
-    if (sq)                                                                                         \
-      hipLaunchKernelGGL((chain_norm_kernel<D_, true>), grid, block, 0, s, src.yc, src.jmap, src.k, \
-                         wdw, norm_part, max_part, g, m, d.C_in, Cg, d.B, prep);                    \
-    else                                                                                            \
-      hipLaunchKernelGGL((chain_norm_kernel<D_, false>), grid, block, 0, s, src.yc, src.jmap,       \
-                         src.k, wdw, norm_part, max_part, g, m, d.C_in, Cg, d.B, prep);             \
+#define WCC_CHAIN_NORM_(D_, SQ_, S_)                                                                   \
+  hipLaunchKernelGGL((chain_norm_kernel<D_, SQ_, S_>), grid, block, 0, s, src.yc, src.jmap, src.k, wdw, \
+                     norm_part, max_part, g, m, d.C_in, Cg, d.B, prep)
+#define WCC_CHAIN_NORM(D_)                                                \
+  do {                                                                    \
+    if (segs == 1) {                                                      \
+      if (sq) WCC_CHAIN_NORM_(D_, true, 1); else WCC_CHAIN_NORM_(D_, false, 1); \
+    } else if (segs == 2) {                                               \
+      if (sq) WCC_CHAIN_NORM_(D_, true, 2); else WCC_CHAIN_NORM_(D_, false, 2); \
+    } else {                                                              \
+      if (sq) WCC_CHAIN_NORM_(D_, true, 4); else WCC_CHAIN_NORM_(D_, false, 4); \
+    }                                                                     \
   } while (0)
   switch (d.levels) {
     case 1: WCC_CHAIN_NORM(1); break;
@@ -654,6 +721,7 @@ hipError_t launch_chain_norm(const wcc_desc &d, const ChainSrc &src, const float
     default: return hipErrorInvalidValue;
   }
 #undef WCC_CHAIN_NORM
+#undef WCC_CHAIN_NORM_
   return hipGetLastError();
 }
 
@@ -661,21 +729,29 @@ hipError_t launch_chain_keep(const wcc_desc &d, int64_t k, const ChainSrc &src, 
                              const int32_t *jmap, void *xc, float *alpha_slots, float q_alpha,
                              const float *alpha_src, int n_alpha, float *alpha_pub, hipStream_t s) {
   const Geo g{d.H, d.W, d.levels, (int64_t)d.H * d.W};
-  const StripMap m = make_map(d, V4);
+  const StripMap m = chain_map(d);
   const int G = groups_for(d, d.C_in, 4096, 8);
   const int Cg = (d.C_in + G - 1) / G;
-  const dim3 grid((m.units + kChainWaves - 1) / kChainWaves, G, d.B), block(kChainWaves * kWave);
+  const int segs = chain_segments(d), waves = chain_waves(segs);
+  if (segs == 0) return hipErrorInvalidValue;
+  const dim3 grid((m.units + waves - 1) / waves, G, d.B), block(waves * kWave);
   const bool q8 = q_alpha > 0.f || alpha_src != nullptr;
-#define WCC_CHAIN_KEEP(D_)                                                                          \
+#define WCC_CHAIN_KEEP_(D_, S_)                                                                     \
   do {                                                                                              \
     if (q8)                                                                                         \
-      hipLaunchKernelGGL((chain_keep_kernel<D_, true>), grid, block, 0, s, src.yc, src.jmap, src.k, \
-                         wdw, jmap, xc, k, nullptr, g, m, d.C_in, Cg, q_alpha, alpha_src, n_alpha,  \
-                         alpha_pub);                                                                \
+      hipLaunchKernelGGL((chain_keep_kernel<D_, true, S_>), grid, block, 0, s, src.yc, src.jmap,    \
+                         src.k, wdw, jmap, xc, k, nullptr, g, m, d.C_in, Cg, q_alpha, alpha_src,    \
+                         n_alpha, alpha_pub);                                                       \
     else                                                                                            \
-      hipLaunchKernelGGL((chain_keep_kernel<D_, false>), grid, block, 0, s, src.yc, src.jmap,       \
+      hipLaunchKernelGGL((chain_keep_kernel<D_, false, S_>), grid, block, 0, s, src.yc, src.jmap,   \
                          src.k, wdw, jmap, xc, k, alpha_slots, g, m, d.C_in, Cg, 0.f, nullptr, 0,   \
                          nullptr);                                                                  \
+  } while (0)
+#define WCC_CHAIN_KEEP(D_)                     \
+  do {                                         \
+    if (segs == 1) WCC_CHAIN_KEEP_(D_, 1);     \
+    else if (segs == 2) WCC_CHAIN_KEEP_(D_, 2); \
+    else WCC_CHAIN_KEEP_(D_, 4);               \
   } while (0)
   switch (d.levels) {
     case 1: WCC_CHAIN_KEEP(1); break;
@@ -684,6 +760,7 @@ hipError_t launch_chain_keep(const wcc_desc &d, int64_t k, const ChainSrc &src, 
     default: return hipErrorInvalidValue;
   }
 #undef WCC_CHAIN_KEEP
+#undef WCC_CHAIN_KEEP_
   return hipGetLastError();
 }
 

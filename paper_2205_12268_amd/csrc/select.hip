@@ -447,6 +447,22 @@ __device__ __forceinline__ void small_pass(const uint32_t (&rel)[4 * kSmallSlots
   __syncthreads();
 }
 
+// The G partial planes of a small map summed (and their maxima taken) by the whole chip before
+// the one-workgroup-a-sample kernel below: with many groups that kernel would otherwise read
+// G x N values per sample through a single compute unit.  grid = (ceil(N / 1024), B), block = 256.
+// The maxima land in group 0's plane of top_part (each position is read and written by one thread).
+__global__ __launch_bounds__(256) void combine_parts_kernel(const float *__restrict__ part,
+                                                            float *__restrict__ norm, int G, int64_t N,
+                                                            int B, float *top_part) {
+  const int64_t pos = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (pos >= N) return;
+  const int64_t at = (int64_t)blockIdx.y * N + pos;
+  load_keys<true>(part, norm, G, (int64_t)B * N, at);
+  if (top_part) *reinterpret_cast<float4 *>(top_part + at) = load_top(top_part, G, (int64_t)B * N, at);
+}
+
+constexpr int kCombineGroups = 4;  // from this many groups on the partial planes are combined first
+
 // grid = B, block = 1024.  REDUCE as in load_keys.
 template <bool REDUCE>
 __global__ __launch_bounds__(kSmallThreads) void select_small_kernel(
@@ -605,7 +621,7 @@ hipError_t launch_select_init(const SelectPrep &p, int B, hipStream_t s) {
 
 hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, float *norm_out,
                          int64_t k, void *ws_base, const WsLayout &L, int32_t *idx, int32_t *jmap,
-                         const float *top_part, float *block_top, hipStream_t s) {
+                         float *top_part, float *block_top, hipStream_t s) {
   const int64_t N = (int64_t)d.H * d.W;
   char *ws = static_cast<char *>(ws_base);
   uint32_t *hist = reinterpret_cast<uint32_t *>(ws + L.hist);
@@ -616,7 +632,12 @@ hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, fl
   const uint32_t k32 = (uint32_t)k;
   if (N <= kSmallMaxN) {
     const int slots = (int)((N + 4 * kSmallThreads - 1) / (4 * kSmallThreads));
-    if (G > 1)
+    if (G >= kCombineGroups) {
+      hipLaunchKernelGGL(combine_parts_kernel, dim3((unsigned)((N + 1023) / 1024), d.B), dim3(256), 0, s,
+                         norm_or_part, norm_out, G, N, d.B, top_part);
+      hipLaunchKernelGGL((select_small_kernel<false>), dim3(d.B), dim3(kSmallThreads), 0, s, norm_out,
+                         nullptr, 1, N, d.B, k32, slots, idx, jmap, top_part, block_top);
+    } else if (G > 1)
       hipLaunchKernelGGL((select_small_kernel<true>), dim3(d.B), dim3(kSmallThreads), 0, s,
                          norm_or_part, norm_out, G, N, d.B, k32, slots, idx, jmap, top_part, block_top);
     else

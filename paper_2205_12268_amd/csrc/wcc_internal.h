@@ -190,9 +190,10 @@ hipError_t launch_select_init(const SelectPrep &p, int B, hipStream_t s);
 // kernel writes the largest of its values over the positions it keeps to block_top
 // (select_top_count() floats); the largest of those is max |kept coefficient|.  Plain stores:
 // thousands of atomics arriving together on a few addresses serialise (25 us on 2048 of them).
+// Group 0's plane of top_part may be overwritten with the maxima over the groups.
 hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, float *norm_out,
                          int64_t k, void *ws_base, const WsLayout &L, int32_t *idx,
-                         int32_t *jmap /*nullable*/, const float *top_part, float *block_top,
+                         int32_t *jmap /*nullable*/, float *top_part, float *block_top,
                          hipStream_t s);
 int select_top_count(const wcc_desc &d, const WsLayout &L);
 hipError_t launch_jmap_from_idx(const int32_t *idx, int B, int64_t N, int64_t k, int32_t *jmap,

@@ -91,12 +91,16 @@ def test_null_arguments_are_reported_not_dereferenced():
 
 def test_which_blocks_are_chained():
     """Pure host function: chained when nobody asks for the middle tensors and W % 4 == 0,
-    W <= 256, levels <= 3, at most a third of the coefficients kept."""
+    a row fits one wave row (W <= 256) or is exactly two or four of them, levels <= 3, at most a
+    third of the coefficients kept."""
     def chained(H, W, levels, num, den):
         return wcc.block_is_chained(wcc.make_block_desc(2, 8, 4, H, W, levels, num, den, wcc.BF16, 8))
     assert chained(256, 256, 3, 1, 4) and chained(96, 96, 3, 1, 8) and chained(48, 64, 1, 1, 3)
     assert not chained(256, 256, 3, 1, 2)        # more than a third kept
-    assert not chained(512, 512, 3, 1, 4)        # rows wider than a wave
+    assert chained(512, 512, 3, 1, 4) and chained(64, 264, 3, 1, 4) and chained(64, 1024, 3, 1, 4)
+    assert chained(64, 776, 2, 1, 4)             # 194 lanes: four wave rows
+    assert not chained(64, 768, 3, 1, 4)         # three wave rows
+    assert not chained(64, 1032, 3, 1, 4)        # five
     assert not chained(64, 64, 4, 1, 4)          # four levels
     assert not chained(16, 10, 1, 1, 4)          # W % 4 != 0
     with pytest.raises(ValueError):

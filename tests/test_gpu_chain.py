@@ -3,12 +3,13 @@ paragraph on memory bandwidth and traffic) against the oracle and against the ro
 the middle tensors (needs an MI355X).
 
 wcc_block_forward chains the two layers when no middle output is asked for and the shape allows
-(W % 4 == 0, W <= 256, d <= 3): the project layer's transform passes rebuild the rows they need
+(W % 4 == 0, d <= 3, W <= 256 or a row of exactly 2 or 4 wave rows): the project layer's transform passes rebuild the rows they need
 from the expand layer's compressed output.  The shapes below walk through what that code
 depends on: one, two and four strips a wave, planes of one strip (no row above or below), many
 strips, rows that leave lanes idle, every level count, kept lists of 4, 8, 16 and 32 rows a wave,
 strips that keep everything (the slot-by-slot route) and strips that keep nothing, no quantiser,
-int8 weights, several samples and channel groups.
+int8 weights, several samples and channel groups, and rows shared by two and by four waves (full
+and ragged last segments; empty strips beside full ones; every level count).
 """
 import numpy as np
 import pytest
@@ -42,11 +43,19 @@ CASES = [
     blk("f32_noquant_d2", 2, 4, 3, 16, 48, 2, 1, 3, F32, 0, 1.0),      # fp32 path, k % 4 != 0
     blk("ragged_k_d3", 1, 8, 2, 24, 40, 3, 2, 7, BF16, 8),             # k % 4 != 0 with the quantiser
     blk("many_channels", 2, 16, 8, 32, 64, 3, 1, 4, BF16, 8),          # 128 middle channels in groups
+    blk("two_segments_d3", 2, 8, 2, 24, 512, 3, 1, 4, BF16, 8, 3.0),   # a row shared by two waves
+    blk("two_segments_ragged", 1, 4, 3, 16, 328, 3, 1, 8, BF16, 8),    # 64 + 18 lanes a row
+    blk("four_segments_d3", 1, 4, 2, 16, 1024, 3, 1, 8, BF16, 8, 3.0), # a row shared by four waves
+    blk("four_segments_d2", 1, 8, 2, 12, 776, 2, 1, 4, I8, 8),         # 64 + 64 + 64 + 2 lanes a row
+    blk("two_segments_d1", 1, 4, 2, 6, 384, 1, 1, 4, BF16, 8),         # d = 1, 64 + 32 lanes
+    blk("two_segments_dense_top", 1, 4, 2, 32, 512, 3, 1, 4, BF16, 8), # packed, slot-by-slot and empty strips in one plane
+    blk("two_segments_f32", 1, 4, 2, 16, 512, 2, 2, 7, F32, 0, 1.0),   # fp32 path through shared rows
 ]
 # Rows of the input from this fraction of the height on are zero, so that the kept positions of
 # both layers crowd into the strips above: strips that keep a half or all of their positions at
 # a keep ratio the chained route takes, and strips that keep nothing.
-ZERO_BELOW = {"d2_dense_top": 0.5, "d3_dense_top": 0.5, "d3_all_on_top": 0.25}
+ZERO_BELOW = {"d2_dense_top": 0.5, "d3_dense_top": 0.5, "d3_all_on_top": 0.25,
+              "two_segments_dense_top": 0.25}
 
 
 def block_inputs(cfg):
