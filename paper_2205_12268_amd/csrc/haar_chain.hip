@@ -246,14 +246,20 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
     if constexpr (SEGS > 1) {
       float *ex = xchg + parity * (SEGS * 2 * RR);
       parity ^= 1;
-      if (lane == 0 || lane == kWave - 1) {
-        float *out = ex + (seg * 2 + (lane == 0 ? 0 : 1)) * RR;
+      // (the lane number is computed afresh here, by instructions the compiler may not move out
+      // of the loop: kept across the loop it is spilled, and the reload of a spilled register
+      // waits for every load in flight, the prefetched channels included)
+      int ln;
+      asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(ln));
+      const bool at0 = ln == 0, at63 = ln == kWave - 1;
+      if (at0 || at63) {
+        float *out = ex + (seg * 2 + (at0 ? 0 : 1)) * RR;
 #pragma unroll
-        for (int i = 0; i < RR; ++i) out[i] = lane == 0 ? six[i][1] : six[i][V];
+        for (int i = 0; i < RR; ++i) out[i] = at0 ? six[i][1] : six[i][V];
       }
-      __syncthreads();
-      if ((lane == 0 && seg > 0) || (lane == kWave - 1 && seg < SEGS - 1)) {
-        const float *in = ex + (lane == 0 ? (seg - 1) * 2 + 1 : (seg + 1) * 2) * RR;
+      workgroup_lds_barrier();  // (the next channels' values keep travelling)
+      if ((at0 && seg > 0) || (at63 && seg < SEGS - 1)) {
+        const float *in = ex + (at0 ? (seg - 1) * 2 + 1 : (seg + 1) * 2) * RR;
 #pragma unroll
         for (int i = 0; i < RR; ++i) beyond[i] = in[i];
       }

@@ -449,6 +449,15 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Workgroup barrier that orders LDS accesses only: loads from global memory that are still in
+// flight (a prefetch for a later iteration) stay in flight across it, where __syncthreads()
+// would wait for them.
+__device__ __forceinline__ void workgroup_lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // A wave covers (64 / lpr) strips x (lpr lanes of V columns).  lpr is the power of two that
 // leaves the fewest lanes idle (ties: the wider one, for longer contiguous row segments);
 // rows narrower than 16 lanes are not split further.
