@@ -219,6 +219,12 @@ def time_block(cfg, args, synth, wcc, torch, np, dense: bool) -> dict:
     def step():
         ctx.wcc_block_forward(d, xd, w1d, None, wdd, w3d, None, y)
 
+    if args.copy_probe:  # a plain copy of known size, for scaling the traffic counters
+        probe = torch.empty_like(xd)
+        for _ in range(args.copy_probe):
+            probe.copy_(xd)
+        torch.cuda.synchronize()
+        del probe
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -308,20 +314,24 @@ def bench_block(args, synth, wcc, torch, np) -> int:
     if chained:
         kernel_of["l1_haar_fwd"], kernel_of["l1_gather"] = "chain_norm_kernel", "chain_keep_kernel"
     dom = max(kernel_of, key=lambda n: stage_us[n])
+    prof = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles")
+    traffic = read_traffic(prof, cfg.name, kernel_of[dom])
+    prof_us = read_profile_column(prof, "kernel_stats", cfg.name, kernel_of[dom], 2)
     if chained and dom in ("l1_haar_fwd", "l1_gather"):
         # the chained passes are bound by fp32 vector arithmetic, not by bytes
         flops = CHAIN_FLOP_PER_PIXEL_CHANNEL * cfg.B * cfg.C_mid * cfg.N
         ach = flops / (stage_us[dom] * 1e-6) / 1e12
         roof = {"bound": "alu", "kernel": kernel_of[dom], "stage": dom, "achieved": round(ach, 2),
                 "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / ALU_PEAK_TFLOPS, 4),
-                "frac_of_unpacked_peak": round(ach / (ALU_PEAK_TFLOPS / 2), 4), "traffic": None,
+                "frac_of_unpacked_peak": round(ach / (ALU_PEAK_TFLOPS / 2), 4), "traffic": traffic,
                 "algorithmic_flops": flops, "algorithmic_bytes": alg[dom],
-                "kernel_us": round(stage_us[dom], 2)}
+                "kernel_us": round(stage_us[dom], 2), "profile_avg_us": prof_us}
     else:
         achieved = alg[dom] / (stage_us[dom] * 1e-6) / 1e9
         roof = {"bound": "hbm", "kernel": kernel_of[dom], "stage": dom, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "algorithmic_bytes": alg[dom], "kernel_us": round(stage_us[dom], 2)}
+                "traffic": traffic, "algorithmic_bytes": alg[dom], "kernel_us": round(stage_us[dom], 2),
+                "profile_avg_us": prof_us}
     pix_ch = cfg.B * cfg.N * cfg.C
     out = {
         "metric": "WCC layer forward throughput", "value": round(pix_ch / dt / 1e9, 3),
@@ -334,6 +344,8 @@ def bench_block(args, synth, wcc, torch, np) -> int:
                    "route": "chained" if chained else "middle tensors formed"},
         "roofline": roof,
         "stages_us": {n: round(v, 2) for n, v in stage_us.items()},
+        "stages_frac_of_hbm_peak": {n: round(alg[n] / (stage_us[n] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+                                    for n in stage_us if stage_us[n] > 0 and alg.get(n)},
         "block_alg_GBs": round(sum(alg.values()) / dt / 1e9, 1),
         "dense_block_ms": {"framework_bf16": None if dense_ms is None else round(dense_ms, 4),
                            "framework_1x1_bf16_plus_own_depthwise_f32":
