@@ -12,6 +12,8 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2205_12268_amd import synth
+
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 # The weight tensor of Eq. (HaarKernel), typed from the paper: four 2x2 kernels, factor 1/2.
@@ -322,6 +324,33 @@ def test_quantiser_matches_equation_literally(ref):
         lv = float(2 ** (bits - 1) - 1)
         want = torch.round(torch.tensor(lv) * t).numpy().astype(np.float64)
         np.testing.assert_array_equal(ref.quant_codes(v, float(alpha), bits), want)
+
+
+def test_fp32_code_decision_stays_within_one_code_of_the_real_valued_one(ref):
+    """The oracle decides the integer code in fp32 (u = v/alpha, clip, rint(127 u), each step
+    rounded to fp32) so that both implementations take the same decision.  Against Eq.
+    (quantweights) evaluated in fp64 on the kept coefficients of the synthetic workloads' kind
+    (and on arbitrary reals) the two may differ only where 127 v/alpha lies within rounding
+    distance of a half-integer: never by more than one code, and on a vanishing share of the
+    values."""
+    rng = np.random.default_rng(43)
+    x, _ = synth.make_inputs(synth.LayerCfg("pin_quant", 1, 8, 8, 64, 128, 2, 1, 4, synth.W_BF16, 8,
+                                            sigma=3.0, seed=synth.SEED_BASE + 0x51))
+    coef = ref.haar_fwd(x.astype(np.float64), 2).ravel()
+    cases = [(coef, float(np.float32(np.abs(coef).max()))),
+             (coef, float(np.float32(0.37 * np.abs(coef).max()))),          # clipping live
+             (rng.standard_normal(200_000) * 3.0, float(np.float32(np.pi))),
+             (rng.uniform(-1, 1, 200_000), float(np.float32(1.0 - 2.0 ** -24)))]
+    for v, alpha in cases:
+        v32 = v.astype(np.float32).astype(np.float64)   # what the fp32 side sees
+        got = ref.quant_codes(v32, alpha, 8)
+        want = np.rint(127.0 * np.clip(v32 / alpha, -1.0, 1.0))  # fp64, half to even
+        diff = np.abs(got - want)
+        assert diff.max() <= 1.0
+        differing = int((diff > 0).sum())
+        # a decision can flip only if 127 v/alpha is within ~2^-16 of k + 1/2: a share of about
+        # 2 * 127 * 2^-17 ~ 2e-3 would already be generous for values spread over the range
+        assert differing <= max(4, int(2e-3 * v.size)), (differing, v.size)
 
 
 def test_round_half_to_even(ref):
