@@ -85,7 +85,7 @@ typedef enum { WCC_NORM_L1 = 0, WCC_NORM_L2 = 1 } wcc_norm;
 /* One WCC layer: the inputs of the explicit algorithm (feature-map shape,
  * kernel shape, wavelet level d, kept fraction gamma) plus storage types. */
 typedef struct {
-  int32_t B, C_in, C_out, H, W; /* B, C_in, C_out <= 65535; H*W < 2^30                       */
+  int32_t B, C_in, C_out, H, W; /* B, C_in, C_out <= 65535; H*W <= 2^30 - 16                 */
   int32_t levels;             /* d >= 1; H and W must be divisible by 2^d (no padding)      */
   int64_t keep_num, keep_den; /* gamma = keep_num/keep_den, the fraction KEPT;
                                  k = ceil(keep_num*H*W/keep_den) in integer arithmetic      */

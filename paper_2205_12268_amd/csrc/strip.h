@@ -214,6 +214,67 @@ __device__ __forceinline__ void store_row_stream(bf16_t *dst, const float (&src)
   }
 }
 
+// Rows through a buffer descriptor of one plane (non-temporal): the lane gives a byte offset
+// into the plane, and an offset at or beyond the descriptor's size makes the hardware drop the
+// store (return zeros for the load) without touching memory.  Lanes that stand outside the
+// plane use that instead of a lane mask or a dummy target (a line of memory shared by all idle
+// lanes of the chip turns into a hot spot: with 24 of 32 lanes a row in use it tripled the
+// inverse's time).
+constexpr uint32_t kRowDropped = 0xFFFFFFF0u;  // beyond any plane (H * W <= 2^30 - 16 elements)
+constexpr int kBufStream = 2;                  // cache policy of the access: non-temporal
+typedef uint32_t buf_u4 __attribute__((ext_vector_type(4)));
+typedef uint32_t buf_u2 __attribute__((ext_vector_type(2)));
+template <class YT>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t plane_rsrc(const YT *plane, int64_t n) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<YT *>(plane), 0, (int)(uint32_t)(n * (int64_t)sizeof(YT)),
+                                           0x00020000 /* raw dwords, no swizzle */);
+}
+template <int V>
+__device__ __forceinline__ void store_row_buf(__amdgpu_buffer_rsrc_t rsrc, uint32_t off,
+                                              const float (&src)[V], float) {
+  if constexpr (V == 4) {
+    buf_u4 t = {__float_as_uint(src[0]), __float_as_uint(src[1]), __float_as_uint(src[2]), __float_as_uint(src[3])};
+    __builtin_amdgcn_raw_buffer_store_b128(t, rsrc, off, 0, kBufStream);
+  } else {
+    buf_u2 t = {__float_as_uint(src[0]), __float_as_uint(src[1])};
+    __builtin_amdgcn_raw_buffer_store_b64(t, rsrc, off, 0, kBufStream);
+  }
+}
+template <int V>
+__device__ __forceinline__ void store_row_buf(__amdgpu_buffer_rsrc_t rsrc, uint32_t off,
+                                              const float (&src)[V], bf16_t) {
+  const uint32_t a = pack_bf16(src[0], src[1]);
+  if constexpr (V == 4) {
+    buf_u2 t = {a, pack_bf16(src[2], src[3])};
+    __builtin_amdgcn_raw_buffer_store_b64(t, rsrc, off, 0, kBufStream);
+  } else {
+    __builtin_amdgcn_raw_buffer_store_b32(a, rsrc, off, 0, kBufStream);
+  }
+}
+template <int V>
+__device__ __forceinline__ void load_row_buf(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, float (&dst)[V],
+                                             float) {
+  if constexpr (V == 4) {
+    const buf_u4 t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, kBufStream);
+    dst[0] = __uint_as_float(t.x); dst[1] = __uint_as_float(t.y);
+    dst[2] = __uint_as_float(t.z); dst[3] = __uint_as_float(t.w);
+  } else {
+    const buf_u2 t = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, kBufStream);
+    dst[0] = __uint_as_float(t.x); dst[1] = __uint_as_float(t.y);
+  }
+}
+template <int V>
+__device__ __forceinline__ void load_row_buf(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, float (&dst)[V],
+                                             bf16_t) {
+  if constexpr (V == 4) {
+    const buf_u2 t = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, kBufStream);
+    dst[0] = bf16_lo(t.x); dst[1] = bf16_hi(t.x); dst[2] = bf16_lo(t.y); dst[3] = bf16_hi(t.y);
+  } else {
+    const uint32_t t = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, kBufStream);
+    dst[0] = bf16_lo(t); dst[1] = bf16_hi(t);
+  }
+}
+
 // What a lane loads of one row, kept as it arrives: the widening of bf16 happens when the
 // values are used, not where the load is issued (a conversion next to the load would wait for it
 // and undo the prefetch).

@@ -62,7 +62,8 @@ wcc_status check_desc(const wcc_desc *d) {
   if (d->H % s || d->W % s) return WCC_ERR_SHAPE;
   // grid limits and 32-bit in-plane offsets
   if (d->B > 65535 || d->C_in > 65535 || d->C_out > 65535) return WCC_ERR_SHAPE;
-  if ((int64_t)d->H * d->W >= ((int64_t)1 << 30)) return WCC_ERR_SHAPE;
+  // (a plane's bytes, and an offset that lies beyond every plane, fit 32 bits: strip.h, kRowDropped)
+  if ((int64_t)d->H * d->W > ((int64_t)1 << 30) - 16) return WCC_ERR_SHAPE;
   if (d->w_dtype != WCC_F32 && d->w_dtype != WCC_BF16 && d->w_dtype != WCC_I8 && d->w_dtype != WCC_I4)
     return WCC_ERR_DTYPE;
   if (d->w_dtype == WCC_I4 && d->C_in % 2) return WCC_ERR_SHAPE;
