@@ -268,6 +268,242 @@ hipError_t mfma_launch(const wcc_desc &d, int64_t k, const void *w, const float 
   return hipGetLastError();
 }
 
+// ---- the contraction where it is bound by arithmetic (hundreds of channels and more) ------------
+// The kernel above is laid out for the memory-bound layers: a wave tile of 32 x 128 re-reads
+// every activation fragment in all eight waves (five 16-byte LDS reads per four matrix
+// instructions) and one LDS buffer costs two barriers a chunk.  With C_in in the hundreds or
+// thousands the matrix cores are what counts, so this variant spends LDS bandwidth and barriers
+// sparingly:
+//   workgroup tile 128 (rows) x 128 (positions), four waves in a 2 x 2 arrangement, wave tile
+//   64 x 64 = 2 x 2 blocks of 32 x 32 (64 accumulator registers, so that two register sets of
+//   loads in flight still leave room for three workgroups a compute unit): four fragment reads
+//   per four matrix instructions;
+//   two LDS stages of 64 bytes of K a row (32 channels of bf16, 64 of int8: the byte addressing
+//   of both operand types is the same), 20 KB each: while the matrix instructions of stage s
+//   run, the registers loaded two stages earlier are converted and written into the other
+//   buffer and the loads of the stage after next are issued; one barrier a stage.
+// Activations are int8 codes only (the fused layer's default route).  Positions are stored
+// permuted inside a wave's 64 columns (row (n % 2) * 32 + n / 2), so that after the two column
+// blocks a lane holds two adjacent positions of one output row and stores 8 bytes.
+// Which tile a workgroup takes: the hardware hands consecutive workgroups to the 8 dies in
+// turn, each die with an L2 of its own; here die x works through the x-th eighth of the tile
+// list (positions fastest, then rows, then samples), so that the tiles a die has in flight share
+// their activation columns and walk through neighbouring weight rows in ITS L2.  With the
+// natural order every die touches every operand and most fetches come from beyond the L2s
+// (1.1 GB at 5 TB/s for 116 GFLOP on 4096 x 1024 weights).
+// Needs k % 4 == 0 and C_in % 8 == 0 (bf16 weights) or % 16 == 0 (int8 weights).
+constexpr int kDies = 8;
+constexpr int kTileM = 128, kTileN = 128, kTileKB = 64, kTileLDR = kTileKB + 16;
+constexpr int kTileMinChannels = 256;
+
+template <bool I8W>
+__global__ __launch_bounds__(256, 2) void pointwise_tile_kernel(
+    const void *__restrict__ w, const float *__restrict__ w_scale, const int8_t *__restrict__ xq,
+    const float *__restrict__ alpha, int n_alpha, float *alpha_out, float *__restrict__ yc, int M,
+    int K, int64_t k, bool stream_out, int gx, int gy, int tiles, int dies) {
+  constexpr int ESZ = I8W ? 1 : 2;        // bytes of a weight / of an activation in LDS
+  constexpr int KC = kTileKB / ESZ;       // channels a stage: 64 or 32
+  constexpr int CPT = KC / 8;             // channels a thread converts: 8 or 4
+  constexpr int LDR = kTileLDR;
+  __shared__ __attribute__((aligned(16))) unsigned char As[2][kTileM * LDR];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[2][kTileN * LDR];
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  const int wm = wv >> 1, wn = wv & 1;    // the wave's place in the 2 x 2 arrangement
+  // grid = 8 * ceil(tiles / 8) workgroups in one dimension
+  // (dies = 1: the natural order, for layers whose weights every L2 holds anyway and whose time
+  // goes into writing yc: there the dies had better write one neighbourhood together)
+  const int tile = (blockIdx.x % dies) * (gridDim.x / dies) + blockIdx.x / dies;
+  const int b = tile / (gx * gy), by = (tile / gx) % gy, bx = tile % gx;
+  const int64_t n0 = (int64_t)bx * kTileN;
+  const int m0 = by * kTileM;
+  const int8_t *xb = xq + (size_t)b * K * k;
+  const unsigned char *wb = static_cast<const unsigned char *>(w);
+  // activation loader: group of four positions, channel group.  A wave takes 8 position groups
+  // x all 8 channel groups: the 32 lanes that an LDS write serves together then hit 8 rows
+  // (160 bytes apart) x 4 channel groups (8 bytes apart) = 32 different 8-byte bank pairs; with
+  // 32 position groups a wave the same write was a four-way bank conflict.
+  const int g = wv * 8 + (lane & 7), kq = lane >> 3;
+  const int stages = (K + KC - 1) / KC;
+
+  const float al = alpha_max(alpha, n_alpha);  // (every thread of the workgroup is here)
+  if (alpha_out && tile == 0 && threadIdx.x == 0) alpha_out[0] = al;
+  if (tile >= tiles) return;  // the workgroups that pad the grid to a multiple of 8
+
+  using Acc = std::conditional_t<I8W, intx16, floatx16>;
+  Acc acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+  // global -> registers: half a weight row (32 of a stage's 64 bytes of K; two threads a row)
+  // and the thread's CPT x 4 activation patch,
+  // through buffer descriptors of the weights and of the sample's compressed signal: what lies
+  // a load never faults (outside the buffer it returns zeros, and an offset that wraps lands
+  // inside it), so there is no branch and no lane mask, a prefetch may run past the last
+  // stage, and the compiler can count the loads in flight exactly.  Weights of channels
+  // >= C_in are zeros (the offset is sent outside, a wave-uniform choice), so whatever the
+  // activation loads return for those channels is multiplied by zero; rows >= M and positions
+  // >= k (last tiles) read something, but their rows and columns are never stored and feed
+  // no other.
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  struct Regs {
+    u32x4 w[2];
+    uint32_t x[CPT];
+  };
+  const __amdgpu_buffer_rsrc_t wdesc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<unsigned char *>(wb), 0, (int)(uint32_t)((int64_t)M * K * ESZ), 0x00020000);
+  const __amdgpu_buffer_rsrc_t xdesc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<int8_t *>(xb), 0, (int)(uint32_t)((int64_t)K * k), 0x00020000);
+  constexpr uint32_t kOutside = 0xFFFFFFF0u;
+  const int a_row = t >> 1, a_half = t & 1;
+  const uint32_t wrow = (uint32_t)(m0 + a_row) * (uint32_t)(K * ESZ);
+  const uint32_t xcol = (uint32_t)(n0 + 4 * g) + (uint32_t)(kq * CPT) * (uint32_t)k;
+  auto fetch = [&](Regs &r, int st) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      // first channel of the 16-byte load; a stage is whole or empty in K (C_in is a multiple of
+      // what 16 bytes hold), but its two halves may differ: the choice is the lane's
+      const int kk = st * KC + (a_half * 2 + q) * (16 / ESZ);
+      r.w[q] = __builtin_amdgcn_raw_buffer_load_b128(wdesc, kk < K ? wrow + (uint32_t)kk * ESZ : kOutside, 0, 0);
+    }
+#pragma unroll
+    for (int c = 0; c < CPT; ++c)  // channel st * KC + c (+ kq * CPT, which xcol carries)
+      r.x[c] = __builtin_amdgcn_raw_buffer_load_b32(xdesc, xcol + (uint32_t)(st * KC + c) * (uint32_t)k, 0, 0);
+  };
+  // registers -> LDS stage `buf`: the weight row as it is; the patch transposed (and widened to
+  // bf16 for bf16 weights: an integer |v| <= 127 is exact there, its pattern is the float's
+  // high half), 8 bytes of K for each of the four positions
+  auto stash = [&](const Regs &r, int buf) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      *reinterpret_cast<u32x4 *>(&As[buf][a_row * LDR + (a_half * 2 + q) * 16]) = r.w[q];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t lo, hi;
+      if constexpr (I8W) {
+        // byte i of eight channel words -> two words of four channels each
+        const uint32_t sel = 0x0C0C0400u + 0x00000101u * i;   // {.., .., b[i], a[i]}
+        const uint32_t p01 = __builtin_amdgcn_perm(r.x[1], r.x[0], sel);
+        const uint32_t p23 = __builtin_amdgcn_perm(r.x[3], r.x[2], sel);
+        const uint32_t p45 = __builtin_amdgcn_perm(r.x[5], r.x[4], sel);
+        const uint32_t p67 = __builtin_amdgcn_perm(r.x[7], r.x[6], sel);
+        lo = (p01 & 0xFFFFu) | (p23 << 16);
+        hi = (p45 & 0xFFFFu) | (p67 << 16);
+      } else {
+        float f[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) f[c] = (float)((int)(r.x[c] << (24 - 8 * i)) >> 24);
+        lo = __builtin_amdgcn_perm(__float_as_uint(f[1]), __float_as_uint(f[0]), 0x07060302u);
+        hi = __builtin_amdgcn_perm(__float_as_uint(f[3]), __float_as_uint(f[2]), 0x07060302u);
+      }
+      const int nl = 4 * g + i;  // position inside the workgroup's tile
+      const int row = (nl & 64) + (nl & 1) * 32 + ((nl & 63) >> 1);
+      *reinterpret_cast<uint2 *>(&Bs[buf][row * LDR + kq * 8]) = make_uint2(lo, hi);
+    }
+  };
+  const int fr = lane & 31, half = lane >> 5;
+  auto multiply = [&](int buf) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      uint4 a[2], bb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        a[i] = *reinterpret_cast<const uint4 *>(&As[buf][(wm * 64 + i * 32 + fr) * LDR + ks * 32 + half * 16]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        bb[j] = *reinterpret_cast<const uint4 *>(&Bs[buf][(wn * 64 + j * 32 + fr) * LDR + ks * 32 + half * 16]);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          if constexpr (I8W)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(intx4, a[i]),
+                                                             __builtin_bit_cast(intx4, bb[j]), acc[i][j], 0, 0, 0);
+          else
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]),
+                                                               __builtin_bit_cast(bf16x8, bb[j]), acc[i][j], 0, 0, 0);
+        }
+    }
+  };
+
+  // Two register sets: the loads of a stage are issued two stages before they are converted,
+  // so that they have a whole stage of matrix instructions (and the other workgroup's) to
+  // arrive.  r0 carries the odd stages, r1 the even ones.
+  Regs r0, r1;
+  fetch(r0, 0);
+  stash(r0, 0);
+  fetch(r0, 1);
+  fetch(r1, 2);
+  __syncthreads();
+  for (int s = 0; s < stages; s += 2) {
+    stash(r0, 1);      // stage s + 1 (every wave left buffer 1 at the last barrier)
+    fetch(r0, s + 3);
+    multiply(0);       // stage s
+    __syncthreads();
+    if (s + 1 >= stages) break;
+    stash(r1, 0);      // stage s + 2
+    fetch(r1, s + 4);
+    multiply(1);       // stage s + 1
+    __syncthreads();
+  }
+
+  // acc[i][j][r]: row wm*64 + i*32 + (r/4)*8 + (lane/32)*4 + r%4, position wn*64 + 2*(lane%32) + j
+  const float sx = al / 127.f;
+  const int64_t n = n0 + wn * 64 + 2 * fr;
+  if (n < k) {  // k % 4 == 0 and n even: both positions inside or both outside
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+        if (m < M) {
+          const float sc = I8W ? sx * w_scale[m] : sx;
+          const float v0 = (float)acc[i][0][r] * sc, v1 = (float)acc[i][1][r] * sc;
+          float *dst = yc + ((size_t)b * M + m) * k + n;
+          if (stream_out) {
+            floatx2 o = {v0, v1};
+            __builtin_nontemporal_store(o, reinterpret_cast<floatx2 *>(dst));
+          } else {
+            *reinterpret_cast<float2 *>(dst) = make_float2(v0, v1);
+          }
+        }
+      }
+  }
+}
+
+template <bool I8W>
+hipError_t tile_launch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale, const void *xc,
+                       const float *alpha, int n_alpha, float *alpha_out, float *yc, hipStream_t s) {
+  const int64_t gx = (k + kTileN - 1) / kTileN, gy = (d.C_out + kTileM - 1) / kTileM;
+  const int64_t tiles = gx * gy * d.B;
+  if (tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((tiles + kDies - 1) / kDies * kDies)), block(256);
+  const bool stream_out = (int64_t)d.B * d.C_out * k * 4 > ((int64_t)512 << 20);
+  hipLaunchKernelGGL((pointwise_tile_kernel<I8W>), grid, block, 0, s, w, w_scale,
+                     static_cast<const int8_t *>(xc), alpha, n_alpha, alpha_out, yc, d.C_out, d.C_in, k,
+                     stream_out, (int)gx, (int)gy, (int)tiles,
+                     (int64_t)d.C_out * d.C_in * (I8W ? 1 : 2) >= ((int64_t)1 << 20) ? kDies : 1);
+  return hipGetLastError();
+}
+
+// Is the layer one for the arithmetic-bound variant?  int8 codes in, enough channels that the
+// matrix instructions outweigh the stream (measured crossover), at least a tile of output
+// rows, and a workgroup for every compute unit.
+static bool wants_tile_kernel(const wcc_desc &d, int64_t k, bool f32) {
+  if (f32 || d.C_in < kTileMinChannels || d.C_out < kTileM) return false;
+  // an expansion layer with few input channels spends its time writing yc: the stream kernel's
+  // 16-byte stores and its walk over the row tiles do that better (1024 x 256: 170 vs 180 us)
+  if (d.C_in < 512 && d.C_out >= 4 * d.C_in) return false;
+  const int64_t wgs = ((k + kTileN - 1) / kTileN) * ((d.C_out + kTileM - 1) / kTileM) * (int64_t)d.B;
+  // (byte offsets into the weights and into a sample's compressed signal fit 32 bits)
+  const int64_t limit = (int64_t)0xFFFFFFF0;
+  if ((int64_t)(d.C_out + kTileM) * d.C_in * 2 > limit || (int64_t)d.C_in * k > limit) return false;
+  return wgs >= 256 && wgs <= ((int64_t)1 << 30);
+}
+
 // Tile choice.  Large tiles first (BM = 256 when C_out needs it: every activation is then read
 // once), as long as they give every compute unit a workgroup; otherwise smaller ones.
 template <bool I8W>
@@ -276,6 +512,8 @@ hipError_t mfma_dispatch(const wcc_desc &d, int64_t k, const void *w, const floa
                          float *yc, hipStream_t s) {
 #define WCC_MFMA(BM_, BN_) \
   return mfma_launch<BM_, BN_, I8W>(d, k, w, w_scale, xc, f32, alpha, n_alpha, alpha_out, yc, s)
+  if (wants_tile_kernel(d, k, f32))
+    return tile_launch<I8W>(d, k, w, w_scale, xc, alpha, n_alpha, alpha_out, yc, s);
   const int64_t want = 256;  // compute units
   auto wgs = [&](int bm, int bn) {
     return ((k + bn - 1) / bn) * ((d.C_out + bm - 1) / bm) * (int64_t)d.B;
