@@ -297,7 +297,7 @@ constexpr int kTileM = 128, kTileN = 128, kTileKB = 64, kTileLDR = kTileKB + 16;
 constexpr int kTileMinChannels = 256;
 
 template <bool I8W>
-__global__ __launch_bounds__(256, 2) void pointwise_tile_kernel(
+__global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
     const void *__restrict__ w, const float *__restrict__ w_scale, const int8_t *__restrict__ xq,
     const float *__restrict__ alpha, int n_alpha, float *alpha_out, float *__restrict__ yc, int M,
     int K, int64_t k, bool stream_out, int gx, int gy, int tiles, int dies) {
@@ -438,16 +438,22 @@ __global__ __launch_bounds__(256, 2) void pointwise_tile_kernel(
   fetch(r0, 1);
   fetch(r1, 2);
   __syncthreads();
+  // (an odd number of stages is rounded up: the stage past the end loads zeros and adds them;
+  // a way out in the middle of the loop body made the compiler keep two copies of the
+  // accumulators and move 64 registers a stage)
   for (int s = 0; s < stages; s += 2) {
     stash(r0, 1);      // stage s + 1 (every wave left buffer 1 at the last barrier)
     fetch(r0, s + 3);
     multiply(0);       // stage s
     __syncthreads();
-    if (s + 1 >= stages) break;
+    // (nothing of the next half moves up across this point: the compiler would start converting
+    // r1 here, a stage early, and wait for loads that have another stage to arrive)
+    __builtin_amdgcn_sched_barrier(0);
     stash(r1, 0);      // stage s + 2
     fetch(r1, s + 4);
     multiply(1);       // stage s + 1
     __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
   }
 
   // acc[i][j][r]: row wm*64 + i*32 + (r/4)*8 + (lane/32)*4 + r%4, position wn*64 + 2*(lane%32) + j
