@@ -296,8 +296,9 @@ constexpr int kDies = 8;
 constexpr int kTileM = 128, kTileN = 128, kTileKB = 64, kTileLDR = kTileKB + 16;
 constexpr int kTileMinChannels = 256;
 
-template <bool I8W>
-__global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
+// WM: 32-row blocks of a wave tile, 2 (workgroup tile 128 rows) or 4 (256 rows)
+template <bool I8W, int WM>
+__global__ __launch_bounds__(256, WM == 2 ? 3 : 2) void pointwise_tile_kernel(
     const void *__restrict__ w, const float *__restrict__ w_scale, const int8_t *__restrict__ xq,
     const float *__restrict__ alpha, int n_alpha, float *alpha_out, float *__restrict__ yc, int M,
     int K, int64_t k, bool stream_out, int gx, int gy, int tiles, int dies) {
@@ -305,7 +306,9 @@ __global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
   constexpr int KC = kTileKB / ESZ;       // channels a stage: 64 or 32
   constexpr int CPT = KC / 8;             // channels a thread converts: 8 or 4
   constexpr int LDR = kTileLDR;
-  __shared__ __attribute__((aligned(16))) unsigned char As[2][kTileM * LDR];
+  constexpr int TM = 64 * WM;             // rows of the workgroup tile
+  constexpr int WQ = WM / 2;              // 16-byte weight loads a thread and stage: half a row, or a whole one
+  __shared__ __attribute__((aligned(16))) unsigned char As[2][TM * LDR];
   __shared__ __attribute__((aligned(16))) unsigned char Bs[2][kTileN * LDR];
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const int wm = wv >> 1, wn = wv & 1;    // the wave's place in the 2 x 2 arrangement
@@ -315,7 +318,7 @@ __global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
   const int tile = (blockIdx.x % dies) * (gridDim.x / dies) + blockIdx.x / dies;
   const int b = tile / (gx * gy), by = (tile / gx) % gy, bx = tile % gx;
   const int64_t n0 = (int64_t)bx * kTileN;
-  const int m0 = by * kTileM;
+  const int m0 = by * TM;
   const int8_t *xb = xq + (size_t)b * K * k;
   const unsigned char *wb = static_cast<const unsigned char *>(w);
   // activation loader: group of four positions, channel group.  A wave takes 8 position groups
@@ -330,9 +333,9 @@ __global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
   if (tile >= tiles) return;  // the workgroups that pad the grid to a multiple of 8
 
   using Acc = std::conditional_t<I8W, intx16, floatx16>;
-  Acc acc[2][2];
+  Acc acc[WM][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < WM; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -350,7 +353,7 @@ __global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
   // no other.
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   struct Regs {
-    u32x4 w[2];
+    u32x4 w[2 * WQ];
     uint32_t x[CPT];
   };
   const __amdgpu_buffer_rsrc_t wdesc = __builtin_amdgcn_make_buffer_rsrc(
@@ -358,12 +361,12 @@ __global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
   const __amdgpu_buffer_rsrc_t xdesc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<int8_t *>(xb), 0, (int)(uint32_t)((int64_t)K * k), 0x00020000);
   constexpr uint32_t kOutside = 0xFFFFFFF0u;
-  const int a_row = t >> 1, a_half = t & 1;
+  const int a_row = WM == 2 ? t >> 1 : t, a_half = WM == 2 ? t & 1 : 0;
   const uint32_t wrow = (uint32_t)(m0 + a_row) * (uint32_t)(K * ESZ);
   const uint32_t xcol = (uint32_t)(n0 + 4 * g) + (uint32_t)(kq * CPT) * (uint32_t)k;
   auto fetch = [&](Regs &r, int st) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+    for (int q = 0; q < 2 * WQ; ++q) {
       // first channel of the 16-byte load; a stage is whole or empty in K (C_in is a multiple of
       // what 16 bytes hold), but its two halves may differ: the choice is the lane's
       const int kk = st * KC + (a_half * 2 + q) * (16 / ESZ);
@@ -378,7 +381,7 @@ __global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
   // high half), 8 bytes of K for each of the four positions
   auto stash = [&](const Regs &r, int buf) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
+    for (int q = 0; q < 2 * WQ; ++q)
       *reinterpret_cast<u32x4 *>(&As[buf][a_row * LDR + (a_half * 2 + q) * 16]) = r.w[q];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -408,15 +411,15 @@ __global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
   auto multiply = [&](int buf) {
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      uint4 a[2], bb[2];
+      uint4 a[WM], bb[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        a[i] = *reinterpret_cast<const uint4 *>(&As[buf][(wm * 64 + i * 32 + fr) * LDR + ks * 32 + half * 16]);
+      for (int i = 0; i < WM; ++i)
+        a[i] = *reinterpret_cast<const uint4 *>(&As[buf][(wm * (32 * WM) + i * 32 + fr) * LDR + ks * 32 + half * 16]);
 #pragma unroll
       for (int j = 0; j < 2; ++j)
         bb[j] = *reinterpret_cast<const uint4 *>(&Bs[buf][(wn * 64 + j * 32 + fr) * LDR + ks * 32 + half * 16]);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < WM; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           if constexpr (I8W)
@@ -461,10 +464,10 @@ __global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
   const int64_t n = n0 + wn * 64 + 2 * fr;
   if (n < k) {  // k % 4 == 0 and n even: both positions inside or both outside
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+        const int m = m0 + wm * (32 * WM) + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
         if (m < M) {
           const float sc = I8W ? sx * w_scale[m] : sx;
           const float v0 = (float)acc[i][0][r] * sc, v1 = (float)acc[i][1][r] * sc;
@@ -480,15 +483,16 @@ __global__ __launch_bounds__(256, 3) void pointwise_tile_kernel(
   }
 }
 
-template <bool I8W>
+template <bool I8W, int WM>
 hipError_t tile_launch(const wcc_desc &d, int64_t k, const void *w, const float *w_scale, const void *xc,
                        const float *alpha, int n_alpha, float *alpha_out, float *yc, hipStream_t s) {
-  const int64_t gx = (k + kTileN - 1) / kTileN, gy = (d.C_out + kTileM - 1) / kTileM;
+  constexpr int TM = 64 * WM;
+  const int64_t gx = (k + kTileN - 1) / kTileN, gy = (d.C_out + TM - 1) / TM;
   const int64_t tiles = gx * gy * d.B;
   if (tiles > (int64_t)1 << 30) return hipErrorInvalidValue;
   dim3 grid((unsigned)((tiles + kDies - 1) / kDies * kDies)), block(256);
   const bool stream_out = (int64_t)d.B * d.C_out * k * 4 > ((int64_t)512 << 20);
-  hipLaunchKernelGGL((pointwise_tile_kernel<I8W>), grid, block, 0, s, w, w_scale,
+  hipLaunchKernelGGL((pointwise_tile_kernel<I8W, WM>), grid, block, 0, s, w, w_scale,
                      static_cast<const int8_t *>(xc), alpha, n_alpha, alpha_out, yc, d.C_out, d.C_in, k,
                      stream_out, (int)gx, (int)gy, (int)tiles,
                      (int64_t)d.C_out * d.C_in * (I8W ? 1 : 2) >= ((int64_t)1 << 20) ? kDies : 1);
@@ -518,8 +522,11 @@ hipError_t mfma_dispatch(const wcc_desc &d, int64_t k, const void *w, const floa
                          float *yc, hipStream_t s) {
 #define WCC_MFMA(BM_, BN_) \
   return mfma_launch<BM_, BN_, I8W>(d, k, w, w_scale, xc, f32, alpha, n_alpha, alpha_out, yc, s)
+  // (WM = 4, 256-row tiles with 128 x 64 wave tiles, two workgroups a compute unit: measured
+  // slower on every layer tried, 176 vs 147 us at 1024 -> 4096 channels; three resident
+  // workgroups hide more than the halved conversion work saves)
   if (wants_tile_kernel(d, k, f32))
-    return tile_launch<I8W>(d, k, w, w_scale, xc, alpha, n_alpha, alpha_out, yc, s);
+    return tile_launch<I8W, 2>(d, k, w, w_scale, xc, alpha, n_alpha, alpha_out, yc, s);
   const int64_t want = 256;  // compute units
   auto wgs = [&](int bm, int bn) {
     return ((k + bn - 1) / bn) * ((d.C_out + bm - 1) / bm) * (int64_t)d.B;

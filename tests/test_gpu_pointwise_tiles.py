@@ -25,6 +25,8 @@ CASES = [
     ("i8_ragged", 2, 272, 300, 64, 512, 2051, 8192, synth.W_I8),         # k = 8204, three row tiles
     ("bf16_full", 1, 1024, 512, 128, 512, 1, 4, synth.W_BF16),           # 32 stages, every tile full
     ("i8_many_samples", 5, 256, 128, 32, 512, 1, 2, synth.W_I8),         # one row tile, 64 x 5 tiles
+    ("bf16_many_tiles", 4, 264, 300, 128, 512, 4097, 16384, synth.W_BF16),  # 1548 tiles in the natural order (small weights)
+    ("i8_big_weights", 2, 1040, 1100, 64, 512, 2051, 8192, synth.W_I8),     # weights over 1 MB: tiles dealt to the dies in chunks, grid padded to a multiple of 8
 ]
 
 
