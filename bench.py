@@ -347,6 +347,15 @@ def bench_block(args, synth, wcc, torch, np) -> int:
         "stages_frac_of_hbm_peak": {n: round(alg[n] / (stage_us[n] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
                                     for n in stage_us if stage_us[n] > 0 and alg.get(n)},
         "block_alg_GBs": round(sum(alg.values()) / dt / 1e9, 1),
+        # the two contractions against the matrix-core peak of their operand type (bf16 weights)
+        "mfma": {f"l{layer}_pointwise": {
+            "flops": 2.0 * cfg.B * cfg.k * cfg.layer(layer).C_in * cfg.layer(layer).C_out,
+            "achieved_tflops": round(2.0 * cfg.B * cfg.k * cfg.layer(layer).C_in * cfg.layer(layer).C_out
+                                     / (stage_us[f"l{layer}_pointwise"] * 1e-6) / 1e12, 1),
+            "peak_tflops": MFMA_PEAK_TFLOPS["bf16"],
+            "frac": round(2.0 * cfg.B * cfg.k * cfg.layer(layer).C_in * cfg.layer(layer).C_out
+                          / (stage_us[f"l{layer}_pointwise"] * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4)}
+            for layer in (0, 1) if stage_us.get(f"l{layer}_pointwise", 0) > 0},
         "dense_block_ms": {"framework_bf16": None if dense_ms is None else round(dense_ms, 4),
                            "framework_1x1_bf16_plus_own_depthwise_f32":
                                None if dense_fair_ms is None else round(dense_fair_ms, 4)},
