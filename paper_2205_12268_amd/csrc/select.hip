@@ -461,7 +461,11 @@ __global__ __launch_bounds__(256) void combine_parts_kernel(const float *__restr
   if (top_part) *reinterpret_cast<float4 *>(top_part + at) = load_top(top_part, G, (int64_t)B * N, at);
 }
 
-constexpr int kCombineGroups = 4;  // from this many groups on the partial planes are combined first
+// The partial planes are combined first from this many groups and this many values a sample on
+// (below that the extra launch costs more than the one workgroup's reads: the deep layers of the
+// 16-layer stack have 2048-8192 positions in up to 32 groups)
+constexpr int kCombineGroups = 4;
+constexpr int64_t kCombineValues = 1 << 18;
 
 // grid = B, block = 1024.  REDUCE as in load_keys.
 template <bool REDUCE>
@@ -632,7 +636,7 @@ hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, fl
   const uint32_t k32 = (uint32_t)k;
   if (N <= kSmallMaxN) {
     const int slots = (int)((N + 4 * kSmallThreads - 1) / (4 * kSmallThreads));
-    if (G >= kCombineGroups) {
+    if (G >= kCombineGroups && (int64_t)G * N >= kCombineValues) {
       hipLaunchKernelGGL(combine_parts_kernel, dim3((unsigned)((N + 1023) / 1024), d.B), dim3(256), 0, s,
                          norm_or_part, norm_out, G, N, d.B, top_part);
       hipLaunchKernelGGL((select_small_kernel<false>), dim3(d.B), dim3(kSmallThreads), 0, s, norm_out,

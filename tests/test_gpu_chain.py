@@ -50,6 +50,11 @@ CASES = [
     blk("two_segments_d1", 1, 4, 2, 6, 384, 1, 1, 4, BF16, 8),         # d = 1, 64 + 32 lanes
     blk("two_segments_dense_top", 1, 4, 2, 32, 512, 3, 1, 4, BF16, 8), # packed, slot-by-slot and empty strips in one plane
     blk("two_segments_f32", 1, 4, 2, 16, 512, 2, 2, 7, F32, 0, 1.0),   # fp32 path through shared rows
+    # enough kept coefficients in the project layer for the int8 route (clipping parameter known
+    # before the second pass; the small cases above take the fp32 route)
+    blk("codes_two_strips", 4, 64, 8, 64, 128, 3, 1, 4, BF16, 8),      # 512 middle channels, k = 2048
+    blk("codes_idle_lanes", 4, 128, 8, 48, 96, 3, 1, 4, I8, 8),        # 1024 middle channels, 24 of 32 lanes
+    blk("codes_two_segments", 2, 64, 8, 32, 512, 3, 1, 4, BF16, 8),    # shared rows, k = 4096
 ]
 # Rows of the input from this fraction of the height on are zero, so that the kept positions of
 # both layers crowd into the strips above: strips that keep a half or all of their positions at

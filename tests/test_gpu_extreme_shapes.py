@@ -1,7 +1,7 @@
 """Shapes at the corners of what the descriptor allows, fused layer against the oracle: many
 samples of a few pixels, thousands of channels on a tiny plane, planes one strip wide or one
 strip tall, the smallest plane there is, k = 1 and k = N - 1 at four levels, widths that are
-not a multiple of four.  Index sets and alpha bit for bit, output to the usual tolerance.
+not a multiple of four, small planes with thousands of channels.  Index sets and alpha bit for bit, output to the usual tolerance.
 """
 import numpy as np
 import pytest
@@ -36,6 +36,12 @@ SHAPES = [
     (1, 8, 8, 6, 6, 1, 1, 3, BF16, 8),            # W % 4 != 0
     (1, 8, 8, 2, 1026, 1, 1, 2, BF16, 8),         # W % 4 != 0 over several segments
     (5, 8, 8, 2, 1026, 1, 2, 2, F32, 8),
+    # small planes (one-workgroup selection) with millions of kept coefficients: the clipping
+    # parameter is then found before the second pass (int8 codes through memory), unlike on the
+    # small layers above
+    (8, 512, 64, 64, 64, 3, 1, 4, BF16, 8),
+    (2, 2048, 32, 96, 96, 3, 1, 2, I8, 8),        # partial planes combined before the selection
+    (4, 1024, 16, 128, 128, 2, 1, 4, BF16, 8),    # the largest plane the one-workgroup selection takes
 ]
 
 
