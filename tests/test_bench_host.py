@@ -97,3 +97,41 @@ def test_copy_calibration_ignores_the_small_copies(tmp_path):
     assert "scale 2.0000" in text and "scale 1.0000" in text
     line = next(ln for ln in text.splitlines() if ln.startswith("some_kernel"))
     assert [float(t) for t in line.split()[1:]] == [204800.0, 307200.0, 512000.0]
+
+
+def test_block_byte_counts_of_both_routes():
+    """Algorithmic bytes of the block (bench.py --config 6): with the middle tensors formed the
+    expand layer's inverse writes, and the project layer's two passes read, the expanded tensor;
+    chained, the inverse is gone and the two passes read the expand layer's compressed output
+    and rank map instead."""
+    cfg = synth.block_config(1, 4)
+    B, C, Cm, N, k = cfg.B, cfg.C, cfg.C_mid, cfg.N, cfg.k
+    assert (B, C, Cm, N, k) == (8, 256, 1024, 65536, 16384)
+    formed = bench.block_algorithmic_bytes(cfg, 4, chained=False)
+    chained = bench.block_algorithmic_bytes(cfg, 4, chained=True)
+    assert formed["l0_scatter_ihaar"] == 4 * B * Cm * k + 4 * B * k + 4 * B * Cm * N
+    assert formed["l1_haar_fwd"] == 4 * B * Cm * N + 4 * B * N
+    assert chained["l0_scatter_ihaar"] == 0
+    src = 4 * B * Cm * k + 4 * B * N
+    assert chained["l1_haar_fwd"] == src + 4 * B * N
+    assert chained["l1_gather"] == src + 4 * B * k + B * Cm * k          # int8 codes out
+    # what the two routes share: the expand layer's passes, both contractions, the last inverse
+    for name in ("l0_haar_fwd", "l0_gather", "l0_pointwise", "l1_pointwise", "l1_scatter_ihaar"):
+        assert formed[name] == chained[name], name
+    assert formed["l1_scatter_ihaar"] == 4 * B * C * k + 4 * B * k + 2 * 4 * B * C * N  # + the skip
+    assert sum(chained.values()) < 0.62 * sum(formed.values())
+
+
+def test_timing_table_rows_are_the_papers():
+    """The 24 rows of the paper's table "Inference timing results": image sides, channel counts
+    and keep ratios as printed; every row builds a valid block descriptor."""
+    assert len(bench.PAPER_TABLE) == 24
+    assert {r[0] for r in bench.PAPER_TABLE} == {96, 128, 256, 512}
+    assert {r[4] for r in bench.PAPER_TABLE} == {(1, 8), (1, 4), (1, 2)}
+    assert sum(1 for r in bench.PAPER_TABLE if r[4] == (1, 2)) == 9
+    for side, c, e, B, (num, den), paper in bench.PAPER_TABLE:
+        cfg = bench.block_from_shape(synth, f"{side},{c},{e},{B}", num, den)
+        assert cfg.N == side * side and cfg.C_mid == c * e and 1.0 < paper < 2.5
+        assert cfg.layer(1).C_in == cfg.C_mid and cfg.layer(0).C_out == cfg.C_mid
+    rect = bench.block_from_shape(synth, "64x128,16,2,3", 1, 8)
+    assert (rect.H, rect.W, rect.C, rect.expansion, rect.B) == (64, 128, 16, 2, 3)
