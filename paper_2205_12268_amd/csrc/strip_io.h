@@ -108,12 +108,21 @@ struct KeepSink {
     constexpr int base = slot_base(D, V, L, J);
     (void)p;
     (void)owner;  // (at[] is kDropped for the lanes that do not own the value)
+    if constexpr (Q8) {
+      // (the quantiser's division path is chosen once per row, not value by value)
+      auto store_codes = [&](auto fast_c) {
+        constexpr bool FAST = decltype(fast_c)::value;
 #pragma unroll
-    for (int e = 0; e < CV; ++e) {
-      const int s = base + i * CV + e;
-      if constexpr (Q8) {
-        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)quant.code(v[e]), xc_c, at[s], 0, 0);
-      } else {
+        for (int e = 0; e < CV; ++e)
+          __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)(int)quant.template level_as<FAST>(v[e]),
+                                               xc_c, at[base + i * CV + e], 0, 0);
+      };
+      if (quant.fast) store_codes(std::true_type{});
+      else store_codes(std::false_type{});
+    } else {
+#pragma unroll
+      for (int e = 0; e < CV; ++e) {
+        const int s = base + i * CV + e;
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[e]), xc_c, at[s], 0, 0);
         vmax = fmaxf(vmax, at[s] != kDropped ? fabsf(v[e]) : 0.f);
       }
@@ -156,12 +165,25 @@ struct KeepStagedSink {
   // once per channel, after the last level
   __device__ __forceinline__ void flush() {
     wave_lds_fence();
+    if constexpr (Q8) {
+      // which division the quantiser takes is the same for every value of the layer: chosen
+      // once per channel here, not value by value (three branches a value otherwise)
+      float v[NI];
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const float v = __uint_as_float(tile[cell[i]]);
-      if constexpr (Q8) {
-        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)quant.code(v), xc_c, at[i], 0, 0);
-      } else {
+      for (int i = 0; i < NI; ++i) v[i] = __uint_as_float(tile[cell[i]]);
+      auto store_codes = [&](auto fast_c) {
+        constexpr bool FAST = decltype(fast_c)::value;
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+          __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)(int)quant.template level_as<FAST>(v[i]),
+                                               xc_c, at[i], 0, 0);
+      };
+      if (quant.fast) store_codes(std::true_type{});
+      else store_codes(std::false_type{});
+    } else {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const float v = __uint_as_float(tile[cell[i]]);
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), xc_c, at[i], 0, 0);
         vmax = fmaxf(vmax, at[i] != kDropped ? fabsf(v) : 0.f);
       }
