@@ -124,11 +124,11 @@ struct Quant {
       const float r = __fmaf_rn(-q0, alpha, v);
       u = __fmaf_rn(r, y, q0);
     } else {
-      if (!on) return 0.f;
-      u = __fdiv_rn(v, alpha);
+      u = __fdiv_rn(v, alpha);  // (alpha <= 0: whatever this gives is dropped below, no branch)
     }
     u = fminf(fmaxf(u, -1.f), 1.f);
-    return rintf(__fmul_rn(127.f, u));
+    const float lv = rintf(__fmul_rn(127.f, u));
+    return (FAST || on) ? lv : 0.f;
   }
   __device__ __forceinline__ float level(float v) const {
     return fast ? level_as<true>(v) : level_as<false>(v);
