@@ -69,6 +69,17 @@ struct Patch {
       }
     }
   }
+  // int8 codes through a buffer descriptor of the sample's compressed signal: off is the byte
+  // offset of this thread's four positions in the patch's first channel.  No branch, no lane
+  // mask: a load never faults (outside the buffer it returns zeros, a wrapped offset lands
+  // inside it); what it returns for channels >= C_in meets zero weights, and for positions >= k
+  // it feeds columns that are never stored.
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t xdesc, uint32_t off, int64_t k) {
+    static_assert(!F32, "codes only");
+#pragma unroll
+    for (int r = 0; r < CPT; ++r)
+      c[r] = __builtin_amdgcn_raw_buffer_load_b32(xdesc, off + (uint32_t)r * (uint32_t)k, 0, 0);
+  }
   // level of channel r, position i, as a float holding an integer in [-127, 127]
   template <bool FAST>
   __device__ __forceinline__ float level(int r, int i, const Quant &q) const {
@@ -109,6 +120,15 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
 
   const float al = load_alpha(alpha, n_alpha, alpha_out);
   const Quant quant(al);
+  // With int8 codes both operands are loaded through buffer descriptors (the host has checked
+  // that their byte offsets fit 32 bits): weights of rows >= M lie beyond the end and come back
+  // as zeros, those of channels >= C_in are sent there by a wave-uniform choice.
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  constexpr uint32_t kOutside = 0xFFFFFFF0u;
+  const __amdgpu_buffer_rsrc_t wdesc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<unsigned char *>(wb), 0, (int)(uint32_t)((int64_t)M * K * ESZ), 0x00020000);
+  const __amdgpu_buffer_rsrc_t xdesc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void *>(xb), 0, (int)(uint32_t)((int64_t)K * k), 0x00020000);
   // A workgroup takes the row tiles blockIdx.y, blockIdx.y + gridDim.y, ...: with one workgroup
   // per column tile (gridDim.y = 1) the stores of a row tile drain while the next one is being
   // computed, instead of holding the compute unit until they are out.
@@ -128,9 +148,15 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
 #pragma unroll
     for (int q = 0; q < APT; ++q) {
       const int kk = kc * BK + (a_half * (BK / 2)) + q * (16 / ESZ);  // first element of the load
-      wreg[q] = make_uint4(0, 0, 0, 0);
-      if (m0 + a_row < M && kk < K)
-        wreg[q] = *reinterpret_cast<const uint4 *>(wb + ((size_t)(m0 + a_row) * K + kk) * ESZ);
+      if constexpr (!F32) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(
+            wdesc, kk < K ? (uint32_t)(m0 + a_row) * (uint32_t)(K * ESZ) + (uint32_t)kk * ESZ : kOutside, 0, 0);
+        wreg[q] = make_uint4(v.x, v.y, v.z, v.w);
+      } else {
+        wreg[q] = make_uint4(0, 0, 0, 0);
+        if (m0 + a_row < M && kk < K)
+          wreg[q] = *reinterpret_cast<const uint4 *>(wb + ((size_t)(m0 + a_row) * K + kk) * ESZ);
+      }
     }
   };
 
@@ -174,8 +200,10 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   // this thread's four positions in channel kq * CPT of chunk 0
   const bool n_in = n0 + 4 * g < k;
   const char *xp = static_cast<const char *>(xb) + ((size_t)(kq * CPT) * k + n0 + 4 * g) * (F32 ? 4 : 1);
+  const uint32_t xoff = (uint32_t)(kq * CPT) * (uint32_t)k + (uint32_t)(n0 + 4 * g);
   load_w(0);
-  raw.load(xp, K, k, kq * CPT, n_in);
+  if constexpr (F32) raw.load(xp, K, k, kq * CPT, n_in);
+  else raw.load(xdesc, xoff, k);
   for (int kc = 0; kc < nchunks; ++kc) {
     {
       if (quant.fast) stage_patch(raw, quant, std::true_type{});
@@ -185,9 +213,14 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
         *reinterpret_cast<uint4 *>(&As[a_row * LDR + a_half * (BK / 2) * ESZ + q * 16]) = wreg[q];
       __syncthreads();
       // both register tiles are in LDS now: the next chunk travels while this one is multiplied
-      if (kc + 1 < nchunks) {
+      if constexpr (F32) {
+        if (kc + 1 < nchunks) {
+          load_w(kc + 1);
+          raw.load(xp + (size_t)(kc + 1) * BK * k * 4, K, k, (kc + 1) * BK + kq * CPT, n_in);
+        }
+      } else {  // (past the last chunk: zeros and values nobody uses, no memory traffic to speak of)
         load_w(kc + 1);
-        raw.load(xp + (size_t)(kc + 1) * BK * k * (F32 ? 4 : 1), K, k, (kc + 1) * BK + kq * CPT, n_in);
+        raw.load(xdesc, xoff + (uint32_t)((kc + 1) * BK) * (uint32_t)k, k);
       }
       const int fr = lane & 31, half = lane >> 5;
       if constexpr (I8W) {
@@ -222,29 +255,43 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   const float sx = al / 127.f;
   const int64_t n = n0 + NB * (lane & 31);
   if (n < k) {  // k % 4 == 0: a lane's NB positions are all inside or all outside
+    // The two choices that are the same for the whole wave are taken once, outside the loop over
+    // the rows: whether all 32 rows of the wave exist (then no store sits under a test) and
+    // whether the output is streamed past the caches.
+    auto store_rows = [&](auto whole_c, auto stream_c) {
+      constexpr bool WHOLE = decltype(whole_c)::value, STREAM = decltype(stream_c)::value;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int m = m0 + wv * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-    if (m < M) {
-      float v[NB];
-      const float sc = I8W ? sx * w_scale[m] : sx;
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wv * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (WHOLE || m < M) {
+          float v[NB];
+          const float sc = I8W ? sx * w_scale[m] : sx;
 #pragma unroll
-      for (int i = 0; i < NB; ++i) v[i] = (float)acc[i][r] * sc;
-      float *dst = yc + ((size_t)b * M + m) * k + n;
-      if (stream_out) {  // (wave-uniform) an output that no cache will hold for its reader
-        if constexpr (NB == 4) {
-          floatx4 o = {v[0], v[1], v[2], v[3]};
-          __builtin_nontemporal_store(o, reinterpret_cast<floatx4 *>(dst));
-        } else {
-          floatx2 o = {v[0], v[1]};
-          __builtin_nontemporal_store(o, reinterpret_cast<floatx2 *>(dst));
+          for (int i = 0; i < NB; ++i) v[i] = (float)acc[i][r] * sc;
+          float *dst = yc + ((size_t)b * M + m) * k + n;
+          if constexpr (STREAM) {  // an output that no cache will hold for its reader
+            if constexpr (NB == 4) {
+              floatx4 o = {v[0], v[1], v[2], v[3]};
+              __builtin_nontemporal_store(o, reinterpret_cast<floatx4 *>(dst));
+            } else {
+              floatx2 o = {v[0], v[1]};
+              __builtin_nontemporal_store(o, reinterpret_cast<floatx2 *>(dst));
+            }
+          } else {
+            if constexpr (NB == 4) *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            else *reinterpret_cast<float2 *>(dst) = make_float2(v[0], v[1]);
+          }
         }
-      } else {
-        if constexpr (NB == 4) *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-        else *reinterpret_cast<float2 *>(dst) = make_float2(v[0], v[1]);
       }
+    };
+    const bool whole = m0 + wv * 32 + 32 <= M;
+    if (whole) {
+      if (stream_out) store_rows(std::true_type{}, std::true_type{});
+      else store_rows(std::true_type{}, std::false_type{});
+    } else {
+      if (stream_out) store_rows(std::false_type{}, std::true_type{});
+      else store_rows(std::false_type{}, std::false_type{});
     }
-  }
   }  // positions inside the signal
   }  // row tiles
 }
@@ -655,9 +702,14 @@ hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const f
                             float *alpha_out, float *yc, hipStream_t s) {
   const bool quant = d.act_quant_bits == 8;
   const int K = d.C_in;
-  if (quant && d.w_dtype == WCC_BF16 && K % 8 == 0 && k % 4 == 0)
+  // the matrix-core kernels address int8 codes and their weights with 32-bit byte offsets
+  // (4 GB of weights or of one sample's compressed signal take the plain kernel below)
+  const int64_t limit = (int64_t)0xFFFFFFF0;
+  const bool narrow = xc_is_f32 || ((int64_t)(d.C_out + 256) * K * 2 <= limit && (int64_t)K * k <= limit);
+  if (!narrow) {
+  } else if (quant && d.w_dtype == WCC_BF16 && K % 8 == 0 && k % 4 == 0)
     return mfma_dispatch<false>(d, k, w, w_scale, xc, xc_is_f32, alpha, n_alpha, alpha_out, yc, s);
-  if (quant && d.w_dtype == WCC_I8 && K % 16 == 0 && k % 4 == 0)
+  else if (quant && d.w_dtype == WCC_I8 && K % 16 == 0 && k % 4 == 0)
     return mfma_dispatch<true>(d, k, w, w_scale, xc, xc_is_f32, alpha, n_alpha, alpha_out, yc, s);
   const int xm = !quant ? 0 : (xc_is_f32 ? 2 : 1);
   switch (d.w_dtype) {
