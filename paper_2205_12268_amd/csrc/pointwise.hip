@@ -513,23 +513,35 @@ __global__ __launch_bounds__(256, WM == 2 ? 3 : 2) void pointwise_tile_kernel(
   const float sx = al / 127.f;
   const int64_t n = n0 + wn * 64 + 2 * fr;
   if (n < k) {  // k % 4 == 0 and n even: both positions inside or both outside
+    // (what is the same for the whole wave is decided once, outside the loops over the rows)
+    auto store_rows = [&](auto whole_c, auto stream_c) {
+      constexpr bool WHOLE = decltype(whole_c)::value, STREAM = decltype(stream_c)::value;
 #pragma unroll
-    for (int i = 0; i < WM; ++i)
+      for (int i = 0; i < WM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * (32 * WM) + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-        if (m < M) {
-          const float sc = I8W ? sx * w_scale[m] : sx;
-          const float v0 = (float)acc[i][0][r] * sc, v1 = (float)acc[i][1][r] * sc;
-          float *dst = yc + ((size_t)b * M + m) * k + n;
-          if (stream_out) {
-            floatx2 o = {v0, v1};
-            __builtin_nontemporal_store(o, reinterpret_cast<floatx2 *>(dst));
-          } else {
-            *reinterpret_cast<float2 *>(dst) = make_float2(v0, v1);
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + wm * (32 * WM) + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+          if (WHOLE || m < M) {
+            const float sc = I8W ? sx * w_scale[m] : sx;
+            const float v0 = (float)acc[i][0][r] * sc, v1 = (float)acc[i][1][r] * sc;
+            float *dst = yc + ((size_t)b * M + m) * k + n;
+            if constexpr (STREAM) {
+              floatx2 o = {v0, v1};
+              __builtin_nontemporal_store(o, reinterpret_cast<floatx2 *>(dst));
+            } else {
+              *reinterpret_cast<float2 *>(dst) = make_float2(v0, v1);
+            }
           }
         }
-      }
+    };
+    const bool whole = m0 + wm * (32 * WM) + 32 * WM <= M;
+    if (whole) {
+      if (stream_out) store_rows(std::true_type{}, std::true_type{});
+      else store_rows(std::true_type{}, std::false_type{});
+    } else {
+      if (stream_out) store_rows(std::false_type{}, std::true_type{});
+      else store_rows(std::false_type{}, std::false_type{});
+    }
   }
 }
 
