@@ -657,6 +657,9 @@ __global__ __launch_bounds__(chain_waves(SEGS) * kWave, 4 / chain_waves(SEGS)) v
         sink.at[s] = (int)sink.at[s] >= 0 ? sink.at[s] * (uint32_t)sizeof(Out) : Sink::kDropped;
       sink.vmax = 0.f;
       sink.aim(plane3, k3);
+      // (a second sink with the quantiser's division path fixed at compile time, as in
+      // haar_keep.hip, was measured here and lost: 761 vs 571 us on 96-wide planes -- this kernel
+      // is short of registers as it is)
       chain_walk<D, SEGS>(plane1, k1, n_ch, kw, cg, tile, p, first_lane, last_lane, xchg, wv,
                     sink, [&plane3, k3](Sink &sk) {
                       plane3 += k3;

@@ -149,10 +149,23 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
 #pragma unroll
     for (int s = 0; s < NS; ++s)
       sink.at[s] = (int)sink.at[s] >= 0 ? sink.at[s] * (uint32_t)sizeof(Out) : Sink::kDropped;
-    mx = walk(sink, [&plane, k, kstep](Sink &sk) {
+    auto next = [&plane, k, kstep](auto &sk) {
       plane += kstep;
       sk.aim(plane, k);
-    });
+    };
+    if constexpr (Q8) {
+      // the quantiser's division path is the same for every value of the layer: one look here
+      // instead of one a row inside the channel walk
+      if (sink.quant.fast) {
+        KeepSink<D, V, Q8, 1> fast(sink);
+        mx = walk(fast, next);
+      } else {
+        KeepSink<D, V, Q8, 2> exact(sink);
+        mx = walk(exact, next);
+      }
+    } else {
+      mx = walk(sink, next);
+    }
   }
   if (alpha_slots == nullptr) return;
 #pragma unroll

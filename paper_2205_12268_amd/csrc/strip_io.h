@@ -81,7 +81,9 @@ __device__ __forceinline__ void write_slots(float *np, const float *vals, const 
 // memory.  Also raises the alpha slots to max |kept coefficient| (nullable).
 // Q8: the clipping parameter is known beforehand (the caller supplied it), so the kept
 // coefficients leave the chip as signed 8-bit codes (Eq. quantweights) instead of fp32.
-template <int D, int V, bool Q8>
+// QF: which division the quantiser takes, 1 = the fast one, 2 = the IEEE divide (the caller has
+// looked at Quant::fast once for the whole walk), 0 = looked up row by row.
+template <int D, int V, bool Q8, int QF = 0>
 struct KeepSink {
   using Out = std::conditional_t<Q8, int8_t, float>;
   // Every slot is stored through a buffer descriptor of the channel's compressed vector, with
@@ -96,6 +98,12 @@ struct KeepSink {
   float vmax;
   Quant quant;
   __device__ __forceinline__ explicit KeepSink(float alpha) : quant(alpha) {}
+  template <int QF2>
+  __device__ __forceinline__ explicit KeepSink(const KeepSink<D, V, Q8, QF2> &o)
+      : xc_c(o.xc_c), vmax(o.vmax), quant(o.quant) {
+#pragma unroll
+    for (int s = 0; s < slot_count(D, V); ++s) at[s] = o.at[s];
+  }
   // plane: xc[b, c, :] (wave-uniform), k elements
   __device__ __forceinline__ void aim(Out *plane, int64_t k) {
     xc_c = __builtin_amdgcn_make_buffer_rsrc(plane, 0, (int)(uint32_t)(k * (int64_t)sizeof(Out)),
@@ -117,7 +125,9 @@ struct KeepSink {
           __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(int8_t)(int)quant.template level_as<FAST>(v[e]),
                                                xc_c, at[base + i * CV + e], 0, 0);
       };
-      if (quant.fast) store_codes(std::true_type{});
+      if constexpr (QF == 1) store_codes(std::true_type{});
+      else if constexpr (QF == 2) store_codes(std::false_type{});
+      else if (quant.fast) store_codes(std::true_type{});
       else store_codes(std::false_type{});
     } else {
 #pragma unroll
