@@ -71,7 +71,9 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
     sink.quant = Quant(q_alpha);
   }
   using Out = typename Sink::Out;
-  const XT *src = x + ((size_t)b * C + c0) * g.N + (size_t)row0 * g.W + col0;
+  // (lanes outside the plane read the plane's first rows: a valid address whatever the wave
+  // does with them; nothing of theirs is ever stored)
+  const XT *src = x + ((size_t)b * C + c0) * g.N + (active ? (size_t)row0 * g.W + col0 : (size_t)0);
   Out *plane = static_cast<Out *>(xc) + ((size_t)b * C + c0) * k;
   // walks the group's channels with whichever sink; returns its max |kept coefficient|
   auto walk = [&](auto &sk, auto &&next_channel) {
@@ -103,7 +105,9 @@ __global__ __launch_bounds__(256) void haar_keep_kernel(const XT *__restrict__ x
 #pragma unroll
     for (int s = 0; s < NS; ++s) count += __popcll(__ballot((int)sink.at[s] >= 0));
     const int ni = (count + kWave - 1) / kWave;
-    const bool whole = __ballot(active) == ~(uint64_t)0;  // (a ragged wave takes the plain path)
+    // a wave with lanes outside the plane may stage too (their slots are in no list), except
+    // with K_dw folded in, whose border handling counts on the lanes' own columns
+    const bool whole = DWM == 0 ? __ballot(active) != 0 : __ballot(active) == ~(uint64_t)0;
     if (whole && n_ch > 0 && ni <= NS / 2 && ni <= 16 && k <= ((int64_t)1 << kRankBits)) {
       const int lane = threadIdx.x & (kWave - 1);
       uint32_t *tile = tiles[threadIdx.x >> 6];
