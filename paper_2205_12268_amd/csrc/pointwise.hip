@@ -54,31 +54,23 @@ template <bool F32, int CPT>
 struct Patch {
   float4 f[F32 ? CPT : 1];
   uint32_t c[F32 ? 1 : CPT];
-  // xp: this thread's position in channel c0 (an element pointer); n_in: the position exists
-  __device__ __forceinline__ void load(const void *__restrict__ xp, int K, int64_t k, int c0,
-                                       bool n_in) {
-#pragma unroll
-    for (int r = 0; r < CPT; ++r) {
-      const bool in = n_in && c0 + r < K;
-      if constexpr (F32) {
-        f[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (in) f[r] = *reinterpret_cast<const float4 *>(static_cast<const float *>(xp) + r * k);
-      } else {
-        c[r] = 0;
-        if (in) c[r] = *reinterpret_cast<const uint32_t *>(static_cast<const int8_t *>(xp) + r * k);
-      }
-    }
-  }
-  // int8 codes through a buffer descriptor of the sample's compressed signal: off is the byte
+  // Loaded through a buffer descriptor of the sample's compressed signal: off is the byte
   // offset of this thread's four positions in the patch's first channel.  No branch, no lane
   // mask: a load never faults (outside the buffer it returns zeros, a wrapped offset lands
-  // inside it); what it returns for channels >= C_in meets zero weights, and for positions >= k
-  // it feeds columns that are never stored.
+  // inside it); what it returns for channels >= C_in meets zero weights (any finite value will
+  // do: fp32 coefficients are clipped by the quantiser, and a NaN quantises to a finite level),
+  // and for positions >= k it feeds columns that are never stored.
   __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t xdesc, uint32_t off, int64_t k) {
-    static_assert(!F32, "codes only");
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int r = 0; r < CPT; ++r)
-      c[r] = __builtin_amdgcn_raw_buffer_load_b32(xdesc, off + (uint32_t)r * (uint32_t)k, 0, 0);
+    for (int r = 0; r < CPT; ++r) {
+      if constexpr (F32) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(xdesc, off + (uint32_t)r * (uint32_t)k * 4u, 0, 0);
+        f[r] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+      } else {
+        c[r] = __builtin_amdgcn_raw_buffer_load_b32(xdesc, off + (uint32_t)r * (uint32_t)k, 0, 0);
+      }
+    }
   }
   // level of channel r, position i, as a float holding an integer in [-127, 127]
   template <bool FAST>
@@ -120,15 +112,15 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
 
   const float al = load_alpha(alpha, n_alpha, alpha_out);
   const Quant quant(al);
-  // With int8 codes both operands are loaded through buffer descriptors (the host has checked
-  // that their byte offsets fit 32 bits): weights of rows >= M lie beyond the end and come back
+  // Both operands are loaded through buffer descriptors (the host has checked that their byte
+  // offsets fit 32 bits): weights of rows >= M lie beyond the end and come back
   // as zeros, those of channels >= C_in are sent there by a wave-uniform choice.
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   constexpr uint32_t kOutside = 0xFFFFFFF0u;
   const __amdgpu_buffer_rsrc_t wdesc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<unsigned char *>(wb), 0, (int)(uint32_t)((int64_t)M * K * ESZ), 0x00020000);
   const __amdgpu_buffer_rsrc_t xdesc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<void *>(xb), 0, (int)(uint32_t)((int64_t)K * k), 0x00020000);
+      const_cast<void *>(xb), 0, (int)(uint32_t)((int64_t)K * k * (F32 ? 4 : 1)), 0x00020000);
   // A workgroup takes the row tiles blockIdx.y, blockIdx.y + gridDim.y, ...: with one workgroup
   // per column tile (gridDim.y = 1) the stores of a row tile drain while the next one is being
   // computed, instead of holding the compute unit until they are out.
@@ -148,15 +140,9 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
 #pragma unroll
     for (int q = 0; q < APT; ++q) {
       const int kk = kc * BK + (a_half * (BK / 2)) + q * (16 / ESZ);  // first element of the load
-      if constexpr (!F32) {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(
-            wdesc, kk < K ? (uint32_t)(m0 + a_row) * (uint32_t)(K * ESZ) + (uint32_t)kk * ESZ : kOutside, 0, 0);
-        wreg[q] = make_uint4(v.x, v.y, v.z, v.w);
-      } else {
-        wreg[q] = make_uint4(0, 0, 0, 0);
-        if (m0 + a_row < M && kk < K)
-          wreg[q] = *reinterpret_cast<const uint4 *>(wb + ((size_t)(m0 + a_row) * K + kk) * ESZ);
-      }
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(
+          wdesc, kk < K ? (uint32_t)(m0 + a_row) * (uint32_t)(K * ESZ) + (uint32_t)kk * ESZ : kOutside, 0, 0);
+      wreg[q] = make_uint4(v.x, v.y, v.z, v.w);
     }
   };
 
@@ -198,12 +184,10 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
   };
 
   // this thread's four positions in channel kq * CPT of chunk 0
-  const bool n_in = n0 + 4 * g < k;
-  const char *xp = static_cast<const char *>(xb) + ((size_t)(kq * CPT) * k + n0 + 4 * g) * (F32 ? 4 : 1);
-  const uint32_t xoff = (uint32_t)(kq * CPT) * (uint32_t)k + (uint32_t)(n0 + 4 * g);
+  constexpr uint32_t XB = F32 ? 4u : 1u;  // bytes of an activation
+  const uint32_t xoff = ((uint32_t)(kq * CPT) * (uint32_t)k + (uint32_t)(n0 + 4 * g)) * XB;
   load_w(0);
-  if constexpr (F32) raw.load(xp, K, k, kq * CPT, n_in);
-  else raw.load(xdesc, xoff, k);
+  raw.load(xdesc, xoff, k);
   for (int kc = 0; kc < nchunks; ++kc) {
     {
       if (quant.fast) stage_patch(raw, quant, std::true_type{});
@@ -213,15 +197,9 @@ __global__ __launch_bounds__(2 * BM) void pointwise_mfma_kernel(
         *reinterpret_cast<uint4 *>(&As[a_row * LDR + a_half * (BK / 2) * ESZ + q * 16]) = wreg[q];
       __syncthreads();
       // both register tiles are in LDS now: the next chunk travels while this one is multiplied
-      if constexpr (F32) {
-        if (kc + 1 < nchunks) {
-          load_w(kc + 1);
-          raw.load(xp + (size_t)(kc + 1) * BK * k * 4, K, k, (kc + 1) * BK + kq * CPT, n_in);
-        }
-      } else {  // (past the last chunk: zeros and values nobody uses, no memory traffic to speak of)
-        load_w(kc + 1);
-        raw.load(xdesc, xoff + (uint32_t)((kc + 1) * BK) * (uint32_t)k, k);
-      }
+      // (past the last chunk: zeros and values nobody uses, no memory traffic to speak of)
+      load_w(kc + 1);
+      raw.load(xdesc, xoff + (uint32_t)((kc + 1) * BK) * (uint32_t)k * XB, k);
       const int fr = lane & 31, half = lane >> 5;
       if constexpr (I8W) {
 #pragma unroll
@@ -714,10 +692,10 @@ hipError_t launch_pointwise(const wcc_desc &d, int64_t k, const void *w, const f
                             float *alpha_out, float *yc, hipStream_t s) {
   const bool quant = d.act_quant_bits == 8;
   const int K = d.C_in;
-  // the matrix-core kernels address int8 codes and their weights with 32-bit byte offsets
+  // the matrix-core kernels address the activations and the weights with 32-bit byte offsets
   // (4 GB of weights or of one sample's compressed signal take the plain kernel below)
   const int64_t limit = (int64_t)0xFFFFFFF0;
-  const bool narrow = xc_is_f32 || ((int64_t)(d.C_out + 256) * K * 2 <= limit && (int64_t)K * k <= limit);
+  const bool narrow = (int64_t)(d.C_out + 256) * K * 2 <= limit && (int64_t)K * k * (xc_is_f32 ? 4 : 1) <= limit;
   if (!narrow) {
   } else if (quant && d.w_dtype == WCC_BF16 && K % 8 == 0 && k % 4 == 0)
     return mfma_dispatch<false>(d, k, w, w_scale, xc, xc_is_f32, alpha, n_alpha, alpha_out, yc, s);
