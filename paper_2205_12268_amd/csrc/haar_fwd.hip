@@ -236,7 +236,7 @@ hipError_t fwd_launch(const wcc_desc &d, const void *x, float *coef, float *norm
 // groups only pay when a layer has fewer strips than that.
 int forward_groups(const wcc_desc &d, int front) {
   const bool busy = front == kFrontChain || arithmetic_bound(d, front == kFrontDw);
-  return groups_for(d, d.C_in, busy ? 4096 : 1024, 16);
+  return groups_for(d, d.C_in, busy ? 4096 : 1024, 4);
 }
 
 template <bool STORE>

@@ -294,7 +294,7 @@ hipError_t inv_dispatch(const wcc_desc &d, int64_t k, const float *yc, const int
 
 hipError_t launch_scatter_ihaar(const wcc_desc &d, int64_t k, const float *yc, const int32_t *jmap,
                                 void *y, float *scratch, const void *residual, hipStream_t s) {
-  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 4096, 8), scratch, residual, s);
+  return inv_dispatch(d, k, yc, jmap, y, groups_for(d, d.C_out, 4096, 4), scratch, residual, s);
 }
 
 }  // namespace wcc

@@ -259,7 +259,7 @@ hipError_t keep_dispatch(const wcc_desc &d, int64_t k, const void *x, const int3
 hipError_t launch_haar_keep(const wcc_desc &d, int64_t k, const void *x, const int32_t *jmap,
                             void *xc, float *alpha_slots, const float *wdw, float q_alpha,
                             const float *alpha_src, int n_alpha, float *alpha_pub, hipStream_t s) {
-  const Plan pl{groups_for(d, d.C_in, arithmetic_bound(d, wdw != nullptr) ? 4096 : 1024, 8), false,
+  const Plan pl{groups_for(d, d.C_in, arithmetic_bound(d, wdw != nullptr) ? 4096 : 1024, 4), false,
                 streams(d)};
   return keep_dispatch(d, k, x, jmap, xc, alpha_slots, pl, wdw, q_alpha, alpha_src, n_alpha, alpha_pub, s);
 }
