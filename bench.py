@@ -69,6 +69,18 @@ def read_profile_column(profile_dir: str, prefix: str, workload: str, kernel: st
     return None
 
 
+def profiled_kernel_name(profile_dir: str, workload: str, prefix: str, default: str) -> str:
+    """Name (without template arguments) of the first kernel starting with `prefix` in the
+    committed `kernel_stats_<workload>.txt`: the library picks between two contraction
+    kernels by shape, and the profile says which one ran."""
+    path = os.path.join(profile_dir, f"kernel_stats_{workload}.txt")
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith(prefix):
+                return line.split()[0].split("<")[0]
+    return default
+
+
 def read_traffic(profile_dir: str, workload: str, kernel: str):
     """HBM bytes per launch of `kernel` (fetch + write, each scaled by the copy-kernel
     calibration) from the committed rocprofv3 counter summary, or None."""
@@ -624,11 +636,12 @@ def main() -> int:
         # the contraction against the matrix-core peak of its operand type, and the counter's
         # own reading of how busy the matrix cores were (profiles/sq_counters_*.txt); the stage
         # is bound by HBM at these shapes, so its HBM fraction stands beside it
-        "mfma": {"kernel": "pointwise_mfma_kernel", "flops": flops,
+        "mfma": {"kernel": profiled_kernel_name(prof, cfg.name, "pointwise_",
+                                                "pointwise_mfma_kernel"), "flops": flops,
                  "achieved_tflops": round(gemm_tflops, 2), "peak_tflops": MFMA_PEAK_TFLOPS[wname],
                  "frac": round(gemm_tflops / MFMA_PEAK_TFLOPS[wname], 4),
                  "busy_frac_counter": read_profile_column(prof, "sq_counters", cfg.name,
-                                                          "pointwise_mfma_kernel", -1),
+                                                          "pointwise_", -1),
                  "arithmetic_intensity_flop_per_byte": round(flops / alg["pointwise"], 1),
                  "frac_of_hbm_peak": round(alg["pointwise"] / (stage_us["pointwise"] * 1e-6) / 1e9
                                            / HBM_PEAK_GBS, 4)},
