@@ -6,7 +6,8 @@ The shapes are chosen to reach that kernel (C_in >= 256, C_out >= 128, at least 
 not a wide expansion of few channels)
 and to walk its edges: a last stage with fewer channels than a stage holds, output rows that
 end inside the second and inside the third tile, a last column tile of four positions, both weight
-types, one and several samples, and a shape whose tiles are all full.  With int8 weights the
+types, one and several samples, and a shape whose tiles are all full.  A second list of shapes
+takes the stream kernel with one workgroup walking all row tiles of its column tile.  With int8 weights the
 sums are exact integers on both sides, so the comparison is to fp32 rounding of the scales;
 with bf16 weights the products are exact and only the fp32 accumulation rounds.
 """
@@ -28,9 +29,20 @@ CASES = [
     ("bf16_many_tiles", 4, 264, 300, 128, 512, 4097, 16384, synth.W_BF16),  # 1548 tiles in the natural order (small weights)
     ("i8_big_weights", 2, 1040, 1100, 64, 512, 2051, 8192, synth.W_I8),     # weights over 1 MB: tiles dealt to the dies in chunks, grid padded to a multiple of 8
 ]
+# The stream kernel where one workgroup walks all row tiles of its column tile (512 column tiles
+# or more; shapes that are not the kernel above's): one to five row tiles, a last row tile that is
+# ragged, two to five chunks of channels, both weight types, an output that is streamed past the
+# caches (over 512 MB).
+WALK_CASES = [
+    ("bf16_walk_4chunks", 4, 200, 384, 128, 512, 1, 4, synth.W_BF16),
+    ("i8_walk_2chunks_ragged_rows", 8, 128, 300, 64, 512, 1, 4, synth.W_I8),
+    ("bf16_walk_expansion_streamed", 9, 256, 1024, 128, 512, 1, 4, synth.W_BF16),   # 604 MB of output
+    ("i8_walk_5chunks", 4, 272, 1100, 128, 512, 1, 4, synth.W_I8),
+    ("bf16_walk_3chunks_two_tiles", 16, 136, 136, 64, 256, 1, 4, synth.W_BF16),
+]
 
 
-@pytest.mark.parametrize("case", CASES, ids=lambda c: c[0])
+@pytest.mark.parametrize("case", CASES + WALK_CASES, ids=lambda c: c[0])
 def test_arithmetic_bound_contraction_matches_oracle(ref, case):
     name, B, Ci, Co, H, W, num, den, wd_t = case
     cfg = synth.LayerCfg(name, B, Ci, Co, H, W, 3, num, den, wd_t, 8,
