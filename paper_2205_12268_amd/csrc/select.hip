@@ -249,7 +249,9 @@ __device__ __forceinline__ void current_state(const uint32_t *hist_b, SelectStat
 // PASS 0 with REDUCE reads partial norms `src` [G, B, N] and writes `norm`; otherwise src is
 // the norm array itself.  PASS 2 also writes this workgroup's suffix sums and its count of
 // keys above the 22-bit prefix.
-template <int PASS, bool REDUCE>
+// SLOTS: 16-byte loads per thread (a workgroup takes 1024 * SLOTS keys; slot s of thread t
+// covers the four positions from (s * 256 + t) * 4 on inside the workgroup's chunk).
+template <int PASS, bool REDUCE, int SLOTS>
 __global__ __launch_bounds__(kThreads) void select_hist_kernel(const float *__restrict__ src,
                                                                float *__restrict__ norm, int G,
                                                                int64_t N, int B, uint32_t k,
@@ -267,19 +269,27 @@ __global__ __launch_bounds__(kThreads) void select_hist_kernel(const float *__re
 
   for (int i = t; i < bins; i += kThreads) lh[i] = 0;
   // the keys do not depend on the digit picked below: their load travels under it
-  const int64_t q0 = (int64_t)blockIdx.x * kSelectChunk + (int64_t)t * kPer;
-  const bool in = q0 < N;  // N is a multiple of 4: a thread's four keys are all in or all out
-  uint4 k4 = make_uint4(0, 0, 0, 0);
-  if (in) k4 = load_keys<REDUCE>(src, norm, G, (int64_t)B * N, (int64_t)b * N + q0);
+  const int64_t q0 = (int64_t)blockIdx.x * (kSelectChunk * SLOTS) + (int64_t)t * kPer;
+  uint4 k4[SLOTS];
+#pragma unroll
+  for (int sl = 0; sl < SLOTS; ++sl) {
+    const int64_t q = q0 + (int64_t)sl * kSelectChunk;
+    k4[sl] = make_uint4(0, 0, 0, 0);  // N is a multiple of 4: a slot's four keys are all in or all out
+    if (q < N) k4[sl] = load_keys<REDUCE>(src, norm, G, (int64_t)B * N, (int64_t)b * N + q);
+  }
   uint32_t prefix, remain;
   current_state<PASS>(hist_b, st + b, k, prefix, remain, tmp, bcast, blockIdx.x == 0);
   __syncthreads();
-  const uint32_t key[4] = {k4.x, k4.y, k4.z, k4.w};
   uint32_t above = 0;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    hist_add(lh, digit_of(key[e], PASS), in && matches(key[e], prefix, PASS));
-    if (PASS == 2) above += (in && (key[e] >> 10) > (prefix >> 10)) ? 1u : 0u;
+  for (int sl = 0; sl < SLOTS; ++sl) {
+    const bool in = q0 + (int64_t)sl * kSelectChunk < N;
+    const uint32_t key[4] = {k4[sl].x, k4[sl].y, k4[sl].z, k4[sl].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      hist_add(lh, digit_of(key[e], PASS), in && matches(key[e], prefix, PASS));
+      if (PASS == 2) above += (in && (key[e] >> 10) > (prefix >> 10)) ? 1u : 0u;
+    }
   }
   __syncthreads();
   for (int i = t; i < bins; i += kThreads) {
@@ -312,6 +322,7 @@ __global__ __launch_bounds__(kThreads) void select_hist_kernel(const float *__re
 // |coefficient| over the channels at every position; its maximum over the positions this
 // workgroup keeps goes to block_top[b, blockIdx.x] (the largest of those is the layer's clipping
 // parameter alpha).
+template <int SLOTS>
 __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__restrict__ norm,
                                                                int64_t N, int64_t k,
                                                                const uint32_t *__restrict__ hist,
@@ -327,12 +338,19 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__re
   const int b = blockIdx.y, t = threadIdx.x;
   const uint32_t *keys = reinterpret_cast<const uint32_t *>(norm) + (size_t)b * N;
   // (the keys do not depend on the threshold: their load travels under its computation)
-  const int64_t q0 = (int64_t)blockIdx.x * kSelectChunk + (int64_t)t * kPer;
-  const bool in = q0 < N;
-  uint4 k4 = make_uint4(0, 0, 0, 0);
-  if (in) k4 = *reinterpret_cast<const uint4 *>(keys + q0);
-  float4 top4 = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (in && top_part) top4 = load_top(top_part, G, (int64_t)B * N, (int64_t)b * N + q0);
+  const int64_t q0 = (int64_t)blockIdx.x * (kSelectChunk * SLOTS) + (int64_t)t * kPer;
+  uint4 k4[SLOTS];
+  float4 top4[SLOTS];
+#pragma unroll
+  for (int sl = 0; sl < SLOTS; ++sl) {
+    const int64_t q = q0 + (int64_t)sl * kSelectChunk;
+    k4[sl] = make_uint4(0, 0, 0, 0);
+    top4[sl] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (q < N) {
+      k4[sl] = *reinterpret_cast<const uint4 *>(keys + q);
+      if (top_part) top4[sl] = load_top(top_part, G, (int64_t)B * N, (int64_t)b * N + q);
+    }
+  }
   uint32_t T, r_take;  // threshold key, and how many keys equal to it are still needed
   current_state<3>(hist + (size_t)b * 3 * kRadixBins, st + b, (uint32_t)k, T, r_take, tmp, bcast,
                    blockIdx.x == 0);
@@ -350,30 +368,44 @@ __global__ __launch_bounds__(kThreads) void select_emit_kernel(const float *__re
   gt0 = block_sum(gt0, tmp);
   eq0 = block_sum(eq0, tmp);
 
-  const uint32_t key[4] = {k4.x, k4.y, k4.z, k4.w};
-  uint32_t packed = 0;  // hi16: keys above T, lo16: keys equal to T (each <= 1024 a workgroup)
-#pragma unroll
-  for (int e = 0; e < 4; ++e)
-    if (in) packed += ((key[e] > T) << 16) + (key[e] == T);
-  const uint32_t ex = block_exclusive_scan(packed, tmp);
-  uint32_t gt = gt0 + (ex >> 16), eq = eq0 + (ex & 0xFFFFu);
-
+  // Position order inside the workgroup's chunk is slot by slot, thread by thread: one block
+  // scan a slot, on top of the totals of the slots before it.  Counts are packed
+  // hi16: keys above T, lo16: keys equal to T (each <= 4096 a workgroup).
   float kept_top = 0.f;
-  if (in) {
-    int32_t *out = idx + (size_t)b * k;
-    const float top[4] = {top4.x, top4.y, top4.z, top4.w};
-    int32_t jm[4];
+  int32_t *out = idx + (size_t)b * k;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const bool is_gt = key[e] > T, is_eq = key[e] == T;
-      const bool keep = is_gt || (is_eq && eq < r_take);
-      const uint32_t j = gt + min(eq, r_take);
-      if (keep) out[j] = (int32_t)(q0 + e);
-      jm[e] = keep ? (int32_t)j : -1;
-      kept_top = fmaxf(kept_top, keep ? top[e] : 0.f);
-      gt += is_gt; eq += is_eq;
+  for (int sl = 0; sl < SLOTS; ++sl) {
+    const int64_t q = q0 + (int64_t)sl * kSelectChunk;
+    const bool in = q < N;
+    const uint32_t key[4] = {k4[sl].x, k4[sl].y, k4[sl].z, k4[sl].w};
+    uint32_t packed = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (in) packed += ((key[e] > T) << 16) + (key[e] == T);
+    const uint32_t ex = block_exclusive_scan(packed, tmp);
+    uint32_t gt = gt0 + (ex >> 16), eq = eq0 + (ex & 0xFFFFu);
+    if (SLOTS > 1) {  // the slot's totals (tmp holds the waves' inclusive sums until the next scan)
+      uint32_t tot = 0;
+#pragma unroll
+      for (int i = 0; i < kWaves; ++i) tot += tmp[i];
+      gt0 += tot >> 16;
+      eq0 += tot & 0xFFFFu;
     }
-    if (jmap) *reinterpret_cast<int4 *>(jmap + (size_t)b * N + q0) = make_int4(jm[0], jm[1], jm[2], jm[3]);
+    if (in) {
+      const float top[4] = {top4[sl].x, top4[sl].y, top4[sl].z, top4[sl].w};
+      int32_t jm[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool is_gt = key[e] > T, is_eq = key[e] == T;
+        const bool keep = is_gt || (is_eq && eq < r_take);
+        const uint32_t j = gt + min(eq, r_take);
+        if (keep) out[j] = (int32_t)(q + e);
+        jm[e] = keep ? (int32_t)j : -1;
+        kept_top = fmaxf(kept_top, keep ? top[e] : 0.f);
+        gt += is_gt; eq += is_eq;
+      }
+      if (jmap) *reinterpret_cast<int4 *>(jmap + (size_t)b * N + q) = make_int4(jm[0], jm[1], jm[2], jm[3]);
+    }
   }
   if (top_part)  // (uniform over the grid)
     publish_top<kWaves>(kept_top, block_top, (size_t)b * nblk + blockIdx.x, tmp);
@@ -623,6 +655,33 @@ hipError_t launch_select_init(const SelectPrep &p, int B, hipStream_t s) {
   return hipGetLastError();
 }
 
+// the three histogram passes and the compaction, SLOTS 16-byte loads a thread
+template <int SLOTS>
+static hipError_t launch_passes(const wcc_desc &d, const float *norm_or_part, int G, float *norm_out,
+                                int64_t k, uint32_t *hist, SelectState *st, uint16_t *sfx,
+                                uint32_t *gthi, int nblk, int32_t *idx, int32_t *jmap,
+                                float *top_part, float *block_top, hipStream_t s) {
+  const int64_t N = (int64_t)d.H * d.W;
+  const uint32_t k32 = (uint32_t)k;
+  dim3 grid(nblk, d.B), block(kThreads);
+  const float *norm = norm_or_part;
+  if (G > 1) {
+    hipLaunchKernelGGL((select_hist_kernel<0, true, SLOTS>), grid, block, 0, s, norm_or_part, norm_out,
+                       G, N, d.B, k32, hist, st, nblk, sfx, gthi);
+    norm = norm_out;
+  } else {
+    hipLaunchKernelGGL((select_hist_kernel<0, false, SLOTS>), grid, block, 0, s, norm, nullptr, 1, N,
+                       d.B, k32, hist, st, nblk, sfx, gthi);
+  }
+  hipLaunchKernelGGL((select_hist_kernel<1, false, SLOTS>), grid, block, 0, s, norm, nullptr, 1, N, d.B,
+                     k32, hist, st, nblk, sfx, gthi);
+  hipLaunchKernelGGL((select_hist_kernel<2, false, SLOTS>), grid, block, 0, s, norm, nullptr, 1, N, d.B,
+                     k32, hist, st, nblk, sfx, gthi);
+  hipLaunchKernelGGL((select_emit_kernel<SLOTS>), grid, block, 0, s, norm, N, k, hist, st, sfx, gthi,
+                     nblk, idx, jmap, top_part, G, d.B, block_top);
+  return hipGetLastError();
+}
+
 hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, float *norm_out,
                          int64_t k, void *ws_base, const WsLayout &L, int32_t *idx, int32_t *jmap,
                          float *top_part, float *block_top, hipStream_t s) {
@@ -649,23 +708,11 @@ hipError_t launch_select(const wcc_desc &d, const float *norm_or_part, int G, fl
                          norm_or_part, nullptr, 1, N, d.B, k32, slots, idx, jmap, top_part, block_top);
     return hipGetLastError();
   }
-  dim3 grid(nblk, d.B), block(kThreads);
-  const float *norm = norm_or_part;
-  if (G > 1) {
-    hipLaunchKernelGGL((select_hist_kernel<0, true>), grid, block, 0, s, norm_or_part, norm_out, G, N,
-                       d.B, k32, hist, st, nblk, sfx, gthi);
-    norm = norm_out;
-  } else {
-    hipLaunchKernelGGL((select_hist_kernel<0, false>), grid, block, 0, s, norm, nullptr, 1, N, d.B,
-                       k32, hist, st, nblk, sfx, gthi);
+  switch (L.sel_slots) {
+    case 4: return launch_passes<4>(d, norm_or_part, G, norm_out, k, hist, st, sfx, gthi, nblk, idx, jmap, top_part, block_top, s);
+    case 2: return launch_passes<2>(d, norm_or_part, G, norm_out, k, hist, st, sfx, gthi, nblk, idx, jmap, top_part, block_top, s);
+    default: return launch_passes<1>(d, norm_or_part, G, norm_out, k, hist, st, sfx, gthi, nblk, idx, jmap, top_part, block_top, s);
   }
-  hipLaunchKernelGGL((select_hist_kernel<1, false>), grid, block, 0, s, norm, nullptr, 1, N, d.B, k32,
-                     hist, st, nblk, sfx, gthi);
-  hipLaunchKernelGGL((select_hist_kernel<2, false>), grid, block, 0, s, norm, nullptr, 1, N, d.B, k32,
-                     hist, st, nblk, sfx, gthi);
-  hipLaunchKernelGGL(select_emit_kernel, grid, block, 0, s, norm, N, k, hist, st, sfx, gthi, nblk, idx,
-                     jmap, top_part, G, d.B, block_top);
-  return hipGetLastError();
 }
 
 hipError_t launch_jmap_from_idx(const int32_t *idx, int B, int64_t N, int64_t k, int32_t *jmap,

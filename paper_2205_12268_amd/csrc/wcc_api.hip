@@ -100,11 +100,21 @@ wcc_status need_ws(const wcc_ctx *ctx, const WsLayout &L) {
 
 }  // namespace
 
+// fewest select workgroups a launch should have (two a compute unit: with fewer the passes
+// get slower again: measured at 256 and 480 workgroups)
+constexpr size_t kSelectMinBlocks = 512;
+
 WsLayout ws_layout(const wcc_desc &d, int front) {
   WsLayout L{};
   const size_t N = (size_t)d.H * d.W, B = d.B, k = (size_t)k_of(d);
   L.G = forward_groups(d, front);
-  L.nblk = (int)((N + kSelectChunk - 1) / kSelectChunk);
+  // select workgroups take 1024, 2048 or 4096 keys: the most that still leaves kSelectMinBlocks
+  // of them (fewer, fatter workgroups merge fewer histograms and read the previous pass's
+  // histogram less often)
+  L.sel_slots = 1;
+  for (int sl = 4; sl > 1; sl /= 2)
+    if ((N + (size_t)kSelectChunk * sl - 1) / ((size_t)kSelectChunk * sl) * B >= kSelectMinBlocks) { L.sel_slots = sl; break; }
+  L.nblk = (int)((N + (size_t)kSelectChunk * L.sel_slots - 1) / ((size_t)kSelectChunk * L.sel_slots));
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
   L.norm_part = take((size_t)L.G * B * N * 4);

@@ -13,7 +13,7 @@ constexpr int kWave = 64;          // CDNA wavefront width
 using bf16_t = uint16_t;           // a bf16 bit pattern in memory
 constexpr int kMaxLevels = 4;      // register-resident strip transform up to 16 rows per lane
 constexpr int kRadixBins = 2048;   // 11 + 11 + 10 bit radix select
-constexpr int kSelectChunk = 1024; // keys per workgroup in the select kernels
+constexpr int kSelectChunk = 1024; // keys a select workgroup takes with one 16-byte load a thread
 constexpr int kSfxStride = 1024;   // per-workgroup suffix sums of the low-digit histogram
 constexpr int kAlphaSlots = 64;    // max|kept c| is reduced into this many slots, then combined
 constexpr int kInvScratchBytes = 1024;  // one 16-byte line per lane for stores that must go nowhere
@@ -47,6 +47,7 @@ struct WsLayout {
   size_t total;
   int G;              // channel groups of the forward transform
   int nblk;           // select workgroups per sample
+  int sel_slots;      // 16-byte loads per thread in the select kernels: 1, 2 or 4
 };
 
 struct SelectState {

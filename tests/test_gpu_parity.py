@@ -199,6 +199,35 @@ def test_random_norms_all_bit_patterns(ref, ctx, W):
     np.testing.assert_array_equal(idx.cpu().numpy().astype(np.int64), ref.topk(norm, k))
 
 
+# Planes of 512 x 1024 positions: with 2 samples a select workgroup takes 2048 keys (two 16-byte
+# loads a thread), with 4 samples 4096 (four) -- the ordered compaction then runs one block scan
+# per load on top of the totals of the loads before it.
+@pytest.mark.parametrize("B", [2, 4])
+@pytest.mark.parametrize("kind", ["constant", "two_tie_classes", "bit_patterns"])
+def test_selection_with_several_loads_per_thread(ref, ctx, kind, B):
+    H, W = 512, 1024
+    N, k = H * W, 70001
+    d = wcc.make_desc(B, 4, 4, H, W, 1, k, N, wcc.F32, 0)
+    assert wcc.k_of(d) == k
+    ctx.ensure_workspace(d)
+    rng = np.random.default_rng(1234 + B)
+    if kind == "constant":
+        norm = np.full((B, N), 0.75, dtype=np.float32)
+    elif kind == "two_tie_classes":
+        norm = np.zeros((B, N), dtype=np.float32)
+        norm[:, rng.choice(N, 40000, replace=False)] = 2.0   # all taken
+        free = np.flatnonzero(norm[0] == 0)
+        norm[:, rng.choice(free, 90000, replace=False)] = 0.25   # the class that straddles k
+    else:
+        bits = rng.integers(0, 0x7F000000, size=(B, N), dtype=np.int64).astype(np.uint32)
+        bits[1] = (0x3F800000 + rng.integers(0, 64, N)).astype(np.uint32)   # a narrow band around 1.0
+        bits[0, ::3] = rng.integers(0, 200, size=len(bits[0, ::3])).astype(np.uint32)  # denormals
+        norm = bits.view(np.float32)
+    idx = torch.full((B, k), -7, dtype=torch.int32, device="cuda")
+    ctx.wcc_joint_topk(d, None, dev(norm), idx)
+    np.testing.assert_array_equal(idx.cpu().numpy().astype(np.int64), ref.topk(norm, k))
+
+
 def test_all_zero_input_gives_zero_alpha_and_output(ref, ctx):
     cfg = case("zero_in", 1, 8, 8, 16, 32, 2, 1, 4, BF16, 8)
     _, w = synth.make_inputs(cfg)
