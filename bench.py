@@ -228,8 +228,12 @@ def time_block(cfg, args, synth, wcc, torch, np, dense: bool) -> dict:
         xd = xd.to(torch.bfloat16)
     y = torch.empty_like(xd)
 
+    # (int8 weight codes come with a scale per output channel)
+    s1d = None if w1.scale is None else up(w1.scale.astype(np.float32))
+    s3d = None if w3.scale is None else up(w3.scale.astype(np.float32))
+
     def step():
-        ctx.wcc_block_forward(d, xd, w1d, None, wdd, w3d, None, y)
+        ctx.wcc_block_forward(d, xd, w1d, s1d, wdd, w3d, s3d, y)
 
     if args.copy_probe:  # a plain copy of known size, for scaling the traffic counters
         probe = torch.empty_like(xd)
@@ -303,18 +307,19 @@ def time_block(cfg, args, synth, wcc, torch, np, dense: bool) -> dict:
             "chained": chained, "dense_ms": dense_ms, "dense_fair_ms": dense_fair_ms, "bf16": bf16}
 
 
-def block_from_shape(synth, shape: str, num: int, den: int):
+def block_from_shape(synth, shape: str, num: int, den: int, weights: str = "bf16"):
     """--shape SIDE,c,e,B or HxW,c,e,B -> a block of the paper's kind (3 levels, 8-bit codes)."""
     side, c, e, B = shape.split(",")
     H, W = (int(t) for t in side.split("x")) if "x" in side else (int(side), int(side))
-    return synth.block_shape(H, W, int(c), int(e), int(B), num, den)
+    return synth.block_shape(H, W, int(c), int(e), int(B), num, den,
+                             synth.W_I8 if weights == "i8" else synth.W_BF16)
 
 
 def bench_block(args, synth, wcc, torch, np) -> int:
     """The inverted residual block the paper timed (appendix "Inference times"): by default
     256x256 image, c_in 256, expansion 4, batch 8, one row of its table per keep ratio."""
     num, den = (int(t) for t in args.keep.split("/"))
-    cfg = block_from_shape(synth, args.shape, num, den) if args.shape else synth.block_config(num, den)
+    cfg = block_from_shape(synth, args.shape or "256,256,4,8", num, den, args.weights)
     r = time_block(cfg, args, synth, wcc, torch, np, dense=not args.no_dense_baseline)
     dt, stage_us, chained, bf16 = r["dt"], r["stage_us"], r["chained"], r["bf16"]
     dense_ms, dense_fair_ms = r["dense_ms"], r["dense_fair_ms"]
@@ -345,11 +350,12 @@ def bench_block(args, synth, wcc, torch, np) -> int:
                 "traffic": traffic, "algorithmic_bytes": alg[dom], "kernel_us": round(stage_us[dom], 2),
                 "profile_avg_us": prof_us}
     pix_ch = cfg.B * cfg.N * cfg.C
+    wname = "int8" if cfg.w_dtype == synth.W_I8 else "bf16"  # operand type of the two contractions
     out = {
         "metric": "WCC layer forward throughput", "value": round(pix_ch / dt / 1e9, 3),
         "unit": "Gpixel*ch/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(dt * 1e3, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": "eager",
+        "vs_baseline": None, "dtype": wname, "data": "synthetic", "launch": "eager",
         "config": {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "expansion": cfg.expansion,
                    "H": cfg.H, "W": cfg.W, "levels": cfg.levels, "keep": f"{num}/{den}",
                    "act_bits": cfg.act_bits, "act": args.act, "norm": args.norm,
@@ -359,14 +365,14 @@ def bench_block(args, synth, wcc, torch, np) -> int:
         "stages_frac_of_hbm_peak": {n: round(alg[n] / (stage_us[n] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
                                     for n in stage_us if stage_us[n] > 0 and alg.get(n)},
         "block_alg_GBs": round(sum(alg.values()) / dt / 1e9, 1),
-        # the two contractions against the matrix-core peak of their operand type (bf16 weights)
+        # the two contractions against the matrix-core peak of their operand type
         "mfma": {f"l{layer}_pointwise": {
             "flops": 2.0 * cfg.B * cfg.k * cfg.layer(layer).C_in * cfg.layer(layer).C_out,
             "achieved_tflops": round(2.0 * cfg.B * cfg.k * cfg.layer(layer).C_in * cfg.layer(layer).C_out
                                      / (stage_us[f"l{layer}_pointwise"] * 1e-6) / 1e12, 1),
-            "peak_tflops": MFMA_PEAK_TFLOPS["bf16"],
+            "peak_tflops": MFMA_PEAK_TFLOPS[wname],
             "frac": round(2.0 * cfg.B * cfg.k * cfg.layer(layer).C_in * cfg.layer(layer).C_out
-                          / (stage_us[f"l{layer}_pointwise"] * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4)}
+                          / (stage_us[f"l{layer}_pointwise"] * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS[wname], 4)}
             for layer in (0, 1) if stage_us.get(f"l{layer}_pointwise", 0) > 0},
         "dense_block_ms": {"framework_bf16": None if dense_ms is None else round(dense_ms, 4),
                            "framework_1x1_bf16_plus_own_depthwise_f32":
@@ -380,7 +386,8 @@ def bench_block(args, synth, wcc, torch, np) -> int:
         cores = min(len(os.sched_getaffinity(0)), 16)
         wcc_ref.set_threads(cores)
         t1 = time.perf_counter()
-        wcc_ref.block_forward(r["x"][:1], r["w1"].values, None, r["w_dw"], r["w3"].values, None, cfg.levels,
+        wcc_ref.block_forward(r["x"][:1], r["w1"].values, r["w1"].scale, r["w_dw"], r["w3"].values,
+                              r["w3"].scale, cfg.levels,
                               cfg.keep_num, cfg.keep_den, cfg.act_bits)
         cpu_dt = time.perf_counter() - t1
         out["cpu_baseline"] = {"value": round(cfg.N * cfg.C / cpu_dt / 1e9, 5), "unit": "Gpixel*ch/s",
@@ -395,7 +402,7 @@ def bench_table(args, synth, wcc, torch, np) -> int:
     dense block on the same GPU, their ratio, and the paper's ratio as context.  One JSON line."""
     rows = []
     for side, c, e, B, (num, den), paper in PAPER_TABLE:
-        cfg = block_from_shape(synth, f"{side},{c},{e},{B}", num, den)
+        cfg = block_from_shape(synth, f"{side},{c},{e},{B}", num, den, args.weights)
         print(f"bench.py: {cfg.name}", file=sys.stderr, flush=True)
         r = time_block(cfg, args, synth, wcc, torch, np, dense=True)
         wcc_ms = r["dt"] * 1e3
@@ -409,7 +416,7 @@ def bench_table(args, synth, wcc, torch, np) -> int:
     won = [r for r in rows if r["speedup"] and r["speedup"] > 1.0]
     out = {"metric": "inverted residual block, WCC vs dense on the same GPU", "unit": "ms",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
-           "dtype": "bf16", "act": args.act,
+           "dtype": "int8" if args.weights == "i8" else "bf16", "act": args.act, "weights": args.weights,
            "dense": "framework bf16 1x1 convolutions + this library's fp32 depthwise kernel",
            "rows_faster_than_dense": len(won), "rows": rows}
     print(json.dumps(out))
@@ -441,6 +448,9 @@ def main() -> int:
     ap.add_argument("--index-list", choices=["select", "prefix"], default="select",
                     help="prefix: wcc_forward_fixed with the first k positions instead of the joint "
                          "shrinkage's top-k (single-layer workloads)")
+    ap.add_argument("--weights", choices=["bf16", "i8"], default="bf16",
+                    help="block (--config 6, --table): storage type of the two 1x1 kernels; i8 = "
+                         "8-bit codes with a scale per output channel (the paper's 8-bit weights)")
     ap.add_argument("--shape", default="", metavar="SIDE,c,e,B",
                     help="--config 6: another block shape (image side or HxW, c_in, expansion, batch)")
     ap.add_argument("--table", action="store_true",

@@ -260,16 +260,18 @@ class BlockCfg:
                         clip_hi=self.clip_hi, seed=self.seed + 17 * which)
 
 
-def block_shape(H: int, W: int, c: int, e: int, B: int, keep_num: int, keep_den: int) -> BlockCfg:
-    """Any row of the paper's timing table: 3 levels, bf16 weights, 8-bit codes."""
-    return BlockCfg(f"block_{H}x{W}_c{c}_e{e}_b{B}_keep{keep_num}of{keep_den}", B, c, e, H, W, 3,
-                    keep_num, keep_den, W_BF16, 8)
+def block_shape(H: int, W: int, c: int, e: int, B: int, keep_num: int, keep_den: int,
+                w_dtype: int = W_BF16) -> BlockCfg:
+    """Any row of the paper's timing table: 3 levels, 8-bit codes, bf16 weights (or int8 codes
+    with a scale per output channel, the paper's 8-bit weight setting)."""
+    tag = "" if w_dtype == W_BF16 else "_w8"
+    return BlockCfg(f"block_{H}x{W}_c{c}_e{e}_b{B}_keep{keep_num}of{keep_den}{tag}", B, c, e, H, W, 3,
+                    keep_num, keep_den, w_dtype, 8)
 
 
-def block_config(keep_num: int = 1, keep_den: int = 4) -> BlockCfg:
+def block_config(keep_num: int = 1, keep_den: int = 4, w_dtype: int = W_BF16) -> BlockCfg:
     """A row of the paper's timing table: 256x256 image, c_in 256, expansion 4, batch 8."""
-    return BlockCfg(f"block_256x256_c256_e4_b8_keep{keep_num}of{keep_den}", 8, 256, 4, 256, 256, 3,
-                    keep_num, keep_den, W_BF16, 8)
+    return block_shape(256, 256, 256, 4, 8, keep_num, keep_den, w_dtype)
 
 
 def make_block_inputs(cfg: BlockCfg):

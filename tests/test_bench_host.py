@@ -135,3 +135,6 @@ def test_timing_table_rows_are_the_papers():
         assert cfg.layer(1).C_in == cfg.C_mid and cfg.layer(0).C_out == cfg.C_mid
     rect = bench.block_from_shape(synth, "64x128,16,2,3", 1, 8)
     assert (rect.H, rect.W, rect.C, rect.expansion, rect.B) == (64, 128, 16, 2, 3)
+    assert rect.w_dtype == synth.W_BF16 and synth.block_config(1, 4).name == "block_256x256_c256_e4_b8_keep1of4"
+    w8 = bench.block_from_shape(synth, "256,256,4,8", 1, 4, "i8")       # --weights i8
+    assert w8.w_dtype == synth.W_I8 and w8.layer(1).w_dtype == synth.W_I8 and w8.name.endswith("_w8")
