@@ -243,6 +243,9 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
     float beyond[RR];
 #pragma unroll
     for (int i = 0; i < RR; ++i) beyond[i] = 0.f;
+    // (a last segment of a single lane: that lane is first and last at once; `beyond` then holds
+    // the column to its left, and to its right lies the plane's border)
+    bool left_only = false;
     if constexpr (SEGS > 1) {
       float *ex = xchg + parity * (SEGS * 2 * RR);
       parity ^= 1;
@@ -263,12 +266,13 @@ __device__ __forceinline__ void chain_walk(const float *__restrict__ plane, int6
 #pragma unroll
         for (int i = 0; i < RR; ++i) beyond[i] = in[i];
       }
+      left_only = at0;
     }
 #pragma unroll
     for (int i = 0; i < RR; ++i) {
       float l = __shfl_up(six[i][V], 1, kWave), r = __shfl_down(six[i][1], 1, kWave);
       if (first_lane) l = beyond[i];
-      if (last_lane) r = beyond[i];
+      if (last_lane) r = left_only ? 0.f : beyond[i];
       six[i][0] = l;
       six[i][V + 1] = r;
     }

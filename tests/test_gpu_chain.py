@@ -9,7 +9,7 @@ depends on: one, two and four strips a wave, planes of one strip (no row above o
 strips, rows that leave lanes idle, every level count, kept lists of 4, 8, 16 and 32 rows a wave,
 strips that keep everything (the slot-by-slot route) and strips that keep nothing, no quantiser,
 int8 weights, several samples and channel groups, and rows shared by two and by four waves (full
-and ragged last segments; empty strips beside full ones; every level count).
+and ragged last segments, a last segment of one lane; empty strips beside full ones; every level count).
 """
 import numpy as np
 import pytest
@@ -50,6 +50,9 @@ CASES = [
     blk("two_segments_d1", 1, 4, 2, 6, 384, 1, 1, 4, BF16, 8),         # d = 1, 64 + 32 lanes
     blk("two_segments_dense_top", 1, 4, 2, 32, 512, 3, 1, 4, BF16, 8), # packed, slot-by-slot and empty strips in one plane
     blk("two_segments_f32", 1, 4, 2, 16, 512, 2, 2, 7, F32, 0, 1.0),   # fp32 path through shared rows
+    blk("two_segments_lone_lane", 1, 4, 2, 14, 260, 1, 1, 5, BF16, 8, 1.0),   # 64 + 1 lanes: the last lane is first and last of its segment
+    blk("four_segments_lone_lane", 3, 16, 8, 14, 772, 1, 1, 5, I8, 8, 1.0),   # 64 + 64 + 64 + 1 lanes
+    blk("two_segments_lone_lane_d2", 2, 4, 3, 16, 260, 2, 1, 4, BF16, 8),      # the same at d = 2 (W % 8 == 4: no d = 3)
     # enough kept coefficients in the project layer for the int8 route (clipping parameter known
     # before the second pass; the small cases above take the fp32 route)
     blk("codes_two_strips", 4, 64, 8, 64, 128, 3, 1, 4, BF16, 8),      # 512 middle channels, k = 2048
