@@ -9,7 +9,8 @@ depends on: one, two and four strips a wave, planes of one strip (no row above o
 strips, rows that leave lanes idle, every level count, kept lists of 4, 8, 16 and 32 rows a wave,
 strips that keep everything (the slot-by-slot route) and strips that keep nothing, no quantiser,
 int8 weights, several samples and channel groups, and rows shared by two and by four waves (full
-and ragged last segments, a last segment of one lane; empty strips beside full ones; every level count).
+and ragged last segments, a last segment of one lane; empty strips beside full ones; every level count),
+followed by 60 seeded random shapes (a sweep of such shapes is what found the one-lane case).
 """
 import numpy as np
 import pytest
@@ -80,12 +81,41 @@ def ctx():
     c.close()
 
 
-@pytest.mark.parametrize("cfg", CASES, ids=lambda c: c.name)
+def draw_chained(seed: int) -> synth.BlockCfg:
+    """A random block of a shape the chained route may take: every level count, widths of one,
+    two and four wave rows with an accent on the ones around the seams (a last segment of one
+    or two lanes, one lane short of full), 1-3 samples, every weight type."""
+    rng = np.random.default_rng(9000 + seed)
+    d = int(rng.choice([1, 2, 3, 3]))
+    s = max(1 << d, 4)
+    kind = int(rng.integers(0, 5))
+    if kind == 0:
+        W = int(rng.integers(2, 65)) * 4          # up to 256
+    elif kind == 1:
+        W = int(rng.integers(65, 129)) * 4        # two wave rows
+    elif kind == 2:
+        W = int(rng.integers(193, 257)) * 4       # four wave rows
+    elif kind == 3:
+        W = int(rng.choice([260, 264, 772, 776, 508, 1020, 252, 132, 36]))
+    else:
+        W = int(rng.choice([64, 96, 128, 256, 512, 1024]))
+    W = max(s, (W // s) * s)
+    H = int(rng.integers(1, 13)) * (1 << d)
+    wd = int(rng.choice([F32, BF16, BF16, I8]))
+    bits = 0 if (wd == F32 and rng.random() < 0.5) else 8
+    return blk(f"rand{seed}", int(rng.integers(1, 4)), int(rng.choice([2, 4, 8, 16, 32])),
+               int(rng.choice([2, 3, 4, 8])), H, W, d, 1, int(rng.choice([3, 4, 5, 8, 16, 40])), wd, bits,
+               float(rng.choice([1.0, 2.0, 3.0])))
+
+
+@pytest.mark.parametrize("cfg", CASES + [draw_chained(s) for s in range(60)], ids=lambda c: c.name)
 def test_chained_block_matches_oracle_and_materialised_route(ref, ctx, cfg):
     print(f"{cfg}", flush=True)
     x, w1, w_dw, w3 = block_inputs(cfg)
     d = wcc.make_block_desc(cfg.B, cfg.C, cfg.expansion, cfg.H, cfg.W, cfg.levels, cfg.keep_num,
                             cfg.keep_den, cfg.w_dtype, cfg.act_bits)
+    if cfg.name.startswith("rand") and not wcc.block_is_chained(d):
+        pytest.skip("a random shape the chained route does not take (3 k > N, or three wave rows)")
     assert wcc.block_is_chained(d)
     ctx.ensure_workspace(d)
     xd = dev(x)
